@@ -1,0 +1,129 @@
+"""Python face of the CPU oracle (oracle/lapis_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Tests, the smoke check and the bench's
+cpu_baseline leg may import this package; the product package never does.
+It builds the C file with gcc (-O2 -ffp-contract=off, no OpenMP: the oracle is
+serial) and marshals NumPy arrays; all arithmetic is in the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lapis_oracle.c")
+_LIB = os.path.join(_HERE, "liblapis_oracle.so")
+
+# The partition definition's parameters as the oracle states them (wavefront width,
+# long-row threshold, tile size, bin count).  A test checks that the GPU
+# library reports the same values.
+WAVE = 64
+LONG_THRESHOLD = 4096
+TILE_NNZ = 4096
+NUM_BINS = 10
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-ffp-contract=off", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, f64, p = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        for name in ("oracle_spmv_f64", "oracle_spmv_f32"):
+            getattr(lib, name).argtypes = [i64, p, p, p, p, f64, f64, p, p, p]
+            getattr(lib, name).restype = None
+        for name in ("oracle_spmm_f64", "oracle_spmm_f32"):
+            getattr(lib, name).argtypes = [i64, i64, p, p, p, p, i64, f64, f64, p, p, i64, p]
+            getattr(lib, name).restype = None
+        lib.oracle_partition_num_bins.argtypes = [i64]
+        lib.oracle_partition_num_bins.restype = ctypes.c_int
+        lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, p, p, p, p]
+        lib.oracle_partition_rows.restype = None
+        lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
+        lib.oracle_partition_tiles.restype = None
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_csr(rowptr, colidx, vals):
+    assert rowptr.dtype == np.int32 and colidx.dtype == np.int32
+    assert rowptr.flags.c_contiguous and colidx.flags.c_contiguous and vals.flags.c_contiguous
+    assert vals.dtype in (np.float32, np.float64)
+
+
+def spmv(rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None):
+    """Returns (y, absAx): y = alpha*A*x + beta*y0 in vals.dtype, absAx = |A||x| in float64."""
+    _check_csr(rowptr, colidx, vals)
+    n = rowptr.size - 1
+    dt = vals.dtype
+    x = np.ascontiguousarray(x, dtype=dt)
+    if beta != 0.0:
+        assert y0 is not None
+        y0 = np.ascontiguousarray(y0, dtype=dt)
+    y = np.empty(n, dtype=dt)
+    absAx = np.empty(n, dtype=np.float64)
+    fn = _load().oracle_spmv_f64 if dt == np.float64 else _load().oracle_spmv_f32
+    fn(n, _p(rowptr), _p(colidx), _p(vals), _p(x), float(alpha), float(beta),
+       _p(y0) if beta != 0.0 else None, _p(y), _p(absAx))
+    return y, absAx
+
+
+def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):
+    """Returns (Y, absAX) for row-major X (ncols x k); Y is nrows x k contiguous."""
+    _check_csr(rowptr, colidx, vals)
+    n = rowptr.size - 1
+    dt = vals.dtype
+    assert X.ndim == 2 and X.dtype == dt and X.strides[1] == X.itemsize
+    k = X.shape[1]
+    ldx = X.strides[0] // X.itemsize if X.shape[0] > 1 else k
+    if beta != 0.0:
+        assert Y0 is not None
+        Y0 = np.ascontiguousarray(Y0, dtype=dt)
+        assert Y0.shape == (n, k)
+    Y = np.empty((n, k), dtype=dt)
+    absAX = np.empty((n, k), dtype=np.float64)
+    fn = _load().oracle_spmm_f64 if dt == np.float64 else _load().oracle_spmm_f32
+    fn(n, k, _p(rowptr), _p(colidx), _p(vals), _p(X), ldx, float(alpha), float(beta),
+       _p(Y0) if beta != 0.0 else None, _p(Y), k, _p(absAX))
+    return Y, absAX
+
+
+def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NNZ):
+    """Reference row partition.  Returns a dict with
+    bin_offset[num_bins+1], row_perm[nrows], long_off[m+1], tile_row[T+1], tile_nz[T+1]."""
+    assert rowptr.dtype == np.int32 and rowptr.flags.c_contiguous
+    lib = _load()
+    n = rowptr.size - 1
+    nb = lib.oracle_partition_num_bins(wave)
+    bin_offset = np.zeros(nb + 1, dtype=np.int32)
+    row_perm = np.empty(n, dtype=np.int32)
+    m = ctypes.c_int64(0)
+    T = ctypes.c_int64(0)
+    lib.oracle_partition_rows(n, _p(rowptr), wave, long_threshold, tile_nnz, _p(bin_offset),
+                              _p(row_perm), ctypes.addressof(m), ctypes.addressof(T))
+    m, T = m.value, T.value
+    long_rows = np.ascontiguousarray(row_perm[bin_offset[nb - 1]:bin_offset[nb]])
+    long_off = np.zeros(m + 1, dtype=np.int32)
+    tile_row = np.zeros(T + 1, dtype=np.int32)
+    tile_nz = np.zeros(T + 1, dtype=np.int32)
+    lib.oracle_partition_tiles(_p(rowptr), tile_nnz, _p(long_rows), m, T, _p(long_off),
+                               _p(tile_row), _p(tile_nz))
+    return {"num_bins": nb, "bin_offset": bin_offset, "row_perm": row_perm,
+            "long_off": long_off, "tile_row": tile_row, "tile_nz": tile_nz}

@@ -1,0 +1,194 @@
+/*
+ * CPU oracle for the CSR sparse matrix-vector product and its multi-vector
+ * form.  TEST INFRASTRUCTURE ONLY: tests, the smoke check and the bench's
+ * cpu_baseline leg may call it; the product path never does, and nothing here
+ * shares code, headers, tables or helpers with the GPU library.
+ *
+ * What it computes is the plain definition the paper gives in Section 6.2
+ * (y := A x, A in CSR, x and y dense), walked with the row / entry loop nest
+ * of Section 4.2 ("Parallelism estimation": for each row i, begin =
+ * offsets[i], end = offsets[i+1], entries begin..end-1), serial, entries taken
+ * left to right.  The scaling y = alpha*A*x + beta*y0 is the BLAS-style
+ * extension of the problem statement; beta == 0 means y0 is never read.
+ *
+ * Precision: every sum and product is formed in double.  For float matrices
+ * the inputs are promoted exactly and the result is rounded to float once.
+ * Build with -ffp-contract=off so that no fused multiply-add is introduced.
+ *
+ * Beside each result the oracle returns (|A||x|)_i = sum_j |a_ij| |x_j|, the
+ * quantity the floating-point tolerance is stated in.
+ *
+ * The row-partition reference at the end is the integer definition of the
+ * analysis pass (row bins by length, stable row lists, equal-nnz tiles over
+ * the long rows), written as plain loops.  Its constants are arguments, so
+ * this file carries no copy of the library's header.
+ *
+ * Pins (tests marked "not gpu"): dense brute force on tiny matrices,
+ * identity and diagonal matrices, the 5-point Laplacian's closed forms on
+ * constant and linear grid functions, exact integer-valued cases, linearity,
+ * SpMM column == SpMV, library cross-checks (SciPy / PyTorch CPU), and
+ * structural invariants of the partition.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+
+/* ---- SpMV, double matrix ------------------------------------------------ */
+void oracle_spmv_f64(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
+                     const double *vals, const double *x, double alpha, double beta,
+                     const double *y0, double *y, double *absAx)
+{
+    for (int64_t i = 0; i < nrows; ++i) {
+        double s = 0.0, t = 0.0;
+        for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+            double a = vals[j], b = x[colidx[j]];
+            s += a * b;
+            t += fabs(a) * fabs(b);
+        }
+        y[i] = (beta == 0.0) ? alpha * s : alpha * s + beta * y0[i];
+        if (absAx) absAx[i] = t;
+    }
+}
+
+/* ---- SpMV, float matrix: double arithmetic, one final rounding ---------- */
+void oracle_spmv_f32(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
+                     const float *vals, const float *x, double alpha, double beta,
+                     const float *y0, float *y, double *absAx)
+{
+    for (int64_t i = 0; i < nrows; ++i) {
+        double s = 0.0, t = 0.0;
+        for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+            double a = (double)vals[j], b = (double)x[colidx[j]];
+            s += a * b;
+            t += fabs(a) * fabs(b);
+        }
+        double r = (beta == 0.0) ? alpha * s : alpha * s + beta * (double)y0[i];
+        y[i] = (float)r;
+        if (absAx) absAx[i] = t;
+    }
+}
+
+/* ---- SpMM: Y = alpha*A*X + beta*Y0, X, Y0, Y row-major with leading
+ * dimensions ldx, ldy (Y0 and Y share ldy); absAX is nrows*k contiguous.
+ * Column c is by definition the SpMV with column c of X. ------------------- */
+void oracle_spmm_f64(int64_t nrows, int64_t k, const int32_t *rowptr, const int32_t *colidx,
+                     const double *vals, const double *X, int64_t ldx, double alpha, double beta,
+                     const double *Y0, double *Y, int64_t ldy, double *absAX)
+{
+    for (int64_t i = 0; i < nrows; ++i) {
+        for (int64_t c = 0; c < k; ++c) {
+            double s = 0.0, t = 0.0;
+            for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+                double a = vals[j], b = X[(int64_t)colidx[j] * ldx + c];
+                s += a * b;
+                t += fabs(a) * fabs(b);
+            }
+            Y[i * ldy + c] = (beta == 0.0) ? alpha * s : alpha * s + beta * Y0[i * ldy + c];
+            if (absAX) absAX[i * k + c] = t;
+        }
+    }
+}
+
+void oracle_spmm_f32(int64_t nrows, int64_t k, const int32_t *rowptr, const int32_t *colidx,
+                     const float *vals, const float *X, int64_t ldx, double alpha, double beta,
+                     const float *Y0, float *Y, int64_t ldy, double *absAX)
+{
+    for (int64_t i = 0; i < nrows; ++i) {
+        for (int64_t c = 0; c < k; ++c) {
+            double s = 0.0, t = 0.0;
+            for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+                double a = (double)vals[j], b = (double)X[(int64_t)colidx[j] * ldx + c];
+                s += a * b;
+                t += fabs(a) * fabs(b);
+            }
+            double r = (beta == 0.0) ? alpha * s : alpha * s + beta * (double)Y0[i * ldy + c];
+            Y[i * ldy + c] = (float)r;
+            if (absAX) absAX[i * k + c] = t;
+        }
+    }
+}
+
+/* ---- Row partition reference --------------------------------------------
+ * Per-row lane count in the spirit of the vector-length estimate of
+ * Section 4.2 (entries per row, rounded up, clamped to the hardware vector
+ * width), applied row by row instead of once per matrix and rounded up to a
+ * power of two, with the wavefront width wave as the clamp:
+ *   bin 0                : L == 0
+ *   bin b, 1 <= b <= B-3 : smallest b with 2^(b-1) >= L, for 1 <= L <= wave
+ *                          (wave = 2^(B-3))
+ *   bin B-2              : wave < L <= long_threshold
+ *   bin B-1              : L > long_threshold
+ * With wave = 64 this gives B = 10 bins.
+ */
+static int bin_of_length(int64_t L, int64_t wave, int64_t long_threshold)
+{
+    if (L == 0) return 0;
+    if (L <= wave) {
+        int b = 1;
+        int64_t g = 1;
+        while (g < L) { g *= 2; ++b; }
+        return b;
+    }
+    int top = 1;
+    for (int64_t g = 1; g < wave; g *= 2) ++top; /* top = 1 + log2(wave) = last group bin */
+    return (L <= long_threshold) ? top + 1 : top + 2;
+}
+
+/* Number of bins for a given wave width. */
+int oracle_partition_num_bins(int64_t wave)
+{
+    return bin_of_length(wave + 1, wave, wave + 1) + 2;
+}
+
+/* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and
+ * row_perm[nrows] (row ids grouped by bin, ascending inside each bin).
+ * Returns through *num_long the number of rows in the last bin and through
+ * *num_tiles the number of tiles T = ceil(total long nnz / tile_nnz). */
+void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
+                           int64_t long_threshold, int64_t tile_nnz, int32_t *bin_offset,
+                           int32_t *row_perm, int64_t *num_long, int64_t *num_tiles)
+{
+    int nb = oracle_partition_num_bins(wave);
+    for (int b = 0; b <= nb; ++b) bin_offset[b] = 0;
+    for (int64_t i = 0; i < nrows; ++i)
+        bin_offset[bin_of_length(rowptr[i + 1] - rowptr[i], wave, long_threshold) + 1] += 1;
+    for (int b = 0; b < nb; ++b) bin_offset[b + 1] += bin_offset[b];
+    int64_t long_nnz = 0;
+    for (int b = 0; b < nb; ++b) {
+        int64_t at = bin_offset[b];
+        for (int64_t i = 0; i < nrows; ++i) {
+            int64_t L = rowptr[i + 1] - rowptr[i];
+            if (bin_of_length(L, wave, long_threshold) != b) continue;
+            row_perm[at++] = (int32_t)i;
+            if (b == nb - 1) long_nnz += L;
+        }
+    }
+    *num_long = bin_offset[nb] - bin_offset[nb - 1];
+    *num_tiles = (long_nnz + tile_nnz - 1) / tile_nnz;
+}
+
+/* Pass 2, over the rows of the last bin in row_perm order:
+ *   long_off[0..m]  exclusive scan of their lengths (their entries laid end
+ *                   to end form the "long nnz space" of size long_off[m]);
+ *   tile t covers long nnz positions [t*tile_nnz, (t+1)*tile_nnz);
+ *   tile_row[t]     index r in 0..m-1 of the long row holding position
+ *                   t*tile_nnz, i.e. the largest r with long_off[r] <= t*tile_nnz;
+ *   tile_nz[t]      t*tile_nnz - long_off[tile_row[t]], the offset inside it;
+ *   sentinel        tile_row[T] = m, tile_nz[T] = 0.
+ */
+void oracle_partition_tiles(const int32_t *rowptr, int64_t tile_nnz, const int32_t *long_rows,
+                            int64_t m, int64_t T, int32_t *long_off, int32_t *tile_row,
+                            int32_t *tile_nz)
+{
+    long_off[0] = 0;
+    for (int64_t r = 0; r < m; ++r)
+        long_off[r + 1] = long_off[r] + (rowptr[long_rows[r] + 1] - rowptr[long_rows[r]]);
+    for (int64_t t = 0; t < T; ++t) {
+        int64_t pos = t * tile_nnz;
+        int64_t r = 0;
+        while (r + 1 <= m - 1 && long_off[r + 1] <= pos) ++r;
+        tile_row[t] = (int32_t)r;
+        tile_nz[t] = (int32_t)(pos - long_off[r]);
+    }
+    tile_row[T] = (int32_t)m;
+    tile_nz[T] = 0;
+}
