@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSR SpMV hot path on one MI355X.
+
+A step is one lapis_spmv call (y = alpha*A*x + beta*y) on the 128^3 27-point
+fp64 stencil matrix, inputs resident in HBM.  Timing follows the paper's
+protocol (Appendix, system configuration: untimed warm-up, then the mean over
+the timed repetitions).  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(w):
+    """vals + colidx + rowptr + x + y (y twice when beta != 0), each counted once."""
+    e = w.vals.itemsize
+    k = max(w.k, 1)
+    y_passes = 2 if w.beta != 0.0 else 1
+    return (w.nnz * (e + 4) + (w.nrows + 1) * 4 + w.ncols * k * e + y_passes * w.nrows * k * e)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import gen
+    import paper_2509_25605_amd as L
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    L.load()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+
+    w = gen.workload(args.config)
+    tdt = torch.float64 if w.dtype == np.float64 else torch.float32
+    rowptr = torch.from_numpy(w.rowptr).to(dev)
+    colidx = torch.from_numpy(w.colidx).to(dev)
+    vals = torch.from_numpy(w.vals).to(dev)
+    x = torch.from_numpy(np.ascontiguousarray(w.x)).to(dev)
+    k = max(w.k, 1)
+    y = (torch.from_numpy(w.y0).to(dev) if w.y0 is not None
+         else torch.zeros(w.nrows * k, dtype=tdt, device=dev))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    A = L.CsrMatrix(w.nrows, w.ncols, rowptr, colidx, vals)
+    torch.cuda.synchronize()
+    create_ms = (time.perf_counter() - t0) * 1e3
+
+    if w.k == 0:
+        step = lambda: L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
+    else:
+        step = lambda: L.lapis_spmm(A.handle, w.k, w.alpha, x, w.k, w.beta, y, w.k)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - wall0) * 1e3
+    ev_ms = start.elapsed_time(stop)
+    ms_per_step = wall_ms / args.steps          # barrier-to-barrier wall clock
+    kernel_ms = ev_ms / args.steps              # events on the launch stream
+
+    nbytes = algorithmic_bytes(w)
+    flops = 2.0 * w.nnz * k
+    gbs = nbytes / (ms_per_step * 1e-3) / 1e9
+    achieved = nbytes / (kernel_ms * 1e-3) / 1e9
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        fn = (lambda: oracle.spmv(w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0)) if w.k == 0 else (
+            lambda: oracle.spmm(w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0))
+        fn()
+        reps, best, spent = 0, float("inf"), 0.0
+        while spent < args.cpu_seconds or reps < 3:
+            t = time.perf_counter()
+            fn()
+            d = time.perf_counter() - t
+            best, spent, reps = min(best, d), spent + d, reps + 1
+        cpu = {"value": round(nbytes / best / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"full workload, best of {reps} serial passes ({best * 1e3:.1f} ms each; "
+                         f"{flops / best / 1e9:.2f} GFLOP/s), 1 of {os.cpu_count()} host cores"}
+
+    out = {
+        "metric": "CSR SpMV effective HBM GB/s (vals+colidx+rowptr+x+y bytes / time); "
+                  "gflops and frac_hbm_peak alongside",
+        "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64" if w.dtype == np.float64 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "nrows": w.nrows, "nnz": w.nnz, "k": w.k, "alpha": w.alpha,
+                   "beta": w.beta, "index": "int32", "bytes_per_step": nbytes},
+        "gflops": round(flops / (ms_per_step * 1e-3) / 1e9, 2),
+        "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+        "create_ms": round(create_ms, 3),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel_ms": round(kernel_ms, 6)},
+        "cpu_baseline": cpu,
+    }
+    A.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,152 @@
+/*
+ * lapis.h - C ABI of the MI355X (gfx950) CSR SpMV / SpMM library.
+ *
+ * The library computes the sparse kernel the LAPIS paper generates and times in
+ * Section 6.2: y := A x with A in compressed sparse row form and x, y dense,
+ * extended BLAS-style to y = alpha*A*x + beta*y, and its multi-vector form
+ * Y = alpha*A*X + beta*Y.  The row / entry traversal is the CSR loop nest of
+ * Section 4.2 ("Parallelism estimation"): row i owns the entries
+ * offsets[i] .. offsets[i+1]-1 of the value and column-index arrays.
+ *
+ * Conventions (after Section 5, where the generated code is wrapped in
+ * unmangled functions taking raw pointers and sizes, and Section 4.3, where
+ * data stays on the device between kernels):
+ *   - every array argument is a DEVICE pointer unless its name starts with h_;
+ *   - the library never copies, frees or writes the caller's matrix arrays;
+ *   - every function returns a status code, never throws, aborts or prints;
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Row indices and column indices are 32-bit; nnz and nrows+1 must fit in int32.
+ */
+#ifndef LAPIS_H
+#define LAPIS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------- */
+#define LAPIS_OK               0
+#define LAPIS_ERR_INVALID_ARG  1   /* null pointer, negative size, size beyond int32, ld < k, k <= 0 */
+#define LAPIS_ERR_UNSUPPORTED  2   /* dtype not LAPIS_F32 / LAPIS_F64 */
+#define LAPIS_ERR_ALLOC        3   /* device or host allocation failed */
+#define LAPIS_ERR_DEVICE       4   /* a HIP call failed; text via lapis_last_error() */
+
+/* ---- value types -------------------------------------------------------- */
+#define LAPIS_F32 0
+#define LAPIS_F64 1
+
+/* ---- row partition constants ---------------------------------------------
+ * The analysis pass generalises the vector-length estimate of Section 4.2
+ * (entries per row, rounded up, clamped to the hardware vector width) from one
+ * value per matrix to one value per row.  With L the number of entries of a row:
+ *   bin 0      L == 0
+ *   bin b      1 <= b <= 7: smallest b with 2^(b-1) >= L   (1 <= L <= 64);
+ *              2^(b-1) is the row's lane-group size, 64 = the gfx950 wavefront
+ *   bin 8      64 < L <= LAPIS_LONG_THRESHOLD  (one wavefront walks the row)
+ *   bin 9      L > LAPIS_LONG_THRESHOLD        (row is cut into tiles)
+ * The entries of the bin-9 rows, laid end to end in row order, are cut into
+ * tiles of LAPIS_TILE_NNZ entries; LAPIS_LONG_THRESHOLD >= LAPIS_TILE_NNZ, so a
+ * tile touches at most two rows.
+ */
+#define LAPIS_NUM_BINS        10
+#define LAPIS_WAVE            64
+#define LAPIS_LONG_THRESHOLD  4096
+#define LAPIS_TILE_NNZ        4096
+
+typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
+
+/*
+ * lapis_csr_create - wrap a device-resident CSR matrix and run the row
+ * partition analysis (the per-row form of the Section 4.2 estimate) on it.
+ *
+ *   out        receives the handle; set to NULL on any error
+ *   nrows, ncols, nnz   sizes, all >= 0; nnz and nrows+1 must fit in int32
+ *   d_rowptr   int32[nrows+1], d_rowptr[0] == 0, non-decreasing,
+ *              d_rowptr[nrows] == nnz
+ *   d_colidx   int32[nnz], 0 <= d_colidx[j] < ncols; columns inside a row need
+ *              be neither sorted nor distinct (repeated columns add up)
+ *   d_vals     float[nnz] or double[nnz] according to dtype
+ *   dtype      LAPIS_F32 or LAPIS_F64; x, y, X, Y of later calls have this type
+ *   hip_stream stream the analysis kernels run on
+ *
+ * Ownership: the three arrays are BORROWED; they must stay allocated and
+ * unchanged until lapis_csr_destroy.  The handle owns only its analysis
+ * buffers (bin offsets, per-bin row lists, tile table, per-tile partial sums).
+ * The call synchronises hip_stream (it reads back the bin counts and checks
+ * d_rowptr[0] == 0 and d_rowptr[nrows] == nnz; a mismatch is
+ * LAPIS_ERR_INVALID_ARG).  d_colidx and d_vals may be NULL when nnz == 0.
+ */
+int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nnz,
+                     const int32_t *d_rowptr, const int32_t *d_colidx, const void *d_vals,
+                     int dtype, void *hip_stream);
+
+/*
+ * lapis_spmv - y = alpha*A*x + beta*y  (Section 6.2: y := A x; alpha = 1, beta = 0).
+ *
+ *   d_x   ncols elements of A's dtype, contiguous
+ *   d_y   nrows elements of A's dtype, contiguous; must not overlap d_x or A
+ *   alpha, beta   passed as double; rounded to float for LAPIS_F32 matrices
+ *
+ * beta == 0 makes d_y write-only: its old contents (NaN included) are ignored.
+ * Rows without entries receive beta*y (exactly +0 when beta == 0).
+ * Asynchronous: the kernels are enqueued on hip_stream and the call returns;
+ * no allocation, no host-device copy, no synchronisation.  Matrices with rows
+ * in bin 9 use per-tile scratch owned by the handle, so two calls on the same
+ * handle must not run concurrently on different streams.
+ */
+int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+               void *hip_stream);
+
+/*
+ * lapis_spmm - Y = alpha*A*X + beta*Y for k right-hand sides; column c of Y is
+ * by definition lapis_spmv applied to column c of X (the paper times only the
+ * single-vector product; this is its multi-vector form).
+ *
+ *   d_X   ncols x k, ROW-MAJOR, leading dimension ldx >= k (in elements)
+ *   d_Y   nrows x k, ROW-MAJOR, leading dimension ldy >= k; must not overlap d_X or A
+ *   k     >= 1
+ *
+ * Same dtype, beta == 0, asynchrony and concurrency rules as lapis_spmv.
+ */
+int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, int64_t ldx,
+               double beta, void *d_Y, int64_t ldy, void *hip_stream);
+
+/*
+ * lapis_csr_destroy - free the handle's own buffers.  NULL is a no-op that
+ * returns LAPIS_OK.  The caller must have synchronised every stream that still
+ * has work using the handle.  The borrowed matrix arrays are left alone.
+ */
+int lapis_csr_destroy(lapis_csr_t *A);
+
+/* ---- inspection of the row partition (for bit-exact checks) --------------
+ * lapis_csr_partition_sizes: *num_long = rows in bin 9, *num_tiles = number of
+ * tiles T.  Either pointer may be NULL.
+ * lapis_csr_copy_partition: copies to HOST buffers the caller owns (any may be
+ * NULL to skip it):
+ *   h_bin_offset int32[LAPIS_NUM_BINS+1]  exclusive scan of per-bin row counts
+ *   h_row_perm   int32[nrows]             row ids grouped by bin, ascending in each bin
+ *   h_long_off   int32[num_long+1]        exclusive scan of the bin-9 rows' lengths
+ *   h_tile_row   int32[T+1]               bin-9 row (index into its list) holding
+ *                                         long position t*LAPIS_TILE_NNZ; [T] = num_long
+ *   h_tile_nz    int32[T+1]               offset of that position inside the row; [T] = 0
+ * Synchronises the device.
+ */
+int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_long, int64_t *num_tiles);
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_bin_offset, int32_t *h_row_perm,
+                             int32_t *h_long_off, int32_t *h_tile_row, int32_t *h_tile_nz);
+
+/* The partition constants compiled into the library, in the order
+ * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ}. */
+int lapis_partition_constants(int64_t h_out[4]);
+
+/* Text of the most recent error on the calling thread ("" if none).  The
+ * pointer stays valid until the next failing call on that thread. */
+const char *lapis_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAPIS_H */

@@ -1,0 +1,136 @@
+"""ctypes binding of liblapis_mi355x.so: argument marshalling only.
+
+The functions carry the names of the C entry points (include/lapis.h).  Array
+arguments are torch tensors on the GPU (their data_ptr() is passed) or plain
+integer device addresses; PyTorch serves for device memory and streams only.
+There is no CPU fallback: if the library is not built, loading it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblapis_mi355x.so")
+
+LAPIS_OK, LAPIS_ERR_INVALID_ARG, LAPIS_ERR_UNSUPPORTED, LAPIS_ERR_ALLOC, LAPIS_ERR_DEVICE = range(5)
+LAPIS_F32, LAPIS_F64 = 0, 1
+
+EXPORTS = [
+    "lapis_csr_create", "lapis_spmv", "lapis_spmm", "lapis_csr_destroy",
+    "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_partition_constants",
+    "lapis_last_error",
+]
+
+
+class LapisError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"lapis error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library (build with `python -m paper_2509_25605_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run paper_2509_25605_amd.build.build() first")
+        lib = ctypes.CDLL(LIB_PATH)
+        i64, f64, p, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
+        lib.lapis_csr_create.argtypes = [ctypes.POINTER(p), i64, i64, i64, p, p, p, i32, p]
+        lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
+        lib.lapis_csr_destroy.argtypes = [p]
+        lib.lapis_csr_partition_sizes.argtypes = [p, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p]
+        lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
+        for name in EXPORTS[:-1]:
+            getattr(lib, name).restype = i32
+        lib.lapis_last_error.restype = ctypes.c_char_p
+        lib.lapis_last_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _addr(a):
+    """Device address of a torch tensor, or the integer / None given."""
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    return a.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc: int):
+    if rc != LAPIS_OK:
+        raise LapisError(rc, load().lapis_last_error().decode())
+
+
+def lapis_last_error() -> str:
+    return load().lapis_last_error().decode()
+
+
+def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, stream=None):
+    """Returns the opaque handle (a ctypes.c_void_p).  The three arrays are borrowed."""
+    out = ctypes.c_void_p()
+    _check(load().lapis_csr_create(ctypes.byref(out), nrows, ncols, nnz, _addr(d_rowptr),
+                                   _addr(d_colidx), _addr(d_vals), dtype, _stream(stream)))
+    return out
+
+
+def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
+    _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_spmm(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream=None):
+    _check(load().lapis_spmm(A, k, float(alpha), _addr(d_X), ldx, float(beta), _addr(d_Y), ldy,
+                             _stream(stream)))
+
+
+def lapis_csr_destroy(A):
+    _check(load().lapis_csr_destroy(A))
+
+
+def lapis_csr_partition_sizes(A):
+    m, t = ctypes.c_int64(), ctypes.c_int64()
+    _check(load().lapis_csr_partition_sizes(A, ctypes.byref(m), ctypes.byref(t)))
+    return m.value, t.value
+
+
+def lapis_partition_constants():
+    out = (ctypes.c_int64 * 4)()
+    _check(load().lapis_partition_constants(out))
+    return {"num_bins": out[0], "wave": out[1], "long_threshold": out[2], "tile_nnz": out[3]}
+
+
+def lapis_csr_copy_partition(A, nrows):
+    """Host copies of the row partition as NumPy int32 arrays."""
+    m, t = lapis_csr_partition_sizes(A)
+    nb = lapis_partition_constants()["num_bins"]
+    res = {
+        "bin_offset": np.empty(nb + 1, dtype=np.int32),
+        "row_perm": np.empty(nrows, dtype=np.int32),
+        "long_off": np.empty(m + 1, dtype=np.int32),
+        "tile_row": np.empty(t + 1, dtype=np.int32),
+        "tile_nz": np.empty(t + 1, dtype=np.int32),
+    }
+    ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    _check(load().lapis_csr_copy_partition(A, ptr(res["bin_offset"]), ptr(res["row_perm"]),
+                                           ptr(res["long_off"]), ptr(res["tile_row"]),
+                                           ptr(res["tile_nz"])))
+    return res

@@ -1,0 +1,166 @@
+// Row-partition analysis on the device.  It is the per-row form of the
+// vector-length estimate of Section 4.2 ("Parallelism estimation": entries per
+// row, rounded up, clamped to the hardware vector width): each row gets the bin
+// of its own length, rows are listed per bin in ascending order, and the rows
+// beyond the long threshold are cut into equal tiles of entries.  All results
+// are integers with a unique value, produced without atomics on ordered data,
+// so they can be compared bit for bit with a CPU reference.
+#pragma once
+#include "device_utils.hpp"
+
+namespace lapis {
+
+constexpr int kNumBins = 10;
+constexpr int kRowsPerThread = 8;
+constexpr int kRowsPerAnalysisBlock = kBlock * kRowsPerThread;  // 2048 rows per workgroup
+
+template <int LONG_THRESHOLD>
+__device__ __forceinline__ int bin_of_length(int32_t len)
+{
+    if (len <= 0) return 0;
+    if (len == 1) return 1;
+    if (len <= kWave) return 33 - __clz(len - 1);  // 1 + ceil(log2(len))
+    return len <= LONG_THRESHOLD ? 8 : 9;
+}
+
+// Exclusive scan of one int per thread across the workgroup; returns the
+// thread's prefix and writes the workgroup total to *total.
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *s_tmp, int32_t *total)
+{
+    // s_tmp: kBlock ints.  Hillis-Steele inclusive scan in LDS.
+    s_tmp[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < kBlock; d <<= 1) {
+        int32_t add = (threadIdx.x >= (unsigned)d) ? s_tmp[threadIdx.x - d] : 0;
+        __syncthreads();
+        s_tmp[threadIdx.x] += add;
+        __syncthreads();
+    }
+    const int32_t incl = s_tmp[threadIdx.x];
+    *total = s_tmp[kBlock - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+// Pass 1: per-workgroup histogram of row bins; hist is bin-major: hist[bin*num_blocks + block].
+template <int LONG_THRESHOLD>
+__global__ __launch_bounds__(kBlock) void bin_count_kernel(int32_t nrows,
+                                                           const int32_t *__restrict__ rowptr,
+                                                           int32_t num_blocks,
+                                                           int32_t *__restrict__ hist)
+{
+    __shared__ int32_t s_hist[kNumBins];
+    if (threadIdx.x < kNumBins) s_hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
+    for (int it = 0; it < kRowsPerThread; ++it) {
+        const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
+        if (i < nrows) atomicAdd(&s_hist[bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i])], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kNumBins) hist[(int64_t)threadIdx.x * num_blocks + blockIdx.x] = s_hist[threadIdx.x];
+}
+
+// Pass 2 (one workgroup): exclusive scan of hist in place, in bin-major order,
+// so hist[bin*num_blocks + block] becomes the first position in row_perm of the
+// rows of `bin` found by `block`; also bin_offset[0..kNumBins].
+__global__ __launch_bounds__(kBlock) void bin_scan_kernel(int64_t count, int32_t num_blocks,
+                                                          int32_t *__restrict__ hist,
+                                                          int32_t *__restrict__ bin_offset)
+{
+    __shared__ int32_t s_tmp[kBlock];
+    int32_t running = 0;
+    for (int64_t base = 0; base < count; base += kBlock) {
+        const int64_t i = base + threadIdx.x;
+        const int32_t v = (i < count) ? hist[i] : 0;
+        int32_t total;
+        const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
+        if (i < count) {
+            hist[i] = running + excl;
+            if (i % num_blocks == 0) bin_offset[i / num_blocks] = running + excl;
+        }
+        running += total;
+    }
+    if (threadIdx.x == 0) bin_offset[kNumBins] = running;
+}
+
+// Pass 3: stable scatter of row ids into row_perm.
+template <int LONG_THRESHOLD>
+__global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
+                                                             const int32_t *__restrict__ rowptr,
+                                                             int32_t num_blocks,
+                                                             const int32_t *__restrict__ hist,
+                                                             int32_t *__restrict__ row_perm)
+{
+    __shared__ int32_t s_base[kNumBins];                     // next free position per bin
+    __shared__ int32_t s_wave[kWavesPerBlock][kNumBins];     // per-wave counts of this pass
+    if (threadIdx.x < kNumBins) s_base[threadIdx.x] = hist[(int64_t)threadIdx.x * num_blocks + blockIdx.x];
+    __syncthreads();
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
+    for (int it = 0; it < kRowsPerThread; ++it) {
+        const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
+        const int bin = (i < nrows) ? bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i]) : -1;
+        int32_t rank_in_wave = 0;
+        for (int b = 0; b < kNumBins; ++b) {
+            const uint64_t mask = __ballot(bin == b);
+            if (bin == b) rank_in_wave = __popcll(mask & ((1ull << lane) - 1));
+            if (lane == 0) s_wave[wave][b] = __popcll(mask);
+        }
+        __syncthreads();
+        if (bin >= 0) {
+            int32_t pos = s_base[bin] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) pos += s_wave[w][bin];
+            row_perm[pos] = (int32_t)i;
+        }
+        __syncthreads();
+        if (threadIdx.x < kNumBins) {
+            int32_t add = 0;
+            for (int w = 0; w < kWavesPerBlock; ++w) add += s_wave[w][threadIdx.x];
+            s_base[threadIdx.x] += add;
+        }
+        __syncthreads();
+    }
+}
+
+// Pass 4 (one workgroup): long_off[0..m] = exclusive scan of the long rows' lengths.
+__global__ __launch_bounds__(kBlock) void long_scan_kernel(int32_t m, const int32_t *__restrict__ long_rows,
+                                                           const int32_t *__restrict__ rowptr,
+                                                           int32_t *__restrict__ long_off)
+{
+    __shared__ int32_t s_tmp[kBlock];
+    int32_t running = 0;
+    for (int64_t base = 0; base < m; base += kBlock) {
+        const int64_t r = base + threadIdx.x;
+        int32_t v = 0;
+        if (r < m) { const int32_t row = long_rows[r]; v = rowptr[row + 1] - rowptr[row]; }
+        int32_t total;
+        const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
+        if (r < m) long_off[r] = running + excl;
+        running += total;
+    }
+    if (threadIdx.x == 0) long_off[m] = running;
+}
+
+// Pass 5: tile t starts at long position t*TILE: tile_row[t] is the largest r
+// with long_off[r] <= t*TILE, tile_nz[t] the offset inside that row.
+template <int TILE>
+__global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t num_tiles,
+                                                             const int32_t *__restrict__ long_off,
+                                                             int32_t *__restrict__ tile_row,
+                                                             int32_t *__restrict__ tile_nz)
+{
+    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t > num_tiles) return;
+    if (t == num_tiles) { tile_row[t] = m; tile_nz[t] = 0; return; }
+    const int64_t pos = t * TILE;
+    int32_t lo = 0, hi = m - 1;  // invariant: long_off[lo] <= pos, answer in [lo, hi]
+    while (lo < hi) {
+        const int32_t mid = lo + (hi - lo + 1) / 2;
+        if (long_off[mid] <= pos) lo = mid; else hi = mid - 1;
+    }
+    tile_row[t] = lo;
+    tile_nz[t] = (int32_t)(pos - long_off[lo]);
+}
+
+}  // namespace lapis

@@ -1,0 +1,383 @@
+// C ABI of the gfx950 CSR SpMV / SpMM library: argument checks, the handle,
+// the analysis driver and the kernel launches.  Declarations and the contract
+// of every entry point are in include/lapis.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/lapis.h"
+#include "analysis_kernels.hpp"
+#include "spmm_kernels.hpp"
+#include "spmv_kernels.hpp"
+
+using namespace lapis;
+
+static_assert(LAPIS_NUM_BINS == kNumBins, "header and kernels disagree on the bin count");
+static_assert(LAPIS_WAVE == kWave, "header and kernels disagree on the wavefront width");
+static_assert(LAPIS_LONG_THRESHOLD >= LAPIS_TILE_NNZ, "a tile must touch at most two rows");
+static_assert(LAPIS_TILE_NNZ % kBlock == 0, "tile size must be a multiple of the workgroup size");
+
+struct lapis_csr {
+    int64_t nrows, ncols, nnz;
+    int dtype;
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    const void *vals;
+    // analysis results (device)
+    int32_t *d_bin_offset;  // [kNumBins + 1]
+    int32_t *d_row_perm;    // [nrows]
+    int32_t *d_long_off;    // [num_long + 1]
+    int32_t *d_tile_row;    // [num_tiles + 1]
+    int32_t *d_tile_nz;     // [num_tiles + 1]
+    void *d_partial;        // [2 * num_tiles] of dtype: per-tile segment sums
+    // host copies
+    int32_t h_bin_offset[kNumBins + 1];
+    int64_t num_long, num_tiles;
+    ShortPlan plan;
+};
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what)
+{
+    return fail(e == hipErrorOutOfMemory ? LAPIS_ERR_ALLOC : LAPIS_ERR_DEVICE,
+                std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define LAPIS_HIP(call)                                        \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return fail_hip(e_, #call);      \
+    } while (0)
+
+template <typename P>
+int device_alloc(P **ptr, size_t bytes)
+{
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 1);
+    if (e != hipSuccess) return fail_hip(e, "hipMalloc");
+    *ptr = static_cast<P *>(p);
+    return LAPIS_OK;
+}
+
+void free_handle(lapis_csr *A)
+{
+    if (!A) return;
+    (void)hipFree(A->d_bin_offset);
+    (void)hipFree(A->d_row_perm);
+    (void)hipFree(A->d_long_off);
+    (void)hipFree(A->d_tile_row);
+    (void)hipFree(A->d_tile_nz);
+    (void)hipFree(A->d_partial);
+    delete A;
+}
+
+// flags[0]: a row has negative length; flags[1]: a column index is out of range
+__global__ __launch_bounds__(kBlock) void validate_kernel(int64_t nrows, int64_t ncols, int64_t nnz,
+                                                          const int32_t *__restrict__ rowptr,
+                                                          const int32_t *__restrict__ colidx,
+                                                          int32_t *__restrict__ flags)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    bool bad_row = false, bad_col = false;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += stride)
+        bad_row |= rowptr[i + 1] < rowptr[i];
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < nnz; j += stride) {
+        const int32_t c = colidx[j];
+        bad_col |= (c < 0) | (c >= ncols);
+    }
+    if (bad_row) flags[0] = 1;
+    if (bad_col) flags[1] = 1;
+}
+
+void build_short_plan(lapis_csr *A)
+{
+    ShortPlan &p = A->plan;
+    uint32_t blocks = 0;
+    for (int b = 0; b < kShortBins; ++b) {
+        p.bin_begin[b] = A->h_bin_offset[b];
+        p.bin_count[b] = A->h_bin_offset[b + 1] - A->h_bin_offset[b];
+        p.block_begin[b] = blocks;
+        const int per_block = short_rows_per_block(b);
+        blocks += (uint32_t)(((int64_t)p.bin_count[b] + per_block - 1) / per_block);
+    }
+    p.block_begin[kShortBins] = blocks;
+    p.num_blocks = blocks;
+    p.padded_blocks = (blocks + kXcds - 1) / kXcds * kXcds;
+}
+
+int run_analysis(lapis_csr *A, hipStream_t stream)
+{
+    const int64_t n = A->nrows;
+    LAPIS_HIP(hipMemsetAsync(A->d_bin_offset, 0, sizeof(int32_t) * (kNumBins + 1), stream));
+    int32_t *d_hist = nullptr;
+    int32_t *d_flags = nullptr;
+    if (int rc = device_alloc(&d_flags, 2 * sizeof(int32_t))) return rc;
+    hipError_t e = hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream);
+    if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "hipMemsetAsync"); }
+
+    // structural checks the kernels rely on: rowptr ends, monotone rowptr, column range
+    int32_t ends[2] = {0, (int32_t)A->nnz};
+    if (n > 0) {
+        e = hipMemcpyAsync(&ends[0], A->rowptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(&ends[1], A->rowptr + n, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "read rowptr ends"); }
+        if (ends[0] != 0 || ends[1] != A->nnz) {
+            (void)hipFree(d_flags);
+            return fail(LAPIS_ERR_INVALID_ARG, "rowptr[0] must be 0 and rowptr[nrows] must equal nnz");
+        }
+    } else if (A->nnz != 0) {
+        (void)hipFree(d_flags);
+        return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
+    }
+
+    const int32_t num_blocks = (int32_t)((n + kRowsPerAnalysisBlock - 1) / kRowsPerAnalysisBlock);
+    int rc = LAPIS_OK;
+    if (n > 0) {
+        const int64_t work = (n > A->nnz ? n : A->nnz);
+        int64_t vblocks = (work + kBlock - 1) / kBlock;
+        if (vblocks > 8192) vblocks = 8192;
+        validate_kernel<<<dim3((uint32_t)vblocks), dim3(kBlock), 0, stream>>>(
+            n, A->ncols, A->nnz, A->rowptr, A->colidx, d_flags);
+        int32_t flags[2] = {0, 0};
+        e = hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "validate"); }
+        if (flags[0] || flags[1]) {
+            (void)hipFree(d_flags);
+            return fail(LAPIS_ERR_INVALID_ARG, flags[0] ? "rowptr is not non-decreasing"
+                                                        : "a column index is outside [0, ncols)");
+        }
+        rc = device_alloc(&d_hist, sizeof(int32_t) * (size_t)kNumBins * num_blocks);
+        if (rc) { (void)hipFree(d_flags); return rc; }
+        bin_count_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, A->rowptr, num_blocks, d_hist);
+        bin_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>((int64_t)kNumBins * num_blocks, num_blocks,
+                                                              d_hist, A->d_bin_offset);
+        bin_scatter_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, A->rowptr, num_blocks, d_hist, A->d_row_perm);
+    }
+    e = hipMemcpyAsync(A->h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
+                       hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    (void)hipFree(d_hist);
+    (void)hipFree(d_flags);
+    if (e != hipSuccess) return fail_hip(e, "row binning");
+
+    // long rows: scan of their lengths, then the tile table
+    const int32_t m = A->h_bin_offset[kNumBins] - A->h_bin_offset[kNumBins - 1];
+    A->num_long = m;
+    if (int r2 = device_alloc(&A->d_long_off, sizeof(int32_t) * ((size_t)m + 1))) return r2;
+    int32_t long_total = 0;
+    if (m > 0) {
+        long_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
+            m, A->d_row_perm + A->h_bin_offset[kNumBins - 1], A->rowptr, A->d_long_off);
+        LAPIS_HIP(hipMemcpyAsync(&long_total, A->d_long_off + m, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+    } else {
+        LAPIS_HIP(hipMemsetAsync(A->d_long_off, 0, sizeof(int32_t), stream));
+    }
+    const int64_t T = ((int64_t)long_total + LAPIS_TILE_NNZ - 1) / LAPIS_TILE_NNZ;
+    A->num_tiles = T;
+    if (int r3 = device_alloc(&A->d_tile_row, sizeof(int32_t) * ((size_t)T + 1))) return r3;
+    if (int r4 = device_alloc(&A->d_tile_nz, sizeof(int32_t) * ((size_t)T + 1))) return r4;
+    const size_t esize = A->dtype == LAPIS_F64 ? sizeof(double) : sizeof(float);
+    if (int r5 = device_alloc(&A->d_partial, esize * 2 * (size_t)T)) return r5;
+    tile_search_kernel<LAPIS_TILE_NNZ><<<dim3((uint32_t)((T + 1 + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+        m, T, A->d_long_off, A->d_tile_row, A->d_tile_nz);
+    LAPIS_HIP(hipGetLastError());
+    LAPIS_HIP(hipStreamSynchronize(stream));
+    build_short_plan(A);
+    return LAPIS_OK;
+}
+
+template <typename T>
+int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, hipStream_t stream)
+{
+    const T a = (T)alpha, b = (T)beta;
+    const T *vals = static_cast<const T *>(A->vals);
+    const T *x = static_cast<const T *>(d_x);
+    T *y = static_cast<T *>(d_y);
+    if (A->plan.num_blocks > 0) {
+        spmv_short_kernel<T, true><<<dim3(A->plan.padded_blocks), dim3(kBlock), 0, stream>>>(
+            A->plan, A->d_row_perm, A->rowptr, A->colidx, vals, x, y, a, b);
+    }
+    if (A->num_long > 0) {
+        const int32_t m = (int32_t)A->num_long;
+        const int32_t *long_rows = A->d_row_perm + A->h_bin_offset[kNumBins - 1];
+        T *partial = static_cast<T *>(A->d_partial);
+        spmv_long_tile_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)A->num_tiles), dim3(kBlock), 0, stream>>>(
+            m, long_rows, A->d_long_off, A->d_tile_row, A->d_tile_nz, A->rowptr, A->colidx, vals, x, partial);
+        spmv_long_fixup_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)((m + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(
+            m, long_rows, A->d_long_off, A->d_tile_row, partial, y, a, b);
+    }
+    LAPIS_HIP(hipGetLastError());
+    return LAPIS_OK;
+}
+
+template <typename T, int VEC, int CL>
+int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b, T *Y, int64_t ldy,
+                hipStream_t stream)
+{
+    const T *vals = static_cast<const T *>(A->vals);
+    const int32_t n_rows_a = A->h_bin_offset[kNumBins - 2];          // bins 0..7: one slot per row
+    const int32_t n_rows_b = (int32_t)A->nrows - n_rows_a;           // bins 8..9: one workgroup per row
+    if (n_rows_a > 0) {
+        constexpr int kSlots = kBlock / CL;
+        const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);
+        const uint32_t padded = (blocks + kXcds - 1) / kXcds * kXcds;
+        spmm_rows_kernel<T, VEC, CL, true><<<dim3(padded), dim3(kBlock), 0, stream>>>(
+            n_rows_a, blocks, padded, A->d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
+    }
+    if (n_rows_b > 0) {
+        spmm_block_rows_kernel<T, VEC, CL><<<dim3((uint32_t)n_rows_b), dim3(kBlock), 0, stream>>>(
+            n_rows_a, A->d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
+    }
+    LAPIS_HIP(hipGetLastError());
+    return LAPIS_OK;
+}
+
+template <typename T, int VEC>
+int spmm_pick_lanes(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b, T *Y, int64_t ldy,
+                    hipStream_t stream)
+{
+    const int64_t need = (k + VEC - 1) / VEC;  // lanes wanted to cover a row of X in one pass
+    if (need <= 1) return spmm_launch<T, VEC, 1>(A, k, a, X, ldx, b, Y, ldy, stream);
+    if (need <= 2) return spmm_launch<T, VEC, 2>(A, k, a, X, ldx, b, Y, ldy, stream);
+    if (need <= 4) return spmm_launch<T, VEC, 4>(A, k, a, X, ldx, b, Y, ldy, stream);
+    if (need <= 8) return spmm_launch<T, VEC, 8>(A, k, a, X, ldx, b, Y, ldy, stream);
+    if (need <= 16) return spmm_launch<T, VEC, 16>(A, k, a, X, ldx, b, Y, ldy, stream);
+    if (need <= 32) return spmm_launch<T, VEC, 32>(A, k, a, X, ldx, b, Y, ldy, stream);
+    return spmm_launch<T, VEC, 64>(A, k, a, X, ldx, b, Y, ldy, stream);
+}
+
+template <typename T>
+int spmm_typed(const lapis_csr *A, int64_t k, double alpha, const void *d_X, int64_t ldx, double beta,
+               void *d_Y, int64_t ldy, hipStream_t stream)
+{
+    constexpr int kVec = 16 / sizeof(T);  // elements per 16-byte load
+    const T *X = static_cast<const T *>(d_X);
+    T *Y = static_cast<T *>(d_Y);
+    const bool wide = (k % kVec == 0) && (ldx % kVec == 0) && (ldy % kVec == 0) &&
+                      (reinterpret_cast<uintptr_t>(X) % 16 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+    if (wide) return spmm_pick_lanes<T, kVec>(A, k, (T)alpha, X, ldx, (T)beta, Y, ldy, stream);
+    return spmm_pick_lanes<T, 1>(A, k, (T)alpha, X, ldx, (T)beta, Y, ldy, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nnz, const int32_t *d_rowptr,
+                     const int32_t *d_colidx, const void *d_vals, int dtype, void *hip_stream)
+{
+    if (!out) return fail(LAPIS_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (nrows < 0 || ncols < 0 || nnz < 0) return fail(LAPIS_ERR_INVALID_ARG, "negative size");
+    if (nnz > INT32_MAX || nrows + 1 > INT32_MAX || ncols > INT32_MAX)
+        return fail(LAPIS_ERR_INVALID_ARG, "nnz, nrows+1 and ncols must fit in int32");
+    if (dtype != LAPIS_F32 && dtype != LAPIS_F64) return fail(LAPIS_ERR_UNSUPPORTED, "dtype must be LAPIS_F32 or LAPIS_F64");
+    if (!d_rowptr) return fail(LAPIS_ERR_INVALID_ARG, "d_rowptr is NULL");
+    if (nnz > 0 && (!d_colidx || !d_vals)) return fail(LAPIS_ERR_INVALID_ARG, "d_colidx / d_vals is NULL with nnz > 0");
+    if (nnz > 0 && (nrows == 0 || ncols == 0)) return fail(LAPIS_ERR_INVALID_ARG, "nnz > 0 in an empty matrix");
+
+    lapis_csr *A = new (std::nothrow) lapis_csr();
+    if (!A) return fail(LAPIS_ERR_ALLOC, "host allocation failed");
+    std::memset(static_cast<void *>(A), 0, sizeof(*A));
+    A->nrows = nrows; A->ncols = ncols; A->nnz = nnz; A->dtype = dtype;
+    A->rowptr = d_rowptr; A->colidx = d_colidx; A->vals = d_vals;
+    int rc = device_alloc(&A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1));
+    if (!rc) rc = device_alloc(&A->d_row_perm, sizeof(int32_t) * (size_t)nrows);
+    if (!rc) rc = run_analysis(A, static_cast<hipStream_t>(hip_stream));
+    if (rc) { free_handle(A); return rc; }
+    *out = A;
+    return LAPIS_OK;
+}
+
+int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y, void *hip_stream)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->nrows > 0 && !d_y) return fail(LAPIS_ERR_INVALID_ARG, "d_y is NULL");
+    if (A->nnz > 0 && !d_x) return fail(LAPIS_ERR_INVALID_ARG, "d_x is NULL");
+    if (A->nrows == 0) return LAPIS_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, stream)
+                                 : spmv_typed<float>(A, alpha, d_x, beta, d_y, stream);
+}
+
+int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, int64_t ldx, double beta,
+               void *d_Y, int64_t ldy, void *hip_stream)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (k <= 0) return fail(LAPIS_ERR_INVALID_ARG, "k must be positive");
+    if (ldx < k || ldy < k) return fail(LAPIS_ERR_INVALID_ARG, "leading dimension smaller than k");
+    if (A->nrows > 0 && !d_Y) return fail(LAPIS_ERR_INVALID_ARG, "d_Y is NULL");
+    if (A->nnz > 0 && !d_X) return fail(LAPIS_ERR_INVALID_ARG, "d_X is NULL");
+    if (A->nrows == 0) return LAPIS_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return A->dtype == LAPIS_F64 ? spmm_typed<double>(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream)
+                                 : spmm_typed<float>(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream);
+}
+
+int lapis_csr_destroy(lapis_csr_t *A)
+{
+    free_handle(A);
+    return LAPIS_OK;
+}
+
+int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_long, int64_t *num_tiles)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (num_long) *num_long = A->num_long;
+    if (num_tiles) *num_tiles = A->num_tiles;
+    return LAPIS_OK;
+}
+
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_bin_offset, int32_t *h_row_perm,
+                             int32_t *h_long_off, int32_t *h_tile_row, int32_t *h_tile_nz)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_bin_offset)
+        LAPIS_HIP(hipMemcpy(h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1), hipMemcpyDeviceToHost));
+    if (h_row_perm && A->nrows > 0)
+        LAPIS_HIP(hipMemcpy(h_row_perm, A->d_row_perm, sizeof(int32_t) * (size_t)A->nrows, hipMemcpyDeviceToHost));
+    if (h_long_off)
+        LAPIS_HIP(hipMemcpy(h_long_off, A->d_long_off, sizeof(int32_t) * ((size_t)A->num_long + 1), hipMemcpyDeviceToHost));
+    if (h_tile_row)
+        LAPIS_HIP(hipMemcpy(h_tile_row, A->d_tile_row, sizeof(int32_t) * ((size_t)A->num_tiles + 1), hipMemcpyDeviceToHost));
+    if (h_tile_nz)
+        LAPIS_HIP(hipMemcpy(h_tile_nz, A->d_tile_nz, sizeof(int32_t) * ((size_t)A->num_tiles + 1), hipMemcpyDeviceToHost));
+    return LAPIS_OK;
+}
+
+int lapis_partition_constants(int64_t h_out[4])
+{
+    if (!h_out) return fail(LAPIS_ERR_INVALID_ARG, "h_out is NULL");
+    h_out[0] = LAPIS_NUM_BINS;
+    h_out[1] = LAPIS_WAVE;
+    h_out[2] = LAPIS_LONG_THRESHOLD;
+    h_out[3] = LAPIS_TILE_NNZ;
+    return LAPIS_OK;
+}
+
+const char *lapis_last_error(void)
+{
+    return g_last_error.c_str();
+}
+
+}  // extern "C"

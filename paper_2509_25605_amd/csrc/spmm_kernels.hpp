@@ -1,0 +1,163 @@
+// SpMM kernels for gfx950: Y = alpha*A*X + beta*Y, X and Y row-major; column c
+// of Y is the SpMV of Section 6.2 applied to column c of X.
+//
+// A "slot" is CL consecutive lanes; lane l of a slot owns columns
+// c0 + l*VEC .. c0 + l*VEC + VEC-1, so one slot reads one row of X with a single
+// coalesced load (k = 16 doubles = one 128-byte line with CL = 8, VEC = 2).
+//
+//  * spmm_rows_kernel (rows of up to 64 entries): one slot per row.  The slot's
+//    lanes load CL consecutive (column, value) pairs of the row at once, park
+//    them in LDS, and every lane then reads them back one by one as LDS
+//    broadcasts - each matrix entry is fetched from memory once and reused for
+//    all k columns.
+//  * spmm_block_rows_kernel (longer rows): one workgroup per row, slots stride
+//    the row's entries, partial sums meet in LDS.
+#pragma once
+#include "device_utils.hpp"
+
+namespace lapis {
+
+template <typename T, int VEC>
+struct alignas(sizeof(T) * VEC) Pack {
+    T v[VEC];
+};
+
+template <typename T, int VEC>
+__device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[VEC], int64_t col,
+                                          int64_t k, T alpha, T beta)
+{
+    if (col >= k) return;
+    if constexpr (VEC > 1) {
+        Pack<T, VEC> out;
+        if (beta == T(0)) {
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) out.v[q] = alpha * acc[q];
+        } else {
+            const Pack<T, VEC> old = *reinterpret_cast<const Pack<T, VEC> *>(yrow + col);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) out.v[q] = alpha * acc[q] + beta * old.v[q];
+        }
+        *reinterpret_cast<Pack<T, VEC> *>(yrow + col) = out;
+    } else {
+        yrow[col] = (beta == T(0)) ? alpha * acc[0] : alpha * acc[0] + beta * yrow[col];
+    }
+}
+
+// positions [0, count) of row_perm, one slot per row.
+template <typename T, int VEC, int CL, bool XCD_REMAP>
+__global__ __launch_bounds__(kBlock) void spmm_rows_kernel(
+    int32_t count, uint32_t num_blocks, uint32_t padded_blocks,
+    const int32_t *__restrict__ row_perm, const int32_t *__restrict__ rowptr,
+    const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k,
+    const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
+{
+    constexpr int kSlots = kBlock / CL;
+    __shared__ int32_t s_col[kBlock];
+    __shared__ T s_val[kBlock];
+
+    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_blocks) : blockIdx.x;
+    if (id >= num_blocks) return;
+    const int slot = threadIdx.x / CL;
+    const int l = threadIdx.x % CL;
+    const int64_t idx = (int64_t)id * kSlots + slot;
+    if (idx >= count) return;  // whole slots leave together; the rest of the wave carries on
+    const int32_t row = row_perm[idx];
+    const int64_t jb = rowptr[row], je = rowptr[row + 1];
+    T *__restrict__ yrow = Y + (int64_t)row * ldy;
+
+    for (int64_t c0 = 0; c0 < k; c0 += CL * VEC) {
+        const int64_t col = c0 + (int64_t)l * VEC;
+        const bool col_ok = col < k;
+        T acc[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] = T(0);
+        for (int64_t j0 = jb; j0 < je; j0 += CL) {
+            // all lanes of the slot take part in the exchange; LDS operations of
+            // one wavefront execute in program order
+            const int64_t j = j0 + l;
+            s_col[threadIdx.x] = (j < je) ? load_stream(colidx + j) : 0;
+            s_val[threadIdx.x] = (j < je) ? load_stream(vals + j) : T(0);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int n_here = (je - j0 < CL) ? (int)(je - j0) : CL;
+            if (col_ok) {
+                // Entries past the end of the row re-read the last valid one (same
+                // X line, no new traffic) and their product is discarded, so all CL
+                // loads can be issued back to back without branches.
+#pragma unroll
+                for (int t = 0; t < CL; ++t) {
+                    const int tt = (t < n_here) ? t : n_here - 1;
+                    const int32_t cj = s_col[slot * CL + tt];
+                    const T vj = s_val[slot * CL + tt];
+                    const T *__restrict__ xr = X + (int64_t)cj * ldx + col;
+                    if constexpr (VEC > 1) {
+                        const Pack<T, VEC> xv = *reinterpret_cast<const Pack<T, VEC> *>(xr);
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) acc[q] += (t < n_here) ? vj * xv.v[q] : T(0);
+                    } else {
+                        acc[0] += (t < n_here) ? vj * xr[0] : T(0);
+                    }
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        store_row<T, VEC>(yrow, acc, col, k, alpha, beta);
+    }
+}
+
+// positions [first, first+count) of row_perm, one workgroup per row.
+template <typename T, int VEC, int CL>
+__global__ __launch_bounds__(kBlock) void spmm_block_rows_kernel(
+    int32_t first, const int32_t *__restrict__ row_perm, const int32_t *__restrict__ rowptr,
+    const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k,
+    const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
+{
+    constexpr int kSlots = kBlock / CL;
+    __shared__ T red[kBlock * VEC];  // [slot][lane*VEC + q]
+
+    const int slot = threadIdx.x / CL;
+    const int l = threadIdx.x % CL;
+    const int32_t row = row_perm[first + (int64_t)blockIdx.x];
+    const int64_t jb = rowptr[row], je = rowptr[row + 1];
+    T *__restrict__ yrow = Y + (int64_t)row * ldy;
+
+    for (int64_t c0 = 0; c0 < k; c0 += CL * VEC) {
+        const int64_t col = c0 + (int64_t)l * VEC;
+        T acc[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] = T(0);
+        if (col < k) {
+            for (int64_t j = jb + slot; j < je; j += kSlots) {
+                const int32_t cj = load_stream(colidx + j);
+                const T vj = load_stream(vals + j);
+                const T *__restrict__ xr = X + (int64_t)cj * ldx + col;
+                if constexpr (VEC > 1) {
+                    const Pack<T, VEC> xv = *reinterpret_cast<const Pack<T, VEC> *>(xr);
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) acc[q] += vj * xv.v[q];
+                } else {
+                    acc[0] += vj * xr[0];
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) red[(slot * CL + l) * VEC + q] = acc[q];
+        __syncthreads();
+        if (slot == 0) {
+            T tot[VEC];
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) tot[q] = T(0);
+            for (int s = 0; s < kSlots; ++s) {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) tot[q] += red[(s * CL + l) * VEC + q];
+            }
+            store_row<T, VEC>(yrow, tot, col, k, alpha, beta);
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace lapis

@@ -1,0 +1,85 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function include/lapis.h declares, and rejects bad arguments before it
+touches the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2509_25605_amd as L
+from paper_2509_25605_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2509_25605_amd.build import build
+        build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lapis.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lapis_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_header_constants_match_library_and_oracle(lib):
+    import oracle
+    c = L.lapis_partition_constants()
+    text = open(os.path.join(ROOT, "include", "lapis.h")).read()
+    macro = lambda n: int(re.search(rf"#define\s+{n}\s+(\d+)", text).group(1))
+    assert c == {"num_bins": macro("LAPIS_NUM_BINS"), "wave": macro("LAPIS_WAVE"),
+                 "long_threshold": macro("LAPIS_LONG_THRESHOLD"), "tile_nnz": macro("LAPIS_TILE_NNZ")}
+    assert (c["num_bins"], c["wave"], c["long_threshold"], c["tile_nnz"]) == (
+        oracle.NUM_BINS, oracle.WAVE, oracle.LONG_THRESHOLD, oracle.TILE_NNZ)
+
+
+def _create(lib, nrows, ncols, nnz, rowptr, colidx, vals, dtype, out=True):
+    h = ctypes.c_void_p(0xdead)
+    rc = lib.lapis_csr_create(ctypes.byref(h) if out else None, nrows, ncols, nnz, rowptr, colidx,
+                              vals, dtype, None)
+    return rc, h
+
+
+@pytest.mark.parametrize("args,code", [
+    ((-1, 4, 0, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),            # negative nrows
+    ((4, -1, 0, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),            # negative ncols
+    ((4, 4, -1, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),            # negative nnz
+    ((4, 4, 2 ** 31, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),       # nnz beyond int32
+    ((2 ** 31 - 1, 4, 0, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),   # nrows + 1 beyond int32
+    ((4, 4, 3, None, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),          # null rowptr
+    ((4, 4, 3, 8, None, 8, 1), L.LAPIS_ERR_INVALID_ARG),          # null colidx with nnz > 0
+    ((4, 4, 3, 8, 8, None, 1), L.LAPIS_ERR_INVALID_ARG),          # null vals with nnz > 0
+    ((0, 4, 3, 8, 8, 8, 1), L.LAPIS_ERR_INVALID_ARG),             # entries in a matrix without rows
+    ((4, 4, 3, 8, 8, 8, 2), L.LAPIS_ERR_UNSUPPORTED),             # unknown dtype
+    ((4, 4, 3, 8, 8, 8, -1), L.LAPIS_ERR_UNSUPPORTED),
+])
+def test_create_rejects_bad_arguments_on_the_host(lib, args, code):
+    rc, h = _create(lib, *args)
+    assert rc == code
+    assert h.value is None                                          # *out = NULL on error
+    assert L.lapis_last_error() != ""
+
+
+def test_null_handles_and_out_pointer(lib):
+    assert _create(lib, 4, 4, 0, 8, 8, 8, 1, out=False)[0] == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_destroy(None) == L.LAPIS_OK
+    assert lib.lapis_spmv(None, 1.0, 8, 0.0, 8, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_spmm(None, 4, 1.0, 8, 4, 0.0, 8, 4, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_partition_sizes(None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_copy_partition(None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_partition_constants(None) == L.LAPIS_ERR_INVALID_ARG
+    with pytest.raises(L.LapisError) as e:
+        L.lapis_spmv(None, 1.0, 8, 0.0, 8, stream=0)
+    assert e.value.code == L.LAPIS_ERR_INVALID_ARG

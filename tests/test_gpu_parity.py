@@ -1,0 +1,231 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Index structures must match bit for bit; floating
+point per element within 8*nnz_row*eps*(|A||x|)_i (eps = 2^-53 double, 2^-24
+float), extended by the alpha/beta terms for the generic unit cases."""
+import sys
+
+import numpy as np
+import pytest
+
+import gen
+import oracle
+from helpers import DeviceCsr, assert_close, general_bound, literal_bound
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", file=sys.stderr, flush=True)
+
+
+def check_partition(dev, rowptr):
+    ref = oracle.partition(rowptr)
+    got = dev.partition()
+    for key in ("bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+        assert got[key].dtype == np.int32
+        assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
+
+
+def check_spmv(dev, rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None, literal=False, what=""):
+    ref, absAx = oracle.spmv(rowptr, colidx, vals, x, alpha, beta, y0)
+    got = dev.spmv(x, alpha, beta, y0)
+    nnz_row = np.diff(rowptr)
+    tol = literal_bound(nnz_row, absAx, vals.dtype) if literal else general_bound(
+        nnz_row, absAx, vals.dtype, alpha, beta, y0)
+    assert got.dtype == vals.dtype
+    assert_close(got, ref, tol, what)
+    empty = nnz_row == 0
+    if empty.any():  # rows without entries: exactly beta*y0, +0 when beta == 0
+        assert np.array_equal(got[empty], ref[empty])
+        if beta == 0.0:
+            assert not np.any(np.signbit(got[empty]))
+    return got
+
+
+def check_spmm(dev, rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None, literal=False, what="",
+               ldx=None, ldy=None):
+    ref, absAX = oracle.spmm(rowptr, colidx, vals, X, alpha, beta, Y0)
+    got = dev.spmm(X, alpha, beta, Y0, ldx, ldy)
+    nnz_row = np.diff(rowptr)[:, None]
+    tol = literal_bound(nnz_row, absAX, vals.dtype) if literal else general_bound(
+        nnz_row, absAX, vals.dtype, alpha, beta, Y0)
+    assert_close(got, ref, tol, what)
+    return got
+
+
+# ---------------------------------------------------------------------------
+# small general matrices: every bin, ragged tails, duplicates, unsorted columns
+# ---------------------------------------------------------------------------
+def mixed_lengths(n, seed, longest):
+    u = gen.uniform(seed, 0, n, 0.0, 1.0)
+    L = np.floor(np.exp(u ** 3 * np.log(longest + 1))).astype(np.int64) - 1
+    L[::53] = 0
+    for i, v in enumerate([1, 2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 63, 64, 65, 127, 128, 129, 4095, 4096, 4097]):
+        if v <= longest and 7 + 11 * i < n:
+            L[7 + 11 * i] = v
+    return L
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n,ncols,longest,srt,dup", [
+    (1, 1, 1, True, False),
+    (5, 3, 3, True, False),
+    (777, 5000, 70, True, False),
+    (3001, 20000, 20000, True, False),       # includes rows beyond the long threshold
+    (3001, 4000, 300, False, True),          # duplicates, unsorted
+    (40, 30000, 30000, False, False),        # few rows, mostly long, unsorted
+])
+def test_spmv_general_matrices(dtype, n, ncols, longest, srt, dup):
+    say(f"spmv general n={n} ncols={ncols} longest={longest} sorted={srt} dup={dup} {np.dtype(dtype).name}")
+    L = np.minimum(mixed_lengths(n, 40 + n, longest), ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 900 + n, dtype, sorted_cols=srt, allow_duplicates=dup)
+    x = gen.uniform(31, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(31, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, -2.5, 0.75, y0, what="alpha=-2.5 beta=0.75")
+        check_spmv(dev, rowptr, colidx, vals, x, 0.0, 2.0, y0, what="alpha=0")
+        a = check_spmv(dev, rowptr, colidx, vals, x, 3.0, 0.0, what="run 1")
+        b = dev.spmv(x, 3.0, 0.0)
+        assert np.array_equal(a, b), "two runs differ: result depends on scheduling"
+    finally:
+        dev.close()
+
+
+def test_spmv_exact_small_integers():
+    """Integer data: any summation order is exact, so the GPU must match bit for bit."""
+    n, ncols = 2000, 9000
+    L = np.minimum(mixed_lengths(n, 5, 9000), ncols)
+    for dtype in (np.float64, np.float32):
+        rowptr, colidx, vals = gen.random_csr(n, ncols, L, 77, dtype, small_ints=True)
+        x = np.floor(gen.uniform(3, gen.STREAM_X, ncols, -8.0, 9.0)).astype(dtype)
+        y0 = np.floor(gen.uniform(3, gen.STREAM_Y0, n, -8.0, 9.0)).astype(dtype)
+        dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+        try:
+            ref, _ = oracle.spmv(rowptr, colidx, vals, x, 2.0, -3.0, y0)
+            assert np.array_equal(dev.spmv(x, 2.0, -3.0, y0), ref)
+        finally:
+            dev.close()
+
+
+def test_beta_zero_ignores_old_y_and_degenerate_shapes():
+    # beta == 0: NaN in the old y must not leak (DeviceCsr.spmv pre-fills y with NaN)
+    w = gen.workload(1)
+    dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
+    try:
+        got = dev.spmv(w.x)
+        assert np.all(np.isfinite(got))
+    finally:
+        dev.close()
+    # rows but no entries at all
+    rowptr = np.zeros(101, dtype=np.int32)
+    dev = DeviceCsr(100, 7, rowptr, np.empty(0, np.int32), np.empty(0, np.float64))
+    try:
+        check_partition(dev, rowptr)
+        y0 = gen.uniform(1, gen.STREAM_Y0, 100)
+        assert np.array_equal(dev.spmv(np.ones(7), 1.0, 0.0), np.zeros(100))
+        assert np.array_equal(dev.spmv(np.ones(7), 1.0, -0.5, y0), -0.5 * y0)
+        X = gen.uniform(1, gen.STREAM_X, 7 * 3).reshape(7, 3)
+        assert np.array_equal(dev.spmm(X), np.zeros((100, 3)))
+    finally:
+        dev.close()
+    # no rows
+    dev = DeviceCsr(0, 5, np.zeros(1, dtype=np.int32), np.empty(0, np.int32), np.empty(0, np.float32))
+    try:
+        part = dev.partition()
+        assert np.all(part["bin_offset"] == 0)
+        assert dev.spmv(np.ones(5, dtype=np.float32)).size == 0
+    finally:
+        dev.close()
+
+
+def test_create_rejects_bad_structure_on_device():
+    import torch
+    import paper_2509_25605_amd as L
+    rowptr = torch.tensor([0, 2, 1, 3], dtype=torch.int32, device="cuda:0")      # decreasing
+    colidx = torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda:0")
+    vals = torch.ones(3, dtype=torch.float64, device="cuda:0")
+    with pytest.raises(L.LapisError) as e:
+        L.CsrMatrix(3, 3, rowptr, colidx, vals)
+    assert e.value.code == L.LAPIS_ERR_INVALID_ARG
+    rowptr = torch.tensor([0, 1, 2, 3], dtype=torch.int32, device="cuda:0")
+    for bad in (3, -1):                                                           # column out of range
+        colidx = torch.tensor([0, bad, 2], dtype=torch.int32, device="cuda:0")
+        with pytest.raises(L.LapisError) as e:
+            L.CsrMatrix(3, 3, rowptr, colidx, vals)
+        assert e.value.code == L.LAPIS_ERR_INVALID_ARG
+    rowptr = torch.tensor([1, 1, 2, 3], dtype=torch.int32, device="cuda:0")      # rowptr[0] != 0
+    with pytest.raises(L.LapisError):
+        L.CsrMatrix(3, 3, rowptr, torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda:0"), vals)
+    A = L.CsrMatrix(3, 3, torch.tensor([0, 1, 2, 3], dtype=torch.int32, device="cuda:0"),
+                    torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda:0"), vals)
+    x = torch.ones(3, dtype=torch.float64, device="cuda:0")
+    for k, ldx, ldy in ((0, 4, 4), (-1, 4, 4), (4, 3, 4), (4, 4, 3)):
+        with pytest.raises(L.LapisError) as e:
+            L.lapis_spmm(A.handle, k, 1.0, x, ldx, 0.0, x, ldy)
+        assert e.value.code == L.LAPIS_ERR_INVALID_ARG
+    A.close()
+
+
+# ---------------------------------------------------------------------------
+# SpMM
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("k,ldx,ldy", [(1, None, None), (2, None, None), (3, 5, 4), (16, None, None),
+                                       (16, 20, 24), (17, None, None), (40, 40, 44), (130, None, None)])
+def test_spmm_general_matrices(dtype, k, ldx, ldy):
+    say(f"spmm general k={k} ldx={ldx} ldy={ldy} {np.dtype(dtype).name}")
+    n, ncols = 1500, 6000
+    L = np.minimum(mixed_lengths(n, 60, 6000), ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 1234, dtype, sorted_cols=False)
+    X = gen.uniform(8, gen.STREAM_X, ncols * k).astype(dtype).reshape(ncols, k)
+    Y0 = gen.uniform(8, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0", ldx=ldx, ldy=ldy)
+        check_spmm(dev, rowptr, colidx, vals, X, 1.25, -0.5, Y0, what="alpha=1.25 beta=-0.5", ldx=ldx, ldy=ldy)
+        if k == 1:  # the single-column product agrees with SpMV
+            y = dev.spmv(X[:, 0])
+            ref, absAx = oracle.spmv(rowptr, colidx, vals, np.ascontiguousarray(X[:, 0]))
+            assert_close(dev.spmm(X)[:, 0], ref, general_bound(np.diff(rowptr), absAx, dtype, 1.0, 0.0, None))
+            assert_close(y, ref, general_bound(np.diff(rowptr), absAx, dtype, 1.0, 0.0, None))
+    finally:
+        dev.close()
+
+
+# ---------------------------------------------------------------------------
+# the five workloads: reduced sizes (several tiles + ragged tail) and full size
+# ---------------------------------------------------------------------------
+REDUCED = {
+    1: None,
+    2: {"nx": 37, "ny": 29, "nz": 31},
+    3: {"n": 100003},
+    4: {"n": 200003, "cap": 60000},
+    5: {"nx": 23, "ny": 19, "nz": 17, "k": 16},
+}
+
+
+def run_workload(cfg, scale):
+    w = gen.workload(cfg, scale)
+    say(f"workload {cfg} {w.name} nrows={w.nrows} nnz={w.nnz}")
+    dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
+    try:
+        check_partition(dev, w.rowptr)
+        if w.k == 0:
+            check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
+        else:
+            check_spmm(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
+    finally:
+        dev.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_workload_reduced(cfg):
+    run_workload(cfg, REDUCED[cfg])
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_workload_full_size(cfg):
+    run_workload(cfg, None)
