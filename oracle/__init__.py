@@ -18,12 +18,14 @@ _SRC = os.path.join(_HERE, "lapis_oracle.c")
 _LIB = os.path.join(_HERE, "liblapis_oracle.so")
 
 # The partition definition's parameters as the oracle states them (wavefront width,
-# long-row threshold, tile size, bin count).  A test checks that the GPU
+# long-row threshold, tile size, bin count, rows and minimum entries of a stream chunk).  A test checks that the GPU
 # library reports the same values.
 WAVE = 64
 LONG_THRESHOLD = 4096
 TILE_NNZ = 4096
 NUM_BINS = 10
+STREAM_ROWS = 32
+STREAM_MIN_NNZ = 256
 
 
 def build(force: bool = False) -> str:
@@ -50,7 +52,9 @@ def _load():
             getattr(lib, name).restype = None
         lib.oracle_partition_num_bins.argtypes = [i64]
         lib.oracle_partition_num_bins.restype = ctypes.c_int
-        lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, p, p, p, p]
+        lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, i64, p]
+        lib.oracle_partition_stream_chunks.restype = i64
+        lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_partition_rows.restype = None
         lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
         lib.oracle_partition_tiles.restype = None
@@ -105,25 +109,33 @@ def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):
     return Y, absAX
 
 
-def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NNZ):
-    """Reference row partition.  Returns a dict with
-    bin_offset[num_bins+1], row_perm[nrows], long_off[m+1], tile_row[T+1], tile_nz[T+1]."""
+def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NNZ,
+              stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_NNZ):
+    """Reference row partition.  Returns a dict with stream_chunks[], bin_offset[num_bins+1],
+    row_perm[rows outside stream chunks], long_off[m+1], tile_row[T+1], tile_nz[T+1]."""
     assert rowptr.dtype == np.int32 and rowptr.flags.c_contiguous
     lib = _load()
     n = rowptr.size - 1
     nb = lib.oracle_partition_num_bins(wave)
+    nchunks = (n + stream_rows - 1) // stream_rows
+    stream_chunks = np.empty(nchunks, dtype=np.int32)
+    ns = lib.oracle_partition_stream_chunks(n, _p(rowptr), wave, stream_rows, stream_min_nnz,
+                                            _p(stream_chunks))
+    stream_chunks = stream_chunks[:ns].copy()
     bin_offset = np.zeros(nb + 1, dtype=np.int32)
     row_perm = np.empty(n, dtype=np.int32)
     m = ctypes.c_int64(0)
     T = ctypes.c_int64(0)
-    lib.oracle_partition_rows(n, _p(rowptr), wave, long_threshold, tile_nnz, _p(bin_offset),
-                              _p(row_perm), ctypes.addressof(m), ctypes.addressof(T))
+    lib.oracle_partition_rows(n, _p(rowptr), wave, long_threshold, tile_nnz, stream_rows,
+                              stream_min_nnz, _p(bin_offset), _p(row_perm),
+                              ctypes.addressof(m), ctypes.addressof(T))
     m, T = m.value, T.value
+    row_perm = row_perm[:bin_offset[nb]].copy()
     long_rows = np.ascontiguousarray(row_perm[bin_offset[nb - 1]:bin_offset[nb]])
     long_off = np.zeros(m + 1, dtype=np.int32)
     tile_row = np.zeros(T + 1, dtype=np.int32)
     tile_nz = np.zeros(T + 1, dtype=np.int32)
     lib.oracle_partition_tiles(_p(rowptr), tile_nnz, _p(long_rows), m, T, _p(long_off),
                                _p(tile_row), _p(tile_nz))
-    return {"num_bins": nb, "bin_offset": bin_offset, "row_perm": row_perm,
-            "long_off": long_off, "tile_row": tile_row, "tile_nz": tile_nz}
+    return {"num_bins": nb, "stream_chunks": stream_chunks, "bin_offset": bin_offset,
+            "row_perm": row_perm, "long_off": long_off, "tile_row": tile_row, "tile_nz": tile_nz}

@@ -19,8 +19,8 @@
  * quantity the floating-point tolerance is stated in.
  *
  * The row-partition reference at the end is the integer definition of the
- * analysis pass (row bins by length, stable row lists, equal-nnz tiles over
- * the long rows), written as plain loops.  Its constants are arguments, so
+ * analysis pass (stream chunks, row bins by length, stable row lists,
+ * equal-nnz tiles over the long rows), written as plain loops.  Its constants are arguments, so
  * this file carries no copy of the library's header.
  *
  * Pins (tests marked "not gpu"): dense brute force on tiny matrices,
@@ -108,10 +108,19 @@ void oracle_spmm_f32(int64_t nrows, int64_t k, const int32_t *rowptr, const int3
 }
 
 /* ---- Row partition reference --------------------------------------------
- * Per-row lane count in the spirit of the vector-length estimate of
- * Section 4.2 (entries per row, rounded up, clamped to the hardware vector
- * width), applied row by row instead of once per matrix and rounded up to a
- * power of two, with the wavefront width wave as the clamp:
+ * Two levels.
+ *
+ * (1) Stream chunks.  Rows are taken in chunks of chunk_rows consecutive rows
+ * (chunk c = rows c*chunk_rows .. min((c+1)*chunk_rows, nrows) - 1).  A chunk
+ * is a stream chunk iff none of its rows has more than `wave` entries and the
+ * chunk holds at least chunk_min_nnz entries in total.  stream_chunks lists
+ * the stream chunk ids in ascending order.
+ *
+ * (2) Bins, over the rows of all other chunks only.  Per-row lane count in the
+ * spirit of the vector-length estimate of Section 4.2 (entries per row,
+ * rounded up, clamped to the hardware vector width), applied row by row
+ * instead of once per matrix and rounded up to a power of two, with the
+ * wavefront width `wave` as the clamp:
  *   bin 0                : L == 0
  *   bin b, 1 <= b <= B-3 : smallest b with 2^(b-1) >= L, for 1 <= L <= wave
  *                          (wave = 2^(B-3))
@@ -139,24 +148,53 @@ int oracle_partition_num_bins(int64_t wave)
     return bin_of_length(wave + 1, wave, wave + 1) + 2;
 }
 
+static int is_stream_chunk(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t wave,
+                           int64_t chunk_rows, int64_t chunk_min_nnz)
+{
+    int64_t first = c * chunk_rows;
+    int64_t last = first + chunk_rows < nrows ? first + chunk_rows : nrows;
+    for (int64_t i = first; i < last; ++i)
+        if (rowptr[i + 1] - rowptr[i] > wave) return 0;
+    return rowptr[last] - rowptr[first] >= chunk_min_nnz;
+}
+
+/* Pass 0: stream_chunks[] (caller provides ceil(nrows/chunk_rows) slots);
+ * returns the number of stream chunks. */
+int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int64_t wave,
+                                       int64_t chunk_rows, int64_t chunk_min_nnz,
+                                       int32_t *stream_chunks)
+{
+    int64_t count = 0;
+    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
+    for (int64_t c = 0; c < nchunks; ++c)
+        if (is_stream_chunk(c, nrows, rowptr, wave, chunk_rows, chunk_min_nnz))
+            stream_chunks[count++] = (int32_t)c;
+    return count;
+}
+
 /* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and
- * row_perm[nrows] (row ids grouped by bin, ascending inside each bin).
- * Returns through *num_long the number of rows in the last bin and through
- * *num_tiles the number of tiles T = ceil(total long nnz / tile_nnz). */
+ * row_perm[] (ids of the rows outside stream chunks, grouped by bin, ascending
+ * inside each bin; bin_offset[num_bins] of them).  Returns through *num_long
+ * the number of rows in the last bin and through *num_tiles the number of
+ * tiles T = ceil(total long nnz / tile_nnz). */
 void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
-                           int64_t long_threshold, int64_t tile_nnz, int32_t *bin_offset,
-                           int32_t *row_perm, int64_t *num_long, int64_t *num_tiles)
+                           int64_t long_threshold, int64_t tile_nnz, int64_t chunk_rows,
+                           int64_t chunk_min_nnz, int32_t *bin_offset, int32_t *row_perm,
+                           int64_t *num_long, int64_t *num_tiles)
 {
     int nb = oracle_partition_num_bins(wave);
     for (int b = 0; b <= nb; ++b) bin_offset[b] = 0;
-    for (int64_t i = 0; i < nrows; ++i)
+    for (int64_t i = 0; i < nrows; ++i) {
+        if (is_stream_chunk(i / chunk_rows, nrows, rowptr, wave, chunk_rows, chunk_min_nnz)) continue;
         bin_offset[bin_of_length(rowptr[i + 1] - rowptr[i], wave, long_threshold) + 1] += 1;
+    }
     for (int b = 0; b < nb; ++b) bin_offset[b + 1] += bin_offset[b];
     int64_t long_nnz = 0;
     for (int b = 0; b < nb; ++b) {
         int64_t at = bin_offset[b];
         for (int64_t i = 0; i < nrows; ++i) {
             int64_t L = rowptr[i + 1] - rowptr[i];
+            if (is_stream_chunk(i / chunk_rows, nrows, rowptr, wave, chunk_rows, chunk_min_nnz)) continue;
             if (bin_of_length(L, wave, long_threshold) != b) continue;
             row_perm[at++] = (int32_t)i;
             if (b == nb - 1) long_nnz += L;

@@ -28,46 +28,82 @@ def test_hand_worked_bins(golden_dir):
     assert bin_of_row.tolist() == [p[1] for p in pairs]
 
 
-def _independent_partition(rowptr, wave, long_threshold, tile_nnz):
-    """The same definition through different primitives: log2, stable argsort, searchsorted."""
+def _independent_partition(rowptr, wave, long_threshold, tile_nnz, stream_rows, stream_min_nnz):
+    """The same definition through different primitives: reduceat, log2, stable argsort, searchsorted."""
     L = np.diff(rowptr).astype(np.int64)
+    n = L.size
+    starts = np.arange(0, n, stream_rows)
+    ends = np.minimum(starts + stream_rows, n)
+    chunk_max = np.maximum.reduceat(L, starts) if n else np.zeros(0, dtype=np.int64)
+    chunk_nnz = rowptr[ends].astype(np.int64) - rowptr[starts]
+    is_stream = (chunk_max <= wave) & (chunk_nnz >= stream_min_nnz)
+    stream_chunks = np.flatnonzero(is_stream).astype(np.int32)
+    binned = np.flatnonzero(~np.repeat(is_stream, ends - starts))
     top = int(math.log2(wave)) + 1
-    b = np.zeros(L.size, dtype=np.int64)
-    pos = L > 0
-    b[pos] = 1 + np.ceil(np.log2(L[pos])).astype(np.int64)
-    b[L > wave] = top + 1
-    b[L > long_threshold] = top + 2
+    Lb = L[binned]
+    b = np.zeros(Lb.size, dtype=np.int64)
+    pos = Lb > 0
+    b[pos] = 1 + np.ceil(np.log2(Lb[pos])).astype(np.int64)
+    b[Lb > wave] = top + 1
+    b[Lb > long_threshold] = top + 2
     nb = top + 3
-    perm = np.argsort(b, kind="stable").astype(np.int32)
+    perm = binned[np.argsort(b, kind="stable")].astype(np.int32)
     off = np.concatenate([[0], np.cumsum(np.bincount(b, minlength=nb))]).astype(np.int32)
     long_rows = perm[off[nb - 1]:]
     lp = np.concatenate([[0], np.cumsum(L[long_rows])]).astype(np.int64)
     T = -(-int(lp[-1]) // tile_nnz)
-    starts = np.arange(T, dtype=np.int64) * tile_nnz
-    tr = np.searchsorted(lp, starts, side="right") - 1
-    tn = starts - lp[tr]
-    return off, perm, lp, np.append(tr, long_rows.size), np.append(tn, 0)
+    tstarts = np.arange(T, dtype=np.int64) * tile_nnz
+    tr = np.searchsorted(lp, tstarts, side="right") - 1
+    tn = tstarts - lp[tr]
+    return stream_chunks, off, perm, lp, np.append(tr, long_rows.size), np.append(tn, 0)
 
 
-@pytest.mark.parametrize("wave,lt,tile", [(64, 4096, 4096), (64, 100, 64), (32, 40, 16), (64, 64, 7)])
+@pytest.mark.parametrize("wave,lt,tile,srows,smin", [(64, 4096, 4096, 32, 256), (64, 100, 64, 32, 256),
+                                                      (32, 40, 16, 8, 20), (64, 64, 7, 16, 1), (64, 4096, 4096, 32, 0)])
 @pytest.mark.parametrize("seed", [1, 2])
-def test_partition_matches_independent_construction(wave, lt, tile, seed):
-    n = 3000
+def test_partition_matches_independent_construction(wave, lt, tile, srows, smin, seed):
+    n = 3001
     u = gen.uniform(seed, 0, n, 0.0, 1.0)
     L = np.floor(np.exp(u * u * 9.5)).astype(np.int64) - 1      # 0 .. ~13000, mostly short
+    L[1000:2000] = np.minimum(L[1000:2000], wave)                 # a stretch without long rows
+    L[1200:1300] = 0                                               # ... part of it empty
     L[::97] = 0
     L[5::211] = wave
     L[7::223] = lt
     L[9::227] = lt + 1
     rowptr = np.zeros(n + 1, dtype=np.int32)
     np.cumsum(L, out=rowptr[1:])
-    part = oracle.partition(rowptr, wave, lt, tile)
-    off, perm, lp, tr, tn = _independent_partition(rowptr, wave, lt, tile)
+    part = oracle.partition(rowptr, wave, lt, tile, srows, smin)
+    sc, off, perm, lp, tr, tn = _independent_partition(rowptr, wave, lt, tile, srows, smin)
+    assert sc.size > 0 and perm.size > 0
+    assert np.array_equal(part["stream_chunks"], sc)
     assert np.array_equal(part["bin_offset"], off)
     assert np.array_equal(part["row_perm"], perm)
     assert np.array_equal(part["long_off"], lp)
     assert np.array_equal(part["tile_row"], tr)
     assert np.array_equal(part["tile_nz"], tn)
+
+
+def test_stream_chunks_hand_worked():
+    """Chunks of 32 rows; a stream chunk has no row above 64 entries and at least 256 entries."""
+    L = np.array([8] * 32            # chunk 0: 256 entries, all short           -> stream
+                 + [8] * 31 + [65]   # chunk 1: one row of 65                     -> binned
+                 + [7] * 32          # chunk 2: 224 entries, below the minimum    -> binned
+                 + [64] * 32         # chunk 3: 2048 entries, rows exactly at 64  -> stream
+                 + [0] * 31 + [64]   # chunk 4: 64 entries                        -> binned
+                 + [40] * 7,         # chunk 5 (ragged, 7 rows): 280 entries      -> stream
+                 dtype=np.int64)
+    rowptr = np.zeros(L.size + 1, dtype=np.int32)
+    np.cumsum(L, out=rowptr[1:])
+    part = oracle.partition(rowptr)
+    assert part["stream_chunks"].tolist() == [0, 3, 5]
+    binned = list(range(32, 96)) + list(range(128, 160))
+    assert sorted(part["row_perm"].tolist()) == binned
+    # bins: 31 empty rows (bin 0); 32 rows of 7 and 31 rows of 8 (bin 4); one row of 64 (bin 7); one of 65 (bin 8)
+    assert np.diff(part["bin_offset"]).tolist() == [31, 0, 0, 0, 63, 0, 0, 1, 1, 0]
+    # with 6 rows in the ragged chunk: 240 entries -> binned
+    part = oracle.partition(rowptr[:-1].copy())
+    assert part["stream_chunks"].tolist() == [0, 3]
 
 
 def test_partition_invariants_on_power_law_workload():
@@ -76,8 +112,12 @@ def test_partition_invariants_on_power_law_workload():
     n = w.nrows
     off, perm = part["bin_offset"], part["row_perm"]
     L = np.diff(w.rowptr)
-    assert off[0] == 0 and off[-1] == n and np.all(np.diff(off) >= 0)
-    assert np.array_equal(np.sort(perm), np.arange(n))          # bins partition the rows
+    assert off[0] == 0 and np.all(np.diff(off) >= 0)
+    in_stream = np.zeros(n, dtype=bool)
+    for c in part["stream_chunks"]:
+        in_stream[32 * c:32 * c + 32] = True
+    assert off[-1] == n - in_stream.sum()
+    assert np.array_equal(np.sort(perm), np.flatnonzero(~in_stream))   # bins partition the other rows
     lo = [0, 1, 2, 3, 5, 9, 17, 33, 65, 4097]
     hi = [0, 1, 2, 4, 8, 16, 32, 64, 4096, 2 ** 31]
     for b in range(10):
