@@ -39,9 +39,19 @@ extern "C" {
 #define LAPIS_F64 1
 
 /* ---- row partition constants ---------------------------------------------
- * The analysis pass generalises the vector-length estimate of Section 4.2
- * (entries per row, rounded up, clamped to the hardware vector width) from one
- * value per matrix to one value per row.  With L the number of entries of a row:
+ * The analysis pass has two levels.
+ *
+ * Level 1, stream chunks.  Rows are taken in chunks of LAPIS_STREAM_ROWS
+ * consecutive rows (chunk c = rows c*LAPIS_STREAM_ROWS ...).  A chunk is a
+ * stream chunk iff none of its rows has more than LAPIS_WAVE entries and it
+ * holds at least LAPIS_STREAM_MIN_NNZ entries.  Its entries are one contiguous
+ * piece of the value / column arrays, which one wavefront streams through LDS.
+ * If d_colidx or d_vals is not 16-byte aligned, no chunk is a stream chunk.
+ *
+ * Level 2, bins, for the rows of all other chunks.  It generalises the
+ * vector-length estimate of Section 4.2 (entries per row, rounded up, clamped
+ * to the hardware vector width) from one value per matrix to one value per row.
+ * With L the number of entries of a row:
  *   bin 0      L == 0
  *   bin b      1 <= b <= 7: smallest b with 2^(b-1) >= L   (1 <= L <= 64);
  *              2^(b-1) is the row's lane-group size, 64 = the gfx950 wavefront
@@ -55,6 +65,8 @@ extern "C" {
 #define LAPIS_WAVE            64
 #define LAPIS_LONG_THRESHOLD  4096
 #define LAPIS_TILE_NNZ        4096
+#define LAPIS_STREAM_ROWS     32
+#define LAPIS_STREAM_MIN_NNZ  256
 
 typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
 
@@ -74,7 +86,8 @@ typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
  *
  * Ownership: the three arrays are BORROWED; they must stay allocated and
  * unchanged until lapis_csr_destroy.  The handle owns only its analysis
- * buffers (bin offsets, per-bin row lists, tile table, per-tile partial sums).
+ * buffers (stream chunk list, bin offsets, per-bin row lists, tile table,
+ * per-tile partial sums).
  * The call synchronises hip_stream (it reads back the bin counts and checks
  * d_rowptr[0] == 0 and d_rowptr[nrows] == nnz; a mismatch is
  * LAPIS_ERR_INVALID_ARG).  d_colidx and d_vals may be NULL when nnz == 0.
@@ -122,25 +135,31 @@ int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, i
 int lapis_csr_destroy(lapis_csr_t *A);
 
 /* ---- inspection of the row partition (for bit-exact checks) --------------
- * lapis_csr_partition_sizes: *num_long = rows in bin 9, *num_tiles = number of
- * tiles T.  Either pointer may be NULL.
+ * lapis_csr_partition_sizes: *num_stream = number of stream chunks,
+ * *num_binned = number of rows outside stream chunks (the length of row_perm),
+ * *num_long = rows in bin 9, *num_tiles = number of tiles T.  Any pointer may
+ * be NULL.
  * lapis_csr_copy_partition: copies to HOST buffers the caller owns (any may be
  * NULL to skip it):
+ *   h_stream_chunks int32[num_stream]     stream chunk ids, ascending
  *   h_bin_offset int32[LAPIS_NUM_BINS+1]  exclusive scan of per-bin row counts
- *   h_row_perm   int32[nrows]             row ids grouped by bin, ascending in each bin
+ *   h_row_perm   int32[num_binned]        row ids grouped by bin, ascending in each bin
  *   h_long_off   int32[num_long+1]        exclusive scan of the bin-9 rows' lengths
  *   h_tile_row   int32[T+1]               bin-9 row (index into its list) holding
  *                                         long position t*LAPIS_TILE_NNZ; [T] = num_long
  *   h_tile_nz    int32[T+1]               offset of that position inside the row; [T] = 0
  * Synchronises the device.
  */
-int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_long, int64_t *num_tiles);
-int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_bin_offset, int32_t *h_row_perm,
-                             int32_t *h_long_off, int32_t *h_tile_row, int32_t *h_tile_nz);
+int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t *num_binned,
+                              int64_t *num_long, int64_t *num_tiles);
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_bin_offset,
+                             int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
+                             int32_t *h_tile_nz);
 
 /* The partition constants compiled into the library, in the order
- * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ}. */
-int lapis_partition_constants(int64_t h_out[4]);
+ * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ,
+ *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ}. */
+int lapis_partition_constants(int64_t h_out[6]);
 
 /* Text of the most recent error on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on that thread. */

@@ -47,8 +47,8 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
         lib.lapis_csr_destroy.argtypes = [p]
-        lib.lapis_csr_partition_sizes.argtypes = [p, ctypes.POINTER(i64), ctypes.POINTER(i64)]
-        lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p]
+        lib.lapis_csr_partition_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 4
+        lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p, p]
         lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
@@ -107,30 +107,33 @@ def lapis_csr_destroy(A):
 
 
 def lapis_csr_partition_sizes(A):
-    m, t = ctypes.c_int64(), ctypes.c_int64()
-    _check(load().lapis_csr_partition_sizes(A, ctypes.byref(m), ctypes.byref(t)))
-    return m.value, t.value
+    """(num_stream_chunks, num_binned_rows, num_long_rows, num_tiles)"""
+    v = [ctypes.c_int64() for _ in range(4)]
+    _check(load().lapis_csr_partition_sizes(A, *[ctypes.byref(x) for x in v]))
+    return tuple(x.value for x in v)
 
 
 def lapis_partition_constants():
-    out = (ctypes.c_int64 * 4)()
+    out = (ctypes.c_int64 * 6)()
     _check(load().lapis_partition_constants(out))
-    return {"num_bins": out[0], "wave": out[1], "long_threshold": out[2], "tile_nnz": out[3]}
+    return {"num_bins": out[0], "wave": out[1], "long_threshold": out[2], "tile_nnz": out[3],
+            "stream_rows": out[4], "stream_min_nnz": out[5]}
 
 
-def lapis_csr_copy_partition(A, nrows):
+def lapis_csr_copy_partition(A):
     """Host copies of the row partition as NumPy int32 arrays."""
-    m, t = lapis_csr_partition_sizes(A)
+    ns, nb_rows, m, t = lapis_csr_partition_sizes(A)
     nb = lapis_partition_constants()["num_bins"]
     res = {
+        "stream_chunks": np.empty(ns, dtype=np.int32),
         "bin_offset": np.empty(nb + 1, dtype=np.int32),
-        "row_perm": np.empty(nrows, dtype=np.int32),
+        "row_perm": np.empty(nb_rows, dtype=np.int32),
         "long_off": np.empty(m + 1, dtype=np.int32),
         "tile_row": np.empty(t + 1, dtype=np.int32),
         "tile_nz": np.empty(t + 1, dtype=np.int32),
     }
     ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
-    _check(load().lapis_csr_copy_partition(A, ptr(res["bin_offset"]), ptr(res["row_perm"]),
-                                           ptr(res["long_off"]), ptr(res["tile_row"]),
-                                           ptr(res["tile_nz"])))
+    _check(load().lapis_csr_copy_partition(A, ptr(res["stream_chunks"]), ptr(res["bin_offset"]),
+                                           ptr(res["row_perm"]), ptr(res["long_off"]),
+                                           ptr(res["tile_row"]), ptr(res["tile_nz"])))
     return res

@@ -1,8 +1,10 @@
-// Row-partition analysis on the device.  It is the per-row form of the
-// vector-length estimate of Section 4.2 ("Parallelism estimation": entries per
-// row, rounded up, clamped to the hardware vector width): each row gets the bin
-// of its own length, rows are listed per bin in ascending order, and the rows
-// beyond the long threshold are cut into equal tiles of entries.  All results
+// Row-partition analysis on the device.  First, chunks of consecutive rows that
+// are short throughout and hold enough entries are marked as stream chunks.
+// The other rows get the per-row form of the vector-length estimate of
+// Section 4.2 ("Parallelism estimation": entries per row, rounded up, clamped
+// to the hardware vector width): each row gets the bin of its own length, rows
+// are listed per bin in ascending order, and the rows beyond the long threshold
+// are cut into equal tiles of entries.  All results
 // are integers with a unique value, produced without atomics on ordered data,
 // so they can be compared bit for bit with a CPU reference.
 #pragma once
@@ -42,10 +44,53 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *s_tm
     return incl - v;
 }
 
-// Pass 1: per-workgroup histogram of row bins; hist is bin-major: hist[bin*num_blocks + block].
+// Pass 0a: flag[c] = 1 iff chunk c (chunk_rows consecutive rows) has no row with
+// more than kWave entries and holds at least min_nnz entries.
+__global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32_t num_chunks,
+                                                            int32_t chunk_rows, int32_t min_nnz,
+                                                            const int32_t *__restrict__ rowptr,
+                                                            int32_t *__restrict__ flag)
+{
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= num_chunks) return;
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    int32_t prev = rowptr[first];
+    const int32_t begin = prev;
+    bool ok = true;
+    for (int64_t i = first + 1; i <= last; ++i) {
+        const int32_t cur = rowptr[i];
+        ok &= (cur - prev) <= kWave;
+        prev = cur;
+    }
+    flag[c] = (ok && prev - begin >= min_nnz) ? 1 : 0;
+}
+
+// Pass 0b (one workgroup): ascending list of the flagged chunk ids; *count = how many.
+__global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunks,
+                                                               const int32_t *__restrict__ flag,
+                                                               int32_t *__restrict__ list,
+                                                               int32_t *__restrict__ count)
+{
+    __shared__ int32_t s_tmp[kBlock];
+    int32_t running = 0;
+    for (int64_t base = 0; base < num_chunks; base += kBlock) {
+        const int64_t c = base + threadIdx.x;
+        const int32_t v = (c < num_chunks) ? flag[c] : 0;
+        int32_t total;
+        const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
+        if (v) list[running + excl] = (int32_t)c;
+        running += total;
+    }
+    if (threadIdx.x == 0) *count = running;
+}
+
+// Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped); hist is bin-major: hist[bin*num_blocks + block].
 template <int LONG_THRESHOLD>
 __global__ __launch_bounds__(kBlock) void bin_count_kernel(int32_t nrows,
                                                            const int32_t *__restrict__ rowptr,
+                                                           int32_t chunk_rows,
+                                                           const int32_t *__restrict__ chunk_flag,
                                                            int32_t num_blocks,
                                                            int32_t *__restrict__ hist)
 {
@@ -55,7 +100,8 @@ __global__ __launch_bounds__(kBlock) void bin_count_kernel(int32_t nrows,
     const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
     for (int it = 0; it < kRowsPerThread; ++it) {
         const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
-        if (i < nrows) atomicAdd(&s_hist[bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i])], 1);
+        if (i < nrows && !chunk_flag[i / chunk_rows])
+            atomicAdd(&s_hist[bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i])], 1);
     }
     __syncthreads();
     if (threadIdx.x < kNumBins) hist[(int64_t)threadIdx.x * num_blocks + blockIdx.x] = s_hist[threadIdx.x];
@@ -88,6 +134,8 @@ __global__ __launch_bounds__(kBlock) void bin_scan_kernel(int64_t count, int32_t
 template <int LONG_THRESHOLD>
 __global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
                                                              const int32_t *__restrict__ rowptr,
+                                                             int32_t chunk_rows,
+                                                             const int32_t *__restrict__ chunk_flag,
                                                              int32_t num_blocks,
                                                              const int32_t *__restrict__ hist,
                                                              int32_t *__restrict__ row_perm)
@@ -100,7 +148,8 @@ __global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
     const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
     for (int it = 0; it < kRowsPerThread; ++it) {
         const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
-        const int bin = (i < nrows) ? bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i]) : -1;
+        const int bin = (i < nrows && !chunk_flag[i / chunk_rows])
+                            ? bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i]) : -1;
         int32_t rank_in_wave = 0;
         for (int b = 0; b < kNumBins; ++b) {
             const uint64_t mask = __ballot(bin == b);

@@ -20,6 +20,8 @@ static_assert(LAPIS_NUM_BINS == kNumBins, "header and kernels disagree on the bi
 static_assert(LAPIS_WAVE == kWave, "header and kernels disagree on the wavefront width");
 static_assert(LAPIS_LONG_THRESHOLD >= LAPIS_TILE_NNZ, "a tile must touch at most two rows");
 static_assert(LAPIS_TILE_NNZ % kBlock == 0, "tile size must be a multiple of the workgroup size");
+static_assert(LAPIS_STREAM_ROWS == kStreamRows, "header and kernels disagree on the stream chunk size");
+static_assert(LAPIS_STREAM_ROWS * LAPIS_WAVE <= 3 * kStreamWindow - 4, "a stream chunk must fit in three LDS windows");
 
 struct lapis_csr {
     int64_t nrows, ncols, nnz;
@@ -28,15 +30,16 @@ struct lapis_csr {
     const int32_t *colidx;
     const void *vals;
     // analysis results (device)
+    int32_t *d_stream_chunks;  // [num_stream] ascending ids of the stream chunks
     int32_t *d_bin_offset;  // [kNumBins + 1]
-    int32_t *d_row_perm;    // [nrows]
+    int32_t *d_row_perm;    // [num_binned] (allocated for nrows)
     int32_t *d_long_off;    // [num_long + 1]
     int32_t *d_tile_row;    // [num_tiles + 1]
     int32_t *d_tile_nz;     // [num_tiles + 1]
     void *d_partial;        // [2 * num_tiles] of dtype: per-tile segment sums
     // host copies
     int32_t h_bin_offset[kNumBins + 1];
-    int64_t num_long, num_tiles;
+    int64_t num_chunks, num_stream, num_binned, num_long, num_tiles;
     ShortPlan plan;
 };
 
@@ -75,6 +78,7 @@ int device_alloc(P **ptr, size_t bytes)
 void free_handle(lapis_csr *A)
 {
     if (!A) return;
+    (void)hipFree(A->d_stream_chunks);
     (void)hipFree(A->d_bin_offset);
     (void)hipFree(A->d_row_perm);
     (void)hipFree(A->d_long_off);
@@ -146,7 +150,15 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     }
 
     const int32_t num_blocks = (int32_t)((n + kRowsPerAnalysisBlock - 1) / kRowsPerAnalysisBlock);
+    const int32_t num_chunks = (int32_t)((n + LAPIS_STREAM_ROWS - 1) / LAPIS_STREAM_ROWS);
+    A->num_chunks = num_chunks;
+    // 16-byte loads need 16-byte aligned arrays; otherwise no chunk qualifies
+    const bool aligned = reinterpret_cast<uintptr_t>(A->colidx) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(A->vals) % 16 == 0;
+    const int32_t min_nnz = aligned ? LAPIS_STREAM_MIN_NNZ : INT32_MAX;
+    int32_t *d_chunk_flag = nullptr;
     int rc = LAPIS_OK;
+    int32_t num_stream = 0;
     if (n > 0) {
         const int64_t work = (n > A->nnz ? n : A->nnz);
         int64_t vblocks = (work + kBlock - 1) / kBlock;
@@ -163,20 +175,34 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
                                                         : "a column index is outside [0, ncols)");
         }
         rc = device_alloc(&d_hist, sizeof(int32_t) * (size_t)kNumBins * num_blocks);
-        if (rc) { (void)hipFree(d_flags); return rc; }
+        if (!rc) rc = device_alloc(&d_chunk_flag, sizeof(int32_t) * (size_t)num_chunks);
+        if (!rc) rc = device_alloc(&A->d_stream_chunks, sizeof(int32_t) * (size_t)num_chunks);
+        if (rc) { (void)hipFree(d_flags); (void)hipFree(d_hist); (void)hipFree(d_chunk_flag); return rc; }
+        chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, d_chunk_flag);
+        chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(num_chunks, d_chunk_flag,
+                                                                   A->d_stream_chunks, d_flags);
         bin_count_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, A->rowptr, num_blocks, d_hist);
+            (int32_t)n, A->rowptr, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks, d_hist);
         bin_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>((int64_t)kNumBins * num_blocks, num_blocks,
                                                               d_hist, A->d_bin_offset);
         bin_scatter_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, A->rowptr, num_blocks, d_hist, A->d_row_perm);
+            (int32_t)n, A->rowptr, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks, d_hist, A->d_row_perm);
+        e = hipMemcpyAsync(&num_stream, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+    } else {
+        rc = device_alloc(&A->d_stream_chunks, 0);
+        if (rc) { (void)hipFree(d_flags); return rc; }
     }
-    e = hipMemcpyAsync(A->h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
-                       hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(A->h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
+                           hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     (void)hipFree(d_hist);
     (void)hipFree(d_flags);
+    (void)hipFree(d_chunk_flag);
     if (e != hipSuccess) return fail_hip(e, "row binning");
+    A->num_stream = num_stream;
+    A->num_binned = A->h_bin_offset[kNumBins];
 
     // long rows: scan of their lengths, then the tile table
     const int32_t m = A->h_bin_offset[kNumBins] - A->h_bin_offset[kNumBins - 1];
@@ -212,6 +238,13 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
     const T *vals = static_cast<const T *>(A->vals);
     const T *x = static_cast<const T *>(d_x);
     T *y = static_cast<T *>(d_y);
+    if (A->num_stream > 0) {
+        const uint32_t chunks = (uint32_t)A->num_stream;
+        const uint32_t padded = (chunks + kXcds - 1) / kXcds * kXcds;
+        const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;
+        spmv_stream_kernel<T, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, A->colidx, vals, x, y, a, b);
+    }
     if (A->plan.num_blocks > 0) {
         spmv_short_kernel<T, true><<<dim3(A->plan.padded_blocks), dim3(kBlock), 0, stream>>>(
             A->plan, A->d_row_perm, A->rowptr, A->colidx, vals, x, y, a, b);
@@ -235,13 +268,23 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
 {
     const T *vals = static_cast<const T *>(A->vals);
     const int32_t n_rows_a = A->h_bin_offset[kNumBins - 2];          // bins 0..7: one slot per row
-    const int32_t n_rows_b = (int32_t)A->nrows - n_rows_a;           // bins 8..9: one workgroup per row
+    const int32_t n_rows_b = (int32_t)A->num_binned - n_rows_a;      // bins 8..9: one workgroup per row
+    constexpr int kSlots = kBlock / CL;
+    if (A->num_stream > 0) {                                          // rows of the stream chunks
+        const int64_t count = A->num_stream * LAPIS_STREAM_ROWS;
+        const uint32_t blocks = (uint32_t)((count + kSlots - 1) / kSlots);
+        const uint32_t padded = (blocks + kXcds - 1) / kXcds * kXcds;
+        const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;
+        spmm_rows_kernel<T, VEC, CL, true, true><<<dim3(padded), dim3(kBlock), 0, stream>>>(
+            (int32_t)count, blocks, padded, (int32_t)A->nrows, LAPIS_STREAM_ROWS, list, A->rowptr, A->colidx,
+            vals, k, X, ldx, Y, ldy, a, b);
+    }
     if (n_rows_a > 0) {
-        constexpr int kSlots = kBlock / CL;
         const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);
         const uint32_t padded = (blocks + kXcds - 1) / kXcds * kXcds;
-        spmm_rows_kernel<T, VEC, CL, true><<<dim3(padded), dim3(kBlock), 0, stream>>>(
-            n_rows_a, blocks, padded, A->d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
+        spmm_rows_kernel<T, VEC, CL, true, false><<<dim3(padded), dim3(kBlock), 0, stream>>>(
+            n_rows_a, blocks, padded, (int32_t)A->nrows, LAPIS_STREAM_ROWS, A->d_row_perm, A->rowptr, A->colidx,
+            vals, k, X, ldx, Y, ldy, a, b);
     }
     if (n_rows_b > 0) {
         spmm_block_rows_kernel<T, VEC, CL><<<dim3((uint32_t)n_rows_b), dim3(kBlock), 0, stream>>>(
@@ -339,23 +382,29 @@ int lapis_csr_destroy(lapis_csr_t *A)
     return LAPIS_OK;
 }
 
-int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_long, int64_t *num_tiles)
+int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t *num_binned,
+                              int64_t *num_long, int64_t *num_tiles)
 {
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (num_stream) *num_stream = A->num_stream;
+    if (num_binned) *num_binned = A->num_binned;
     if (num_long) *num_long = A->num_long;
     if (num_tiles) *num_tiles = A->num_tiles;
     return LAPIS_OK;
 }
 
-int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_bin_offset, int32_t *h_row_perm,
-                             int32_t *h_long_off, int32_t *h_tile_row, int32_t *h_tile_nz)
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_bin_offset,
+                             int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
+                             int32_t *h_tile_nz)
 {
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
     LAPIS_HIP(hipDeviceSynchronize());
+    if (h_stream_chunks && A->num_stream > 0)
+        LAPIS_HIP(hipMemcpy(h_stream_chunks, A->d_stream_chunks, sizeof(int32_t) * (size_t)A->num_stream, hipMemcpyDeviceToHost));
     if (h_bin_offset)
         LAPIS_HIP(hipMemcpy(h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1), hipMemcpyDeviceToHost));
-    if (h_row_perm && A->nrows > 0)
-        LAPIS_HIP(hipMemcpy(h_row_perm, A->d_row_perm, sizeof(int32_t) * (size_t)A->nrows, hipMemcpyDeviceToHost));
+    if (h_row_perm && A->num_binned > 0)
+        LAPIS_HIP(hipMemcpy(h_row_perm, A->d_row_perm, sizeof(int32_t) * (size_t)A->num_binned, hipMemcpyDeviceToHost));
     if (h_long_off)
         LAPIS_HIP(hipMemcpy(h_long_off, A->d_long_off, sizeof(int32_t) * ((size_t)A->num_long + 1), hipMemcpyDeviceToHost));
     if (h_tile_row)
@@ -365,13 +414,15 @@ int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_bin_offset, int32_
     return LAPIS_OK;
 }
 
-int lapis_partition_constants(int64_t h_out[4])
+int lapis_partition_constants(int64_t h_out[6])
 {
     if (!h_out) return fail(LAPIS_ERR_INVALID_ARG, "h_out is NULL");
     h_out[0] = LAPIS_NUM_BINS;
     h_out[1] = LAPIS_WAVE;
     h_out[2] = LAPIS_LONG_THRESHOLD;
     h_out[3] = LAPIS_TILE_NNZ;
+    h_out[4] = LAPIS_STREAM_ROWS;
+    h_out[5] = LAPIS_STREAM_MIN_NNZ;
     return LAPIS_OK;
 }
 

@@ -1,6 +1,13 @@
 // SpMV kernels for gfx950: y = alpha*A*x + beta*y with A in CSR (Section 6.2),
 // rows walked with the CSR loop nest of Section 4.2.
 //
+//  * spmv_stream_kernel: one wavefront per stream chunk (32 consecutive rows of
+//    at most 64 entries).  The chunk's entries are one contiguous range of the
+//    value / column arrays: the wavefront streams it with 16-byte non-temporal
+//    loads into LDS, then a group of 2 lanes per row walks the row out of LDS
+//    and gathers x.  Consecutive rows sit in consecutive lane groups, so for
+//    banded matrices (stencils, FEM) every gather instruction reads a nearly
+//    contiguous piece of x.
 //  * spmv_short_kernel: one launch covers bins 0..8 of the row partition.  A
 //    group of G = 2^(bin-1) lanes owns a row, the lanes stride the row's
 //    entries (the ThreadVector level of Section 4.2 "Loop translation", with
@@ -159,6 +166,138 @@ __global__ __launch_bounds__(kBlock) void spmv_short_kernel(
         break;
     }
 #undef LAPIS_SHORT_CASE
+}
+
+// ---- stream chunks ----------------------------------------------------------
+constexpr int kStreamRows = 32;                      // rows per chunk
+constexpr int kStreamGroup = kWave / kStreamRows;    // lanes per row (2)
+constexpr int kStreamWindow = 1024;                  // entries staged in LDS at a time
+constexpr int kStreamUnroll = 16;                    // gathers in flight per lane and batch
+
+template <typename T> struct StreamVec;
+template <> struct StreamVec<double> { typedef double type __attribute__((ext_vector_type(2))); };
+template <> struct StreamVec<float> { typedef float type __attribute__((ext_vector_type(4))); };
+typedef int32_t int4v __attribute__((ext_vector_type(4)));
+
+// Copy the first n_vec (a multiple of 4, <= kStreamWindow) entries of the window to LDS with
+// N 16-byte column loads per lane and the matching value loads.  Lanes past the end repeat the
+// last group: same address, same data, no extra memory traffic and no divergent control flow.
+template <typename T, int N>
+__device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, const T *__restrict__ vw,
+                                            int lane, int n_vec, int32_t *s_col, T *s_val)
+{
+    typedef typename StreamVec<T>::type vec_t;
+    constexpr int kPerVec = 16 / sizeof(T);          // values per 16-byte load
+    constexpr int kValLoads = N * (4 / kPerVec);     // value loads covering N*256 entries
+    const int last_c = n_vec - 4;
+    const int last_v = n_vec - kPerVec;
+    int4v cq[N];
+    vec_t vq[kValLoads];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        int idx = i * (kWave * 4) + lane * 4;
+        idx = idx < last_c ? idx : last_c;
+        cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cw + idx));
+    }
+#pragma unroll
+    for (int i = 0; i < kValLoads; ++i) {
+        int idx = i * (kWave * kPerVec) + lane * kPerVec;
+        idx = idx < last_v ? idx : last_v;
+        vq[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(vw + idx));
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        int idx = i * (kWave * 4) + lane * 4;
+        idx = idx < last_c ? idx : last_c;
+        *reinterpret_cast<int4v *>(s_col + idx) = cq[i];
+    }
+#pragma unroll
+    for (int i = 0; i < kValLoads; ++i) {
+        int idx = i * (kWave * kPerVec) + lane * kPerVec;
+        idx = idx < last_v ? idx : last_v;
+        *reinterpret_cast<vec_t *>(s_val + idx) = vq[i];
+    }
+}
+
+// One wavefront (= one workgroup) per stream chunk.  stream_chunks == nullptr
+// means every chunk of the matrix is a stream chunk (chunk id = wave id).
+// colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a
+// multiple of 4: 16-byte loads never reach past it, the last nnz % 4 entries of
+// the matrix are fetched one by one.
+template <typename T, bool XCD_REMAP>
+__global__ __launch_bounds__(kWave) void spmv_stream_kernel(
+    int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
+    const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
+    const int32_t *__restrict__ colidx, const T *__restrict__ vals, const T *__restrict__ x,
+    T *__restrict__ y, T alpha, T beta)
+{
+    constexpr int G = kStreamGroup;
+    __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
+    __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
+
+    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_chunks) : blockIdx.x;
+    if (id >= num_chunks) return;
+    const int lane = threadIdx.x;
+    const int sub = lane % G;
+    const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
+    const int64_t row = chunk * kStreamRows + lane / G;
+    const bool row_ok = row < nrows;
+    const int64_t row_c = row_ok ? row : nrows - 1;
+    const int32_t p0 = rowptr[row_c], p1 = rowptr[row_c + 1];
+    const int32_t rb = row_ok ? p0 : p1, re = p1;      // rows past the end: empty range
+    const int32_t base = __builtin_amdgcn_readfirstlane(rb);
+    const int32_t end = __builtin_amdgcn_readlane(re, kWave - 1);
+    const int32_t nnz4 = nnz & ~3;
+
+    T s = T(0);
+    // windows of kStreamWindow entries starting at a multiple of 4 (16-byte aligned loads)
+    for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
+        const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
+        const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // 16-byte loads stop here
+        const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
+        const int32_t *__restrict__ cw = colidx + w0;
+        const T *__restrict__ vw = vals + w0;
+        if (n_vec > 3 * kWave * 4) stream_fill<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
+        else if (n_vec > 2 * kWave * 4) stream_fill<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
+        else if (n_vec > kWave * 4) stream_fill<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
+        else if (n_vec > 0) stream_fill<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
+        if (w0 + n_vec < w1) {                          // the matrix's last nnz % 4 entries
+            const int32_t j = w0 + n_vec + lane;
+            if (j < w1) { s_col[j - w0] = colidx[j]; s_val[j - w0] = vals[j]; }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
+        const int32_t ub = (rb > w0 ? rb : w0) - w0;
+        const int32_t ue = (re < w1 ? re : w1) - w0;
+        const int my_n = (ue - ub - sub + G - 1) / G;                  // <= 0: nothing to do
+        const int first = my_n > 0 ? ub + sub : 0;                     // idle lanes re-read entry 0
+        const int last_u = my_n > 0 ? my_n - 1 : 0;
+        const int32_t *sc = s_col + first;
+        const T *sv = s_val + first;
+#pragma unroll 1
+        for (int u0 = 0; __builtin_amdgcn_ballot_w64(u0 < my_n) != 0; u0 += kStreamUnroll) {
+            int32_t cc[kStreamUnroll];
+            T vv[kStreamUnroll], xx[kStreamUnroll];
+#pragma unroll
+            for (int t = 0; t < kStreamUnroll; ++t) {
+                const int u = (u0 + t < last_u ? u0 + t : last_u) * G;  // past the end: repeat the last
+                cc[t] = sc[u];
+                vv[t] = sv[u];
+            }
+#pragma unroll
+            for (int t = 0; t < kStreamUnroll; ++t) xx[t] = x[cc[t]];
+#pragma unroll
+            for (int t = 0; t < kStreamUnroll; ++t) s += (u0 + t < my_n) ? vv[t] * xx[t] : T(0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    s = group_sum<G>(s);
+    if (sub == G - 1 && row_ok) store_result(y, (int32_t)row, s, alpha, beta);
 }
 
 // ---- long rows -------------------------------------------------------------

@@ -48,7 +48,7 @@ class CsrMatrix:
         return Y
 
     def partition(self):
-        return B.lapis_csr_copy_partition(self.handle, self.nrows)
+        return B.lapis_csr_copy_partition(self.handle)
 
     def close(self):
         if self.handle is not None:

@@ -21,7 +21,7 @@ def say(msg):
 def check_partition(dev, rowptr):
     ref = oracle.partition(rowptr)
     got = dev.partition()
-    for key in ("bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+    for key in ("stream_chunks", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
         assert got[key].dtype == np.int32
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
 
@@ -168,6 +168,67 @@ def test_create_rejects_bad_structure_on_device():
         assert e.value.code == L.LAPIS_ERR_INVALID_ARG
     A.close()
 
+
+
+# ---------------------------------------------------------------------------
+# stream chunks: windows, alignment offsets, the matrix's last nnz % 4 entries
+# ---------------------------------------------------------------------------
+STREAM_LAYOUTS = {
+    # chunk-by-chunk row lengths (32 rows per chunk unless ragged)
+    "tail1": [[9] * 31 + [10]],                                  # nnz % 4 == 1... see below
+    "tail2": [[9] * 31 + [11]],
+    "tail3": [[9] * 31 + [12]],
+    "dense": [[64] * 32, [64] * 32],                             # 2048 entries per chunk: 2 windows
+    "offset": [[3] * 31 + [70], [64] * 32, [33] * 32, [17] * 32, [8] * 32],   # odd prefix, mixed
+    "ragged": [[27] * 32, [27] * 32, [27] * 11],                 # last chunk has 11 rows (297 entries)
+    "mixed": [[8] * 32, [0] * 16 + [16] * 16, [1] * 32, [64] + [7] * 31, [5] * 32, [40] * 7],
+}
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("layout", sorted(STREAM_LAYOUTS))
+def test_spmv_stream_chunks(layout, dtype):
+    say(f"stream layout={layout} {np.dtype(dtype).name}")
+    L = np.array(sum(STREAM_LAYOUTS[layout], []), dtype=np.int64)
+    n, ncols = L.size, 5000
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 4242, dtype, sorted_cols=(layout != "mixed"))
+    x = gen.uniform(77, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(77, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        part = dev.partition()
+        assert part["stream_chunks"].size > 0
+        check_partition(dev, rowptr)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, 0.5, -1.5, y0, what="alpha=0.5 beta=-1.5")
+        X = gen.uniform(78, gen.STREAM_X, ncols * 16).astype(dtype).reshape(ncols, 16)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=16")
+    finally:
+        dev.close()
+    if layout.startswith("tail"):
+        assert int(rowptr[-1]) % 4 == int(layout[-1])
+
+
+def test_unaligned_arrays_fall_back_to_bins():
+    """colidx / vals that are not 16-byte aligned: no stream chunks, same results."""
+    import torch
+    import paper_2509_25605_amd as L
+    w = gen.workload(2, {"nx": 16, "ny": 16, "nz": 16})
+    ref, absAx = oracle.spmv(w.rowptr, w.colidx, w.vals, w.x)
+    pad_c = torch.zeros(w.nnz + 1, dtype=torch.int32, device="cuda:0")
+    pad_v = torch.zeros(w.nnz + 1, dtype=torch.float64, device="cuda:0")
+    pad_c[1:] = torch.from_numpy(w.colidx).cuda()
+    pad_v[1:] = torch.from_numpy(w.vals).cuda()
+    rowptr = torch.from_numpy(w.rowptr).cuda()
+    x = torch.from_numpy(w.x).cuda()
+    for colidx, vals, expect_stream in ((pad_c[1:], pad_v[1:], False), (pad_c[1:].clone(), pad_v[1:].clone(), True)):
+        y = torch.full((w.nrows,), float("nan"), dtype=torch.float64, device="cuda:0")
+        A = L.CsrMatrix(w.nrows, w.ncols, rowptr, colidx, vals)
+        assert (A.partition()["stream_chunks"].size > 0) == expect_stream
+        A.spmv(x, y)
+        torch.cuda.synchronize()
+        A.close()
+        assert_close(y.cpu().numpy(), ref, literal_bound(np.diff(w.rowptr), absAx, np.float64))
 
 # ---------------------------------------------------------------------------
 # SpMM
