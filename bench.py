@@ -21,6 +21,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of
+# this script, each scaled by what the same counter reads for a plain 1 GiB device copy
+# (FETCH_SIZE x2.000, WRITE_SIZE x1.000).  Re-measure after a kernel change.
+MEASURED_TRAFFIC_BYTES = {
+    "stencil27_128x128x128_f64": 715.65e6,
+}
+
 
 def algorithmic_bytes(w):
     """vals + colidx + rowptr + x + y (y twice when beta != 0), each counted once."""
@@ -38,6 +45,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain device copy of known size instead (reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
@@ -50,6 +60,16 @@ def main():
         sys.exit("bench.py: no GPU visible")
     L.load()  # fails loudly if the HIP library is not built
     dev = torch.device("cuda:0")
+
+    if args.copy_calibration:
+        nbytes = 1 << 30
+        src = torch.ones(nbytes // 8, dtype=torch.float64, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(max(args.steps, 1) if args.steps < 50 else 5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": nbytes, "bytes_written": nbytes}))
+        return
 
     w = gen.workload(args.config)
     tdt = torch.float64 if w.dtype == np.float64 else torch.float32
@@ -119,7 +139,9 @@ def main():
         "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "create_ms": round(create_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "algorithmic_bytes": nbytes,
+                     "kernel": "spmv_stream_kernel" if w.k == 0 else "spmm_rows_kernel",
                      "kernel_ms": round(kernel_ms, 6)},
         "cpu_baseline": cpu,
     }
