@@ -271,13 +271,14 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
     const int32_t n_rows_b = (int32_t)A->num_binned - n_rows_a;      // bins 8..9: one workgroup per row
     constexpr int kSlots = kBlock / CL;
     if (A->num_stream > 0) {                                          // rows of the stream chunks
-        const int64_t count = A->num_stream * LAPIS_STREAM_ROWS;
-        const uint32_t blocks = (uint32_t)((count + kSlots - 1) / kSlots);
-        const uint32_t padded = (blocks + kXcds - 1) / kXcds * kXcds;
+        const uint32_t chunks = (uint32_t)A->num_stream;
+        const uint32_t padded = (chunks + kXcds - 1) / kXcds * kXcds;
         const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;
-        spmm_rows_kernel<T, VEC, CL, true, true><<<dim3(padded), dim3(kBlock), 0, stream>>>(
-            (int32_t)count, blocks, padded, (int32_t)A->nrows, LAPIS_STREAM_ROWS, list, A->rowptr, A->colidx,
-            vals, k, X, ldx, Y, ldy, a, b);
+        constexpr int kStreamLanes = CL > 16 ? 16 : CL;               // wider rows of X: several column blocks
+        for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC)
+            spmm_stream_kernel<T, VEC, kStreamLanes, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, A->colidx, vals, k, c0,
+                X, ldx, Y, ldy, a, b);
     }
     if (n_rows_a > 0) {
         const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);

@@ -5,7 +5,13 @@
 // c0 + l*VEC .. c0 + l*VEC + VEC-1, so one slot reads one row of X with a single
 // coalesced load (k = 16 doubles = one 128-byte line with CL = 8, VEC = 2).
 //
-//  * spmm_rows_kernel (rows of up to 64 entries): one slot per row.  The slot's
+//  * spmm_stream_kernel (rows of stream chunks): one wavefront per chunk of 32
+//    rows.  The chunk's (column, value) pairs are streamed into LDS exactly as in
+//    the SpMV stream kernel; then 64/CL slots walk 64/CL rows at a time, reading
+//    each pair back as an LDS broadcast and one row of X with a 16-byte load per
+//    lane.  Consecutive rows sit in consecutive slots, so on banded matrices one
+//    load instruction reads consecutive rows of X.
+//  * spmm_rows_kernel (other rows of up to 64 entries): one slot per row.  The slot's
 //    lanes load CL consecutive (column, value) pairs of the row at once, park
 //    them in LDS, and every lane then reads them back one by one as LDS
 //    broadcasts - each matrix entry is fetched from memory once and reused for
@@ -14,6 +20,7 @@
 //    the row's entries, partial sums meet in LDS.
 #pragma once
 #include "device_utils.hpp"
+#include "spmv_kernels.hpp"
 
 namespace lapis {
 
@@ -40,6 +47,98 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
         *reinterpret_cast<Pack<T, VEC> *>(yrow + col) = out;
     } else {
         yrow[col] = (beta == T(0)) ? alpha * acc[0] : alpha * acc[0] + beta * yrow[col];
+    }
+}
+
+
+// Columns [c0, min(c0 + CL*VEC, k)) of Y for the rows of the stream chunks.
+// One wavefront (= one workgroup) per chunk; stream_chunks == nullptr means
+// every chunk of the matrix.  colidx and vals 16-byte aligned, nnz4 = nnz & ~3.
+constexpr int kSpmmUnroll = 8;   // X rows in flight per lane and batch
+
+template <typename T, int VEC, int CL, bool XCD_REMAP>
+__global__ __launch_bounds__(kWave) void spmm_stream_kernel(
+    int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
+    const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
+    const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k, int64_t c0,
+    const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
+{
+    static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
+    constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
+    constexpr int kPasses = kStreamRows / kSlots;
+    __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
+    __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
+    __shared__ int32_t s_rp[kStreamRows + 1];
+
+    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_chunks) : blockIdx.x;
+    if (id >= num_chunks) return;
+    const int lane = threadIdx.x;
+    const int slot = lane / CL;
+    const int l = lane % CL;
+    const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
+    const int64_t row0 = chunk * kStreamRows;
+    if (lane <= kStreamRows) {
+        const int64_t r = row0 + lane;
+        s_rp[lane] = rowptr[r < nrows ? r : nrows];     // rows past the end: empty
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int32_t base = s_rp[0], end = s_rp[kStreamRows];
+    const int32_t nnz4 = nnz & ~3;
+    const int64_t col = c0 + (int64_t)l * VEC;
+    const bool active = slot < kSlots && col < k;
+
+    T acc[kPasses][VEC];
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p)
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
+
+    for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform
+        const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
+        stream_window_to_lds<T>(colidx, vals, w0, w1, nnz4, lane, s_col, s_val);
+        if (active) {
+#pragma unroll
+            for (int p = 0; p < kPasses; ++p) {
+                const int r = p * kSlots + slot;
+                const int32_t rb = s_rp[r], re = s_rp[r + 1];
+                const int32_t ub = (rb > w0 ? rb : w0) - w0;
+                const int32_t ue = (re < w1 ? re : w1) - w0;
+                const int n = ue - ub;                                 // <= 0: row not in this window
+                const int first = n > 0 ? ub : 0;
+                const int last_u = n > 0 ? n - 1 : 0;
+#pragma unroll 1
+                for (int u0 = 0; u0 < n; u0 += kSpmmUnroll) {
+                    int32_t cj[kSpmmUnroll];
+                    T vj[kSpmmUnroll];
+                    Pack<T, VEC> xv[kSpmmUnroll];
+#pragma unroll
+                    for (int t = 0; t < kSpmmUnroll; ++t) {
+                        const int u = first + (u0 + t < last_u ? u0 + t : last_u);  // past the end: repeat
+                        cj[t] = s_col[u];
+                        vj[t] = s_val[u];
+                    }
+#pragma unroll
+                    for (int t = 0; t < kSpmmUnroll; ++t)
+                        xv[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (int64_t)cj[t] * ldx + col);
+#pragma unroll
+                    for (int t = 0; t < kSpmmUnroll; ++t)
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) acc[p][q] += (u0 + t < n) ? vj[t] * xv[t].v[q] : T(0);
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (active) {
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
+            const int64_t row = row0 + p * kSlots + slot;
+            if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[p], col, k, alpha, beta);
+        }
     }
 }
 

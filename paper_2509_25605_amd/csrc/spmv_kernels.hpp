@@ -219,6 +219,31 @@ __device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, cons
     }
 }
 
+// Stage entries [w0, w1) of the matrix (w0 a multiple of 4, w1 - w0 <= kStreamWindow) in LDS:
+// 16-byte loads up to nnz4 (= nnz rounded down to a multiple of 4), the matrix's last nnz % 4
+// entries one by one.  Ends with a wavefront-level fence so every lane may read what others wrote.
+template <typename T>
+__device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__ colidx,
+                                                     const T *__restrict__ vals, int32_t w0, int32_t w1,
+                                                     int32_t nnz4, int lane, int32_t *s_col, T *s_val)
+{
+    const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // 16-byte loads stop here
+    const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
+    const int32_t *__restrict__ cw = colidx + w0;
+    const T *__restrict__ vw = vals + w0;
+    if (n_vec > 3 * kWave * 4) stream_fill<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 2 * kWave * 4) stream_fill<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > kWave * 4) stream_fill<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 0) stream_fill<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
+    if (w0 + n_vec < w1) {                              // the matrix's last nnz % 4 entries
+        const int32_t j = w0 + n_vec + lane;
+        if (j < w1) { s_col[j - w0] = colidx[j]; s_val[j - w0] = vals[j]; }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // One wavefront (= one workgroup) per stream chunk.  stream_chunks == nullptr
 // means every chunk of the matrix is a stream chunk (chunk id = wave id).
 // colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a
@@ -253,21 +278,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     // windows of kStreamWindow entries starting at a multiple of 4 (16-byte aligned loads)
     for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
-        const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // 16-byte loads stop here
-        const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
-        const int32_t *__restrict__ cw = colidx + w0;
-        const T *__restrict__ vw = vals + w0;
-        if (n_vec > 3 * kWave * 4) stream_fill<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
-        else if (n_vec > 2 * kWave * 4) stream_fill<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
-        else if (n_vec > kWave * 4) stream_fill<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
-        else if (n_vec > 0) stream_fill<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
-        if (w0 + n_vec < w1) {                          // the matrix's last nnz % 4 entries
-            const int32_t j = w0 + n_vec + lane;
-            if (j < w1) { s_col[j - w0] = colidx[j]; s_val[j - w0] = vals[j]; }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        stream_window_to_lds<T>(colidx, vals, w0, w1, nnz4, lane, s_col, s_val);
 
         // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
         const int32_t ub = (rb > w0 ? rb : w0) - w0;
