@@ -54,7 +54,7 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 // Columns [c0, min(c0 + CL*VEC, k)) of Y for the rows of the stream chunks.
 // One wavefront (= one workgroup) per chunk; stream_chunks == nullptr means
 // every chunk of the matrix.  colidx and vals 16-byte aligned, nnz4 = nnz & ~3.
-constexpr int kSpmmUnroll = 8;   // X rows in flight per lane and batch
+constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 template <typename T, int VEC, int CL, bool XCD_REMAP>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
