@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--variant", choices=["tuned", "paper-shape"], default="tuned",
+                    help="paper-shape: the single-vector-length kernel of the paper's loop mapping")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -86,7 +88,9 @@ def main():
     torch.cuda.synchronize()
     create_ms = (time.perf_counter() - t0) * 1e3
 
-    if w.k == 0:
+    if w.k == 0 and args.variant == "paper-shape":
+        step = lambda: L.lapis_spmv_paper_shape(A.handle, w.alpha, x, w.beta, y)
+    elif w.k == 0:
         step = lambda: L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
     else:
         step = lambda: L.lapis_spmm(A.handle, w.k, w.alpha, x, w.k, w.beta, y, w.k)
@@ -134,7 +138,7 @@ def main():
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64" if w.dtype == np.float64 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "nrows": w.nrows, "nnz": w.nnz, "k": w.k, "alpha": w.alpha,
-                   "beta": w.beta, "index": "int32", "bytes_per_step": nbytes},
+                   "beta": w.beta, "index": "int32", "bytes_per_step": nbytes, "variant": args.variant},
         "gflops": round(flops / (ms_per_step * 1e-3) / 1e9, 2),
         "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
         "create_ms": round(create_ms, 3),

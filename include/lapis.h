@@ -114,6 +114,25 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
                void *hip_stream);
 
 /*
+ * lapis_spmv_paper_shape - the same product as lapis_spmv, computed with the
+ * kernel shape the paper's loop mapping generates (Section 4.2): one vector
+ * length for the whole matrix, g = the average number of entries per row
+ * rounded up ("Parallelism estimation": (k+N-1)/N with k = offsets[N]), clamped
+ * to the back end's maximum (the 64-lane wavefront here; the paper names 32 for
+ * CUDA) and rounded up to a power of two; g lanes stride each row, their sums
+ * are reduced and one lane stores y[i].  It ignores the row partition.  It
+ * exists to put the paper's method beside the tuned kernels on the same
+ * hardware.  Arguments, dtype, beta == 0 and asynchrony rules as lapis_spmv.
+ */
+int lapis_spmv_paper_shape(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
+                           void *d_y, void *hip_stream);
+
+/* The vector length lapis_spmv_paper_shape uses: (nnz + nrows - 1) / nrows (Section 4.2,
+ * "Parallelism estimation"), clamped to LAPIS_WAVE and rounded up to a power of two; 1 for an
+ * empty matrix.  Host-only, no device access. */
+int lapis_paper_vector_length(int64_t nrows, int64_t nnz);
+
+/*
  * lapis_spmm - Y = alpha*A*X + beta*Y for k right-hand sides; column c of Y is
  * by definition lapis_spmv applied to column c of X (the paper times only the
  * single-vector product; this is its multi-vector form).

@@ -19,7 +19,7 @@ LAPIS_OK, LAPIS_ERR_INVALID_ARG, LAPIS_ERR_UNSUPPORTED, LAPIS_ERR_ALLOC, LAPIS_E
 LAPIS_F32, LAPIS_F64 = 0, 1
 
 EXPORTS = [
-    "lapis_csr_create", "lapis_spmv", "lapis_spmm", "lapis_csr_destroy",
+    "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_partition_constants",
     "lapis_last_error",
 ]
@@ -45,6 +45,8 @@ def load() -> ctypes.CDLL:
         i64, f64, p, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         lib.lapis_csr_create.argtypes = [ctypes.POINTER(p), i64, i64, i64, p, p, p, i32, p]
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_paper_vector_length.argtypes = [i64, i64]
         lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
         lib.lapis_csr_destroy.argtypes = [p]
         lib.lapis_csr_partition_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 4
@@ -95,6 +97,15 @@ def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, strea
 
 def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
     _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_spmv_paper_shape(A, alpha, d_x, beta, d_y, stream=None):
+    _check(load().lapis_spmv_paper_shape(A, float(alpha), _addr(d_x), float(beta), _addr(d_y),
+                                         _stream(stream)))
+
+
+def lapis_paper_vector_length(nrows, nnz):
+    return load().lapis_paper_vector_length(nrows, nnz)
 
 
 def lapis_spmm(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream=None):

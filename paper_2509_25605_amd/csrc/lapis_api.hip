@@ -262,6 +262,36 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
     return LAPIS_OK;
 }
 
+
+template <typename T, int G>
+void launch_vector(const lapis_csr *A, T a, const T *x, T b, T *y, hipStream_t stream)
+{
+    const uint32_t blocks = (uint32_t)((A->nrows + (kBlock / G) - 1) / (kBlock / G));
+    spmv_vector_kernel<T, G><<<dim3(blocks), dim3(kBlock), 0, stream>>>(
+        (int32_t)A->nrows, A->rowptr, A->colidx, static_cast<const T *>(A->vals), x, y, a, b);
+}
+
+template <typename T>
+int spmv_paper_shape_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y,
+                           hipStream_t stream)
+{
+    const int g = lapis_paper_vector_length(A->nrows, A->nnz);
+    const T a = (T)alpha, b = (T)beta;
+    const T *x = static_cast<const T *>(d_x);
+    T *y = static_cast<T *>(d_y);
+    switch (g) {
+    case 1: launch_vector<T, 1>(A, a, x, b, y, stream); break;
+    case 2: launch_vector<T, 2>(A, a, x, b, y, stream); break;
+    case 4: launch_vector<T, 4>(A, a, x, b, y, stream); break;
+    case 8: launch_vector<T, 8>(A, a, x, b, y, stream); break;
+    case 16: launch_vector<T, 16>(A, a, x, b, y, stream); break;
+    case 32: launch_vector<T, 32>(A, a, x, b, y, stream); break;
+    default: launch_vector<T, 64>(A, a, x, b, y, stream); break;
+    }
+    LAPIS_HIP(hipGetLastError());
+    return LAPIS_OK;
+}
+
 template <typename T, int VEC, int CL>
 int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b, T *Y, int64_t ldy,
                 hipStream_t stream)
@@ -361,6 +391,27 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, stream)
                                  : spmv_typed<float>(A, alpha, d_x, beta, d_y, stream);
+}
+
+int lapis_paper_vector_length(int64_t nrows, int64_t nnz)
+{
+    if (nrows <= 0 || nnz < 0) return 1;
+    const int64_t mean = (nnz + nrows - 1) / nrows;   // (k + N - 1) / N
+    int g = 1;
+    while (g < mean && g < LAPIS_WAVE) g *= 2;
+    return g;
+}
+
+int lapis_spmv_paper_shape(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+                           void *hip_stream)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->nrows > 0 && !d_y) return fail(LAPIS_ERR_INVALID_ARG, "d_y is NULL");
+    if (A->nnz > 0 && !d_x) return fail(LAPIS_ERR_INVALID_ARG, "d_x is NULL");
+    if (A->nrows == 0) return LAPIS_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return A->dtype == LAPIS_F64 ? spmv_paper_shape_typed<double>(A, alpha, d_x, beta, d_y, stream)
+                                 : spmv_paper_shape_typed<float>(A, alpha, d_x, beta, d_y, stream);
 }
 
 int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, int64_t ldx, double beta,

@@ -311,6 +311,30 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     if (sub == G - 1 && row_ok) store_result(y, (int32_t)row, s, alpha, beta);
 }
 
+// ---- the paper's own kernel shape --------------------------------------------
+// What the loop mapping of Section 4.2 produces for the CSR loop nest on a 64-lane
+// back end: every row gets the same vector length G (one value per matrix, the
+// average row length rounded up, clamped to the wavefront and, here, rounded up
+// to a power of two), the ThreadVector lanes stride the row ("Loop translation",
+// depth 2), the lane sums are reduced and one lane stores y[i] (`single`).  No
+// row partition is used.  Kept beside the tuned kernels as the reference point.
+template <typename T, int G>
+__global__ __launch_bounds__(kBlock) void spmv_vector_kernel(
+    int32_t nrows, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const T *__restrict__ vals, const T *__restrict__ x, T *__restrict__ y, T alpha, T beta)
+{
+    constexpr int kGroups = kBlock / G;
+    const int lane = threadIdx.x % G;
+    const int64_t row = (int64_t)blockIdx.x * kGroups + threadIdx.x / G;
+    T s = T(0);
+    if (row < nrows) {
+        const int64_t je = rowptr[row + 1];
+        for (int64_t j = (int64_t)rowptr[row] + lane; j < je; j += G) s += vals[j] * x[colidx[j]];
+    }
+    s = group_sum<G>(s);
+    if (lane == G - 1 && row < nrows) store_result(y, (int32_t)row, s, alpha, beta);
+}
+
 // ---- long rows -------------------------------------------------------------
 // Tile t covers positions [t*TILE, (t+1)*TILE) of the long rows' entries laid
 // end to end.  Since every long row has more than TILE entries, a tile touches

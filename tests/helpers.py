@@ -49,7 +49,7 @@ class DeviceCsr:
             0, dtype=torch.float64 if vals.dtype == np.float64 else torch.float32, device=dev)
         self.mat = L.CsrMatrix(nrows, ncols, self.rowptr, self.colidx, self.vals)
 
-    def spmv(self, x, alpha=1.0, beta=0.0, y0=None, y_fill=None):
+    def spmv(self, x, alpha=1.0, beta=0.0, y0=None, y_fill=None, paper_shape=False):
         torch = self.torch
         dx = torch.from_numpy(np.ascontiguousarray(x, dtype=self.np_dtype)).cuda()
         if y0 is not None:
@@ -57,7 +57,10 @@ class DeviceCsr:
         else:
             dy = torch.full((self.nrows,), float("nan") if y_fill is None else y_fill,
                             dtype=dx.dtype, device="cuda:0")
-        self.mat.spmv(dx, dy, alpha, beta)
+        if paper_shape:
+            self.L.lapis_spmv_paper_shape(self.mat.handle, alpha, dx, beta, dy)
+        else:
+            self.mat.spmv(dx, dy, alpha, beta)
         torch.cuda.synchronize()
         return dy.cpu().numpy()
 

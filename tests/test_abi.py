@@ -78,6 +78,7 @@ def test_null_handles_and_out_pointer(lib):
     assert _create(lib, 4, 4, 0, 8, 8, 8, 1, out=False)[0] == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_destroy(None) == L.LAPIS_OK
     assert lib.lapis_spmv(None, 1.0, 8, 0.0, 8, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_spmv_paper_shape(None, 1.0, 8, 0.0, 8, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_spmm(None, 4, 1.0, 8, 4, 0.0, 8, 4, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_partition_sizes(None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_copy_partition(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
@@ -85,3 +86,20 @@ def test_null_handles_and_out_pointer(lib):
     with pytest.raises(L.LapisError) as e:
         L.lapis_spmv(None, 1.0, 8, 0.0, 8, stream=0)
     assert e.value.code == L.LAPIS_ERR_INVALID_ARG
+
+
+def test_paper_vector_length_on_table3(lib, golden_dir):
+    """The per-matrix vector length of the paper's estimate on the matrices of its Table 3."""
+    for line in open(os.path.join(golden_dir, "paper_table3.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, rows, mean, _mx, expect = line.split()
+        rows, nnz = int(rows), int(round(int(rows) * float(mean)))
+        assert L.lapis_paper_vector_length(rows, nnz) == int(expect), name
+    assert L.lapis_paper_vector_length(10, 10) == 1
+    assert L.lapis_paper_vector_length(10, 11) == 2
+    assert L.lapis_paper_vector_length(10, 30) == 4
+    assert L.lapis_paper_vector_length(10, 31) == 4
+    assert L.lapis_paper_vector_length(10, 41) == 8
+    assert L.lapis_paper_vector_length(1, 10 ** 9) == 64
+    assert L.lapis_paper_vector_length(0, 0) == 1

@@ -26,9 +26,10 @@ def check_partition(dev, rowptr):
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
 
 
-def check_spmv(dev, rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None, literal=False, what=""):
+def check_spmv(dev, rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None, literal=False, what="",
+               paper_shape=False):
     ref, absAx = oracle.spmv(rowptr, colidx, vals, x, alpha, beta, y0)
-    got = dev.spmv(x, alpha, beta, y0)
+    got = dev.spmv(x, alpha, beta, y0, paper_shape=paper_shape)
     nnz_row = np.diff(rowptr)
     tol = literal_bound(nnz_row, absAx, vals.dtype) if literal else general_bound(
         nnz_row, absAx, vals.dtype, alpha, beta, y0)
@@ -87,6 +88,8 @@ def test_spmv_general_matrices(dtype, n, ncols, longest, srt, dup):
         check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
         check_spmv(dev, rowptr, colidx, vals, x, -2.5, 0.75, y0, what="alpha=-2.5 beta=0.75")
         check_spmv(dev, rowptr, colidx, vals, x, 0.0, 2.0, y0, what="alpha=0")
+        check_spmv(dev, rowptr, colidx, vals, x, what="paper shape", paper_shape=True)
+        check_spmv(dev, rowptr, colidx, vals, x, -2.5, 0.75, y0, what="paper shape, alpha beta", paper_shape=True)
         a = check_spmv(dev, rowptr, colidx, vals, x, 3.0, 0.0, what="run 1")
         b = dev.spmv(x, 3.0, 0.0)
         assert np.array_equal(a, b), "two runs differ: result depends on scheduling"
@@ -276,6 +279,8 @@ def run_workload(cfg, scale):
         check_partition(dev, w.rowptr)
         if w.k == 0:
             check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
+            check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True,
+                       what=w.name + " (paper shape)", paper_shape=True)
         else:
             check_spmm(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
     finally:
