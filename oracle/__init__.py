@@ -26,6 +26,8 @@ TILE_NNZ = 4096
 NUM_BINS = 10
 STREAM_ROWS = 32
 STREAM_MIN_NNZ = 256
+SPLIT_BLOCK_BYTES = 1 << 21   # target size of one column block of x
+SPLIT_MAX_BLOCKS = 32
 
 
 def build(force: bool = False) -> str:
@@ -58,6 +60,8 @@ def _load():
         lib.oracle_partition_rows.restype = None
         lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
         lib.oracle_partition_tiles.restype = None
+        lib.oracle_split_cuts.argtypes = [p, p, p, i64, i64, i64, p, p]
+        lib.oracle_split_cuts.restype = None
         _lib = lib
     return _lib
 
@@ -139,3 +143,42 @@ def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NN
                                _p(tile_row), _p(tile_nz))
     return {"num_bins": nb, "stream_chunks": stream_chunks, "bin_offset": bin_offset,
             "row_perm": row_perm, "long_off": long_off, "tile_row": tile_row, "tile_nz": tile_nz}
+
+
+def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):
+    """(number of column blocks, block width); (0, 0) when x is too small to be worth splitting."""
+    target = block_bytes // itemsize
+    nb = min(max_blocks, -(-ncols // target))
+    if nb < 2:
+        return 0, 0
+    return nb, -(-ncols // nb)
+
+
+def split_partition(rowptr, colidx, ncols, itemsize, part=None, wave=WAVE, long_threshold=LONG_THRESHOLD,
+                    tile_nnz=TILE_NNZ, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):
+    """Reference column split of the rows of the last two bins into virtual rows, and the bins /
+    tiles of those virtual rows.  Returns a dict; 'num_blocks' == 0 means the split is off (x
+    small, no such rows, or a split row with unsorted columns)."""
+    part = part or partition(rowptr, wave, long_threshold, tile_nnz)
+    nb_bins = part["num_bins"]
+    off = part["bin_offset"]
+    split_rows = np.ascontiguousarray(part["row_perm"][off[nb_bins - 2]:off[nb_bins]])
+    S = split_rows.size
+    nb, W = split_geometry(ncols, itemsize, block_bytes, max_blocks)
+    none = {"num_blocks": 0, "block_width": 0, "num_split_rows": 0}
+    if nb == 0 or S == 0:
+        return none
+    cut = np.empty((nb + 1) * S, dtype=np.int32)
+    sorted_flag = ctypes.c_int32(0)
+    _load().oracle_split_cuts(_p(rowptr), _p(colidx), _p(split_rows), S, nb, W, _p(cut),
+                              ctypes.addressof(sorted_flag))
+    if not sorted_flag.value:
+        return none
+    vlen = (cut[S:] - cut[:-S]).astype(np.int64)
+    fake = np.zeros(vlen.size + 1, dtype=np.int32)      # only row lengths enter bins and tiles
+    np.cumsum(vlen, out=fake[1:])
+    vp = partition(fake, wave, long_threshold, tile_nnz, stream_rows=STREAM_ROWS, stream_min_nnz=2 ** 31 - 1)
+    assert vp["stream_chunks"].size == 0
+    return {"num_blocks": nb, "block_width": W, "num_split_rows": S, "cut": cut,
+            "bin_offset": vp["bin_offset"], "row_perm": vp["row_perm"], "long_off": vp["long_off"],
+            "tile_row": vp["tile_row"], "tile_nz": vp["tile_nz"]}

@@ -230,3 +230,28 @@ void oracle_partition_tiles(const int32_t *rowptr, int64_t tile_nnz, const int32
     tile_row[T] = (int32_t)m;
     tile_nz[T] = 0;
 }
+
+/* ---- Column split of the rows with more than `wave` entries ---------------
+ * When x is much larger than a level-2 cache, the rows of the last two bins
+ * (split_rows[0..S-1], in row_perm order) are cut at the column-block
+ * boundaries b*W, b = 0..nb: cut[b*S + r] is the first entry j of row
+ * split_rows[r] with colidx[j] >= b*W (so cut[0*S + r] = rowptr[row] and
+ * cut[nb*S + r] = rowptr[row+1]).  Virtual row v = b*S + r owns the entries
+ * cut[v] .. cut[v + S] - 1.  The cut is only meaningful when every split row
+ * has non-decreasing columns; *sorted reports that.
+ */
+void oracle_split_cuts(const int32_t *rowptr, const int32_t *colidx, const int32_t *split_rows,
+                       int64_t S, int64_t nb, int64_t W, int32_t *cut, int32_t *sorted)
+{
+    *sorted = 1;
+    for (int64_t r = 0; r < S; ++r) {
+        int64_t rb = rowptr[split_rows[r]], re = rowptr[split_rows[r] + 1];
+        for (int64_t j = rb; j + 1 < re; ++j)
+            if (colidx[j] > colidx[j + 1]) *sorted = 0;
+        int64_t j = rb;
+        for (int64_t b = 0; b <= nb; ++b) {
+            while (j < re && (int64_t)colidx[j] < b * W) ++j;
+            cut[b * S + r] = (int32_t)(b == nb ? re : j);
+        }
+    }
+}

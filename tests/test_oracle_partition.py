@@ -155,3 +155,53 @@ def test_partition_degenerate_inputs():
     # 12289 long entries -> 4 tiles starting at 0, 4096, 8192, 12288
     assert part["tile_row"].tolist() == [0, 0, 1, 1, 2]
     assert part["tile_nz"].tolist() == [0, 4096, 4095, 8191, 0]
+
+
+def test_split_geometry():
+    assert oracle.split_geometry(1 << 23, 4) == (16, 1 << 19)       # 32 MiB of floats: 16 blocks of 2 MiB
+    assert oracle.split_geometry(1 << 22, 8) == (16, 1 << 18)
+    assert oracle.split_geometry(1 << 18, 8) == (0, 0)              # 2 MiB: not worth it
+    assert oracle.split_geometry((1 << 18) + 1, 8) == (2, (1 << 17) + 1)
+    assert oracle.split_geometry(1 << 30, 8) == (32, 1 << 25)       # capped at 32 blocks
+    assert oracle.split_geometry(1000003, 4) == (2, 500002)
+
+
+def test_split_cuts_hand_worked():
+    """Two rows above 64 entries in a 30-column-block world: blocks of width 10 (nb = 3)."""
+    cols0 = list(range(0, 70))                   # row 0: columns 0..69 -> cuts at 10, 20, then the end
+    cols1 = [5] * 3 + [12] * 60 + [29] * 7        # row 2: duplicates allowed (non-decreasing)
+    rowptr = np.array([0, 70, 72, 142], dtype=np.int32)
+    colidx = np.array(cols0 + [1, 2] + cols1, dtype=np.int32)
+    part = oracle.partition(rowptr)
+    assert part["row_perm"].tolist() == [1, 0, 2]                   # bin 2 (row 1), bin 8 (rows 0, 2)
+    sp = oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, max_blocks=32)
+    assert (sp["num_blocks"], sp["block_width"], sp["num_split_rows"]) == (3, 10, 2)
+    # cut[b*S + r]: b = 0..3, r = 0 (row 0), 1 (row 2)
+    assert sp["cut"].tolist() == [0, 72, 10, 75, 20, 135, 70, 142]
+    # virtual rows (b, r): lengths 10, 3, 10, 60, 50, 7 -> bins 5, 3, 5, 7, 7, 4
+    assert np.diff(sp["bin_offset"]).tolist() == [0, 0, 0, 1, 1, 2, 0, 2, 0, 0]
+    assert sp["row_perm"].tolist() == [1, 5, 0, 2, 3, 4]
+    # an unsorted split row switches the split off
+    colidx[3], colidx[4] = colidx[4], colidx[3]
+    assert oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80)["num_blocks"] == 0
+
+
+def test_split_matches_searchsorted():
+    n, ncols = 400, 1 << 20
+    L = np.full(n, 3, dtype=np.int64)
+    L[::7] = 100 + 37 * np.arange(L[::7].size)        # rows above 64 entries, some above 4096
+    L[5] = 9000
+    rowptr, colidx, _ = gen.random_csr(n, ncols, L, 99)
+    part = oracle.partition(rowptr)
+    sp = oracle.split_partition(rowptr, colidx, ncols, 8, part)
+    nb, W, S = sp["num_blocks"], sp["block_width"], sp["num_split_rows"]
+    assert (nb, W) == (4, 1 << 18) and S == (L > 64).sum()
+    rows = part["row_perm"][part["bin_offset"][8]:]
+    for r, row in enumerate(rows):
+        cols = colidx[rowptr[row]:rowptr[row + 1]]
+        expect = rowptr[row] + np.searchsorted(cols, np.arange(nb + 1) * W, side="left")
+        expect[-1] = rowptr[row + 1]
+        assert np.array_equal(sp["cut"][r::S], expect)
+    vlen = sp["cut"][S:] - sp["cut"][:-S]
+    assert vlen.sum() == L[L > 64].sum() and np.all(vlen >= 0)
+    assert np.array_equal(np.sort(sp["row_perm"]), np.arange(nb * S))
