@@ -60,6 +60,19 @@ extern "C" {
  * The entries of the bin-9 rows, laid end to end in row order, are cut into
  * tiles of LAPIS_TILE_NNZ entries; LAPIS_LONG_THRESHOLD >= LAPIS_TILE_NNZ, so a
  * tile touches at most two rows.
+ *
+ * Level 3, column split (lapis_spmv only), for the rows of bins 8 and 9 when x
+ * is far larger than a level-2 cache.  With e the size of a value in bytes:
+ * nb = min(LAPIS_SPLIT_MAX_BLOCKS, ceil(ncols / (LAPIS_SPLIT_BLOCK_BYTES / e)))
+ * column blocks of width W = ceil(ncols / nb); the split is off when nb < 2,
+ * when bins 8 and 9 are empty, or when one of their rows has decreasing
+ * columns.  Let split_rows[0..S-1] be the rows of bins 8 and 9 in row_perm
+ * order.  cut[b*S + r] is the first entry of row split_rows[r] whose column is
+ * >= b*W (b = 0..nb; cut[nb*S + r] is the row's end).  Virtual row v = b*S + r
+ * owns the entries cut[v] .. cut[v+S]-1; the virtual rows are binned and tiled
+ * by the level-2 rule (no stream chunks), processed block after block so that
+ * the gathers of one column block stay cache resident, and each split row's nb
+ * partial sums are added in ascending block order.
  */
 #define LAPIS_NUM_BINS        10
 #define LAPIS_WAVE            64
@@ -67,6 +80,8 @@ extern "C" {
 #define LAPIS_TILE_NNZ        4096
 #define LAPIS_STREAM_ROWS     32
 #define LAPIS_STREAM_MIN_NNZ  256
+#define LAPIS_SPLIT_BLOCK_BYTES 2097152   /* 2 MiB of x per column block */
+#define LAPIS_SPLIT_MAX_BLOCKS  32
 
 typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
 
@@ -107,8 +122,9 @@ int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nn
  * Rows without entries receive beta*y (exactly +0 when beta == 0).
  * Asynchronous: the kernels are enqueued on hip_stream and the call returns;
  * no allocation, no host-device copy, no synchronisation.  Matrices with rows
- * in bin 9 use per-tile scratch owned by the handle, so two calls on the same
- * handle must not run concurrently on different streams.
+ * in bin 9 or with a column split use scratch owned by the handle (per-tile and
+ * per-virtual-row sums), so two calls on the same handle must not run
+ * concurrently on different streams.
  */
 int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
                void *hip_stream);
@@ -175,10 +191,23 @@ int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int
                              int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
                              int32_t *h_tile_nz);
 
+/* The column split (level 3).  lapis_csr_split_sizes: *num_blocks = nb (0: the split is off),
+ * *block_width = W, *num_split_rows = S, and for the virtual rows *num_binned (= nb*S),
+ * *num_long, *num_tiles as in lapis_csr_partition_sizes.  lapis_csr_copy_split copies to HOST
+ * buffers (any may be NULL): h_cut int32[(nb+1)*S] and the bins / row lists / tile table of the
+ * virtual rows, laid out as in lapis_csr_copy_partition.  It returns LAPIS_ERR_INVALID_ARG when
+ * the split is off.  Synchronises the device. */
+int lapis_csr_split_sizes(const lapis_csr_t *A, int64_t *num_blocks, int64_t *block_width,
+                          int64_t *num_split_rows, int64_t *num_binned, int64_t *num_long,
+                          int64_t *num_tiles);
+int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_offset,
+                         int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
+                         int32_t *h_tile_nz);
+
 /* The partition constants compiled into the library, in the order
  * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ,
- *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ}. */
-int lapis_partition_constants(int64_t h_out[6]);
+ *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ, LAPIS_SPLIT_BLOCK_BYTES, LAPIS_SPLIT_MAX_BLOCKS}. */
+int lapis_partition_constants(int64_t h_out[8]);
 
 /* Text of the most recent error on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on that thread. */

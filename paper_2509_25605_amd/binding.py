@@ -20,7 +20,8 @@ LAPIS_F32, LAPIS_F64 = 0, 1
 
 EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
-    "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_partition_constants",
+    "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
+    "lapis_csr_copy_split", "lapis_partition_constants",
     "lapis_last_error",
 ]
 
@@ -51,6 +52,8 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_destroy.argtypes = [p]
         lib.lapis_csr_partition_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 4
         lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p, p]
+        lib.lapis_csr_split_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 6
+        lib.lapis_csr_copy_split.argtypes = [p, p, p, p, p, p, p]
         lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
@@ -125,10 +128,11 @@ def lapis_csr_partition_sizes(A):
 
 
 def lapis_partition_constants():
-    out = (ctypes.c_int64 * 6)()
+    out = (ctypes.c_int64 * 8)()
     _check(load().lapis_partition_constants(out))
     return {"num_bins": out[0], "wave": out[1], "long_threshold": out[2], "tile_nnz": out[3],
-            "stream_rows": out[4], "stream_min_nnz": out[5]}
+            "stream_rows": out[4], "stream_min_nnz": out[5], "split_block_bytes": out[6],
+            "split_max_blocks": out[7]}
 
 
 def lapis_csr_copy_partition(A):
@@ -147,4 +151,32 @@ def lapis_csr_copy_partition(A):
     _check(load().lapis_csr_copy_partition(A, ptr(res["stream_chunks"]), ptr(res["bin_offset"]),
                                            ptr(res["row_perm"]), ptr(res["long_off"]),
                                            ptr(res["tile_row"]), ptr(res["tile_nz"])))
+    return res
+
+
+def lapis_csr_split_sizes(A):
+    """(num_blocks, block_width, num_split_rows, num_virtual_rows, num_long, num_tiles)"""
+    v = [ctypes.c_int64() for _ in range(6)]
+    _check(load().lapis_csr_split_sizes(A, *[ctypes.byref(x) for x in v]))
+    return tuple(x.value for x in v)
+
+
+def lapis_csr_copy_split(A):
+    """Host copies of the column split; {'num_blocks': 0, ...} when the split is off."""
+    nb, W, S, nv, m, t = lapis_csr_split_sizes(A)
+    if nb == 0:
+        return {"num_blocks": 0, "block_width": 0, "num_split_rows": 0}
+    nbins = lapis_partition_constants()["num_bins"]
+    res = {
+        "num_blocks": nb, "block_width": W, "num_split_rows": S,
+        "cut": np.empty((nb + 1) * S, dtype=np.int32),
+        "bin_offset": np.empty(nbins + 1, dtype=np.int32),
+        "row_perm": np.empty(nv, dtype=np.int32),
+        "long_off": np.empty(m + 1, dtype=np.int32),
+        "tile_row": np.empty(t + 1, dtype=np.int32),
+        "tile_nz": np.empty(t + 1, dtype=np.int32),
+    }
+    ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    _check(load().lapis_csr_copy_split(A, ptr(res["cut"]), ptr(res["bin_offset"]), ptr(res["row_perm"]),
+                                       ptr(res["long_off"]), ptr(res["tile_row"]), ptr(res["tile_nz"])))
     return res

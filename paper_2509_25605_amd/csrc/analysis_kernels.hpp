@@ -85,10 +85,13 @@ __global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunk
     if (threadIdx.x == 0) *count = running;
 }
 
-// Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped); hist is bin-major: hist[bin*num_blocks + block].
+// Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped; chunk_flag
+// may be null); hist is bin-major: hist[bin*num_blocks + block].  row_begin[i] / row_end[i]
+// delimit row i: (rowptr, rowptr + 1) for the matrix's rows, the cut table for virtual rows.
 template <int LONG_THRESHOLD>
 __global__ __launch_bounds__(kBlock) void bin_count_kernel(int32_t nrows,
-                                                           const int32_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ row_begin,
+                                                           const int32_t *__restrict__ row_end,
                                                            int32_t chunk_rows,
                                                            const int32_t *__restrict__ chunk_flag,
                                                            int32_t num_blocks,
@@ -100,8 +103,8 @@ __global__ __launch_bounds__(kBlock) void bin_count_kernel(int32_t nrows,
     const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
     for (int it = 0; it < kRowsPerThread; ++it) {
         const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
-        if (i < nrows && !chunk_flag[i / chunk_rows])
-            atomicAdd(&s_hist[bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i])], 1);
+        if (i < nrows && !(chunk_flag && chunk_flag[i / chunk_rows]))
+            atomicAdd(&s_hist[bin_of_length<LONG_THRESHOLD>(row_end[i] - row_begin[i])], 1);
     }
     __syncthreads();
     if (threadIdx.x < kNumBins) hist[(int64_t)threadIdx.x * num_blocks + blockIdx.x] = s_hist[threadIdx.x];
@@ -133,7 +136,8 @@ __global__ __launch_bounds__(kBlock) void bin_scan_kernel(int64_t count, int32_t
 // Pass 3: stable scatter of row ids into row_perm.
 template <int LONG_THRESHOLD>
 __global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
-                                                             const int32_t *__restrict__ rowptr,
+                                                             const int32_t *__restrict__ row_begin,
+                                                             const int32_t *__restrict__ row_end,
                                                              int32_t chunk_rows,
                                                              const int32_t *__restrict__ chunk_flag,
                                                              int32_t num_blocks,
@@ -148,8 +152,8 @@ __global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
     const int64_t base = (int64_t)blockIdx.x * kRowsPerAnalysisBlock;
     for (int it = 0; it < kRowsPerThread; ++it) {
         const int64_t i = base + (int64_t)it * kBlock + threadIdx.x;
-        const int bin = (i < nrows && !chunk_flag[i / chunk_rows])
-                            ? bin_of_length<LONG_THRESHOLD>(rowptr[i + 1] - rowptr[i]) : -1;
+        const int bin = (i < nrows && !(chunk_flag && chunk_flag[i / chunk_rows]))
+                            ? bin_of_length<LONG_THRESHOLD>(row_end[i] - row_begin[i]) : -1;
         int32_t rank_in_wave = 0;
         for (int b = 0; b < kNumBins; ++b) {
             const uint64_t mask = __ballot(bin == b);
@@ -174,7 +178,8 @@ __global__ __launch_bounds__(kBlock) void bin_scatter_kernel(int32_t nrows,
 
 // Pass 4 (one workgroup): long_off[0..m] = exclusive scan of the long rows' lengths.
 __global__ __launch_bounds__(kBlock) void long_scan_kernel(int32_t m, const int32_t *__restrict__ long_rows,
-                                                           const int32_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ row_begin,
+                                                           const int32_t *__restrict__ row_end,
                                                            int32_t *__restrict__ long_off)
 {
     __shared__ int32_t s_tmp[kBlock];
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void long_scan_kernel(int32_t m, const int3
     for (int64_t base = 0; base < m; base += kBlock) {
         const int64_t r = base + threadIdx.x;
         int32_t v = 0;
-        if (r < m) { const int32_t row = long_rows[r]; v = rowptr[row + 1] - rowptr[row]; }
+        if (r < m) { const int32_t row = long_rows[r]; v = row_end[row] - row_begin[row]; }
         int32_t total;
         const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
         if (r < m) long_off[r] = running + excl;
@@ -210,6 +215,67 @@ __global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t 
     }
     tile_row[t] = lo;
     tile_nz[t] = (int32_t)(pos - long_off[lo]);
+}
+
+
+// ---- column split of the rows above kWave entries ---------------------------
+// When x is far larger than a level-2 cache, the rows of the last two bins are cut at the
+// column-block boundaries b*W (b = 0..nb) into virtual rows, so that the gathers of one block
+// stay cache resident while all rows' pieces in that block are processed.
+
+// flag[0] = 1 if some split row has decreasing columns (the cut would then be wrong).
+__global__ __launch_bounds__(kBlock) void split_sorted_kernel(int32_t S, const int32_t *__restrict__ split_rows,
+                                                              const int32_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ colidx,
+                                                              int32_t *__restrict__ flag)
+{
+    bool bad = false;
+    for (int64_t r = blockIdx.x; r < S; r += gridDim.x) {
+        const int32_t row = split_rows[r];
+        const int64_t je = rowptr[row + 1];
+        for (int64_t j = (int64_t)rowptr[row] + threadIdx.x; j + 1 < je; j += kBlock)
+            bad |= colidx[j] > colidx[j + 1];
+    }
+    if (bad) flag[0] = 1;
+}
+
+// cut[b*S + r] = first entry j of row split_rows[r] with colidx[j] >= b*W; cut[nb*S + r] = row end.
+__global__ __launch_bounds__(kBlock) void split_cut_kernel(int32_t S, int32_t nb, int64_t W,
+                                                           const int32_t *__restrict__ split_rows,
+                                                           const int32_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ colidx,
+                                                           int32_t *__restrict__ cut)
+{
+    const int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= (int64_t)(nb + 1) * S) return;
+    const int64_t b = v / S, r = v % S;
+    const int32_t row = split_rows[r];
+    int32_t lo = rowptr[row], hi = rowptr[row + 1];   // answer in [lo, hi]
+    if (b < nb) {
+        const int64_t target = b * W;
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if ((int64_t)colidx[mid] < target) lo = mid + 1; else hi = mid;
+        }
+    } else {
+        lo = hi;
+    }
+    cut[v] = lo;
+}
+
+// y[row] = alpha * sum_b vsum[b*S + r] + beta * y[row], blocks added in ascending order.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void split_combine_kernel(int32_t S, int32_t nb,
+                                                               const int32_t *__restrict__ split_rows,
+                                                               const T *__restrict__ vsum,
+                                                               T *__restrict__ y, T alpha, T beta)
+{
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= S) return;
+    T s = T(0);
+    for (int b = 0; b < nb; ++b) s += vsum[(int64_t)b * S + r];
+    const int32_t row = split_rows[r];
+    y[row] = (beta == T(0)) ? alpha * s : alpha * s + beta * y[row];
 }
 
 }  // namespace lapis

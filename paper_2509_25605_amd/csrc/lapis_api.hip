@@ -23,24 +23,46 @@ static_assert(LAPIS_TILE_NNZ % kBlock == 0, "tile size must be a multiple of the
 static_assert(LAPIS_STREAM_ROWS == kStreamRows, "header and kernels disagree on the stream chunk size");
 static_assert(LAPIS_STREAM_ROWS * LAPIS_WAVE <= 3 * kStreamWindow - 4, "a stream chunk must fit in three LDS windows");
 
+namespace {
+
+// A set of rows (the matrix's own rows outside stream chunks, or the virtual rows of the column
+// split) partitioned into bins, plus the tile table of its last bin.  Row i of the set owns the
+// entries row_begin[i] .. row_end[i] - 1.
+struct BinnedSet {
+    int64_t num_rows = 0;            // rows offered to the binning (before stream chunks are skipped)
+    const int32_t *row_begin = nullptr;
+    const int32_t *row_end = nullptr;
+    int32_t *d_bin_offset = nullptr; // [kNumBins + 1]
+    int32_t *d_row_perm = nullptr;   // [num_binned], allocated for num_rows
+    int32_t *d_long_off = nullptr;   // [num_long + 1]
+    int32_t *d_tile_row = nullptr;   // [num_tiles + 1]
+    int32_t *d_tile_nz = nullptr;    // [num_tiles + 1]
+    void *d_partial = nullptr;       // [2 * num_tiles] of the value type: per-tile segment sums
+    int32_t h_bin_offset[kNumBins + 1] = {0};
+    int64_t num_binned = 0, num_long = 0, num_tiles = 0;
+};
+
+}  // namespace
+
 struct lapis_csr {
-    int64_t nrows, ncols, nnz;
-    int dtype;
-    const int32_t *rowptr;
-    const int32_t *colidx;
-    const void *vals;
-    // analysis results (device)
-    int32_t *d_stream_chunks;  // [num_stream] ascending ids of the stream chunks
-    int32_t *d_bin_offset;  // [kNumBins + 1]
-    int32_t *d_row_perm;    // [num_binned] (allocated for nrows)
-    int32_t *d_long_off;    // [num_long + 1]
-    int32_t *d_tile_row;    // [num_tiles + 1]
-    int32_t *d_tile_nz;     // [num_tiles + 1]
-    void *d_partial;        // [2 * num_tiles] of dtype: per-tile segment sums
-    // host copies
-    int32_t h_bin_offset[kNumBins + 1];
-    int64_t num_chunks, num_stream, num_binned, num_long, num_tiles;
-    ShortPlan plan;
+    int64_t nrows = 0, ncols = 0, nnz = 0;
+    int dtype = 0;
+    const int32_t *rowptr = nullptr;
+    const int32_t *colidx = nullptr;
+    const void *vals = nullptr;
+    // level 1: stream chunks
+    int32_t *d_stream_chunks = nullptr;  // [num_stream] ascending ids
+    int64_t num_chunks = 0, num_stream = 0;
+    // level 2: bins over the rows outside stream chunks
+    BinnedSet rows;
+    // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
+    int64_t num_blocks = 0, block_width = 0, num_split = 0;
+    int32_t *d_cut = nullptr;            // [(num_blocks + 1) * num_split]
+    void *d_vsum = nullptr;              // [num_blocks * num_split] of the value type
+    BinnedSet vrows;
+    // launch plans for spmv_short_kernel
+    ShortPlan plan_rows;       // bins 0..8 of `rows` (0..7 when the split is on)
+    ShortPlan plan_vrows;      // bins 0..8 of `vrows`
 };
 
 namespace {
@@ -75,18 +97,36 @@ int device_alloc(P **ptr, size_t bytes)
     return LAPIS_OK;
 }
 
+// Frees on scope exit; for the temporaries of the analysis.
+struct DeviceTemp {
+    void *p = nullptr;
+    ~DeviceTemp() { (void)hipFree(p); }
+    template <typename P> P *as() { return static_cast<P *>(p); }
+    int alloc(size_t bytes) { return device_alloc(&p, bytes); }
+};
+
+void free_set(BinnedSet &s)
+{
+    (void)hipFree(s.d_bin_offset);
+    (void)hipFree(s.d_row_perm);
+    (void)hipFree(s.d_long_off);
+    (void)hipFree(s.d_tile_row);
+    (void)hipFree(s.d_tile_nz);
+    (void)hipFree(s.d_partial);
+}
+
 void free_handle(lapis_csr *A)
 {
     if (!A) return;
     (void)hipFree(A->d_stream_chunks);
-    (void)hipFree(A->d_bin_offset);
-    (void)hipFree(A->d_row_perm);
-    (void)hipFree(A->d_long_off);
-    (void)hipFree(A->d_tile_row);
-    (void)hipFree(A->d_tile_nz);
-    (void)hipFree(A->d_partial);
+    (void)hipFree(A->d_cut);
+    (void)hipFree(A->d_vsum);
+    free_set(A->rows);
+    free_set(A->vrows);
     delete A;
 }
+
+size_t value_size(const lapis_csr *A) { return A->dtype == LAPIS_F64 ? sizeof(double) : sizeof(float); }
 
 // flags[0]: a row has negative length; flags[1]: a column index is out of range
 __global__ __launch_bounds__(kBlock) void validate_kernel(int64_t nrows, int64_t ncols, int64_t nnz,
@@ -106,129 +146,197 @@ __global__ __launch_bounds__(kBlock) void validate_kernel(int64_t nrows, int64_t
     if (bad_col) flags[1] = 1;
 }
 
-void build_short_plan(lapis_csr *A)
+// Workgroup ranges of bins 0..last_bin of a set; every bin is padded to a multiple of the XCD count.
+void build_short_plan(const BinnedSet &s, int last_bin, ShortPlan *p)
 {
-    ShortPlan &p = A->plan;
     uint32_t blocks = 0;
     for (int b = 0; b < kShortBins; ++b) {
-        p.bin_begin[b] = A->h_bin_offset[b];
-        p.bin_count[b] = A->h_bin_offset[b + 1] - A->h_bin_offset[b];
-        p.block_begin[b] = blocks;
+        p->bin_begin[b] = s.h_bin_offset[b];
+        p->bin_count[b] = (b <= last_bin) ? s.h_bin_offset[b + 1] - s.h_bin_offset[b] : 0;
+        p->block_begin[b] = blocks;
         const int per_block = short_rows_per_block(b);
-        blocks += (uint32_t)(((int64_t)p.bin_count[b] + per_block - 1) / per_block);
+        const uint32_t need = (uint32_t)(((int64_t)p->bin_count[b] + per_block - 1) / per_block);
+        blocks += (need + kXcds - 1) / kXcds * kXcds;
     }
-    p.block_begin[kShortBins] = blocks;
-    p.num_blocks = blocks;
-    p.padded_blocks = (blocks + kXcds - 1) / kXcds * kXcds;
+    p->block_begin[kShortBins] = blocks;
+    p->num_blocks = blocks;
+}
+
+// Bins, stable row lists and the tile table of a row set.  chunk_flag (may be null) marks the
+// chunks whose rows are left out.  Synchronises the stream.
+int bin_row_set(BinnedSet *s, const int32_t *d_chunk_flag, size_t esize, hipStream_t stream)
+{
+    const int64_t n = s->num_rows;
+    if (int rc = device_alloc(&s->d_bin_offset, sizeof(int32_t) * (kNumBins + 1))) return rc;
+    if (int rc = device_alloc(&s->d_row_perm, sizeof(int32_t) * (size_t)n)) return rc;
+    LAPIS_HIP(hipMemsetAsync(s->d_bin_offset, 0, sizeof(int32_t) * (kNumBins + 1), stream));
+    if (n > 0) {
+        const int32_t num_blocks = (int32_t)((n + kRowsPerAnalysisBlock - 1) / kRowsPerAnalysisBlock);
+        DeviceTemp hist;
+        if (int rc = hist.alloc(sizeof(int32_t) * (size_t)kNumBins * num_blocks)) return rc;
+        bin_count_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, s->row_begin, s->row_end, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks, hist.as<int32_t>());
+        bin_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>((int64_t)kNumBins * num_blocks, num_blocks,
+                                                              hist.as<int32_t>(), s->d_bin_offset);
+        bin_scatter_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, s->row_begin, s->row_end, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks,
+            hist.as<int32_t>(), s->d_row_perm);
+        LAPIS_HIP(hipGetLastError());
+        LAPIS_HIP(hipMemcpyAsync(s->h_bin_offset, s->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
+                                 hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));   // hist is freed on return
+    }
+    s->num_binned = s->h_bin_offset[kNumBins];
+
+    // long rows: scan of their lengths, then the tile table
+    const int32_t m = s->h_bin_offset[kNumBins] - s->h_bin_offset[kNumBins - 1];
+    s->num_long = m;
+    if (int rc = device_alloc(&s->d_long_off, sizeof(int32_t) * ((size_t)m + 1))) return rc;
+    int32_t long_total = 0;
+    if (m > 0) {
+        long_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
+            m, s->d_row_perm + s->h_bin_offset[kNumBins - 1], s->row_begin, s->row_end, s->d_long_off);
+        LAPIS_HIP(hipMemcpyAsync(&long_total, s->d_long_off + m, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+    } else {
+        LAPIS_HIP(hipMemsetAsync(s->d_long_off, 0, sizeof(int32_t), stream));
+    }
+    const int64_t T = ((int64_t)long_total + LAPIS_TILE_NNZ - 1) / LAPIS_TILE_NNZ;
+    s->num_tiles = T;
+    if (int rc = device_alloc(&s->d_tile_row, sizeof(int32_t) * ((size_t)T + 1))) return rc;
+    if (int rc = device_alloc(&s->d_tile_nz, sizeof(int32_t) * ((size_t)T + 1))) return rc;
+    if (int rc = device_alloc(&s->d_partial, esize * 2 * (size_t)T)) return rc;
+    tile_search_kernel<LAPIS_TILE_NNZ><<<dim3((uint32_t)((T + 1 + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+        m, T, s->d_long_off, s->d_tile_row, s->d_tile_nz);
+    LAPIS_HIP(hipGetLastError());
+    LAPIS_HIP(hipStreamSynchronize(stream));
+    return LAPIS_OK;
+}
+
+// Number of column blocks and their width for the split (0: x is too small to bother).
+void split_geometry(int64_t ncols, size_t esize, int64_t *num_blocks, int64_t *width)
+{
+    const int64_t target = (int64_t)LAPIS_SPLIT_BLOCK_BYTES / (int64_t)esize;
+    int64_t nb = (ncols + target - 1) / target;
+    if (nb > LAPIS_SPLIT_MAX_BLOCKS) nb = LAPIS_SPLIT_MAX_BLOCKS;
+    if (nb < 2) { *num_blocks = 0; *width = 0; return; }
+    *num_blocks = nb;
+    *width = (ncols + nb - 1) / nb;
 }
 
 int run_analysis(lapis_csr *A, hipStream_t stream)
 {
     const int64_t n = A->nrows;
-    LAPIS_HIP(hipMemsetAsync(A->d_bin_offset, 0, sizeof(int32_t) * (kNumBins + 1), stream));
-    int32_t *d_hist = nullptr;
-    int32_t *d_flags = nullptr;
-    if (int rc = device_alloc(&d_flags, 2 * sizeof(int32_t))) return rc;
-    hipError_t e = hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream);
-    if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "hipMemsetAsync"); }
+    const size_t esize = value_size(A);
+    DeviceTemp flags_mem;
+    if (int rc = flags_mem.alloc(2 * sizeof(int32_t))) return rc;
+    int32_t *d_flags = flags_mem.as<int32_t>();
+    LAPIS_HIP(hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream));
 
     // structural checks the kernels rely on: rowptr ends, monotone rowptr, column range
-    int32_t ends[2] = {0, (int32_t)A->nnz};
     if (n > 0) {
-        e = hipMemcpyAsync(&ends[0], A->rowptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(&ends[1], A->rowptr + n, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
-        if (e == hipSuccess) e = hipStreamSynchronize(stream);
-        if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "read rowptr ends"); }
-        if (ends[0] != 0 || ends[1] != A->nnz) {
-            (void)hipFree(d_flags);
+        int32_t ends[2] = {0, 0};
+        LAPIS_HIP(hipMemcpyAsync(&ends[0], A->rowptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipMemcpyAsync(&ends[1], A->rowptr + n, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (ends[0] != 0 || ends[1] != A->nnz)
             return fail(LAPIS_ERR_INVALID_ARG, "rowptr[0] must be 0 and rowptr[nrows] must equal nnz");
-        }
-    } else if (A->nnz != 0) {
-        (void)hipFree(d_flags);
-        return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
-    }
-
-    const int32_t num_blocks = (int32_t)((n + kRowsPerAnalysisBlock - 1) / kRowsPerAnalysisBlock);
-    const int32_t num_chunks = (int32_t)((n + LAPIS_STREAM_ROWS - 1) / LAPIS_STREAM_ROWS);
-    A->num_chunks = num_chunks;
-    // 16-byte loads need 16-byte aligned arrays; otherwise no chunk qualifies
-    const bool aligned = reinterpret_cast<uintptr_t>(A->colidx) % 16 == 0 &&
-                         reinterpret_cast<uintptr_t>(A->vals) % 16 == 0;
-    const int32_t min_nnz = aligned ? LAPIS_STREAM_MIN_NNZ : INT32_MAX;
-    int32_t *d_chunk_flag = nullptr;
-    int rc = LAPIS_OK;
-    int32_t num_stream = 0;
-    if (n > 0) {
         const int64_t work = (n > A->nnz ? n : A->nnz);
         int64_t vblocks = (work + kBlock - 1) / kBlock;
         if (vblocks > 8192) vblocks = 8192;
         validate_kernel<<<dim3((uint32_t)vblocks), dim3(kBlock), 0, stream>>>(
             n, A->ncols, A->nnz, A->rowptr, A->colidx, d_flags);
         int32_t flags[2] = {0, 0};
-        e = hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream);
-        if (e == hipSuccess) e = hipStreamSynchronize(stream);
-        if (e != hipSuccess) { (void)hipFree(d_flags); return fail_hip(e, "validate"); }
-        if (flags[0] || flags[1]) {
-            (void)hipFree(d_flags);
-            return fail(LAPIS_ERR_INVALID_ARG, flags[0] ? "rowptr is not non-decreasing"
-                                                        : "a column index is outside [0, ncols)");
-        }
-        rc = device_alloc(&d_hist, sizeof(int32_t) * (size_t)kNumBins * num_blocks);
-        if (!rc) rc = device_alloc(&d_chunk_flag, sizeof(int32_t) * (size_t)num_chunks);
-        if (!rc) rc = device_alloc(&A->d_stream_chunks, sizeof(int32_t) * (size_t)num_chunks);
-        if (rc) { (void)hipFree(d_flags); (void)hipFree(d_hist); (void)hipFree(d_chunk_flag); return rc; }
-        chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, d_chunk_flag);
-        chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(num_chunks, d_chunk_flag,
-                                                                   A->d_stream_chunks, d_flags);
-        bin_count_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, A->rowptr, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks, d_hist);
-        bin_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>((int64_t)kNumBins * num_blocks, num_blocks,
-                                                              d_hist, A->d_bin_offset);
-        bin_scatter_kernel<LAPIS_LONG_THRESHOLD><<<dim3(num_blocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, A->rowptr, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks, d_hist, A->d_row_perm);
-        e = hipMemcpyAsync(&num_stream, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
-    } else {
-        rc = device_alloc(&A->d_stream_chunks, 0);
-        if (rc) { (void)hipFree(d_flags); return rc; }
-    }
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(A->h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
-                           hipMemcpyDeviceToHost, stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(stream);
-    (void)hipFree(d_hist);
-    (void)hipFree(d_flags);
-    (void)hipFree(d_chunk_flag);
-    if (e != hipSuccess) return fail_hip(e, "row binning");
-    A->num_stream = num_stream;
-    A->num_binned = A->h_bin_offset[kNumBins];
-
-    // long rows: scan of their lengths, then the tile table
-    const int32_t m = A->h_bin_offset[kNumBins] - A->h_bin_offset[kNumBins - 1];
-    A->num_long = m;
-    if (int r2 = device_alloc(&A->d_long_off, sizeof(int32_t) * ((size_t)m + 1))) return r2;
-    int32_t long_total = 0;
-    if (m > 0) {
-        long_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
-            m, A->d_row_perm + A->h_bin_offset[kNumBins - 1], A->rowptr, A->d_long_off);
-        LAPIS_HIP(hipMemcpyAsync(&long_total, A->d_long_off + m, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
         LAPIS_HIP(hipStreamSynchronize(stream));
-    } else {
-        LAPIS_HIP(hipMemsetAsync(A->d_long_off, 0, sizeof(int32_t), stream));
+        if (flags[0]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr is not non-decreasing");
+        if (flags[1]) return fail(LAPIS_ERR_INVALID_ARG, "a column index is outside [0, ncols)");
+    } else if (A->nnz != 0) {
+        return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
     }
-    const int64_t T = ((int64_t)long_total + LAPIS_TILE_NNZ - 1) / LAPIS_TILE_NNZ;
-    A->num_tiles = T;
-    if (int r3 = device_alloc(&A->d_tile_row, sizeof(int32_t) * ((size_t)T + 1))) return r3;
-    if (int r4 = device_alloc(&A->d_tile_nz, sizeof(int32_t) * ((size_t)T + 1))) return r4;
-    const size_t esize = A->dtype == LAPIS_F64 ? sizeof(double) : sizeof(float);
-    if (int r5 = device_alloc(&A->d_partial, esize * 2 * (size_t)T)) return r5;
-    tile_search_kernel<LAPIS_TILE_NNZ><<<dim3((uint32_t)((T + 1 + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
-        m, T, A->d_long_off, A->d_tile_row, A->d_tile_nz);
-    LAPIS_HIP(hipGetLastError());
-    LAPIS_HIP(hipStreamSynchronize(stream));
-    build_short_plan(A);
+
+    // level 1: stream chunks (16-byte loads need 16-byte aligned arrays; otherwise no chunk qualifies)
+    const int32_t num_chunks = (int32_t)((n + LAPIS_STREAM_ROWS - 1) / LAPIS_STREAM_ROWS);
+    A->num_chunks = num_chunks;
+    const bool aligned = reinterpret_cast<uintptr_t>(A->colidx) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(A->vals) % 16 == 0;
+    const int32_t min_nnz = aligned ? LAPIS_STREAM_MIN_NNZ : INT32_MAX;
+    DeviceTemp chunk_flag;
+    if (int rc = chunk_flag.alloc(sizeof(int32_t) * (size_t)num_chunks)) return rc;
+    if (int rc = device_alloc(&A->d_stream_chunks, sizeof(int32_t) * (size_t)num_chunks)) return rc;
+    int32_t num_stream = 0;
+    if (n > 0) {
+        chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, chunk_flag.as<int32_t>());
+        chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(num_chunks, chunk_flag.as<int32_t>(),
+                                                                   A->d_stream_chunks, d_flags);
+        LAPIS_HIP(hipGetLastError());
+        LAPIS_HIP(hipMemcpyAsync(&num_stream, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+    }
+    A->num_stream = num_stream;
+
+    // level 2: bins over the remaining rows
+    A->rows.num_rows = n;
+    A->rows.row_begin = A->rowptr;
+    A->rows.row_end = A->rowptr + 1;
+    if (int rc = bin_row_set(&A->rows, chunk_flag.as<int32_t>(), esize, stream)) return rc;
+
+    // column split of the rows of the last two bins
+    int64_t nb = 0, W = 0;
+    split_geometry(A->ncols, esize, &nb, &W);
+    const int64_t S = A->rows.h_bin_offset[kNumBins] - A->rows.h_bin_offset[kNumBins - 2];
+    bool split = nb > 0 && S > 0 && (nb + 1) * S <= INT32_MAX;
+    const int32_t *split_rows = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
+    if (split) {
+        LAPIS_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), stream));
+        const uint32_t sblocks = (uint32_t)(S < 65536 ? S : 65536);
+        split_sorted_kernel<<<dim3(sblocks), dim3(kBlock), 0, stream>>>((int32_t)S, split_rows, A->rowptr,
+                                                                        A->colidx, d_flags);
+        int32_t unsorted = 0;
+        LAPIS_HIP(hipMemcpyAsync(&unsorted, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        split = !unsorted;
+    }
+    if (split) {
+        const int64_t cuts = (nb + 1) * S;
+        if (int rc = device_alloc(&A->d_cut, sizeof(int32_t) * (size_t)cuts)) return rc;
+        if (int rc = device_alloc(&A->d_vsum, esize * (size_t)(nb * S))) return rc;
+        split_cut_kernel<<<dim3((uint32_t)((cuts + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+            (int32_t)S, (int32_t)nb, W, split_rows, A->rowptr, A->colidx, A->d_cut);
+        LAPIS_HIP(hipGetLastError());
+        A->num_blocks = nb;
+        A->block_width = W;
+        A->num_split = S;
+        A->vrows.num_rows = nb * S;
+        A->vrows.row_begin = A->d_cut;
+        A->vrows.row_end = A->d_cut + S;
+        if (int rc = bin_row_set(&A->vrows, nullptr, esize, stream)) return rc;
+    }
+    build_short_plan(A->rows, split ? kNumBins - 3 : kShortBins - 1, &A->plan_rows);
+    if (split) build_short_plan(A->vrows, kShortBins - 1, &A->plan_vrows);
     return LAPIS_OK;
+}
+
+// Short-row and long-row kernels over one binned set; results go to out[row id of the set].
+template <typename T>
+void launch_binned(const lapis_csr *A, const BinnedSet &s, const ShortPlan &plan, bool with_long, const T *x,
+                   T *out, T a, T b, hipStream_t stream)
+{
+    const T *vals = static_cast<const T *>(A->vals);
+    if (plan.num_blocks > 0) {
+        spmv_short_kernel<T, true><<<dim3(plan.num_blocks), dim3(kBlock), 0, stream>>>(
+            plan, s.d_row_perm, s.row_begin, s.row_end, A->colidx, vals, x, out, a, b);
+    }
+    if (with_long && s.num_long > 0) {
+        const int32_t m = (int32_t)s.num_long;
+        const int32_t *long_rows = s.d_row_perm + s.h_bin_offset[kNumBins - 1];
+        T *partial = static_cast<T *>(s.d_partial);
+        spmv_long_tile_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)s.num_tiles), dim3(kBlock), 0, stream>>>(
+            m, long_rows, s.d_long_off, s.d_tile_row, s.d_tile_nz, s.row_begin, A->colidx, vals, x, partial);
+        spmv_long_fixup_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)((m + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(
+            m, long_rows, s.d_long_off, s.d_tile_row, partial, out, a, b);
+    }
 }
 
 template <typename T>
@@ -245,23 +353,19 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
         spmv_stream_kernel<T, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
             (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, A->colidx, vals, x, y, a, b);
     }
-    if (A->plan.num_blocks > 0) {
-        spmv_short_kernel<T, true><<<dim3(A->plan.padded_blocks), dim3(kBlock), 0, stream>>>(
-            A->plan, A->d_row_perm, A->rowptr, A->colidx, vals, x, y, a, b);
-    }
-    if (A->num_long > 0) {
-        const int32_t m = (int32_t)A->num_long;
-        const int32_t *long_rows = A->d_row_perm + A->h_bin_offset[kNumBins - 1];
-        T *partial = static_cast<T *>(A->d_partial);
-        spmv_long_tile_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)A->num_tiles), dim3(kBlock), 0, stream>>>(
-            m, long_rows, A->d_long_off, A->d_tile_row, A->d_tile_nz, A->rowptr, A->colidx, vals, x, partial);
-        spmv_long_fixup_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)((m + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(
-            m, long_rows, A->d_long_off, A->d_tile_row, partial, y, a, b);
+    const bool split = A->num_blocks > 0;
+    launch_binned<T>(A, A->rows, A->plan_rows, !split, x, y, a, b, stream);
+    if (split) {
+        // rows above 64 entries: their column-block pieces first, then one sum per row
+        T *vsum = static_cast<T *>(A->d_vsum);
+        launch_binned<T>(A, A->vrows, A->plan_vrows, true, x, vsum, T(1), T(0), stream);
+        const int32_t *split_rows = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
+        split_combine_kernel<T><<<dim3((uint32_t)((A->num_split + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+            (int32_t)A->num_split, (int32_t)A->num_blocks, split_rows, vsum, y, a, b);
     }
     LAPIS_HIP(hipGetLastError());
     return LAPIS_OK;
 }
-
 
 template <typename T, int G>
 void launch_vector(const lapis_csr *A, T a, const T *x, T b, T *y, hipStream_t stream)
@@ -297,8 +401,9 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
                 hipStream_t stream)
 {
     const T *vals = static_cast<const T *>(A->vals);
-    const int32_t n_rows_a = A->h_bin_offset[kNumBins - 2];          // bins 0..7: one slot per row
-    const int32_t n_rows_b = (int32_t)A->num_binned - n_rows_a;      // bins 8..9: one workgroup per row
+    const BinnedSet &s = A->rows;
+    const int32_t n_rows_a = s.h_bin_offset[kNumBins - 2];            // bins 0..7: one slot per row
+    const int32_t n_rows_b = (int32_t)s.num_binned - n_rows_a;        // bins 8..9: one workgroup per row
     constexpr int kSlots = kBlock / CL;
     if (A->num_stream > 0) {                                          // rows of the stream chunks
         const uint32_t chunks = (uint32_t)A->num_stream;
@@ -313,13 +418,12 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
     if (n_rows_a > 0) {
         const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);
         const uint32_t padded = (blocks + kXcds - 1) / kXcds * kXcds;
-        spmm_rows_kernel<T, VEC, CL, true, false><<<dim3(padded), dim3(kBlock), 0, stream>>>(
-            n_rows_a, blocks, padded, (int32_t)A->nrows, LAPIS_STREAM_ROWS, A->d_row_perm, A->rowptr, A->colidx,
-            vals, k, X, ldx, Y, ldy, a, b);
+        spmm_rows_kernel<T, VEC, CL, true><<<dim3(padded), dim3(kBlock), 0, stream>>>(
+            n_rows_a, blocks, padded, s.d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
     }
     if (n_rows_b > 0) {
         spmm_block_rows_kernel<T, VEC, CL><<<dim3((uint32_t)n_rows_b), dim3(kBlock), 0, stream>>>(
-            n_rows_a, A->d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
+            n_rows_a, s.d_row_perm, A->rowptr, A->colidx, vals, k, X, ldx, Y, ldy, a, b);
     }
     LAPIS_HIP(hipGetLastError());
     return LAPIS_OK;
@@ -352,6 +456,21 @@ int spmm_typed(const lapis_csr *A, int64_t k, double alpha, const void *d_X, int
     return spmm_pick_lanes<T, 1>(A, k, (T)alpha, X, ldx, (T)beta, Y, ldy, stream);
 }
 
+int copy_set(const BinnedSet &s, int32_t *h_bin_offset, int32_t *h_row_perm, int32_t *h_long_off,
+             int32_t *h_tile_row, int32_t *h_tile_nz)
+{
+    if (h_bin_offset) std::memcpy(h_bin_offset, s.h_bin_offset, sizeof(s.h_bin_offset));
+    if (h_row_perm && s.num_binned > 0)
+        LAPIS_HIP(hipMemcpy(h_row_perm, s.d_row_perm, sizeof(int32_t) * (size_t)s.num_binned, hipMemcpyDeviceToHost));
+    if (h_long_off)
+        LAPIS_HIP(hipMemcpy(h_long_off, s.d_long_off, sizeof(int32_t) * ((size_t)s.num_long + 1), hipMemcpyDeviceToHost));
+    if (h_tile_row)
+        LAPIS_HIP(hipMemcpy(h_tile_row, s.d_tile_row, sizeof(int32_t) * ((size_t)s.num_tiles + 1), hipMemcpyDeviceToHost));
+    if (h_tile_nz)
+        LAPIS_HIP(hipMemcpy(h_tile_nz, s.d_tile_nz, sizeof(int32_t) * ((size_t)s.num_tiles + 1), hipMemcpyDeviceToHost));
+    return LAPIS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -371,12 +490,9 @@ int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nn
 
     lapis_csr *A = new (std::nothrow) lapis_csr();
     if (!A) return fail(LAPIS_ERR_ALLOC, "host allocation failed");
-    std::memset(static_cast<void *>(A), 0, sizeof(*A));
     A->nrows = nrows; A->ncols = ncols; A->nnz = nnz; A->dtype = dtype;
     A->rowptr = d_rowptr; A->colidx = d_colidx; A->vals = d_vals;
-    int rc = device_alloc(&A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1));
-    if (!rc) rc = device_alloc(&A->d_row_perm, sizeof(int32_t) * (size_t)nrows);
-    if (!rc) rc = run_analysis(A, static_cast<hipStream_t>(hip_stream));
+    const int rc = run_analysis(A, static_cast<hipStream_t>(hip_stream));
     if (rc) { free_handle(A); return rc; }
     *out = A;
     return LAPIS_OK;
@@ -439,9 +555,9 @@ int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t
 {
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
     if (num_stream) *num_stream = A->num_stream;
-    if (num_binned) *num_binned = A->num_binned;
-    if (num_long) *num_long = A->num_long;
-    if (num_tiles) *num_tiles = A->num_tiles;
+    if (num_binned) *num_binned = A->rows.num_binned;
+    if (num_long) *num_long = A->rows.num_long;
+    if (num_tiles) *num_tiles = A->rows.num_tiles;
     return LAPIS_OK;
 }
 
@@ -453,20 +569,35 @@ int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int
     LAPIS_HIP(hipDeviceSynchronize());
     if (h_stream_chunks && A->num_stream > 0)
         LAPIS_HIP(hipMemcpy(h_stream_chunks, A->d_stream_chunks, sizeof(int32_t) * (size_t)A->num_stream, hipMemcpyDeviceToHost));
-    if (h_bin_offset)
-        LAPIS_HIP(hipMemcpy(h_bin_offset, A->d_bin_offset, sizeof(int32_t) * (kNumBins + 1), hipMemcpyDeviceToHost));
-    if (h_row_perm && A->num_binned > 0)
-        LAPIS_HIP(hipMemcpy(h_row_perm, A->d_row_perm, sizeof(int32_t) * (size_t)A->num_binned, hipMemcpyDeviceToHost));
-    if (h_long_off)
-        LAPIS_HIP(hipMemcpy(h_long_off, A->d_long_off, sizeof(int32_t) * ((size_t)A->num_long + 1), hipMemcpyDeviceToHost));
-    if (h_tile_row)
-        LAPIS_HIP(hipMemcpy(h_tile_row, A->d_tile_row, sizeof(int32_t) * ((size_t)A->num_tiles + 1), hipMemcpyDeviceToHost));
-    if (h_tile_nz)
-        LAPIS_HIP(hipMemcpy(h_tile_nz, A->d_tile_nz, sizeof(int32_t) * ((size_t)A->num_tiles + 1), hipMemcpyDeviceToHost));
+    return copy_set(A->rows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);
+}
+
+int lapis_csr_split_sizes(const lapis_csr_t *A, int64_t *num_blocks, int64_t *block_width,
+                          int64_t *num_split_rows, int64_t *num_binned, int64_t *num_long,
+                          int64_t *num_tiles)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (num_blocks) *num_blocks = A->num_blocks;
+    if (block_width) *block_width = A->block_width;
+    if (num_split_rows) *num_split_rows = A->num_split;
+    if (num_binned) *num_binned = A->vrows.num_binned;
+    if (num_long) *num_long = A->vrows.num_long;
+    if (num_tiles) *num_tiles = A->vrows.num_tiles;
     return LAPIS_OK;
 }
 
-int lapis_partition_constants(int64_t h_out[6])
+int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_offset, int32_t *h_row_perm,
+                         int32_t *h_long_off, int32_t *h_tile_row, int32_t *h_tile_nz)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->num_blocks == 0) return fail(LAPIS_ERR_INVALID_ARG, "this matrix has no column split");
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_cut)
+        LAPIS_HIP(hipMemcpy(h_cut, A->d_cut, sizeof(int32_t) * (size_t)((A->num_blocks + 1) * A->num_split), hipMemcpyDeviceToHost));
+    return copy_set(A->vrows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);
+}
+
+int lapis_partition_constants(int64_t h_out[8])
 {
     if (!h_out) return fail(LAPIS_ERR_INVALID_ARG, "h_out is NULL");
     h_out[0] = LAPIS_NUM_BINS;
@@ -475,6 +606,8 @@ int lapis_partition_constants(int64_t h_out[6])
     h_out[3] = LAPIS_TILE_NNZ;
     h_out[4] = LAPIS_STREAM_ROWS;
     h_out[5] = LAPIS_STREAM_MIN_NNZ;
+    h_out[6] = LAPIS_SPLIT_BLOCK_BYTES;
+    h_out[7] = LAPIS_SPLIT_MAX_BLOCKS;
     return LAPIS_OK;
 }
 

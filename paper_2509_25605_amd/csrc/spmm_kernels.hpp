@@ -142,14 +142,11 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     }
 }
 
-// One slot per row.  FROM_CHUNKS == false: the rows are positions [0, count) of
-// row_list (a bin list).  FROM_CHUNKS == true: the rows are those of the stream
-// chunks, chunk_rows rows each; row_list holds the chunk ids (nullptr = every
-// chunk of the matrix) and count = number of chunks * chunk_rows.
-template <typename T, int VEC, int CL, bool XCD_REMAP, bool FROM_CHUNKS>
+// positions [0, count) of row_perm, one slot per row.
+template <typename T, int VEC, int CL, bool XCD_REMAP>
 __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(
-    int32_t count, uint32_t num_blocks, uint32_t padded_blocks, int32_t nrows, int32_t chunk_rows,
-    const int32_t *__restrict__ row_list, const int32_t *__restrict__ rowptr,
+    int32_t count, uint32_t num_blocks, uint32_t padded_blocks,
+    const int32_t *__restrict__ row_perm, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k,
     const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
 {
@@ -163,15 +160,7 @@ __global__ __launch_bounds__(kBlock) void spmm_rows_kernel(
     const int l = threadIdx.x % CL;
     const int64_t idx = (int64_t)id * kSlots + slot;
     if (idx >= count) return;  // whole slots leave together; the rest of the wave carries on
-    int32_t row;
-    if constexpr (FROM_CHUNKS) {
-        const int64_t c = idx / chunk_rows;
-        const int64_t r = (row_list ? (int64_t)row_list[c] : c) * chunk_rows + idx % chunk_rows;
-        if (r >= nrows) return;  // ragged last chunk
-        row = (int32_t)r;
-    } else {
-        row = row_list[idx];
-    }
+    const int32_t row = row_perm[idx];
     const int64_t jb = rowptr[row], je = rowptr[row + 1];
     T *__restrict__ yrow = Y + (int64_t)row * ldy;
 

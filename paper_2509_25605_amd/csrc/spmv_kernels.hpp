@@ -40,12 +40,14 @@ __host__ __device__ constexpr int short_rows_per_block(int bin)
     return (kBlock / short_group_size(bin)) * short_rows_per_group(bin);
 }
 
+// Workgroups of bin b occupy hardware ids [block_begin[b], block_begin[b+1]); every bin's count
+// is padded to a multiple of the XCD count, so inside a bin hardware id h runs on XCD h % 8 and
+// xcd_contiguous_id gives each XCD one contiguous stretch of the bin's row list.
 struct ShortPlan {
     int32_t bin_begin[kShortBins];        // first position of bin b in row_perm
     int32_t bin_count[kShortBins];        // rows in bin b
-    uint32_t block_begin[kShortBins + 1]; // logical workgroups of bin b: [block_begin[b], block_begin[b+1])
-    uint32_t num_blocks;                  // block_begin[kShortBins]
-    uint32_t padded_blocks;               // num_blocks rounded up to a multiple of the XCD count
+    uint32_t block_begin[kShortBins + 1]; // padded workgroup ranges per bin
+    uint32_t num_blocks;                  // block_begin[kShortBins] = grid size
 };
 
 template <typename T>
@@ -58,7 +60,8 @@ __device__ __forceinline__ void store_result(T *__restrict__ y, int32_t row, T s
 template <typename T, int G, int U>
 __device__ __forceinline__ void short_rows(uint32_t local_block, int32_t begin, int32_t count,
                                            const int32_t *__restrict__ row_perm,
-                                           const int32_t *__restrict__ rowptr,
+                                           const int32_t *__restrict__ row_begin,
+                                           const int32_t *__restrict__ row_end,
                                            const int32_t *__restrict__ colidx,
                                            const T *__restrict__ vals, const T *__restrict__ x,
                                            T *__restrict__ y, T alpha, T beta)
@@ -77,8 +80,8 @@ __device__ __forceinline__ void short_rows(uint32_t local_block, int32_t begin, 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        jb[u] = (row[u] >= 0) ? rowptr[row[u]] : 0;
-        je[u] = (row[u] >= 0) ? rowptr[row[u] + 1] : 0;
+        jb[u] = (row[u] >= 0) ? row_begin[row[u]] : 0;
+        je[u] = (row[u] >= 0) ? row_end[row[u]] : 0;
     }
     int32_t c[U];
     T v[U];
@@ -103,7 +106,8 @@ __device__ __forceinline__ void short_rows(uint32_t local_block, int32_t begin, 
 template <typename T>
 __device__ __forceinline__ void wave_rows(uint32_t local_block, int32_t begin, int32_t count,
                                           const int32_t *__restrict__ row_perm,
-                                          const int32_t *__restrict__ rowptr,
+                                          const int32_t *__restrict__ row_begin,
+                                          const int32_t *__restrict__ row_end,
                                           const int32_t *__restrict__ colidx,
                                           const T *__restrict__ vals, const T *__restrict__ x,
                                           T *__restrict__ y, T alpha, T beta)
@@ -112,8 +116,8 @@ __device__ __forceinline__ void wave_rows(uint32_t local_block, int32_t begin, i
     const int lane = threadIdx.x % kWave;
     const int64_t idx = (int64_t)local_block * kWavesPerBlock + wave;
     const int32_t row = (idx < count) ? row_perm[begin + idx] : -1;
-    const int64_t jb = (row >= 0) ? rowptr[row] : 0;
-    const int64_t je = (row >= 0) ? rowptr[row + 1] : 0;
+    const int64_t jb = (row >= 0) ? row_begin[row] : 0;
+    const int64_t je = (row >= 0) ? row_end[row] : 0;
     T s0 = T(0), s1 = T(0), s2 = T(0), s3 = T(0);
     int64_t j = jb + lane;
     for (; j + 3 * kWave < je; j += 4 * kWave) {
@@ -131,22 +135,26 @@ __device__ __forceinline__ void wave_rows(uint32_t local_block, int32_t begin, i
     if (lane == kWave - 1 && row >= 0) store_result(y, row, s, alpha, beta);
 }
 
+// row_begin[i] / row_end[i] delimit row i's entries: (rowptr, rowptr + 1) for the rows of the
+// matrix, the cut table for virtual rows.
 template <typename T, bool XCD_REMAP>
 __global__ __launch_bounds__(kBlock) void spmv_short_kernel(
-    ShortPlan plan, const int32_t *__restrict__ row_perm, const int32_t *__restrict__ rowptr,
-    const int32_t *__restrict__ colidx, const T *__restrict__ vals, const T *__restrict__ x,
-    T *__restrict__ y, T alpha, T beta)
+    ShortPlan plan, const int32_t *__restrict__ row_perm, const int32_t *__restrict__ row_begin,
+    const int32_t *__restrict__ row_end, const int32_t *__restrict__ colidx,
+    const T *__restrict__ vals, const T *__restrict__ x, T *__restrict__ y, T alpha, T beta)
 {
-    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, plan.padded_blocks) : blockIdx.x;
-    if (id >= plan.num_blocks) return;
+    const uint32_t hw = blockIdx.x;
     int bin = 0;
-    while (id >= plan.block_begin[bin + 1]) ++bin;  // uniform over the workgroup
-    const uint32_t local = id - plan.block_begin[bin];
+    while (hw >= plan.block_begin[bin + 1]) ++bin;  // uniform over the workgroup
+    const uint32_t in_bin = hw - plan.block_begin[bin];
+    const uint32_t padded = plan.block_begin[bin + 1] - plan.block_begin[bin];
+    const uint32_t local = XCD_REMAP ? xcd_contiguous_id(in_bin, padded) : in_bin;
     const int32_t begin = plan.bin_begin[bin], count = plan.bin_count[bin];
+    // workgroups past the bin's last row (padding) find idx >= count everywhere and do nothing
 #define LAPIS_SHORT_CASE(B)                                                                     \
     case B:                                                                                     \
         short_rows<T, short_group_size(B), short_rows_per_group(B)>(local, begin, count,        \
-            row_perm, rowptr, colidx, vals, x, y, alpha, beta);                                 \
+            row_perm, row_begin, row_end, colidx, vals, x, y, alpha, beta);                     \
         break;
     switch (bin) {
     case 0: {  // rows without entries: y = beta*y
@@ -162,7 +170,7 @@ __global__ __launch_bounds__(kBlock) void spmv_short_kernel(
         LAPIS_SHORT_CASE(6)
         LAPIS_SHORT_CASE(7)
     default:
-        wave_rows<T>(local, begin, count, row_perm, rowptr, colidx, vals, x, y, alpha, beta);
+        wave_rows<T>(local, begin, count, row_perm, row_begin, row_end, colidx, vals, x, y, alpha, beta);
         break;
     }
 #undef LAPIS_SHORT_CASE
@@ -344,7 +352,7 @@ template <typename T, int TILE>
 __global__ __launch_bounds__(kBlock) void spmv_long_tile_kernel(
     int32_t num_long, const int32_t *__restrict__ long_rows, const int32_t *__restrict__ long_off,
     const int32_t *__restrict__ tile_row, const int32_t *__restrict__ tile_nz,
-    const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    const int32_t *__restrict__ row_begin, const int32_t *__restrict__ colidx,
     const T *__restrict__ vals, const T *__restrict__ x, T *__restrict__ partial)
 {
     constexpr int kPerThread = TILE / kBlock;
@@ -359,8 +367,8 @@ __global__ __launch_bounds__(kBlock) void spmv_long_tile_kernel(
     const int64_t tile_len = (total - tile_begin < TILE) ? (total - tile_begin) : TILE;
     const int64_t len_a_row = long_off[ra + 1] - long_off[ra];
     const int64_t len_a = (len_a_row - za < tile_len) ? (len_a_row - za) : tile_len;
-    const int64_t ja = (int64_t)rowptr[long_rows[ra]] + za;           // first entry of segment A
-    const int64_t jb = (len_a < tile_len) ? (int64_t)rowptr[long_rows[ra + 1]] : 0;  // segment B
+    const int64_t ja = (int64_t)row_begin[long_rows[ra]] + za;        // first entry of segment A
+    const int64_t jb = (len_a < tile_len) ? (int64_t)row_begin[long_rows[ra + 1]] : 0;  // segment B
 
     int32_t c[kPerThread];
     T v[kPerThread];

@@ -50,6 +50,9 @@ class CsrMatrix:
     def partition(self):
         return B.lapis_csr_copy_partition(self.handle)
 
+    def split(self):
+        return B.lapis_csr_copy_split(self.handle)
+
     def close(self):
         if self.handle is not None:
             B.lapis_csr_destroy(self.handle)

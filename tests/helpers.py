@@ -85,5 +85,8 @@ class DeviceCsr:
     def partition(self):
         return self.mat.partition()
 
+    def split(self):
+        return self.mat.split()
+
     def close(self):
         self.mat.close()

@@ -41,7 +41,10 @@ def test_header_constants_match_library_and_oracle(lib):
     macro = lambda n: int(re.search(rf"#define\s+{n}\s+(\d+)", text).group(1))
     assert c == {"num_bins": macro("LAPIS_NUM_BINS"), "wave": macro("LAPIS_WAVE"),
                  "long_threshold": macro("LAPIS_LONG_THRESHOLD"), "tile_nnz": macro("LAPIS_TILE_NNZ"),
-                 "stream_rows": macro("LAPIS_STREAM_ROWS"), "stream_min_nnz": macro("LAPIS_STREAM_MIN_NNZ")}
+                 "stream_rows": macro("LAPIS_STREAM_ROWS"), "stream_min_nnz": macro("LAPIS_STREAM_MIN_NNZ"),
+                 "split_block_bytes": macro("LAPIS_SPLIT_BLOCK_BYTES"),
+                 "split_max_blocks": macro("LAPIS_SPLIT_MAX_BLOCKS")}
+    assert (c["split_block_bytes"], c["split_max_blocks"]) == (oracle.SPLIT_BLOCK_BYTES, oracle.SPLIT_MAX_BLOCKS)
     assert (c["num_bins"], c["wave"], c["long_threshold"], c["tile_nnz"], c["stream_rows"],
             c["stream_min_nnz"]) == (oracle.NUM_BINS, oracle.WAVE, oracle.LONG_THRESHOLD, oracle.TILE_NNZ,
                                      oracle.STREAM_ROWS, oracle.STREAM_MIN_NNZ)
@@ -82,6 +85,8 @@ def test_null_handles_and_out_pointer(lib):
     assert lib.lapis_spmm(None, 4, 1.0, 8, 4, 0.0, 8, 4, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_partition_sizes(None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_copy_partition(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_split_sizes(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_copy_split(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_partition_constants(None) == L.LAPIS_ERR_INVALID_ARG
     with pytest.raises(L.LapisError) as e:
         L.lapis_spmv(None, 1.0, 8, 0.0, 8, stream=0)

@@ -26,6 +26,19 @@ def check_partition(dev, rowptr):
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
 
 
+def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):
+    ref = oracle.split_partition(rowptr, colidx, ncols, itemsize)
+    got = dev.split()
+    if expect_on is not None:
+        assert (ref["num_blocks"] > 0) == expect_on
+    for key in ("num_blocks", "block_width", "num_split_rows"):
+        assert got[key] == ref[key], f"split field {key} differs"
+    if ref["num_blocks"]:
+        for key in ("cut", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+            assert got[key].dtype == np.int32
+            assert np.array_equal(got[key], ref[key]), f"split field {key} differs"
+
+
 def check_spmv(dev, rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None, literal=False, what="",
                paper_shape=False):
     ref, absAx = oracle.spmv(rowptr, colidx, vals, x, alpha, beta, y0)
@@ -233,6 +246,39 @@ def test_unaligned_arrays_fall_back_to_bins():
         A.close()
         assert_close(y.cpu().numpy(), ref, literal_bound(np.diff(w.rowptr), absAx, np.float64))
 
+
+# ---------------------------------------------------------------------------
+# column split: wide matrices whose x exceeds the split block size
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("srt", [True, False])
+def test_spmv_column_split(dtype, srt):
+    say(f"column split sorted={srt} {np.dtype(dtype).name}")
+    n, ncols = 3000, 3 * (1 << 19) + 12345          # 12.6 MB (f64) / 6.3 MB (f32) of x
+    L = mixed_lengths(n, 71, 40000)
+    L[3::17] = 65 + (np.arange(L[3::17].size) * 61) % 4000   # plenty of rows in bin 8
+    L = np.minimum(L, ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 555, dtype, sorted_cols=srt)
+    x = gen.uniform(12, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(12, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        check_split(dev, rowptr, colidx, ncols, np.dtype(dtype).itemsize, expect_on=srt)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, -1.5, 0.25, y0, what="alpha=-1.5 beta=0.25")
+        a = dev.spmv(x, 2.0, 0.0)
+        assert np.array_equal(a, dev.spmv(x, 2.0, 0.0)), "two runs differ"
+        X = gen.uniform(13, gen.STREAM_X, ncols * 4).astype(dtype).reshape(ncols, 4)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=4")
+    finally:
+        dev.close()
+
+
+def test_workload4_wide_reduced():
+    """Power-law rows over 2^21 columns: x = 8 MB of floats, so the column split is on."""
+    run_workload(4, {"n": 1 << 21, "cap": 200000})
+
 # ---------------------------------------------------------------------------
 # SpMM
 # ---------------------------------------------------------------------------
@@ -277,6 +323,7 @@ def run_workload(cfg, scale):
     dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
     try:
         check_partition(dev, w.rowptr)
+        check_split(dev, w.rowptr, w.colidx, w.ncols, w.vals.itemsize)
         if w.k == 0:
             check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
             check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True,
