@@ -48,6 +48,19 @@ __device__ __forceinline__ T group_sum(T v)
     return v;
 }
 
+// Maximum of a non-negative int over the wavefront, returned as a wave-uniform value.
+// Every lane must be active.
+__device__ __forceinline__ int wave_max_nonneg(int v)
+{
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));   // rows 1, 3 <- lane 15 of rows 0, 2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));   // rows 2, 3 <- lane 31
+    return __builtin_amdgcn_readlane(v, kWave - 1);
+}
+
 // Streaming load: data read once per product (values, column indices) is
 // fetched with the non-temporal hint so it does not evict x from the caches.
 template <typename T>

@@ -188,43 +188,59 @@ template <> struct StreamVec<float> { typedef float type __attribute__((ext_vect
 typedef int32_t int4v __attribute__((ext_vector_type(4)));
 
 // Copy the first n_vec (a multiple of 4, <= kStreamWindow) entries of the window to LDS with
-// N 16-byte column loads per lane and the matching value loads.  Lanes past the end repeat the
+// NC 16-byte column loads and NV 16-byte value loads per lane.  Lanes past the end repeat the
 // last group: same address, same data, no extra memory traffic and no divergent control flow.
-template <typename T, int N>
+template <typename T, int NC, int NV>
 __device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, const T *__restrict__ vw,
                                             int lane, int n_vec, int32_t *s_col, T *s_val)
 {
     typedef typename StreamVec<T>::type vec_t;
     constexpr int kPerVec = 16 / sizeof(T);          // values per 16-byte load
-    constexpr int kValLoads = N * (4 / kPerVec);     // value loads covering N*256 entries
     const int last_c = n_vec - 4;
     const int last_v = n_vec - kPerVec;
-    int4v cq[N];
-    vec_t vq[kValLoads];
+    int4v cq[NC];
+    vec_t vq[NV];
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
+    for (int i = 0; i < NC; ++i) {
         int idx = i * (kWave * 4) + lane * 4;
         idx = idx < last_c ? idx : last_c;
         cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cw + idx));
     }
 #pragma unroll
-    for (int i = 0; i < kValLoads; ++i) {
+    for (int i = 0; i < NV; ++i) {
         int idx = i * (kWave * kPerVec) + lane * kPerVec;
         idx = idx < last_v ? idx : last_v;
         vq[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(vw + idx));
     }
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
+    for (int i = 0; i < NC; ++i) {
         int idx = i * (kWave * 4) + lane * 4;
         idx = idx < last_c ? idx : last_c;
         *reinterpret_cast<int4v *>(s_col + idx) = cq[i];
     }
 #pragma unroll
-    for (int i = 0; i < kValLoads; ++i) {
+    for (int i = 0; i < NV; ++i) {
         int idx = i * (kWave * kPerVec) + lane * kPerVec;
         idx = idx < last_v ? idx : last_v;
         *reinterpret_cast<vec_t *>(s_val + idx) = vq[i];
     }
+}
+
+// NC column loads cover NC*256 entries; the value loads needed for n_vec entries are either
+// NC*R or NC*R - 1 (R = value loads per 256 entries: 2 for double, 1 for float).
+template <typename T, int NC>
+__device__ __forceinline__ void stream_fill_pick(const int32_t *__restrict__ cw, const T *__restrict__ vw,
+                                                 int lane, int n_vec, int32_t *s_col, T *s_val)
+{
+    constexpr int kPerLoad = kWave * (16 / (int)sizeof(T));   // entries per value load instruction
+    constexpr int kFull = NC * (kWave * 4) / kPerLoad;
+    if constexpr (kFull > 1 && kPerLoad < kWave * 4) {
+        if (n_vec <= (kFull - 1) * kPerLoad) {
+            stream_fill<T, NC, kFull - 1>(cw, vw, lane, n_vec, s_col, s_val);
+            return;
+        }
+    }
+    stream_fill<T, NC, kFull>(cw, vw, lane, n_vec, s_col, s_val);
 }
 
 // Stage entries [w0, w1) of the matrix (w0 a multiple of 4, w1 - w0 <= kStreamWindow) in LDS:
@@ -239,10 +255,10 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
     const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
     const int32_t *__restrict__ cw = colidx + w0;
     const T *__restrict__ vw = vals + w0;
-    if (n_vec > 3 * kWave * 4) stream_fill<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 2 * kWave * 4) stream_fill<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > kWave * 4) stream_fill<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 0) stream_fill<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
+    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > kWave * 4) stream_fill_pick<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 0) stream_fill_pick<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
     if (w0 + n_vec < w1) {                              // the matrix's last nnz % 4 entries
         const int32_t j = w0 + n_vec + lane;
         if (j < w1) { s_col[j - w0] = colidx[j]; s_val[j - w0] = vals[j]; }
@@ -252,12 +268,34 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// B entries of this lane's share of a row: (column, value) pairs out of LDS, the B gathers of x
+// issued back to back, then the FMAs.  Lanes with fewer than u0 + B entries repeat their last
+// entry and discard the product (no divergent control flow).
+template <typename T, int B, int G>
+__device__ __forceinline__ T stream_batch(const int32_t *sc, const T *sv, int u0, int my_n, int last_u,
+                                          const T *__restrict__ x, T s)
+{
+    int32_t cc[B];
+    T vv[B], xx[B];
+#pragma unroll
+    for (int t = 0; t < B; ++t) {
+        const int u = (u0 + t < last_u ? u0 + t : last_u) * G;
+        cc[t] = sc[u];
+        vv[t] = sv[u];
+    }
+#pragma unroll
+    for (int t = 0; t < B; ++t) xx[t] = x[cc[t]];
+#pragma unroll
+    for (int t = 0; t < B; ++t) s += (u0 + t < my_n) ? vv[t] * xx[t] : T(0);
+    return s;
+}
+
 // One wavefront (= one workgroup) per stream chunk.  stream_chunks == nullptr
 // means every chunk of the matrix is a stream chunk (chunk id = wave id).
 // colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a
 // multiple of 4: 16-byte loads never reach past it, the last nnz % 4 entries of
 // the matrix are fetched one by one.
-template <typename T, bool XCD_REMAP>
+template <typename T, bool XCD_REMAP, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
@@ -265,6 +303,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     T *__restrict__ y, T alpha, T beta)
 {
     constexpr int G = kStreamGroup;
+    static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
 
@@ -296,20 +335,22 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
         const int last_u = my_n > 0 ? my_n - 1 : 0;
         const int32_t *sc = s_col + first;
         const T *sv = s_val + first;
+        // batches of UNR entries per lane; the last batch is cut to the longest share in the
+        // wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane, not 16
+        int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
+        int u0 = 0;
 #pragma unroll 1
-        for (int u0 = 0; __builtin_amdgcn_ballot_w64(u0 < my_n) != 0; u0 += kStreamUnroll) {
-            int32_t cc[kStreamUnroll];
-            T vv[kStreamUnroll], xx[kStreamUnroll];
-#pragma unroll
-            for (int t = 0; t < kStreamUnroll; ++t) {
-                const int u = (u0 + t < last_u ? u0 + t : last_u) * G;  // past the end: repeat the last
-                cc[t] = sc[u];
-                vv[t] = sv[u];
-            }
-#pragma unroll
-            for (int t = 0; t < kStreamUnroll; ++t) xx[t] = x[cc[t]];
-#pragma unroll
-            for (int t = 0; t < kStreamUnroll; ++t) s += (u0 + t < my_n) ? vv[t] * xx[t] : T(0);
+        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch<T, UNR, G>(sc, sv, u0, my_n, last_u, x, s);
+        switch ((rem + 1) / 2) {
+        case 0: break;
+        case 1: s = stream_batch<T, 2, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 2: s = stream_batch<T, 4, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 3: s = stream_batch<T, 6, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 4: s = stream_batch<T, 8, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 5: s = stream_batch<T, 10, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 6: s = stream_batch<T, 12, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 7: s = stream_batch<T, 14, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        default: s = stream_batch<T, UNR, G>(sc, sv, u0, my_n, last_u, x, s); break;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
