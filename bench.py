@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload)")
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload); 6..9 = stand-ins for the paper's Table 3")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--variant", choices=["tuned", "paper-shape"], default="tuned",

@@ -62,6 +62,12 @@ def _load():
         lib.lapis_gen_rowptr_from_lengths.argtypes = [i64, p, p]
         lib.lapis_gen_stratified_cols.restype = i32
         lib.lapis_gen_stratified_cols.argtypes = [i64, i64, p, u64, p]
+        lib.lapis_gen_block_stencil_rowptr.restype = i64
+        lib.lapis_gen_block_stencil_rowptr.argtypes = [i64, i64, i64, i64, p]
+        lib.lapis_gen_block_stencil_fill.argtypes = [i64, i64, i64, i64, u64, p, p, p]
+        lib.lapis_gen_gamma_lengths.argtypes = [i64, f64, i64, u64, p]
+        lib.lapis_gen_banded_cols.restype = i32
+        lib.lapis_gen_banded_cols.argtypes = [i64, i64, p, i64, u64, p]
         _lib = lib
     return _lib
 
@@ -159,6 +165,61 @@ def rows_from_lengths(length: np.ndarray, ncols: int, seed: int):
     return rowptr, colidx
 
 
+def block_stencil(nx: int, ny: int, nz: int, dof: int, seed: int):
+    """27-point stencil with dof unknowns per grid point; returns (rowptr, colidx, vals)."""
+    n = nx * ny * nz * dof
+    rowptr = np.empty(n + 1, dtype=np.int32)
+    nnz = _load().lapis_gen_block_stencil_rowptr(nx, ny, nz, dof, _ptr(rowptr))
+    colidx = np.empty(nnz, dtype=np.int32)
+    vals = np.empty(nnz, dtype=np.float64)
+    _load().lapis_gen_block_stencil_fill(nx, ny, nz, dof, seed, _ptr(rowptr), _ptr(colidx), _ptr(vals))
+    return rowptr, colidx, vals
+
+
+def banded_rows(nrows: int, mean: float, max_len: int, seed: int, band_factor: int = 40):
+    """Row lengths with the given mean (approximately) and maximum (exactly), columns in a band
+    around the diagonal, sorted and distinct; returns (rowptr, colidx)."""
+    length = np.empty(nrows, dtype=np.int32)
+    _load().lapis_gen_gamma_lengths(nrows, mean, max_len, seed, _ptr(length))
+    rowptr = np.empty(nrows + 1, dtype=np.int32)
+    nnz = _load().lapis_gen_rowptr_from_lengths(nrows, _ptr(length), _ptr(rowptr))
+    if nnz < 0:
+        raise ValueError("banded_rows: nnz exceeds int32")
+    colidx = np.empty(nnz, dtype=np.int32)
+    if _load().lapis_gen_banded_cols(nrows, nrows, _ptr(rowptr), band_factor, seed, _ptr(colidx)):
+        raise ValueError("banded_rows: a row is longer than the matrix is wide")
+    return rowptr, colidx
+
+
+# Shapes of the four matrices of the paper's Table 3 (rows, mean and maximum entries per row).
+# The matrices themselves are not available offline; these are synthetic stand-ins of the same shape.
+TABLE3_SHAPES = {
+    "StocF-1465": (1465137, 14.34, 189),
+    "PFlow_742": (742793, 50.0, 137),
+    "Elasticity3D_60": (648000, 78.33, 81),
+    "audikw_1": (943695, 82.28, 345),
+}
+
+
+def table3_standin(name: str, scale: float = 1.0) -> "Workload":
+    """Synthetic f64 matrix with the row count, mean and maximum row length of a Table 3 matrix.
+    Elasticity3D_60 is a 60^3 grid with 3 unknowns per point and a 27-point block stencil (the
+    construction the paper describes for it); the others get gamma-distributed row lengths and
+    banded columns.  `scale` < 1 shrinks the row count (and the grid) for tests."""
+    rows, mean, mx = TABLE3_SHAPES[name]
+    seed = BASE_SEED + 100 + sorted(TABLE3_SHAPES).index(name)
+    if name == "Elasticity3D_60":
+        g = max(2, int(round(60 * scale ** (1.0 / 3.0))))
+        rowptr, colidx, vals = block_stencil(g, g, g, 3, seed)
+    else:
+        n = max(mx + 1, int(rows * scale))
+        rowptr, colidx = banded_rows(n, mean, mx, seed)
+        vals = uniform(seed, STREAM_VALUES, int(rowptr[-1]))
+    n = rowptr.size - 1
+    return Workload(f"table3_{name}_n{n}_f64", n, n, rowptr, colidx, vals,
+                    uniform(seed, STREAM_X, n), 1.0, 0.0, meta={"stands_in_for": name})
+
+
 # --------------------------------------------------------------------------
 # the five workloads
 # --------------------------------------------------------------------------
@@ -194,6 +255,7 @@ def workload(cfg: int, scale: Optional[dict] = None) -> Workload:
       cfg 2, 5: nx, ny, nz   (default 128^3); cfg 5 also k (default 16)
       cfg 3: n, per_row      (default 2^22, 16)
       cfg 4: n, s, cap       (default 2^23, 1.8, 200000)
+      cfg 6..9: scale        (default 1.0; stand-ins for the four matrices of the paper's Table 3)
     """
     sc = dict(scale or {})
     seed = BASE_SEED + cfg
@@ -229,6 +291,9 @@ def workload(cfg: int, scale: Optional[dict] = None) -> Workload:
         return Workload(f"zipf{s}_cap{cap}_n{n}_f32", n, n, rowptr, colidx, vals,
                         uniform(seed, STREAM_X, n, dtype=np.float32), 1.0, 0.0,
                         meta={"s": s, "cap": cap})
+    if cfg in (6, 7, 8, 9):   # stand-ins for the paper's Table 3, in the table's order
+        name = ["StocF-1465", "PFlow_742", "Elasticity3D_60", "audikw_1"][cfg - 6]
+        return table3_standin(name, sc.get("scale", 1.0))
     raise ValueError(f"unknown workload {cfg}")
 
 

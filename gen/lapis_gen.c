@@ -268,3 +268,107 @@ int lapis_gen_stratified_cols(int64_t nrows, int64_t ncols, const int32_t *rowpt
     }
     return bad ? -1 : 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Block stencil: 27-point stencil on an nx*ny*nz grid with `dof` unknowns per
+ * grid point, every pair of unknowns of neighbouring points coupled (3-D
+ * elasticity on a regular grid has this shape: 81 entries per interior row for
+ * dof = 3).  Row = node*dof + d, node = (z*ny + y)*nx + x; columns ascending.
+ * One draw per stored entry (stream 1, index = CSR position): diagonal
+ * 27*dof + u, others -1 + u.
+ * ---------------------------------------------------------------------- */
+int64_t lapis_gen_block_stencil_rowptr(int64_t nx, int64_t ny, int64_t nz, int64_t dof, int32_t *rowptr)
+{
+    int64_t e = 0, r = 0;
+    for (int64_t z = 0; z < nz; ++z)
+        for (int64_t y = 0; y < ny; ++y)
+            for (int64_t x = 0; x < nx; ++x) {
+                int64_t nb = (int64_t)span(x, nx) * span(y, ny) * span(z, nz);
+                for (int64_t d = 0; d < dof; ++d) { rowptr[r++] = (int32_t)e; e += nb * dof; }
+            }
+    rowptr[r] = (int32_t)e;
+    return e;
+}
+
+void lapis_gen_block_stencil_fill(int64_t nx, int64_t ny, int64_t nz, int64_t dof, uint64_t seed,
+                                  const int32_t *rowptr, int32_t *colidx, double *vals)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t node = 0; node < nx * ny * nz; ++node) {
+        int64_t x = node % nx, y = (node / nx) % ny, z = node / (nx * ny);
+        for (int64_t d = 0; d < dof; ++d) {
+            int64_t r = node * dof + d;
+            int64_t e = rowptr[r];
+            for (int64_t dz = -1; dz <= 1; ++dz) {
+                if (z + dz < 0 || z + dz >= nz) continue;
+                for (int64_t dy = -1; dy <= 1; ++dy) {
+                    if (y + dy < 0 || y + dy >= ny) continue;
+                    for (int64_t dx = -1; dx <= 1; ++dx) {
+                        if (x + dx < 0 || x + dx >= nx) continue;
+                        int64_t nbr = ((z + dz) * ny + (y + dy)) * nx + (x + dx);
+                        for (int64_t q = 0; q < dof; ++q) {
+                            int64_t c = nbr * dof + q;
+                            double u = u01(seed, 1, (uint64_t)e);
+                            colidx[e] = (int32_t)c;
+                            vals[e] = (c == r) ? 27.0 * (double)dof + u : -1.0 + u;
+                            ++e;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Row lengths with a prescribed mean and maximum: L = clamp(round(mean * g), 1,
+ * max_len) with g a Gamma(4, 1/4) variate (mean 1, built from four uniform
+ * draws: -log(u1 u2 u3 u4)/4; stream 0, indices 4i..4i+3); row 0 is set to
+ * max_len so the maximum is attained.
+ * ---------------------------------------------------------------------- */
+void lapis_gen_gamma_lengths(int64_t nrows, double mean, int64_t max_len, uint64_t seed, int32_t *len)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        double p = 1.0;
+        for (int q = 0; q < 4; ++q)
+            p *= ((double)(lapis_gen_bits(seed, 0, 4 * (uint64_t)i + q) >> 11) + 1.0) * 0x1.0p-53;
+        double L = floor(mean * (-log(p) / 4.0) + 0.5);
+        if (L < 1.0) L = 1.0;
+        if (L > (double)max_len) L = (double)max_len;
+        len[i] = (int32_t)L;
+    }
+    if (nrows > 0) len[0] = (int32_t)max_len;
+}
+
+/* ------------------------------------------------------------------------
+ * Banded distinct sorted columns: the L columns of row i are spread by
+ * stratified jitter over the window of width min(ncols, band_factor * L)
+ * centred on the diagonal (shifted to stay inside [0, ncols)).
+ * Draw index = 2^41 + entry position (stream 0).
+ * ---------------------------------------------------------------------- */
+int lapis_gen_banded_cols(int64_t nrows, int64_t ncols, const int32_t *rowptr, int64_t band_factor,
+                          uint64_t seed, int32_t *colidx)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1024) reduction(| : bad)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t b = rowptr[i], L = rowptr[i + 1] - b;
+        if (L > ncols) { bad = 1; continue; }
+        int64_t width = band_factor * L;
+        if (width > ncols) width = ncols;
+        if (width < L) width = L;
+        int64_t centre = (int64_t)(((unsigned __int128)i * (uint64_t)ncols) / (uint64_t)(nrows > 0 ? nrows : 1));
+        int64_t lo = centre - width / 2;
+        if (lo < 0) lo = 0;
+        if (lo + width > ncols) lo = ncols - width;
+        for (int64_t j = 0; j < L; ++j) {
+            int64_t s0 = (int64_t)(((unsigned __int128)j * (uint64_t)width) / (uint64_t)L);
+            int64_t s1 = (int64_t)(((unsigned __int128)(j + 1) * (uint64_t)width) / (uint64_t)L);
+            uint64_t bits = lapis_gen_bits(seed, 0, (1ULL << 41) + (uint64_t)(b + j));
+            int64_t off = (int64_t)(((unsigned __int128)bits * (uint64_t)(s1 - s0)) >> 64);
+            colidx[b + j] = (int32_t)(lo + s0 + off);
+        }
+    }
+    return bad ? -1 : 0;
+}

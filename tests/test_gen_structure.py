@@ -106,3 +106,24 @@ def test_workload4_structure():
     assert np.all(np.diff(w.colidx)[inner[1:]] > 0)          # sorted and distinct per row
     assert w.colidx.min() >= 0 and w.colidx.max() < n
     assert w.vals.min() >= -1.0 and w.vals.max() < 1.0
+
+
+def test_table3_standins_have_the_papers_shapes(golden_dir):
+    """Rows, mean and maximum entries per row as printed in the paper's Table 3."""
+    for line in open(os.path.join(golden_dir, "paper_table3.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, rows, mean, mx, _ = line.split()
+        w = gen.table3_standin(name)
+        L = np.diff(w.rowptr)
+        assert w.nrows == int(rows) and L.max() == int(mx) and L.min() >= 1
+        assert abs(L.mean() - float(mean)) < 0.01 * float(mean)
+        inner = np.ones(w.nnz, dtype=bool)
+        inner[w.rowptr[1:-1]] = False
+        assert np.all(np.diff(w.colidx)[inner[1:]] > 0)
+        assert w.colidx.min() >= 0 and w.colidx.max() < w.ncols
+    # Elasticity3D_60 is exactly the 60^3 x 3-dof block stencil: nnz = 9 * 178^3
+    w = gen.table3_standin("Elasticity3D_60")
+    assert w.nnz == 9 * 178 ** 3
+    rows = np.repeat(np.arange(w.nrows), np.diff(w.rowptr))
+    assert np.all(np.abs(w.colidx // 3 % 60 - rows // 3 % 60) <= 1)

@@ -309,6 +309,7 @@ def test_spmm_general_matrices(dtype, k, ldx, ldy):
 # the five workloads: reduced sizes (several tiles + ragged tail) and full size
 # ---------------------------------------------------------------------------
 REDUCED = {
+    6: {"scale": 0.03}, 7: {"scale": 0.04}, 8: {"scale": 0.02}, 9: {"scale": 0.03},
     1: None,
     2: {"nx": 37, "ny": 29, "nz": 31},
     3: {"n": 100003},
@@ -334,11 +335,11 @@ def run_workload(cfg, scale):
         dev.close()
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5, 6, 7, 8, 9])
 def test_workload_reduced(cfg):
     run_workload(cfg, REDUCED[cfg])
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 8, 9])
 def test_workload_full_size(cfg):
     run_workload(cfg, None)
