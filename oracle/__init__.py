@@ -54,7 +54,7 @@ def _load():
             getattr(lib, name).restype = None
         lib.oracle_partition_num_bins.argtypes = [i64]
         lib.oracle_partition_num_bins.restype = ctypes.c_int
-        lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, i64, p]
+        lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, p, p]
         lib.oracle_partition_stream_chunks.restype = i64
         lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_partition_rows.restype = None
@@ -115,7 +115,8 @@ def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):
 
 def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NNZ,
               stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_NNZ):
-    """Reference row partition.  Returns a dict with stream_chunks[], bin_offset[num_bins+1],
+    """Reference row partition.  Returns a dict with stream_chunks[] (class by class),
+    stream_offset[5], bin_offset[num_bins+1],
     row_perm[rows outside stream chunks], long_off[m+1], tile_row[T+1], tile_nz[T+1]."""
     assert rowptr.dtype == np.int32 and rowptr.flags.c_contiguous
     lib = _load()
@@ -123,8 +124,9 @@ def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NN
     nb = lib.oracle_partition_num_bins(wave)
     nchunks = (n + stream_rows - 1) // stream_rows
     stream_chunks = np.empty(nchunks, dtype=np.int32)
-    ns = lib.oracle_partition_stream_chunks(n, _p(rowptr), wave, stream_rows, stream_min_nnz,
-                                            _p(stream_chunks))
+    stream_offset = np.zeros(5, dtype=np.int32)
+    ns = lib.oracle_partition_stream_chunks(n, _p(rowptr), stream_rows, stream_min_nnz,
+                                            _p(stream_chunks), _p(stream_offset))
     stream_chunks = stream_chunks[:ns].copy()
     bin_offset = np.zeros(nb + 1, dtype=np.int32)
     row_perm = np.empty(n, dtype=np.int32)
@@ -141,7 +143,8 @@ def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NN
     tile_nz = np.zeros(T + 1, dtype=np.int32)
     lib.oracle_partition_tiles(_p(rowptr), tile_nnz, _p(long_rows), m, T, _p(long_off),
                                _p(tile_row), _p(tile_nz))
-    return {"num_bins": nb, "stream_chunks": stream_chunks, "bin_offset": bin_offset,
+    return {"num_bins": nb, "stream_chunks": stream_chunks, "stream_offset": stream_offset,
+            "bin_offset": bin_offset,
             "row_perm": row_perm, "long_off": long_off, "tile_row": tile_row, "tile_nz": tile_nz}
 
 

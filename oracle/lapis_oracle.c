@@ -111,10 +111,16 @@ void oracle_spmm_f32(int64_t nrows, int64_t k, const int32_t *rowptr, const int3
  * Two levels.
  *
  * (1) Stream chunks.  Rows are taken in chunks of chunk_rows consecutive rows
- * (chunk c = rows c*chunk_rows .. min((c+1)*chunk_rows, nrows) - 1).  A chunk
- * is a stream chunk iff none of its rows has more than `wave` entries and the
- * chunk holds at least chunk_min_nnz entries in total.  stream_chunks lists
- * the stream chunk ids in ascending order.
+ * (chunk c = rows c*chunk_rows .. min((c+1)*chunk_rows, nrows) - 1).  With M
+ * the largest row length in the chunk, the chunk's class is
+ *   0 (not a stream chunk)  if it holds fewer than chunk_min_nnz entries or
+ *                           M > 16*chunk_rows,
+ *   k = 1, 2, 3, 4          otherwise, the smallest k with M <= 2^k * chunk_rows
+ *                           (lane groups of 2^k lanes per row: rows up to 64,
+ *                           128, 256, 512 entries for chunk_rows = 32 - the
+ *                           per-chunk form of "entries per row, rounded up").
+ * stream_chunks lists the chunk ids class by class (class 1 first), ascending
+ * inside a class; stream_offset[0..4] are the class boundaries in that list.
  *
  * (2) Bins, over the rows of all other chunks only.  Per-row lane count in the
  * spirit of the vector-length estimate of Section 4.2 (entries per row,
@@ -148,27 +154,35 @@ int oracle_partition_num_bins(int64_t wave)
     return bin_of_length(wave + 1, wave, wave + 1) + 2;
 }
 
-static int is_stream_chunk(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t wave,
-                           int64_t chunk_rows, int64_t chunk_min_nnz)
+static int chunk_class(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
+                       int64_t chunk_min_nnz)
 {
     int64_t first = c * chunk_rows;
     int64_t last = first + chunk_rows < nrows ? first + chunk_rows : nrows;
+    int64_t longest = 0;
     for (int64_t i = first; i < last; ++i)
-        if (rowptr[i + 1] - rowptr[i] > wave) return 0;
-    return rowptr[last] - rowptr[first] >= chunk_min_nnz;
+        if (rowptr[i + 1] - rowptr[i] > longest) longest = rowptr[i + 1] - rowptr[i];
+    if (rowptr[last] - rowptr[first] < chunk_min_nnz) return 0;
+    for (int k = 1; k <= 4; ++k)
+        if (longest <= ((int64_t)1 << k) * chunk_rows) return k;
+    return 0;
 }
 
-/* Pass 0: stream_chunks[] (caller provides ceil(nrows/chunk_rows) slots);
- * returns the number of stream chunks. */
-int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int64_t wave,
-                                       int64_t chunk_rows, int64_t chunk_min_nnz,
-                                       int32_t *stream_chunks)
+/* Pass 0: stream_chunks[] (caller provides ceil(nrows/chunk_rows) slots) and
+ * stream_offset[5]; returns the number of stream chunks. */
+int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
+                                       int64_t chunk_min_nnz, int32_t *stream_chunks,
+                                       int32_t *stream_offset)
 {
     int64_t count = 0;
     int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
-    for (int64_t c = 0; c < nchunks; ++c)
-        if (is_stream_chunk(c, nrows, rowptr, wave, chunk_rows, chunk_min_nnz))
-            stream_chunks[count++] = (int32_t)c;
+    for (int k = 1; k <= 4; ++k) {
+        stream_offset[k - 1] = (int32_t)count;
+        for (int64_t c = 0; c < nchunks; ++c)
+            if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == k)
+                stream_chunks[count++] = (int32_t)c;
+    }
+    stream_offset[4] = (int32_t)count;
     return count;
 }
 
@@ -185,7 +199,7 @@ void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
     int nb = oracle_partition_num_bins(wave);
     for (int b = 0; b <= nb; ++b) bin_offset[b] = 0;
     for (int64_t i = 0; i < nrows; ++i) {
-        if (is_stream_chunk(i / chunk_rows, nrows, rowptr, wave, chunk_rows, chunk_min_nnz)) continue;
+        if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz)) continue;
         bin_offset[bin_of_length(rowptr[i + 1] - rowptr[i], wave, long_threshold) + 1] += 1;
     }
     for (int b = 0; b < nb; ++b) bin_offset[b + 1] += bin_offset[b];
@@ -194,7 +208,7 @@ void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
         int64_t at = bin_offset[b];
         for (int64_t i = 0; i < nrows; ++i) {
             int64_t L = rowptr[i + 1] - rowptr[i];
-            if (is_stream_chunk(i / chunk_rows, nrows, rowptr, wave, chunk_rows, chunk_min_nnz)) continue;
+            if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz)) continue;
             if (bin_of_length(L, wave, long_threshold) != b) continue;
             row_perm[at++] = (int32_t)i;
             if (b == nb - 1) long_nnz += L;

@@ -36,8 +36,13 @@ def _independent_partition(rowptr, wave, long_threshold, tile_nnz, stream_rows, 
     ends = np.minimum(starts + stream_rows, n)
     chunk_max = np.maximum.reduceat(L, starts) if n else np.zeros(0, dtype=np.int64)
     chunk_nnz = rowptr[ends].astype(np.int64) - rowptr[starts]
-    is_stream = (chunk_max <= wave) & (chunk_nnz >= stream_min_nnz)
-    stream_chunks = np.flatnonzero(is_stream).astype(np.int32)
+    ratio = np.maximum(chunk_max, 1) / stream_rows
+    cls = np.clip(np.ceil(np.log2(np.maximum(ratio, 1e-9))).astype(np.int64), 1, None)   # 2^k * rows >= max
+    cls[(cls > 4) | (chunk_nnz < stream_min_nnz)] = 0
+    is_stream = cls > 0
+    order = np.argsort(np.where(is_stream, cls, 99), kind="stable")
+    stream_chunks = order[:is_stream.sum()].astype(np.int32)
+    stream_offset = np.concatenate([[0], np.cumsum(np.bincount(cls, minlength=5)[1:5])]).astype(np.int32)
     binned = np.flatnonzero(~np.repeat(is_stream, ends - starts))
     top = int(math.log2(wave)) + 1
     Lb = L[binned]
@@ -55,7 +60,7 @@ def _independent_partition(rowptr, wave, long_threshold, tile_nnz, stream_rows, 
     tstarts = np.arange(T, dtype=np.int64) * tile_nnz
     tr = np.searchsorted(lp, tstarts, side="right") - 1
     tn = tstarts - lp[tr]
-    return stream_chunks, off, perm, lp, np.append(tr, long_rows.size), np.append(tn, 0)
+    return stream_chunks, stream_offset, off, perm, lp, np.append(tr, long_rows.size), np.append(tn, 0)
 
 
 @pytest.mark.parametrize("wave,lt,tile,srows,smin", [(64, 4096, 4096, 32, 256), (64, 100, 64, 32, 256),
@@ -74,9 +79,10 @@ def test_partition_matches_independent_construction(wave, lt, tile, srows, smin,
     rowptr = np.zeros(n + 1, dtype=np.int32)
     np.cumsum(L, out=rowptr[1:])
     part = oracle.partition(rowptr, wave, lt, tile, srows, smin)
-    sc, off, perm, lp, tr, tn = _independent_partition(rowptr, wave, lt, tile, srows, smin)
+    sc, so, off, perm, lp, tr, tn = _independent_partition(rowptr, wave, lt, tile, srows, smin)
     assert sc.size > 0 and perm.size > 0
     assert np.array_equal(part["stream_chunks"], sc)
+    assert np.array_equal(part["stream_offset"], so)
     assert np.array_equal(part["bin_offset"], off)
     assert np.array_equal(part["row_perm"], perm)
     assert np.array_equal(part["long_off"], lp)
@@ -85,25 +91,31 @@ def test_partition_matches_independent_construction(wave, lt, tile, srows, smin,
 
 
 def test_stream_chunks_hand_worked():
-    """Chunks of 32 rows; a stream chunk has no row above 64 entries and at least 256 entries."""
-    L = np.array([8] * 32            # chunk 0: 256 entries, all short           -> stream
-                 + [8] * 31 + [65]   # chunk 1: one row of 65                     -> binned
+    """Chunks of 32 rows; class k = smallest k with max row length <= 2^k * 32 (k <= 4), class 0
+    (binned) when the chunk holds fewer than 256 entries or a row exceeds 512 entries."""
+    L = np.array([8] * 32            # chunk 0: 256 entries, max 8                -> class 1
+                 + [8] * 31 + [65]   # chunk 1: max 65                            -> class 2
                  + [7] * 32          # chunk 2: 224 entries, below the minimum    -> binned
-                 + [64] * 32         # chunk 3: 2048 entries, rows exactly at 64  -> stream
+                 + [64] * 32         # chunk 3: rows exactly at 64                -> class 1
                  + [0] * 31 + [64]   # chunk 4: 64 entries                        -> binned
-                 + [40] * 7,         # chunk 5 (ragged, 7 rows): 280 entries      -> stream
+                 + [128] * 2 + [1] * 30   # chunk 5: max 128                      -> class 2
+                 + [129] + [5] * 31  # chunk 6: max 129 (284 entries)             -> class 3
+                 + [512] + [0] * 31  # chunk 7: max 512                           -> class 4
+                 + [513] + [9] * 31  # chunk 8: a row above 512                   -> binned
+                 + [40] * 7,         # chunk 9 (ragged, 7 rows): 280 entries      -> class 1
                  dtype=np.int64)
     rowptr = np.zeros(L.size + 1, dtype=np.int32)
     np.cumsum(L, out=rowptr[1:])
     part = oracle.partition(rowptr)
-    assert part["stream_chunks"].tolist() == [0, 3, 5]
-    binned = list(range(32, 96)) + list(range(128, 160))
+    assert part["stream_chunks"].tolist() == [0, 3, 9, 1, 5, 6, 7]
+    assert part["stream_offset"].tolist() == [0, 3, 5, 6, 7]
+    binned = list(range(64, 96)) + list(range(128, 160)) + list(range(256, 288))
     assert sorted(part["row_perm"].tolist()) == binned
-    # bins: 31 empty rows (bin 0); 32 rows of 7 and 31 rows of 8 (bin 4); one row of 64 (bin 7); one of 65 (bin 8)
-    assert np.diff(part["bin_offset"]).tolist() == [31, 0, 0, 0, 63, 0, 0, 1, 1, 0]
+    # bins: 31 empty rows; 32 rows of 7 (bin 4); 31 rows of 9 (bin 5); one row of 64 (bin 7); one of 513 (bin 8)
+    assert np.diff(part["bin_offset"]).tolist() == [31, 0, 0, 0, 32, 31, 0, 1, 1, 0]
     # with 6 rows in the ragged chunk: 240 entries -> binned
     part = oracle.partition(rowptr[:-1].copy())
-    assert part["stream_chunks"].tolist() == [0, 3]
+    assert part["stream_chunks"].tolist() == [0, 3, 1, 5, 6, 7]
 
 
 def test_partition_invariants_on_power_law_workload():
@@ -174,6 +186,7 @@ def test_split_cuts_hand_worked():
     colidx = np.array(cols0 + [1, 2] + cols1, dtype=np.int32)
     part = oracle.partition(rowptr)
     assert part["row_perm"].tolist() == [1, 0, 2]                   # bin 2 (row 1), bin 8 (rows 0, 2)
+    assert part["stream_chunks"].size == 0                           # 142 entries: below the minimum
     sp = oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, max_blocks=32)
     assert (sp["num_blocks"], sp["block_width"], sp["num_split_rows"]) == (3, 10, 2)
     # cut[b*S + r]: b = 0..3, r = 0 (row 0), 1 (row 2)
@@ -195,13 +208,13 @@ def test_split_matches_searchsorted():
     part = oracle.partition(rowptr)
     sp = oracle.split_partition(rowptr, colidx, ncols, 8, part)
     nb, W, S = sp["num_blocks"], sp["block_width"], sp["num_split_rows"]
-    assert (nb, W) == (4, 1 << 18) and S == (L > 64).sum()
-    rows = part["row_perm"][part["bin_offset"][8]:]
+    rows = part["row_perm"][part["bin_offset"][8]:]          # rows above 64 entries outside stream chunks
+    assert (nb, W) == (4, 1 << 18) and S == rows.size and 0 < S <= (L > 64).sum()
     for r, row in enumerate(rows):
         cols = colidx[rowptr[row]:rowptr[row + 1]]
         expect = rowptr[row] + np.searchsorted(cols, np.arange(nb + 1) * W, side="left")
         expect[-1] = rowptr[row + 1]
         assert np.array_equal(sp["cut"][r::S], expect)
     vlen = sp["cut"][S:] - sp["cut"][:-S]
-    assert vlen.sum() == L[L > 64].sum() and np.all(vlen >= 0)
+    assert vlen.sum() == L[rows].sum() and np.all(vlen >= 0)
     assert np.array_equal(np.sort(sp["row_perm"]), np.arange(nb * S))
