@@ -42,11 +42,15 @@ extern "C" {
  * The analysis pass has two levels.
  *
  * Level 1, stream chunks.  Rows are taken in chunks of LAPIS_STREAM_ROWS
- * consecutive rows (chunk c = rows c*LAPIS_STREAM_ROWS ...).  A chunk is a
- * stream chunk iff none of its rows has more than LAPIS_WAVE entries and it
- * holds at least LAPIS_STREAM_MIN_NNZ entries.  Its entries are one contiguous
- * piece of the value / column arrays, which one wavefront streams through LDS.
- * If d_colidx or d_vals is not 16-byte aligned, no chunk is a stream chunk.
+ * consecutive rows (chunk c = rows c*LAPIS_STREAM_ROWS ...).  With M the longest
+ * row of the chunk, its class is 0 (not a stream chunk) if the chunk holds fewer
+ * than LAPIS_STREAM_MIN_NNZ entries or M > 16*LAPIS_STREAM_ROWS, else the
+ * smallest k in 1..4 with M <= 2^k * LAPIS_STREAM_ROWS: groups of 2^k lanes per
+ * row, rows up to 64 / 128 / 256 / 512 entries - the per-chunk form of the
+ * estimate of Section 4.2 (entries per row, rounded up).  A stream chunk's
+ * entries are one contiguous piece of the value / column arrays, which
+ * wavefronts stream through LDS.  If d_colidx or d_vals is not 16-byte aligned,
+ * no chunk is a stream chunk.
  *
  * Level 2, bins, for the rows of all other chunks.  It generalises the
  * vector-length estimate of Section 4.2 (entries per row, rounded up, clamped
@@ -176,7 +180,8 @@ int lapis_csr_destroy(lapis_csr_t *A);
  * be NULL.
  * lapis_csr_copy_partition: copies to HOST buffers the caller owns (any may be
  * NULL to skip it):
- *   h_stream_chunks int32[num_stream]     stream chunk ids, ascending
+ *   h_stream_chunks int32[num_stream]     stream chunk ids, class 1 first, ascending in a class
+ *   h_stream_offset int32[5]              class boundaries in h_stream_chunks
  *   h_bin_offset int32[LAPIS_NUM_BINS+1]  exclusive scan of per-bin row counts
  *   h_row_perm   int32[num_binned]        row ids grouped by bin, ascending in each bin
  *   h_long_off   int32[num_long+1]        exclusive scan of the bin-9 rows' lengths
@@ -187,9 +192,9 @@ int lapis_csr_destroy(lapis_csr_t *A);
  */
 int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t *num_binned,
                               int64_t *num_long, int64_t *num_tiles);
-int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_bin_offset,
-                             int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
-                             int32_t *h_tile_nz);
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_stream_offset,
+                             int32_t *h_bin_offset, int32_t *h_row_perm, int32_t *h_long_off,
+                             int32_t *h_tile_row, int32_t *h_tile_nz);
 
 /* The column split (level 3).  lapis_csr_split_sizes: *num_blocks = nb (0: the split is off),
  * *block_width = W, *num_split_rows = S, and for the virtual rows *num_binned (= nb*S),

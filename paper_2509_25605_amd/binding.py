@@ -51,7 +51,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
         lib.lapis_csr_destroy.argtypes = [p]
         lib.lapis_csr_partition_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 4
-        lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p, p]
+        lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p, p, p]
         lib.lapis_csr_split_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 6
         lib.lapis_csr_copy_split.argtypes = [p, p, p, p, p, p, p]
         lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
@@ -141,6 +141,7 @@ def lapis_csr_copy_partition(A):
     nb = lapis_partition_constants()["num_bins"]
     res = {
         "stream_chunks": np.empty(ns, dtype=np.int32),
+        "stream_offset": np.empty(5, dtype=np.int32),
         "bin_offset": np.empty(nb + 1, dtype=np.int32),
         "row_perm": np.empty(nb_rows, dtype=np.int32),
         "long_off": np.empty(m + 1, dtype=np.int32),
@@ -148,7 +149,8 @@ def lapis_csr_copy_partition(A):
         "tile_nz": np.empty(t + 1, dtype=np.int32),
     }
     ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
-    _check(load().lapis_csr_copy_partition(A, ptr(res["stream_chunks"]), ptr(res["bin_offset"]),
+    _check(load().lapis_csr_copy_partition(A, ptr(res["stream_chunks"]), ptr(res["stream_offset"]),
+                                           ptr(res["bin_offset"]),
                                            ptr(res["row_perm"]), ptr(res["long_off"]),
                                            ptr(res["tile_row"]), ptr(res["tile_nz"])))
     return res

@@ -44,8 +44,9 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *s_tm
     return incl - v;
 }
 
-// Pass 0a: flag[c] = 1 iff chunk c (chunk_rows consecutive rows) has no row with
-// more than kWave entries and holds at least min_nnz entries.
+// Pass 0a: flag[c] = class of chunk c (chunk_rows consecutive rows): 0 if the chunk holds fewer
+// than min_nnz entries or a row has more than 16*chunk_rows entries, else the smallest k in 1..4
+// with (longest row) <= 2^k * chunk_rows.
 __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32_t num_chunks,
                                                             int32_t chunk_rows, int32_t min_nnz,
                                                             const int32_t *__restrict__ rowptr,
@@ -57,17 +58,22 @@ __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32
     const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
     int32_t prev = rowptr[first];
     const int32_t begin = prev;
-    bool ok = true;
+    int32_t longest = 0;
     for (int64_t i = first + 1; i <= last; ++i) {
         const int32_t cur = rowptr[i];
-        ok &= (cur - prev) <= kWave;
+        longest = (cur - prev > longest) ? cur - prev : longest;
         prev = cur;
     }
-    flag[c] = (ok && prev - begin >= min_nnz) ? 1 : 0;
+    int cls = 0;
+    if (prev - begin >= min_nnz) {
+        for (int k = 4; k >= 1; --k)
+            if (longest <= (chunk_rows << k)) cls = k;
+    }
+    flag[c] = cls;
 }
 
-// Pass 0b (one workgroup): ascending list of the flagged chunk ids; *count = how many.
-__global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunks,
+// Pass 0b (one workgroup): ascending list of the chunk ids of class `cls`; *count = how many.
+__global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunks, int32_t cls,
                                                                const int32_t *__restrict__ flag,
                                                                int32_t *__restrict__ list,
                                                                int32_t *__restrict__ count)
@@ -76,7 +82,7 @@ __global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunk
     int32_t running = 0;
     for (int64_t base = 0; base < num_chunks; base += kBlock) {
         const int64_t c = base + threadIdx.x;
-        const int32_t v = (c < num_chunks) ? flag[c] : 0;
+        const int32_t v = (c < num_chunks && flag[c] == cls) ? 1 : 0;
         int32_t total;
         const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
         if (v) list[running + excl] = (int32_t)c;

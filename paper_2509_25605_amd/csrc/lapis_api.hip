@@ -51,7 +51,8 @@ struct lapis_csr {
     const int32_t *colidx = nullptr;
     const void *vals = nullptr;
     // level 1: stream chunks
-    int32_t *d_stream_chunks = nullptr;  // [num_stream] ascending ids
+    int32_t *d_stream_chunks = nullptr;  // [num_stream] chunk ids, class by class, ascending in a class
+    int32_t h_stream_offset[kStreamClasses + 1] = {0};   // class boundaries in that list
     int64_t num_chunks = 0, num_stream = 0;
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
@@ -268,11 +269,17 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     if (n > 0) {
         chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, chunk_flag.as<int32_t>());
-        chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(num_chunks, chunk_flag.as<int32_t>(),
-                                                                   A->d_stream_chunks, d_flags);
-        LAPIS_HIP(hipGetLastError());
-        LAPIS_HIP(hipMemcpyAsync(&num_stream, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        for (int cls = 1; cls <= kStreamClasses; ++cls) {
+            A->h_stream_offset[cls - 1] = num_stream;
+            chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
+                num_chunks, cls, chunk_flag.as<int32_t>(), A->d_stream_chunks + num_stream, d_flags);
+            LAPIS_HIP(hipGetLastError());
+            int32_t count = 0;
+            LAPIS_HIP(hipMemcpyAsync(&count, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+            LAPIS_HIP(hipStreamSynchronize(stream));
+            num_stream += count;
+        }
+        A->h_stream_offset[kStreamClasses] = num_stream;
     }
     A->num_stream = num_stream;
 
@@ -339,20 +346,30 @@ void launch_binned(const lapis_csr *A, const BinnedSet &s, const ShortPlan &plan
     }
 }
 
+// Stream chunks of one class (G lanes per row): one wavefront per 64/G rows.
+template <typename T, int G>
+void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipStream_t stream)
+{
+    const int64_t count = A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
+    if (count == 0) return;
+    const uint32_t waves = (uint32_t)(count * (G / 2));
+    const uint32_t padded = (waves + kXcds - 1) / kXcds * kXcds;
+    const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
+    spmv_stream_kernel<T, G, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+        (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx,
+        static_cast<const T *>(A->vals), x, y, a, b);
+}
+
 template <typename T>
 int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, hipStream_t stream)
 {
     const T a = (T)alpha, b = (T)beta;
-    const T *vals = static_cast<const T *>(A->vals);
     const T *x = static_cast<const T *>(d_x);
     T *y = static_cast<T *>(d_y);
-    if (A->num_stream > 0) {
-        const uint32_t chunks = (uint32_t)A->num_stream;
-        const uint32_t padded = (chunks + kXcds - 1) / kXcds * kXcds;
-        const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;
-        spmv_stream_kernel<T, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, A->colidx, vals, x, y, a, b);
-    }
+    launch_stream<T, 2>(A, 1, x, y, a, b, stream);
+    launch_stream<T, 4>(A, 2, x, y, a, b, stream);
+    launch_stream<T, 8>(A, 3, x, y, a, b, stream);
+    launch_stream<T, 16>(A, 4, x, y, a, b, stream);
     const bool split = A->num_blocks > 0;
     launch_binned<T>(A, A->rows, A->plan_rows, !split, x, y, a, b, stream);
     if (split) {
@@ -408,7 +425,7 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
     if (A->num_stream > 0) {                                          // rows of the stream chunks
         const uint32_t chunks = (uint32_t)A->num_stream;
         const uint32_t padded = (chunks + kXcds - 1) / kXcds * kXcds;
-        const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;
+        const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;  // any order
         constexpr int kStreamLanes = CL > 16 ? 16 : CL;               // wider rows of X: several column blocks
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC)
             spmm_stream_kernel<T, VEC, kStreamLanes, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
@@ -561,12 +578,13 @@ int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t
     return LAPIS_OK;
 }
 
-int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_bin_offset,
-                             int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
-                             int32_t *h_tile_nz)
+int lapis_csr_copy_partition(const lapis_csr_t *A, int32_t *h_stream_chunks, int32_t *h_stream_offset,
+                             int32_t *h_bin_offset, int32_t *h_row_perm, int32_t *h_long_off,
+                             int32_t *h_tile_row, int32_t *h_tile_nz)
 {
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
     LAPIS_HIP(hipDeviceSynchronize());
+    if (h_stream_offset) std::memcpy(h_stream_offset, A->h_stream_offset, sizeof(A->h_stream_offset));
     if (h_stream_chunks && A->num_stream > 0)
         LAPIS_HIP(hipMemcpy(h_stream_chunks, A->d_stream_chunks, sizeof(int32_t) * (size_t)A->num_stream, hipMemcpyDeviceToHost));
     return copy_set(A->rows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);

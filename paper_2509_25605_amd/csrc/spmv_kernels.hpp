@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kBlock) void spmv_short_kernel(
 
 // ---- stream chunks ----------------------------------------------------------
 constexpr int kStreamRows = 32;                      // rows per chunk
-constexpr int kStreamGroup = kWave / kStreamRows;    // lanes per row (2)
+constexpr int kStreamClasses = 4;                    // chunk classes 1..4: 2, 4, 8, 16 lanes per row
 constexpr int kStreamWindow = 1024;                  // entries staged in LDS at a time
 constexpr int kStreamUnroll = 16;                    // gathers in flight per lane and batch
 
@@ -290,29 +290,32 @@ __device__ __forceinline__ T stream_batch(const int32_t *sc, const T *sv, int u0
     return s;
 }
 
-// One wavefront (= one workgroup) per stream chunk.  stream_chunks == nullptr
-// means every chunk of the matrix is a stream chunk (chunk id = wave id).
-// colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a
-// multiple of 4: 16-byte loads never reach past it, the last nnz % 4 entries of
-// the matrix are fetched one by one.
-template <typename T, bool XCD_REMAP, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
+// One wavefront (= one workgroup) per 64/G consecutive rows of a stream chunk of the class with
+// G lanes per row (G = 2, 4, 8, 16: a chunk of 32 rows is shared by G/2 wavefronts).
+// stream_chunks lists the chunks of that class; nullptr means every chunk of the matrix.
+// colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a multiple of 4:
+// 16-byte loads never reach past it, the last nnz % 4 entries of the matrix are fetched one by one.
+template <typename T, int G, bool XCD_REMAP, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
-    int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
+    int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ colidx, const T *__restrict__ vals, const T *__restrict__ x,
     T *__restrict__ y, T alpha, T beta)
 {
-    constexpr int G = kStreamGroup;
+    constexpr int kRowsPerWave = kWave / G;
+    constexpr int kWavesPerChunk = kStreamRows / kRowsPerWave;
+    static_assert(G >= 2 && G <= 16 && kWavesPerChunk * kRowsPerWave == kStreamRows, "G must be 2, 4, 8 or 16");
     static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
 
-    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_chunks) : blockIdx.x;
-    if (id >= num_chunks) return;
+    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_waves) : blockIdx.x;
+    if (id >= num_waves) return;
     const int lane = threadIdx.x;
     const int sub = lane % G;
-    const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
-    const int64_t row = chunk * kStreamRows + lane / G;
+    const uint32_t list_pos = id / kWavesPerChunk;
+    const int64_t chunk = stream_chunks ? stream_chunks[list_pos] : (int64_t)list_pos;
+    const int64_t row = chunk * kStreamRows + (id % kWavesPerChunk) * kRowsPerWave + lane / G;
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
     const int32_t p0 = rowptr[row_c], p1 = rowptr[row_c + 1];

@@ -84,7 +84,7 @@ def test_null_handles_and_out_pointer(lib):
     assert lib.lapis_spmv_paper_shape(None, 1.0, 8, 0.0, 8, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_spmm(None, 4, 1.0, 8, 4, 0.0, 8, 4, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_partition_sizes(None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
-    assert lib.lapis_csr_copy_partition(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_copy_partition(None, None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_split_sizes(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_copy_split(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_partition_constants(None) == L.LAPIS_ERR_INVALID_ARG

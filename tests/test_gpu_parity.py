@@ -21,7 +21,7 @@ def say(msg):
 def check_partition(dev, rowptr):
     ref = oracle.partition(rowptr)
     got = dev.partition()
-    for key in ("stream_chunks", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+    for key in ("stream_chunks", "stream_offset", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
         assert got[key].dtype == np.int32
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
 
@@ -198,6 +198,8 @@ STREAM_LAYOUTS = {
     "offset": [[3] * 31 + [70], [64] * 32, [33] * 32, [17] * 32, [8] * 32],   # odd prefix, mixed
     "ragged": [[27] * 32, [27] * 32, [27] * 11],                 # last chunk has 11 rows (297 entries)
     "mixed": [[8] * 32, [0] * 16 + [16] * 16, [1] * 32, [64] + [7] * 31, [5] * 32, [40] * 7],
+    "classes": [[81] * 32, [128] + [3] * 31, [129] * 32, [256] * 32, [300, 0, 512] + [77] * 29, [513] + [9] * 31,
+                [345] + [60] * 10],
 }
 
 
