@@ -45,9 +45,12 @@ extern "C" {
  * consecutive rows (chunk c = rows c*LAPIS_STREAM_ROWS ...).  With M the longest
  * row of the chunk, its class is 0 (not a stream chunk) if the chunk holds fewer
  * than LAPIS_STREAM_MIN_NNZ entries or M > 16*LAPIS_STREAM_ROWS, else the
- * smallest k in 1..4 with M <= 2^k * LAPIS_STREAM_ROWS: groups of 2^k lanes per
+ * smallest k in 1..4 with M <= 2^k * LAPIS_STREAM_ROWS (groups of 2^k lanes per
  * row, rows up to 64 / 128 / 256 / 512 entries - the per-chunk form of the
- * estimate of Section 4.2 (entries per row, rounded up).  A stream chunk's
+ * estimate of Section 4.2, entries per row, rounded up) and with at most
+ * 2^k * 16 * LAPIS_STREAM_ROWS entries in the chunk (so each of the 2^(k-1)
+ * wavefronts sharing it gets about one LDS window); if no k <= 4 meets the
+ * second condition, the first alone decides.  A stream chunk's
  * entries are one contiguous piece of the value / column arrays, which
  * wavefronts stream through LDS.  If d_colidx or d_vals is not 16-byte aligned,
  * no chunk is a stream chunk.

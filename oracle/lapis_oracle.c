@@ -118,7 +118,12 @@ void oracle_spmm_f32(int64_t nrows, int64_t k, const int32_t *rowptr, const int3
  *   k = 1, 2, 3, 4          otherwise, the smallest k with M <= 2^k * chunk_rows
  *                           (lane groups of 2^k lanes per row: rows up to 64,
  *                           128, 256, 512 entries for chunk_rows = 32 - the
- *                           per-chunk form of "entries per row, rounded up").
+ *                           per-chunk form of "entries per row, rounded up")
+ *                           that also satisfies (entries of the chunk) <=
+ *                           2^k * 16 * chunk_rows, so that the 2^(k-1)
+ *                           wavefronts sharing the chunk get at most 1024
+ *                           entries each on average; if no k <= 4 does, the
+ *                           first condition alone decides.
  * stream_chunks lists the chunk ids class by class (class 1 first), ascending
  * inside a class; stream_offset[0..4] are the class boundaries in that list.
  *
@@ -162,10 +167,15 @@ static int chunk_class(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t 
     int64_t longest = 0;
     for (int64_t i = first; i < last; ++i)
         if (rowptr[i + 1] - rowptr[i] > longest) longest = rowptr[i + 1] - rowptr[i];
-    if (rowptr[last] - rowptr[first] < chunk_min_nnz) return 0;
-    for (int k = 1; k <= 4; ++k)
-        if (longest <= ((int64_t)1 << k) * chunk_rows) return k;
-    return 0;
+    int64_t entries = rowptr[last] - rowptr[first];
+    if (entries < chunk_min_nnz) return 0;
+    int by_length = 0;
+    for (int k = 4; k >= 1; --k)
+        if (longest <= ((int64_t)1 << k) * chunk_rows) by_length = k;
+    if (by_length == 0) return 0;
+    for (int k = by_length; k <= 4; ++k)
+        if (entries <= ((int64_t)1 << k) * 16 * chunk_rows) return k;
+    return by_length;
 }
 
 /* Pass 0: stream_chunks[] (caller provides ceil(nrows/chunk_rows) slots) and

@@ -46,7 +46,8 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *s_tm
 
 // Pass 0a: flag[c] = class of chunk c (chunk_rows consecutive rows): 0 if the chunk holds fewer
 // than min_nnz entries or a row has more than 16*chunk_rows entries, else the smallest k in 1..4
-// with (longest row) <= 2^k * chunk_rows.
+// with (longest row) <= 2^k * chunk_rows and (entries) <= 2^k * 16 * chunk_rows (the length
+// condition alone if no k meets the second one).
 __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32_t num_chunks,
                                                             int32_t chunk_rows, int32_t min_nnz,
                                                             const int32_t *__restrict__ rowptr,
@@ -65,9 +66,16 @@ __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32
         prev = cur;
     }
     int cls = 0;
-    if (prev - begin >= min_nnz) {
+    const int32_t entries = prev - begin;
+    if (entries >= min_nnz) {
         for (int k = 4; k >= 1; --k)
             if (longest <= (chunk_rows << k)) cls = k;
+        if (cls) {
+            int fit = 0;
+            for (int k = 4; k >= cls; --k)
+                if (entries <= ((chunk_rows * 16) << k)) fit = k;
+            if (fit) cls = fit;
+        }
     }
     flag[c] = cls;
 }

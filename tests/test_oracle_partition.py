@@ -38,6 +38,8 @@ def _independent_partition(rowptr, wave, long_threshold, tile_nnz, stream_rows, 
     chunk_nnz = rowptr[ends].astype(np.int64) - rowptr[starts]
     ratio = np.maximum(chunk_max, 1) / stream_rows
     cls = np.clip(np.ceil(np.log2(np.maximum(ratio, 1e-9))).astype(np.int64), 1, None)   # 2^k * rows >= max
+    fit = np.clip(np.ceil(np.log2(np.maximum(chunk_nnz, 1) / (16.0 * stream_rows))).astype(np.int64), 1, None)
+    cls = np.where((cls <= 4) & (fit <= 4), np.maximum(cls, fit), cls)                    # entries <= 2^k * 16 * rows
     cls[(cls > 4) | (chunk_nnz < stream_min_nnz)] = 0
     is_stream = cls > 0
     order = np.argsort(np.where(is_stream, cls, 99), kind="stable")
@@ -91,12 +93,13 @@ def test_partition_matches_independent_construction(wave, lt, tile, srows, smin,
 
 
 def test_stream_chunks_hand_worked():
-    """Chunks of 32 rows; class k = smallest k with max row length <= 2^k * 32 (k <= 4), class 0
-    (binned) when the chunk holds fewer than 256 entries or a row exceeds 512 entries."""
+    """Chunks of 32 rows; class k = smallest k with max row length <= 2^k * 32 and entries <=
+    2^k * 512 (k <= 4; the length alone if no k fits the entries), class 0 (binned) when the chunk
+    holds fewer than 256 entries or a row exceeds 512 entries."""
     L = np.array([8] * 32            # chunk 0: 256 entries, max 8                -> class 1
                  + [8] * 31 + [65]   # chunk 1: max 65                            -> class 2
                  + [7] * 32          # chunk 2: 224 entries, below the minimum    -> binned
-                 + [64] * 32         # chunk 3: rows exactly at 64                -> class 1
+                 + [64] * 32         # chunk 3: rows at 64, 2048 entries > 2*512  -> class 2
                  + [0] * 31 + [64]   # chunk 4: 64 entries                        -> binned
                  + [128] * 2 + [1] * 30   # chunk 5: max 128                      -> class 2
                  + [129] + [5] * 31  # chunk 6: max 129 (284 entries)             -> class 3
@@ -107,15 +110,21 @@ def test_stream_chunks_hand_worked():
     rowptr = np.zeros(L.size + 1, dtype=np.int32)
     np.cumsum(L, out=rowptr[1:])
     part = oracle.partition(rowptr)
-    assert part["stream_chunks"].tolist() == [0, 3, 9, 1, 5, 6, 7]
-    assert part["stream_offset"].tolist() == [0, 3, 5, 6, 7]
+    assert part["stream_chunks"].tolist() == [0, 9, 1, 3, 5, 6, 7]
+    assert part["stream_offset"].tolist() == [0, 2, 5, 6, 7]
+    # 32 rows of 300 entries: by length class 4 (300 <= 512); 9600 entries fit no 2^k * 512 -> stays 4
+    rp = np.arange(33, dtype=np.int32) * 300
+    assert oracle.partition(rp)["stream_offset"].tolist() == [0, 0, 0, 0, 1]
+    # 32 rows of 81 entries (2592 entries): by length class 2, by entries class 3
+    rp = np.arange(33, dtype=np.int32) * 81
+    assert oracle.partition(rp)["stream_offset"].tolist() == [0, 0, 0, 1, 1]
     binned = list(range(64, 96)) + list(range(128, 160)) + list(range(256, 288))
     assert sorted(part["row_perm"].tolist()) == binned
     # bins: 31 empty rows; 32 rows of 7 (bin 4); 31 rows of 9 (bin 5); one row of 64 (bin 7); one of 513 (bin 8)
     assert np.diff(part["bin_offset"]).tolist() == [31, 0, 0, 0, 32, 31, 0, 1, 1, 0]
     # with 6 rows in the ragged chunk: 240 entries -> binned
     part = oracle.partition(rowptr[:-1].copy())
-    assert part["stream_chunks"].tolist() == [0, 3, 1, 5, 6, 7]
+    assert part["stream_chunks"].tolist() == [0, 1, 3, 5, 6, 7]
 
 
 def test_partition_invariants_on_power_law_workload():
