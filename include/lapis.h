@@ -212,6 +212,11 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
                          int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
                          int32_t *h_tile_nz);
 
+/* max |column - row| over the matrix's entries, found by lapis_csr_create; lapis_spmm uses it to
+ * decide how workgroups are dealt to the 8 XCDs (band-wide windows of X rows that overflow one
+ * L2 are shared by all 8). */
+int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth);
+
 /* The partition constants compiled into the library, in the order
  * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ,
  *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ, LAPIS_SPLIT_BLOCK_BYTES, LAPIS_SPLIT_MAX_BLOCKS}. */

@@ -21,7 +21,7 @@ LAPIS_F32, LAPIS_F64 = 0, 1
 EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
-    "lapis_csr_copy_split", "lapis_partition_constants",
+    "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
     "lapis_last_error",
 ]
 
@@ -54,6 +54,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_copy_partition.argtypes = [p, p, p, p, p, p, p, p]
         lib.lapis_csr_split_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 6
         lib.lapis_csr_copy_split.argtypes = [p, p, p, p, p, p, p]
+        lib.lapis_csr_half_bandwidth.argtypes = [p, ctypes.POINTER(i64)]
         lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
@@ -182,3 +183,9 @@ def lapis_csr_copy_split(A):
     _check(load().lapis_csr_copy_split(A, ptr(res["cut"]), ptr(res["bin_offset"]), ptr(res["row_perm"]),
                                        ptr(res["long_off"]), ptr(res["tile_row"]), ptr(res["tile_nz"])))
     return res
+
+
+def lapis_csr_half_bandwidth(A):
+    v = ctypes.c_int64()
+    _check(load().lapis_csr_half_bandwidth(A, ctypes.byref(v)))
+    return v.value

@@ -232,6 +232,22 @@ __global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t 
 }
 
 
+// *out = max over all entries of |column - row| (the matrix's half bandwidth); *out must be 0 on entry.
+__global__ __launch_bounds__(kBlock) void half_bandwidth_kernel(int32_t nrows, const int32_t *__restrict__ rowptr,
+                                                                const int32_t *__restrict__ colidx,
+                                                                int32_t *__restrict__ out)
+{
+    int32_t best = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += (int64_t)gridDim.x * kBlock) {
+        const int32_t je = rowptr[i + 1];
+        for (int32_t j = rowptr[i]; j < je; ++j) {
+            const int32_t d = colidx[j] - (int32_t)i;
+            best = max(best, d < 0 ? -d : d);
+        }
+    }
+    if (best > 0) atomicMax(out, best);
+}
+
 // ---- column split of the rows above kWave entries ---------------------------
 // When x is far larger than a level-2 cache, the rows of the last two bins are cut at the
 // column-block boundaries b*W (b = 0..nb) into virtual rows, so that the gathers of one block

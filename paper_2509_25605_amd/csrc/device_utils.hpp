@@ -80,4 +80,16 @@ __device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t hw_id, uint32_t p
     return (hw_id % kXcds) * (padded / kXcds) + hw_id / kXcds;
 }
 
+// Block-cyclic variant: logical ids are dealt to the XCDs in blocks of `block` consecutive ids
+// (block b goes to XCD b % 8), and each XCD walks its blocks in ascending order.  With rows
+// numbered along a band of half-width h and block = h/8 rows, the 8 XCDs share every band-wide
+// window of rows instead of each owning one eighth of the matrix, so the dense operand rows a
+// window needs are spread over the 8 L2s rather than replicated in time.  `hw_id` < a grid
+// padded to a multiple of 8*block; ids >= the real count must be skipped by the caller.
+__device__ __forceinline__ uint32_t xcd_block_cyclic_id(uint32_t hw_id, uint32_t block)
+{
+    const uint32_t xcd = hw_id % kXcds, j = hw_id / kXcds;
+    return ((j / block) * kXcds + xcd) * block + j % block;
+}
+
 }  // namespace lapis

@@ -54,6 +54,7 @@ struct lapis_csr {
     int32_t *d_stream_chunks = nullptr;  // [num_stream] chunk ids, class by class, ascending in a class
     int32_t h_stream_offset[kStreamClasses + 1] = {0};   // class boundaries in that list
     int64_t num_chunks = 0, num_stream = 0;
+    int64_t half_bandwidth = 0;          // max |column - row| over the entries
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -252,6 +253,14 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         LAPIS_HIP(hipStreamSynchronize(stream));
         if (flags[0]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr is not non-decreasing");
         if (flags[1]) return fail(LAPIS_ERR_INVALID_ARG, "a column index is outside [0, ncols)");
+        LAPIS_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), stream));
+        half_bandwidth_kernel<<<dim3((uint32_t)((n + kBlock - 1) / kBlock < 65536 ? (n + kBlock - 1) / kBlock : 65536)),
+                                dim3(kBlock), 0, stream>>>((int32_t)n, A->rowptr, A->colidx, d_flags);
+        int32_t hb = 0;
+        LAPIS_HIP(hipMemcpyAsync(&hb, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        A->half_bandwidth = hb;
+        LAPIS_HIP(hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream));
     } else if (A->nnz != 0) {
         return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
     }
@@ -424,13 +433,25 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
     constexpr int kSlots = kBlock / CL;
     if (A->num_stream > 0) {                                          // rows of the stream chunks
         const uint32_t chunks = (uint32_t)A->num_stream;
-        const uint32_t padded = (chunks + kXcds - 1) / kXcds * kXcds;
         const int32_t *list = (A->num_stream == A->num_chunks) ? nullptr : A->d_stream_chunks;  // any order
         constexpr int kStreamLanes = CL > 16 ? 16 : CL;               // wider rows of X: several column blocks
+        // Rows of X a band-wide window of matrix rows touches: if they overflow an XCD's L2 when one
+        // XCD walks the window alone, deal the chunks to the XCDs block-cyclically (block = 1/8 of
+        // the half bandwidth) so that the 8 L2s share the window.  Only when every chunk streams
+        // (the list is then the identity and chunk order = row order).
+        const int64_t cols_here = k < (int64_t)kStreamLanes * VEC ? k : (int64_t)kStreamLanes * VEC;
+        const int64_t window_bytes = (2 * A->half_bandwidth + 1) * cols_here * (int64_t)sizeof(T);
+        uint32_t xcd_block = 0;
+        if (!list && window_bytes > (int64_t)LAPIS_SPLIT_BLOCK_BYTES) {
+            const int64_t b = A->half_bandwidth / kXcds / LAPIS_STREAM_ROWS;
+            if (b >= 1 && b * kXcds < chunks) xcd_block = (uint32_t)b;
+        }
+        const uint32_t unit = xcd_block ? xcd_block * kXcds : kXcds;
+        const uint32_t padded = (chunks + unit - 1) / unit * unit;
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC)
             spmm_stream_kernel<T, VEC, kStreamLanes, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, A->colidx, vals, k, c0,
-                X, ldx, Y, ldy, a, b);
+                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx, vals,
+                k, c0, X, ldx, Y, ldy, a, b);
     }
     if (n_rows_a > 0) {
         const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);
@@ -613,6 +634,13 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
     if (h_cut)
         LAPIS_HIP(hipMemcpy(h_cut, A->d_cut, sizeof(int32_t) * (size_t)((A->num_blocks + 1) * A->num_split), hipMemcpyDeviceToHost));
     return copy_set(A->vrows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);
+}
+
+int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth)
+{
+    if (!A || !half_bandwidth) return fail(LAPIS_ERR_INVALID_ARG, "NULL argument");
+    *half_bandwidth = A->half_bandwidth;
+    return LAPIS_OK;
 }
 
 int lapis_partition_constants(int64_t h_out[8])

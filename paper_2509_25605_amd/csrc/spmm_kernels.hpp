@@ -54,14 +54,16 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 // Columns [c0, min(c0 + CL*VEC, k)) of Y for the rows of the stream chunks.
 // One wavefront (= one workgroup) per chunk; stream_chunks == nullptr means
 // every chunk of the matrix.  colidx and vals 16-byte aligned, nnz4 = nnz & ~3.
+// xcd_block == 0: each XCD owns a contiguous stretch of the chunk list; otherwise chunks are
+// dealt to the XCDs block-cyclically, xcd_block chunks at a time (see xcd_block_cyclic_id).
 constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 template <typename T, int VEC, int CL, bool XCD_REMAP>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
-    const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k, int64_t c0,
-    const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
+    uint32_t xcd_block, const int32_t *__restrict__ colidx, const T *__restrict__ vals, int64_t k,
+    int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
 {
     static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
     constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
@@ -70,7 +72,9 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
     __shared__ int32_t s_rp[kStreamRows + 1];
 
-    const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_chunks) : blockIdx.x;
+    const uint32_t id = !XCD_REMAP ? blockIdx.x
+                        : xcd_block ? xcd_block_cyclic_id(blockIdx.x, xcd_block)
+                                    : xcd_contiguous_id(blockIdx.x, padded_chunks);
     if (id >= num_chunks) return;
     const int lane = threadIdx.x;
     const int slot = lane / CL;

@@ -87,6 +87,7 @@ def test_null_handles_and_out_pointer(lib):
     assert lib.lapis_csr_copy_partition(None, None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_split_sizes(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_csr_copy_split(None, None, None, None, None, None, None) == L.LAPIS_ERR_INVALID_ARG
+    assert lib.lapis_csr_half_bandwidth(None, None) == L.LAPIS_ERR_INVALID_ARG
     assert lib.lapis_partition_constants(None) == L.LAPIS_ERR_INVALID_ARG
     with pytest.raises(L.LapisError) as e:
         L.lapis_spmv(None, 1.0, 8, 0.0, 8, stream=0)

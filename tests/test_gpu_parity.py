@@ -18,6 +18,12 @@ def say(msg):
     print(f"[case] {msg}", file=sys.stderr, flush=True)
 
 
+def check_half_bandwidth(dev, rowptr, colidx):
+    rows = np.repeat(np.arange(rowptr.size - 1, dtype=np.int64), np.diff(rowptr))
+    expect = int(np.abs(colidx.astype(np.int64) - rows).max()) if colidx.size else 0
+    assert dev.L.lapis_csr_half_bandwidth(dev.mat.handle) == expect
+
+
 def check_partition(dev, rowptr):
     ref = oracle.partition(rowptr)
     got = dev.partition()
@@ -326,6 +332,7 @@ def run_workload(cfg, scale):
     dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
     try:
         check_partition(dev, w.rowptr)
+        check_half_bandwidth(dev, w.rowptr, w.colidx)
         check_split(dev, w.rowptr, w.colidx, w.ncols, w.vals.itemsize)
         if w.k == 0:
             check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0, literal=True, what=w.name)
