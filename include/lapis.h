@@ -222,6 +222,42 @@ int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth);
  *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ, LAPIS_SPLIT_BLOCK_BYTES, LAPIS_SPLIT_MAX_BLOCKS}. */
 int lapis_partition_constants(int64_t h_out[8]);
 
+/* ---- host-side buffers with lazy synchronisation (after Section 4.3) ---------
+ * A dual view pairs a pinned host buffer with a device buffer of the same size and keeps one
+ * "modified" flag per side.  lapis_dualview_modify_host / _device only set a flag;
+ * lapis_dualview_sync_device / _host copy the whole allocation to the named side only if the
+ * other side was modified since the last sync, so a sync with nothing to do costs a flag test
+ * (Section 4.3: lazy kokkos.sync / kokkos.modify instead of copying every buffer around every
+ * kernel).  A sync while both sides are marked modified returns LAPIS_ERR_INVALID_ARG.
+ * lapis_dualview_sync_host also synchronises the stream, so the host may read at once.
+ * lapis_dualview_subview creates a view of `bytes` bytes at `offset_bytes` inside a parent: it
+ * aliases the parent's memory, shares its flags (syncing a sub-view syncs the whole parent) and
+ * keeps the memory alive until the last view of the allocation is destroyed.
+ * lapis_dualview_host returns a HOST pointer, lapis_dualview_device a device pointer.
+ * lapis_dualview_copy_counts reports how many host-to-device and device-to-host copies the
+ * allocation has actually performed.
+ * lapis_spmv_dualview: y = alpha*A*x + beta*y on dual views holding x (ncols values) and y
+ * (nrows values) of A's dtype: syncs x and y to the device if needed (y's host copy is dropped
+ * instead when beta == 0 and y is a whole allocation), runs lapis_spmv, marks y modified on the
+ * device.  x and y may be sub-views of one allocation but must not overlap; a view smaller than
+ * its operand is LAPIS_ERR_INVALID_ARG.  All functions here return a LAPIS_* status except the
+ * two pointer getters (NULL for a NULL view); lapis_dualview_destroy(NULL) is a no-op.
+ */
+typedef struct lapis_dualview lapis_dualview_t;
+int lapis_dualview_create(lapis_dualview_t **out, int64_t bytes);
+int lapis_dualview_subview(lapis_dualview_t **out, lapis_dualview_t *parent, int64_t offset_bytes,
+                           int64_t bytes);
+void *lapis_dualview_host(lapis_dualview_t *v);
+void *lapis_dualview_device(lapis_dualview_t *v);
+int lapis_dualview_modify_host(lapis_dualview_t *v);
+int lapis_dualview_modify_device(lapis_dualview_t *v);
+int lapis_dualview_sync_device(lapis_dualview_t *v, void *hip_stream);
+int lapis_dualview_sync_host(lapis_dualview_t *v, void *hip_stream);
+int lapis_dualview_copy_counts(const lapis_dualview_t *v, int64_t *h2d, int64_t *d2h);
+int lapis_dualview_destroy(lapis_dualview_t *v);
+int lapis_spmv_dualview(const lapis_csr_t *A, double alpha, lapis_dualview_t *x, double beta,
+                        lapis_dualview_t *y, void *hip_stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on that thread. */
 const char *lapis_last_error(void);

@@ -22,6 +22,10 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
+    "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
+    "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
+    "lapis_dualview_sync_host", "lapis_dualview_copy_counts", "lapis_dualview_destroy",
+    "lapis_spmv_dualview",
     "lapis_last_error",
 ]
 
@@ -42,6 +46,10 @@ def load() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(
                 f"{LIB_PATH} is not built; run paper_2509_25605_amd.build.build() first")
+        # One HIP runtime per process: PyTorch (which owns the streams and the device memory the
+        # callers pass in) ships its own, so it is loaded first and this library binds to it.
+        import torch  # noqa: F401
+
         lib = ctypes.CDLL(LIB_PATH)
         i64, f64, p, i32 = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_int
         lib.lapis_csr_create.argtypes = [ctypes.POINTER(p), i64, i64, i64, p, p, p, i32, p]
@@ -56,8 +64,20 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_copy_split.argtypes = [p, p, p, p, p, p, p]
         lib.lapis_csr_half_bandwidth.argtypes = [p, ctypes.POINTER(i64)]
         lib.lapis_partition_constants.argtypes = [ctypes.POINTER(i64)]
+        lib.lapis_dualview_create.argtypes = [ctypes.POINTER(p), i64]
+        lib.lapis_dualview_subview.argtypes = [ctypes.POINTER(p), p, i64, i64]
+        for name in ("lapis_dualview_host", "lapis_dualview_device"):
+            getattr(lib, name).argtypes = [p]
+        for name in ("lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_destroy"):
+            getattr(lib, name).argtypes = [p]
+        for name in ("lapis_dualview_sync_device", "lapis_dualview_sync_host"):
+            getattr(lib, name).argtypes = [p, p]
+        lib.lapis_dualview_copy_counts.argtypes = [p, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        lib.lapis_spmv_dualview.argtypes = [p, f64, p, f64, p, p]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
+        lib.lapis_dualview_host.restype = p
+        lib.lapis_dualview_device.restype = p
         lib.lapis_last_error.restype = ctypes.c_char_p
         lib.lapis_last_error.argtypes = []
         _lib = lib
@@ -189,3 +209,60 @@ def lapis_csr_half_bandwidth(A):
     v = ctypes.c_int64()
     _check(load().lapis_csr_half_bandwidth(A, ctypes.byref(v)))
     return v.value
+
+
+class DualView:
+    """Thin owner of a lapis_dualview_t: a pinned host buffer (exposed as a NumPy array) paired
+    with a device buffer, synchronised lazily."""
+
+    def __init__(self, count=None, dtype=np.float64, _handle=None, _count=None):
+        self.dtype = np.dtype(dtype)
+        if _handle is None:
+            h = ctypes.c_void_p()
+            _check(load().lapis_dualview_create(ctypes.byref(h), int(count) * self.dtype.itemsize))
+            self.handle, self.count = h, int(count)
+        else:
+            self.handle, self.count = _handle, _count
+
+    def subview(self, first, count):
+        h = ctypes.c_void_p()
+        _check(load().lapis_dualview_subview(ctypes.byref(h), self.handle, first * self.dtype.itemsize,
+                                             count * self.dtype.itemsize))
+        return DualView(dtype=self.dtype, _handle=h, _count=count)
+
+    @property
+    def host(self):
+        """NumPy view of the host buffer (call modify_host() after writing to it)."""
+        addr = load().lapis_dualview_host(self.handle)
+        buf = (ctypes.c_char * (self.count * self.dtype.itemsize)).from_address(addr)
+        return np.frombuffer(buf, dtype=self.dtype, count=self.count)
+
+    @property
+    def device_ptr(self):
+        return load().lapis_dualview_device(self.handle)
+
+    def modify_host(self):
+        _check(load().lapis_dualview_modify_host(self.handle))
+
+    def modify_device(self):
+        _check(load().lapis_dualview_modify_device(self.handle))
+
+    def sync_device(self, stream=None):
+        _check(load().lapis_dualview_sync_device(self.handle, _stream(stream)))
+
+    def sync_host(self, stream=None):
+        _check(load().lapis_dualview_sync_host(self.handle, _stream(stream)))
+
+    def copy_counts(self):
+        a, b = ctypes.c_int64(), ctypes.c_int64()
+        _check(load().lapis_dualview_copy_counts(self.handle, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+    def close(self):
+        if self.handle is not None:
+            _check(load().lapis_dualview_destroy(self.handle))
+            self.handle = None
+
+
+def lapis_spmv_dualview(A, alpha, x: "DualView", beta, y: "DualView", stream=None):
+    _check(load().lapis_spmv_dualview(A, float(alpha), x.handle, float(beta), y.handle, _stream(stream)))

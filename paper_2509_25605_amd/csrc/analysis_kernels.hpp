@@ -80,23 +80,68 @@ __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32
     flag[c] = cls;
 }
 
-// Pass 0b (one workgroup): ascending list of the chunk ids of class `cls`; *count = how many.
-__global__ __launch_bounds__(kBlock) void chunk_compact_kernel(int32_t num_chunks, int32_t cls,
-                                                               const int32_t *__restrict__ flag,
-                                                               int32_t *__restrict__ list,
-                                                               int32_t *__restrict__ count)
+// Pass 0b (one workgroup of kCompactBlock threads): list = the chunk ids of class 1, then of
+// class 2, ... each class ascending; offset[k] = position of the first chunk of class k+1,
+// offset[kChunkClasses] = number of listed chunks.  flag holds values 0..kChunkClasses.
+constexpr int kChunkClasses = 4;
+constexpr int kCompactBlock = 1024;
+__global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t num_chunks,
+                                                                      const int32_t *__restrict__ flag,
+                                                                      int32_t *__restrict__ list,
+                                                                      int32_t *__restrict__ offset)
 {
-    __shared__ int32_t s_tmp[kBlock];
-    int32_t running = 0;
-    for (int64_t base = 0; base < num_chunks; base += kBlock) {
-        const int64_t c = base + threadIdx.x;
-        const int32_t v = (c < num_chunks && flag[c] == cls) ? 1 : 0;
-        int32_t total;
-        const int32_t excl = block_exclusive_scan(v, s_tmp, &total);
-        if (v) list[running + excl] = (int32_t)c;
-        running += total;
+    constexpr int kWaves = kCompactBlock / kWave;
+    __shared__ int32_t s_base[kChunkClasses + 1];
+    __shared__ int32_t s_wave[kWaves][kChunkClasses];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    if (threadIdx.x <= kChunkClasses) s_base[threadIdx.x] = 0;
+    __syncthreads();
+    // class totals
+    int32_t cnt[kChunkClasses] = {0, 0, 0, 0};
+    for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
+        const int32_t f = flag[c];
+#pragma unroll
+        for (int k = 0; k < kChunkClasses; ++k) cnt[k] += (f == k + 1);
     }
-    if (threadIdx.x == 0) *count = running;
+#pragma unroll
+    for (int k = 0; k < kChunkClasses; ++k)
+        if (cnt[k]) atomicAdd(&s_base[k + 1], cnt[k]);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k <= kChunkClasses; ++k) s_base[k] += s_base[k - 1];
+        for (int k = 0; k <= kChunkClasses; ++k) offset[k] = s_base[k];
+    }
+    __syncthreads();
+    int32_t running[kChunkClasses];
+#pragma unroll
+    for (int k = 0; k < kChunkClasses; ++k) running[k] = s_base[k];
+    // ordered scatter: ballots give the position inside the wavefront, LDS the counts of the others
+    for (int64_t base = 0; base < num_chunks; base += kCompactBlock) {
+        const int64_t c = base + threadIdx.x;
+        const int32_t f = (c < num_chunks) ? flag[c] : 0;
+        uint64_t mine = 0;
+#pragma unroll
+        for (int k = 0; k < kChunkClasses; ++k) {
+            const uint64_t m = __builtin_amdgcn_ballot_w64(f == k + 1);
+            if (lane == 0) s_wave[wave][k] = __popcll(m);
+            if (f == k + 1) mine = m;
+        }
+        __syncthreads();
+        int32_t before = 0;
+#pragma unroll
+        for (int k = 0; k < kChunkClasses; ++k) {
+            int32_t all = 0;
+            for (int w = 0; w < kWaves; ++w) {
+                const int32_t n = s_wave[w][k];
+                if (w < wave && f == k + 1) before += n;
+                all += n;
+            }
+            if (f == k + 1) before += running[k];
+            running[k] += all;
+        }
+        if (f) list[before + __popcll(mine & ((1ull << lane) - 1))] = (int32_t)c;
+        __syncthreads();
+    }
 }
 
 // Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped; chunk_flag
@@ -232,20 +277,54 @@ __global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t 
 }
 
 
-// *out = max over all entries of |column - row| (the matrix's half bandwidth); *out must be 0 on entry.
-__global__ __launch_bounds__(kBlock) void half_bandwidth_kernel(int32_t nrows, const int32_t *__restrict__ rowptr,
-                                                                const int32_t *__restrict__ colidx,
-                                                                int32_t *__restrict__ out)
+// One pass over the structure, entry-parallel (each entry finds its row by bisection of rowptr
+// inside the row range of its tile of kCheckTile consecutive entries).  flags must be 0 on entry:
+//   flags[0] = 1 if rowptr decreases somewhere     flags[1] = 1 if a column is outside [0, ncols)
+//   flags[2] = max |column - row| over the entries (the half bandwidth)
+//   flags[3] = 1 if some row has a column smaller than its predecessor
+//   flags[4] = 1 if rowptr[0] != 0 or rowptr[nrows] != nnz
+// With flags[0] or flags[4] set, flags[2] and flags[3] are meaningless (every access stays in
+// bounds all the same: row ids stay in [0, nrows) and entry ids in [0, nnz)).  nrows >= 1.
+constexpr int kCheckTile = kBlock * 8;
+constexpr int kNumCheckFlags = 5;
+__global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, int64_t ncols, int32_t nnz,
+                                                                 const int32_t *__restrict__ rowptr,
+                                                                 const int32_t *__restrict__ colidx,
+                                                                 int32_t *__restrict__ flags)
 {
+    bool bad_row = false, bad_col = false, unsorted = false;
     int32_t best = 0;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += (int64_t)gridDim.x * kBlock) {
-        const int32_t je = rowptr[i + 1];
-        for (int32_t j = rowptr[i]; j < je; ++j) {
-            const int32_t d = colidx[j] - (int32_t)i;
-            best = max(best, d < 0 ? -d : d);
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += stride)
+        bad_row |= rowptr[i + 1] < rowptr[i];
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (rowptr[0] != 0 || rowptr[nrows] != nnz)) flags[4] = 1;
+    // largest row id r in [lo, hi] with rowptr[r] <= j (rows before it that start at the same
+    // entry are empty)
+    auto row_of = [&](int32_t j, int32_t lo, int32_t hi) {
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo + 1) / 2;
+            if (rowptr[mid] <= j) lo = mid; else hi = mid - 1;
+        }
+        return lo;
+    };
+    for (int64_t t0 = (int64_t)blockIdx.x * kCheckTile; t0 < nnz; t0 += (int64_t)gridDim.x * kCheckTile) {
+        const int32_t j0 = (int32_t)t0;
+        const int32_t j1 = (int32_t)((t0 + kCheckTile < nnz) ? t0 + kCheckTile : nnz);
+        const int32_t first = row_of(j0, 0, nrows - 1), last = row_of(j1 - 1, first, nrows - 1);
+        for (int32_t j = j0 + (int32_t)threadIdx.x; j < j1; j += kBlock) {
+            const int32_t r = row_of(j, first, last);
+            const int32_t c = colidx[j];
+            bad_col |= (c < 0) | (c >= ncols);
+            const int64_t d = (int64_t)c - r;
+            const int64_t ad = d < 0 ? -d : d;
+            best = max(best, (int32_t)(ad < INT32_MAX ? ad : INT32_MAX));
+            if (j + 1 < nnz && j + 1 < rowptr[r + 1]) unsorted |= c > colidx[j + 1];
         }
     }
-    if (best > 0) atomicMax(out, best);
+    if (bad_row) flags[0] = 1;
+    if (bad_col) flags[1] = 1;
+    if (best > 0) atomicMax(&flags[2], best);
+    if (unsorted) flags[3] = 1;
 }
 
 // ---- column split of the rows above kWave entries ---------------------------

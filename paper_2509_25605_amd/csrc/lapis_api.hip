@@ -9,6 +9,7 @@
 #include <new>
 #include <string>
 
+#include "internal.hpp"
 #include "../../include/lapis.h"
 #include "analysis_kernels.hpp"
 #include "spmm_kernels.hpp"
@@ -68,14 +69,25 @@ struct lapis_csr {
 };
 
 namespace {
-
 thread_local std::string g_last_error;
+}
 
-int fail(int code, const std::string &msg)
+int lapis::fail(int code, const std::string &msg)
 {
     g_last_error = msg;
     return code;
 }
+
+void lapis::vector_bytes(const lapis_csr *A, int64_t *x_bytes, int64_t *y_bytes)
+{
+    const int64_t esize = A->dtype == LAPIS_F64 ? 8 : 4;
+    *x_bytes = A->ncols * esize;
+    *y_bytes = A->nrows * esize;
+}
+
+namespace {
+
+using lapis::fail;
 
 int fail_hip(hipError_t e, const char *what)
 {
@@ -129,24 +141,6 @@ void free_handle(lapis_csr *A)
 }
 
 size_t value_size(const lapis_csr *A) { return A->dtype == LAPIS_F64 ? sizeof(double) : sizeof(float); }
-
-// flags[0]: a row has negative length; flags[1]: a column index is out of range
-__global__ __launch_bounds__(kBlock) void validate_kernel(int64_t nrows, int64_t ncols, int64_t nnz,
-                                                          const int32_t *__restrict__ rowptr,
-                                                          const int32_t *__restrict__ colidx,
-                                                          int32_t *__restrict__ flags)
-{
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    bool bad_row = false, bad_col = false;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += stride)
-        bad_row |= rowptr[i + 1] < rowptr[i];
-    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < nnz; j += stride) {
-        const int32_t c = colidx[j];
-        bad_col |= (c < 0) | (c >= ncols);
-    }
-    if (bad_row) flags[0] = 1;
-    if (bad_col) flags[1] = 1;
-}
 
 // Workgroup ranges of bins 0..last_bin of a set; every bin is padded to a multiple of the XCD count.
 void build_short_plan(const BinnedSet &s, int last_bin, ShortPlan *p)
@@ -231,36 +225,27 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     const int64_t n = A->nrows;
     const size_t esize = value_size(A);
     DeviceTemp flags_mem;
-    if (int rc = flags_mem.alloc(2 * sizeof(int32_t))) return rc;
+    if (int rc = flags_mem.alloc(kNumCheckFlags * sizeof(int32_t))) return rc;
     int32_t *d_flags = flags_mem.as<int32_t>();
-    LAPIS_HIP(hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream));
+    LAPIS_HIP(hipMemsetAsync(d_flags, 0, kNumCheckFlags * sizeof(int32_t), stream));
 
-    // structural checks the kernels rely on: rowptr ends, monotone rowptr, column range
+    // structural checks the kernels rely on (rowptr ends, monotone rowptr, column range), the half
+    // bandwidth and whether every row's columns ascend: one pass
+    bool rows_sorted = false;
     if (n > 0) {
-        int32_t ends[2] = {0, 0};
-        LAPIS_HIP(hipMemcpyAsync(&ends[0], A->rowptr, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipMemcpyAsync(&ends[1], A->rowptr + n, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
-        if (ends[0] != 0 || ends[1] != A->nnz)
-            return fail(LAPIS_ERR_INVALID_ARG, "rowptr[0] must be 0 and rowptr[nrows] must equal nnz");
-        const int64_t work = (n > A->nnz ? n : A->nnz);
-        int64_t vblocks = (work + kBlock - 1) / kBlock;
-        if (vblocks > 8192) vblocks = 8192;
-        validate_kernel<<<dim3((uint32_t)vblocks), dim3(kBlock), 0, stream>>>(
-            n, A->ncols, A->nnz, A->rowptr, A->colidx, d_flags);
-        int32_t flags[2] = {0, 0};
+        int64_t vblocks = ((n > A->nnz ? n : A->nnz) + kCheckTile - 1) / kCheckTile;
+        if (vblocks > 16384) vblocks = 16384;
+        structure_check_kernel<<<dim3((uint32_t)vblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, A->ncols, (int32_t)A->nnz, A->rowptr, A->colidx, d_flags);
+        LAPIS_HIP(hipGetLastError());
+        int32_t flags[kNumCheckFlags] = {0};
         LAPIS_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
         LAPIS_HIP(hipStreamSynchronize(stream));
+        if (flags[4]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr[0] must be 0 and rowptr[nrows] must equal nnz");
         if (flags[0]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr is not non-decreasing");
         if (flags[1]) return fail(LAPIS_ERR_INVALID_ARG, "a column index is outside [0, ncols)");
-        LAPIS_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), stream));
-        half_bandwidth_kernel<<<dim3((uint32_t)((n + kBlock - 1) / kBlock < 65536 ? (n + kBlock - 1) / kBlock : 65536)),
-                                dim3(kBlock), 0, stream>>>((int32_t)n, A->rowptr, A->colidx, d_flags);
-        int32_t hb = 0;
-        LAPIS_HIP(hipMemcpyAsync(&hb, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
-        A->half_bandwidth = hb;
-        LAPIS_HIP(hipMemsetAsync(d_flags, 0, 2 * sizeof(int32_t), stream));
+        A->half_bandwidth = flags[2];
+        rows_sorted = !flags[3];
     } else if (A->nnz != 0) {
         return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
     }
@@ -278,17 +263,16 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     if (n > 0) {
         chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, chunk_flag.as<int32_t>());
-        for (int cls = 1; cls <= kStreamClasses; ++cls) {
-            A->h_stream_offset[cls - 1] = num_stream;
-            chunk_compact_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
-                num_chunks, cls, chunk_flag.as<int32_t>(), A->d_stream_chunks + num_stream, d_flags);
-            LAPIS_HIP(hipGetLastError());
-            int32_t count = 0;
-            LAPIS_HIP(hipMemcpyAsync(&count, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-            LAPIS_HIP(hipStreamSynchronize(stream));
-            num_stream += count;
-        }
-        A->h_stream_offset[kStreamClasses] = num_stream;
+        static_assert(kChunkClasses == kStreamClasses, "one list per stream class");
+        DeviceTemp offsets;
+        if (int rc = offsets.alloc(sizeof(int32_t) * (kStreamClasses + 1))) return rc;
+        chunk_compact_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
+            num_chunks, chunk_flag.as<int32_t>(), A->d_stream_chunks, offsets.as<int32_t>());
+        LAPIS_HIP(hipGetLastError());
+        LAPIS_HIP(hipMemcpyAsync(A->h_stream_offset, offsets.as<int32_t>(), sizeof(int32_t) * (kStreamClasses + 1),
+                                 hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        num_stream = A->h_stream_offset[kStreamClasses];
     }
     A->num_stream = num_stream;
 
@@ -304,7 +288,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     const int64_t S = A->rows.h_bin_offset[kNumBins] - A->rows.h_bin_offset[kNumBins - 2];
     bool split = nb > 0 && S > 0 && (nb + 1) * S <= INT32_MAX;
     const int32_t *split_rows = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
-    if (split) {
+    if (split && !rows_sorted) {   // some row is unsorted: look at the split rows themselves
         LAPIS_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), stream));
         const uint32_t sblocks = (uint32_t)(S < 65536 ? S : 65536);
         split_sorted_kernel<<<dim3(sblocks), dim3(kBlock), 0, stream>>>((int32_t)S, split_rows, A->rowptr,

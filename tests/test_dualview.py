@@ -1,0 +1,116 @@
+"""Host buffers with lazy synchronisation (Section 4.3 of the paper): copies happen only when
+the other side was modified, sub-views share their parent's flags, and the product computed
+through them equals the oracle's."""
+import numpy as np
+import pytest
+
+import gen
+import oracle
+import paper_2509_25605_amd as lapis
+from helpers import DeviceCsr, assert_close, general_bound
+
+
+def test_null_arguments_are_errors():
+    L = lapis.load()
+    assert L.lapis_dualview_create(None, 16) == lapis.LAPIS_ERR_INVALID_ARG
+    assert "out is NULL" in lapis.lapis_last_error()
+    assert L.lapis_dualview_modify_host(None) == lapis.LAPIS_ERR_INVALID_ARG
+    assert L.lapis_dualview_sync_device(None, None) == lapis.LAPIS_ERR_INVALID_ARG
+    assert L.lapis_dualview_sync_host(None, None) == lapis.LAPIS_ERR_INVALID_ARG
+    assert L.lapis_dualview_copy_counts(None, None, None) == lapis.LAPIS_ERR_INVALID_ARG
+    assert L.lapis_spmv_dualview(None, 1.0, None, 0.0, None, None) == lapis.LAPIS_ERR_INVALID_ARG
+    assert L.lapis_dualview_destroy(None) == lapis.LAPIS_OK
+    assert L.lapis_dualview_host(None) is None and L.lapis_dualview_device(None) is None
+
+
+@pytest.mark.gpu
+def test_sync_copies_only_when_modified():
+    v = lapis.DualView(1000, np.float64)
+    try:
+        assert v.copy_counts() == (0, 0)
+        v.sync_device(); v.sync_host()
+        assert v.copy_counts() == (0, 0)           # nothing modified: nothing copied
+        v.host[:] = np.arange(1000)
+        v.modify_host()
+        v.sync_device(); v.sync_device()
+        assert v.copy_counts() == (1, 0)
+        v.host[:] = -1.0                           # host scribble without modify(): device copy wins below
+        v.modify_device()
+        v.sync_host(); v.sync_host()
+        assert v.copy_counts() == (1, 1)
+        assert np.array_equal(v.host, np.arange(1000, dtype=np.float64))
+        v.modify_host(); v.modify_device()         # both sides modified: no copy can be right
+        with pytest.raises(lapis.LapisError) as e:
+            v.sync_device()
+        assert e.value.code == lapis.LAPIS_ERR_INVALID_ARG
+        with pytest.raises(lapis.LapisError):
+            v.sync_host()
+    finally:
+        v.close()
+
+
+@pytest.mark.gpu
+def test_subviews_share_flags_and_keep_memory_alive():
+    parent = lapis.DualView(300, np.float32)
+    a, b = parent.subview(0, 100), parent.subview(100, 200)
+    with pytest.raises(lapis.LapisError):
+        parent.subview(200, 101)
+    parent.host[:] = np.arange(300, dtype=np.float32)
+    assert np.array_equal(b.host, np.arange(100, 300, dtype=np.float32))   # aliases, not copies
+    a.modify_host()
+    b.sync_device()                                # the flag set through a is seen through b
+    assert parent.copy_counts() == (1, 0) and a.copy_counts() == (1, 0)
+    parent.close()                                 # children keep the allocation alive
+    b.host[:] = 7.0
+    b.modify_host(); a.sync_device()
+    assert b.copy_counts() == (2, 0)
+    a.modify_device(); b.sync_host()
+    assert np.all(b.host == 7.0) and np.array_equal(a.host, np.arange(100, dtype=np.float32))
+    a.close(); b.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+def test_spmv_through_dualviews_matches_oracle_and_skips_copies(dtype):
+    rng = np.random.default_rng(5)
+    lengths = rng.integers(0, 90, size=3001)
+    rowptr, colidx, vals = gen.random_csr(3001, 2777, lengths, seed=11, dtype=dtype)
+    x = gen.normal(12, 2, 2777).astype(dtype)
+    y0 = gen.normal(12, 3, 3001).astype(dtype)
+    nnz_row = np.diff(rowptr)
+    A = DeviceCsr(3001, 2777, rowptr, colidx, vals)
+    xv, yv = lapis.DualView(2777, dtype), lapis.DualView(3001, dtype)
+    try:
+        xv.host[:] = x; xv.modify_host()
+        yv.host[:] = y0; yv.modify_host()
+        lapis.lapis_spmv_dualview(A.mat.handle, 1.5, xv, -0.5, yv)
+        assert xv.copy_counts() == (1, 0) and yv.copy_counts() == (1, 0)
+        yv.sync_host()
+        ref, absax = oracle.spmv(rowptr, colidx, vals, x, 1.5, -0.5, y0)
+        assert_close(yv.host, ref, general_bound(nnz_row, absax, dtype, 1.5, -0.5, y0))
+        # same A, same x, beta = 0: nothing travels to the device, one copy back
+        lapis.lapis_spmv_dualview(A.mat.handle, 2.0, xv, 0.0, yv)
+        lapis.lapis_spmv_dualview(A.mat.handle, 2.0, xv, 0.0, yv)
+        assert xv.copy_counts() == (1, 0) and yv.copy_counts() == (1, 1)
+        yv.sync_host(); yv.sync_host()
+        assert yv.copy_counts() == (1, 2)
+        ref, absax = oracle.spmv(rowptr, colidx, vals, x, 2.0, 0.0, None)
+        assert_close(yv.host, ref, general_bound(nnz_row, absax, dtype, 2.0, 0.0, None))
+        # x and y as sub-views of one allocation; too-small and overlapping views are refused
+        both = lapis.DualView(2777 + 3001, dtype)
+        xs, ys = both.subview(0, 2777), both.subview(2777, 3001)
+        xs.host[:] = x; ys.host[:] = y0; both.modify_host()
+        lapis.lapis_spmv_dualview(A.mat.handle, 1.0, xs, 1.0, ys)
+        ys.sync_host()
+        assert both.copy_counts() == (1, 1)
+        ref, absax = oracle.spmv(rowptr, colidx, vals, x, 1.0, 1.0, y0)
+        assert_close(ys.host, ref, general_bound(nnz_row, absax, dtype, 1.0, 1.0, y0))
+        assert np.array_equal(xs.host, x)
+        with pytest.raises(lapis.LapisError):
+            lapis.lapis_spmv_dualview(A.mat.handle, 1.0, both, 0.0, ys)
+        with pytest.raises(lapis.LapisError):
+            lapis.lapis_spmv_dualview(A.mat.handle, 1.0, ys, 0.0, xs)
+        for v in (xs, ys, both):
+            v.close()
+    finally:
+        xv.close(); yv.close(); A.close()

@@ -283,6 +283,38 @@ def test_spmv_column_split(dtype, srt):
         dev.close()
 
 
+def test_column_split_looks_only_at_the_split_rows():
+    """Unsorted columns in rows of at most 64 entries do not switch the split off; a single
+    descent inside one split row does."""
+    say("column split with unsorted short rows")
+    n, ncols = 2000, (1 << 19) + 777
+    L = mixed_lengths(n, 72, 30000)
+    L[5::13] = 65 + (np.arange(L[5::13].size) * 37) % 3000
+    L = np.minimum(L, ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 556, np.float64, sorted_cols=True)
+    x = gen.uniform(14, gen.STREAM_X, ncols)
+    short = np.flatnonzero((np.diff(rowptr) >= 2) & (np.diff(rowptr) <= 64))
+    for r in short[::3]:                             # reverse the columns of some short rows
+        a, b = rowptr[r], rowptr[r + 1]
+        colidx[a:b] = colidx[a:b][::-1].copy()
+        vals[a:b] = vals[a:b][::-1].copy()
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_split(dev, rowptr, colidx, ncols, 8, expect_on=True)
+        check_spmv(dev, rowptr, colidx, vals, x, what="short rows unsorted")
+    finally:
+        dev.close()
+    long_row = int(np.flatnonzero(np.diff(rowptr) > 4096)[0])
+    a = rowptr[long_row] + 2000
+    colidx[a], colidx[a + 1] = colidx[a + 1], colidx[a]      # the last pair of a check tile or not: any place
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_split(dev, rowptr, colidx, ncols, 8, expect_on=False)
+        check_spmv(dev, rowptr, colidx, vals, x, what="one descent in a long row")
+    finally:
+        dev.close()
+
+
 def test_workload4_wide_reduced():
     """Power-law rows over 2^21 columns: x = 8 MB of floats, so the column split is on."""
     run_workload(4, {"n": 1 << 21, "cap": 200000})
