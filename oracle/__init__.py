@@ -49,6 +49,9 @@ def _load():
         for name in ("oracle_spmv_f64", "oracle_spmv_f32"):
             getattr(lib, name).argtypes = [i64, p, p, p, p, f64, f64, p, p, p]
             getattr(lib, name).restype = None
+        for name in ("oracle_spmv_transpose_f64", "oracle_spmv_transpose_f32"):
+            getattr(lib, name).argtypes = [i64, i64, p, p, p, p, f64, f64, p, p, p, p]
+            getattr(lib, name).restype = None
         for name in ("oracle_spmm_f64", "oracle_spmm_f32"):
             getattr(lib, name).argtypes = [i64, i64, p, p, p, p, i64, f64, f64, p, p, i64, p]
             getattr(lib, name).restype = None
@@ -91,6 +94,27 @@ def spmv(rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None):
     fn(n, _p(rowptr), _p(colidx), _p(vals), _p(x), float(alpha), float(beta),
        _p(y0) if beta != 0.0 else None, _p(y), _p(absAx))
     return y, absAx
+
+
+def spmv_transpose(rowptr, colidx, vals, ncols, x, alpha=1.0, beta=0.0, y0=None):
+    """Returns (y, absATx): y = alpha*A^T*x + beta*y0 (ncols values, vals.dtype) for x of nrows
+    values, and |A^T||x| in float64."""
+    _check_csr(rowptr, colidx, vals)
+    n = rowptr.size - 1
+    dt = vals.dtype
+    x = np.ascontiguousarray(x, dtype=dt)
+    assert x.size == n
+    if beta != 0.0:
+        assert y0 is not None
+        y0 = np.ascontiguousarray(y0, dtype=dt)
+        assert y0.size == ncols
+    y = np.empty(ncols, dtype=dt)
+    absATx = np.empty(ncols, dtype=np.float64)
+    acc = np.empty(2 * max(ncols, 1), dtype=np.float64)
+    fn = _load().oracle_spmv_transpose_f64 if dt == np.float64 else _load().oracle_spmv_transpose_f32
+    fn(n, ncols, _p(rowptr), _p(colidx), _p(vals), _p(x), float(alpha), float(beta),
+       _p(y0) if beta != 0.0 else None, _p(y), _p(absATx), _p(acc))
+    return y, absATx
 
 
 def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):

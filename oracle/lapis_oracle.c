@@ -26,7 +26,9 @@
  * Pins (tests marked "not gpu"): dense brute force on tiny matrices,
  * identity and diagonal matrices, the 5-point Laplacian's closed forms on
  * constant and linear grid functions, exact integer-valued cases, linearity,
- * SpMM column == SpMV, library cross-checks (SciPy / PyTorch CPU), and
+ * SpMM column == SpMV, library cross-checks (SciPy / PyTorch CPU), the
+ * transposed product against dense A^T, the adjoint identity and symmetric
+ * matrices, and
  * structural invariants of the partition.  No function here is unpinned.
  */
 #include <math.h>
@@ -64,6 +66,46 @@ void oracle_spmv_f32(int64_t nrows, const int32_t *rowptr, const int32_t *colidx
         double r = (beta == 0.0) ? alpha * s : alpha * s + beta * (double)y0[i];
         y[i] = (float)r;
         if (absAx) absAx[i] = t;
+    }
+}
+
+/* ---- transposed product: y = alpha * A^T x + beta * y0 --------------------
+ * The column-wise (CSC) traversal of the loop pattern of Section 4.2: the CSR arrays of A are
+ * the CSC arrays of A^T, so entry j of row i contributes vals[j] * x[i] to y[colidx[j]].
+ * Definition written out: the sums are accumulated in double in row order, then scaled once.
+ * x has nrows elements, y0 / y / absATx have ncols; acc is caller scratch of 2*ncols doubles. */
+void oracle_spmv_transpose_f64(int64_t nrows, int64_t ncols, const int32_t *rowptr, const int32_t *colidx,
+                               const double *vals, const double *x, double alpha, double beta,
+                               const double *y0, double *y, double *absATx, double *acc)
+{
+    double *s = acc, *t = acc + ncols;
+    for (int64_t c = 0; c < ncols; ++c) s[c] = t[c] = 0.0;
+    for (int64_t i = 0; i < nrows; ++i)
+        for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+            s[colidx[j]] += vals[j] * x[i];
+            t[colidx[j]] += fabs(vals[j]) * fabs(x[i]);
+        }
+    for (int64_t c = 0; c < ncols; ++c) {
+        y[c] = (beta == 0.0) ? alpha * s[c] : alpha * s[c] + beta * y0[c];
+        if (absATx) absATx[c] = t[c];
+    }
+}
+
+void oracle_spmv_transpose_f32(int64_t nrows, int64_t ncols, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *x, double alpha, double beta,
+                               const float *y0, float *y, double *absATx, double *acc)
+{
+    double *s = acc, *t = acc + ncols;
+    for (int64_t c = 0; c < ncols; ++c) s[c] = t[c] = 0.0;
+    for (int64_t i = 0; i < nrows; ++i)
+        for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+            s[colidx[j]] += (double)vals[j] * (double)x[i];
+            t[colidx[j]] += fabs((double)vals[j]) * fabs((double)x[i]);
+        }
+    for (int64_t c = 0; c < ncols; ++c) {
+        double r = (beta == 0.0) ? alpha * s[c] : alpha * s[c] + beta * (double)y0[c];
+        y[c] = (float)r;
+        if (absATx) absATx[c] = t[c];
     }
 }
 
