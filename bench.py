@@ -45,6 +45,10 @@ def algorithmic_bytes(w):
     return (w.nnz * (e + 4) + (w.nrows + 1) * 4 + w.ncols * k * e + y_passes * w.nrows * k * e)
 
 
+VARIANT_KERNEL = {"paper-shape": "spmv_vector_kernel", "transpose": "transpose_scatter_kernel",
+                  "host-buffers": "all kernels and copies of the step"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,8 +57,11 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload); 6..9 = stand-ins for the paper's Table 3")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--variant", choices=["tuned", "paper-shape"], default="tuned",
-                    help="paper-shape: the single-vector-length kernel of the paper's loop mapping")
+    ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "host-buffers"], default="tuned",
+                    help="paper-shape: the single-vector-length kernel of the paper's loop mapping; "
+                         "transpose: y = alpha*A^T*x + beta*y (column-wise traversal); host-buffers: the "
+                         "product on lazily synchronised host buffers with x rewritten on the host and y "
+                         "read back every step (PCIe-inclusive rate, never the headline value)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -96,8 +103,24 @@ def main():
     torch.cuda.synchronize()
     create_ms = (time.perf_counter() - t0) * 1e3
 
-    if w.k == 0 and args.variant == "paper-shape":
+    if args.variant != "tuned" and w.k != 0:
+        sys.exit("bench.py: --variant applies to the SpMV workloads only")
+    if args.variant in ("transpose", "host-buffers") and w.nrows != w.ncols:
+        sys.exit("bench.py: this variant expects a square workload")
+    if args.variant == "paper-shape":
         step = lambda: L.lapis_spmv_paper_shape(A.handle, w.alpha, x, w.beta, y)
+    elif args.variant == "transpose":
+        step = lambda: L.lapis_spmv_transpose(A.handle, w.alpha, x, w.beta, y)
+    elif args.variant == "host-buffers":
+        xv, yv = L.DualView(w.ncols, w.dtype), L.DualView(w.nrows, w.dtype)
+        xv.host[:] = w.x
+        yv.host[:] = 0.0 if w.y0 is None else w.y0
+        yv.modify_host()
+
+        def step():
+            xv.modify_host()                     # the caller rewrote x on the host
+            L.lapis_spmv_dualview(A.handle, w.alpha, xv, w.beta, yv)
+            yv.sync_host()                       # and reads y on the host
     elif w.k == 0:
         step = lambda: L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
     else:
@@ -152,8 +175,10 @@ def main():
         "create_ms": round(create_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "algorithmic_bytes": nbytes,
-                     "kernel": DOMINANT_KERNEL.get(w.name, "all kernels of the step"),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if args.variant == "tuned" else None,
+                     "algorithmic_bytes": nbytes,
+                     "kernel": (DOMINANT_KERNEL.get(w.name, "all kernels of the step") if args.variant == "tuned"
+                                else VARIANT_KERNEL[args.variant]),
                      "kernel_ms": round(kernel_ms, 6)},
         "cpu_baseline": cpu,
     }

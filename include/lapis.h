@@ -137,6 +137,23 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
                void *hip_stream);
 
 /*
+ * lapis_spmv_transpose - y = alpha*A^T*x + beta*y from the CSR arrays of A: the column-wise
+ * (CSC) traversal of the sparse loop pattern of Section 4.2 (the CSR arrays of A are the CSC
+ * arrays of A^T; equivalently, the product of a CSC-stored matrix with a vector).
+ *
+ *   d_x   nrows elements of A's dtype, contiguous
+ *   d_y   ncols elements of A's dtype, contiguous; must not overlap d_x or A
+ *
+ * beta == 0 makes d_y write-only; columns without entries receive beta*y.  The sums are formed
+ * by floating-point atomic additions in memory, in no fixed order: each element lies within
+ * the rounding bound of a serial evaluation, but two calls may differ in the last bits.
+ * Asynchronous on hip_stream; no allocation, copy or synchronisation; uses no scratch of the
+ * handle.
+ */
+int lapis_spmv_transpose(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+                         void *hip_stream);
+
+/*
  * lapis_spmv_paper_shape - the same product as lapis_spmv, computed with the
  * kernel shape the paper's loop mapping generates (Section 4.2): one vector
  * length for the whole matrix, g = the average number of entries per row

@@ -52,6 +52,8 @@ def _load():
         for name in ("oracle_spmv_transpose_f64", "oracle_spmv_transpose_f32"):
             getattr(lib, name).argtypes = [i64, i64, p, p, p, p, f64, f64, p, p, p, p]
             getattr(lib, name).restype = None
+        lib.oracle_transpose.argtypes = [i64, i64, p, p, p, i64, p, p, p]
+        lib.oracle_transpose.restype = None
         for name in ("oracle_spmm_f64", "oracle_spmm_f32"):
             getattr(lib, name).argtypes = [i64, i64, p, p, p, p, i64, f64, f64, p, p, i64, p]
             getattr(lib, name).restype = None
@@ -115,6 +117,18 @@ def spmv_transpose(rowptr, colidx, vals, ncols, x, alpha=1.0, beta=0.0, y0=None)
     fn(n, ncols, _p(rowptr), _p(colidx), _p(vals), _p(x), float(alpha), float(beta),
        _p(y0) if beta != 0.0 else None, _p(y), _p(absATx), _p(acc))
     return y, absATx
+
+
+def transpose(rowptr, colidx, vals, ncols):
+    """CSR arrays (tptr, tidx, tvals) of A^T; entries of a row of A^T ordered by (row of A,
+    position in that row)."""
+    _check_csr(rowptr, colidx, vals)
+    n = rowptr.size - 1
+    tptr = np.empty(ncols + 1, dtype=np.int32)
+    tidx = np.empty(colidx.size, dtype=np.int32)
+    tvals = np.empty(vals.size, dtype=vals.dtype)
+    _load().oracle_transpose(n, ncols, _p(rowptr), _p(colidx), _p(vals), vals.itemsize, _p(tptr), _p(tidx), _p(tvals))
+    return tptr, tidx, tvals
 
 
 def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):

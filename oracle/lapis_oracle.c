@@ -109,6 +109,30 @@ void oracle_spmv_transpose_f32(int64_t nrows, int64_t ncols, const int32_t *rowp
     }
 }
 
+/* ---- explicit transposition: CSR arrays of A^T ---------------------------
+ * The textbook counting transposition: count the entries of every column, prefix-sum the
+ * counts into tptr, then walk A in row order and append each entry to its column.  Walking in
+ * row order makes the result unique: inside row c of A^T the entries are ordered by (row of A,
+ * position inside that row), duplicates included.  tptr has ncols+1 elements, tidx and tvals
+ * have nnz; esize is the size of one value in bytes (values are moved, not computed with). */
+void oracle_transpose(int64_t nrows, int64_t ncols, const int32_t *rowptr, const int32_t *colidx,
+                      const void *vals, int64_t esize, int32_t *tptr, int32_t *tidx, void *tvals)
+{
+    for (int64_t c = 0; c <= ncols; ++c) tptr[c] = 0;
+    for (int64_t j = 0; j < rowptr[nrows]; ++j) tptr[colidx[j] + 1] += 1;
+    for (int64_t c = 0; c < ncols; ++c) tptr[c + 1] += tptr[c];
+    /* tptr[c] is advanced while filling and restored by the shift afterwards */
+    for (int64_t i = 0; i < nrows; ++i)
+        for (int64_t j = rowptr[i]; j < rowptr[i + 1]; ++j) {
+            const int64_t p = tptr[colidx[j]]++;
+            tidx[p] = (int32_t)i;
+            for (int64_t b = 0; b < esize; ++b)
+                ((unsigned char *)tvals)[p * esize + b] = ((const unsigned char *)vals)[j * esize + b];
+        }
+    for (int64_t c = ncols; c > 0; --c) tptr[c] = tptr[c - 1];
+    tptr[0] = 0;
+}
+
 /* ---- SpMM: Y = alpha*A*X + beta*Y0, X, Y0, Y row-major with leading
  * dimensions ldx, ldy (Y0 and Y share ldy); absAX is nrows*k contiguous.
  * Column c is by definition the SpMV with column c of X. ------------------- */

@@ -22,6 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
+    "lapis_spmv_transpose",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
     "lapis_dualview_sync_host", "lapis_dualview_copy_counts", "lapis_dualview_destroy",
@@ -55,6 +56,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_create.argtypes = [ctypes.POINTER(p), i64, i64, i64, p, p, p, i32, p]
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_paper_vector_length.argtypes = [i64, i64]
         lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
         lib.lapis_csr_destroy.argtypes = [p]
@@ -121,6 +123,10 @@ def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, strea
 
 def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
     _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_spmv_transpose(A, alpha, d_x, beta, d_y, stream=None):
+    _check(load().lapis_spmv_transpose(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
 
 
 def lapis_spmv_paper_shape(A, alpha, d_x, beta, d_y, stream=None):

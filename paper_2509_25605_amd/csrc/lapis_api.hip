@@ -9,6 +9,7 @@
 #include <new>
 #include <string>
 
+#include "transpose_kernels.hpp"
 #include "internal.hpp"
 #include "../../include/lapis.h"
 #include "analysis_kernels.hpp"
@@ -353,6 +354,25 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
         static_cast<const T *>(A->vals), x, y, a, b);
 }
 
+// y (ncols values) = beta*y, then every entry of A adds alpha*vals[j]*x[row] into y[colidx[j]].
+template <typename T>
+int spmv_transpose_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y,
+                         hipStream_t stream)
+{
+    T *y = static_cast<T *>(d_y);
+    int64_t blocks = (A->ncols + kBlock - 1) / kBlock;
+    if (blocks > 16384) blocks = 16384;
+    transpose_scale_kernel<T><<<dim3((uint32_t)blocks), dim3(kBlock), 0, stream>>>(A->ncols, y, (T)beta);
+    if (A->nnz > 0) {
+        const uint32_t tiles = (uint32_t)((A->nnz + kScatterTile - 1) / kScatterTile);
+        transpose_scatter_kernel<T><<<dim3(tiles), dim3(kBlock), 0, stream>>>(
+            (int32_t)A->nrows, (int32_t)A->nnz, A->rowptr, A->colidx, static_cast<const T *>(A->vals),
+            static_cast<const T *>(d_x), y, (T)alpha);
+    }
+    LAPIS_HIP(hipGetLastError());
+    return LAPIS_OK;
+}
+
 template <typename T>
 int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, hipStream_t stream)
 {
@@ -529,6 +549,18 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, stream)
                                  : spmv_typed<float>(A, alpha, d_x, beta, d_y, stream);
+}
+
+int lapis_spmv_transpose(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+                         void *hip_stream)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->ncols > 0 && !d_y) return fail(LAPIS_ERR_INVALID_ARG, "d_y is NULL");
+    if (A->nnz > 0 && !d_x) return fail(LAPIS_ERR_INVALID_ARG, "d_x is NULL");
+    if (A->ncols == 0) return LAPIS_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return A->dtype == LAPIS_F64 ? spmv_transpose_typed<double>(A, alpha, d_x, beta, d_y, stream)
+                                 : spmv_transpose_typed<float>(A, alpha, d_x, beta, d_y, stream);
 }
 
 int lapis_paper_vector_length(int64_t nrows, int64_t nnz)

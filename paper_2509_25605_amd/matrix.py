@@ -35,6 +35,13 @@ class CsrMatrix:
         B.lapis_spmv(self.handle, alpha, x, beta, y, stream)
         return y
 
+    def spmv_transpose(self, x, y, alpha=1.0, beta=0.0, stream=None):
+        """y = alpha*A^T*x + beta*y for x of nrows and y of ncols values, in place on y; returns y."""
+        self._check_vec(x, self.nrows, "x")
+        self._check_vec(y, self.ncols, "y")
+        B.lapis_spmv_transpose(self.handle, alpha, x, beta, y, stream)
+        return y
+
     def spmm(self, X, Y, alpha=1.0, beta=0.0, stream=None):
         """Y = alpha*A*X + beta*Y for row-major X (ncols x k) and Y (nrows x k)."""
         k = X.shape[1]

@@ -64,6 +64,17 @@ class DeviceCsr:
         torch.cuda.synchronize()
         return dy.cpu().numpy()
 
+    def spmv_transpose(self, x, alpha=1.0, beta=0.0, y0=None):
+        torch = self.torch
+        dx = torch.from_numpy(np.ascontiguousarray(x, dtype=self.np_dtype)).cuda()
+        if y0 is not None:
+            dy = torch.from_numpy(np.ascontiguousarray(y0, dtype=self.np_dtype)).cuda()
+        else:
+            dy = torch.full((self.ncols,), float("nan"), dtype=dx.dtype, device="cuda:0")
+        self.mat.spmv_transpose(dx, dy, alpha, beta)
+        torch.cuda.synchronize()
+        return dy.cpu().numpy()
+
     def spmm(self, X, alpha=1.0, beta=0.0, Y0=None, ldx=None, ldy=None):
         torch = self.torch
         k = X.shape[1]

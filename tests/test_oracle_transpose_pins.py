@@ -130,3 +130,72 @@ def test_beta_zero_never_reads_y0_and_empty_columns():
     assert np.array_equal(y, [2.0, 0.0, 0.0, -4.0, 0.0]) and np.array_equal(t, [1.0, 0.0, 0.0, 6.0, 0.0])
     y, _ = oracle.spmv_transpose(rowptr, colidx, vals, 5, x, 0.0, 3.0, np.arange(5.0))
     assert np.array_equal(y, 3.0 * np.arange(5.0))
+
+
+# ---- explicit transposition -------------------------------------------------
+def dense(nrows, ncols, rowptr, colidx, vals):
+    A = np.zeros((nrows, ncols))
+    for i in range(nrows):
+        for j in range(int(rowptr[i]), int(rowptr[i + 1])):
+            A[i, int(colidx[j])] += float(vals[j])
+    return A
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("case", range(len(TINY_CASES)))
+def test_transpose_dense_brute_force_and_order(case, dtype):
+    nrows, ncols, lengths, srt, dup = TINY_CASES[case]
+    rowptr, colidx, vals = gen.random_csr(nrows, ncols, np.array(lengths), 100 + case, dtype,
+                                          sorted_cols=srt, allow_duplicates=dup, small_ints=dup)
+    tptr, tidx, tvals = oracle.transpose(rowptr, colidx, vals, ncols)
+    assert tptr.dtype == np.int32 and tidx.dtype == np.int32 and tvals.dtype == dtype
+    assert tptr[0] == 0 and tptr[-1] == colidx.size and np.all(np.diff(tptr) >= 0)
+    assert np.array_equal(np.diff(tptr), col_counts(colidx, ncols))
+    assert np.array_equal(dense(ncols, nrows, tptr, tidx, tvals), dense(nrows, ncols, rowptr, colidx, vals).T)
+    # the unique order: brute force, column by column, scanning A in row order
+    rows_of = np.repeat(np.arange(nrows), np.diff(rowptr))
+    for c in range(ncols):
+        js = [j for j in range(colidx.size) if colidx[j] == c]
+        assert np.array_equal(tidx[tptr[c]:tptr[c + 1]], rows_of[js])
+        assert np.array_equal(tvals[tptr[c]:tptr[c + 1]], vals[js])
+
+
+def test_transpose_hand_example():
+    """A = [[a . b], [. . .], [c d .]]  ->  A^T rows: [a c], [d], [b]."""
+    rowptr = np.array([0, 2, 2, 4], dtype=np.int32)
+    colidx = np.array([0, 2, 0, 1], dtype=np.int32)
+    vals = np.array([1.0, 2.0, 3.0, 4.0])
+    tptr, tidx, tvals = oracle.transpose(rowptr, colidx, vals, 3)
+    assert tptr.tolist() == [0, 2, 3, 4] and tidx.tolist() == [0, 2, 2, 0] and tvals.tolist() == [1.0, 3.0, 4.0, 2.0]
+
+
+def test_transpose_twice_is_identity_for_sorted_rows():
+    n, ncols = 900, 1300
+    L = (np.arange(n) * 11) % 70
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 13, np.float64)
+    t = oracle.transpose(rowptr, colidx, vals, ncols)
+    b = oracle.transpose(*t, n)
+    assert np.array_equal(b[0], rowptr) and np.array_equal(b[1], colidx) and np.array_equal(b[2], vals)
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, None), (4, {"n": 1 << 12, "cap": 1000})])
+def test_transpose_against_scipy(cfg, scale):
+    w = gen.workload(cfg, scale)
+    tptr, tidx, tvals = oracle.transpose(w.rowptr, w.colidx, w.vals, w.ncols)
+    ref = sp.csr_matrix((w.vals, w.colidx, w.rowptr), shape=(w.nrows, w.ncols)).T.tocsr()
+    ref.sort_indices()
+    assert np.array_equal(tptr, ref.indptr) and np.array_equal(tidx, ref.indices) and np.array_equal(tvals, ref.data)
+
+
+def test_product_with_transposed_arrays_is_the_transposed_product_bitwise():
+    """Row c of A^T lists column c of A in row order, which is the order the transposed product
+    adds in: the two oracle functions must agree to the bit."""
+    n, ncols = 1200, 800
+    L = (np.arange(n) * 5) % 90
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 14, np.float64, sorted_cols=False)
+    x = gen.uniform(6, gen.STREAM_X, n)
+    y0 = gen.uniform(6, gen.STREAM_Y0, ncols)
+    t = oracle.transpose(rowptr, colidx, vals, ncols)
+    y1, a1 = oracle.spmv(*t, x, 1.5, -2.0, y0)
+    y2, a2 = oracle.spmv_transpose(rowptr, colidx, vals, ncols, x, 1.5, -2.0, y0)
+    assert np.array_equal(y1, y2) and np.array_equal(a1, a2)
