@@ -46,6 +46,7 @@ def algorithmic_bytes(w):
 
 
 VARIANT_KERNEL = {"paper-shape": "spmv_vector_kernel", "transpose": "transpose_scatter_kernel",
+                  "transposed-handle": "all kernels of the step",
                   "host-buffers": "all kernels and copies of the step"}
 
 
@@ -57,9 +58,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload); 6..9 = stand-ins for the paper's Table 3")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "host-buffers"], default="tuned",
+    ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers"], default="tuned",
                     help="paper-shape: the single-vector-length kernel of the paper's loop mapping; "
-                         "transpose: y = alpha*A^T*x + beta*y (column-wise traversal); host-buffers: the "
+                         "transpose: y = alpha*A^T*x + beta*y (column-wise traversal, atomics); transposed-handle: "
+                         "the same product through a handle for A^T built on the device; host-buffers: the "
                          "product on lazily synchronised host buffers with x rewritten on the host and y "
                          "read back every step (PCIe-inclusive rate, never the headline value)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -105,12 +107,19 @@ def main():
 
     if args.variant != "tuned" and w.k != 0:
         sys.exit("bench.py: --variant applies to the SpMV workloads only")
-    if args.variant in ("transpose", "host-buffers") and w.nrows != w.ncols:
+    if args.variant in ("transpose", "transposed-handle", "host-buffers") and w.nrows != w.ncols:
         sys.exit("bench.py: this variant expects a square workload")
     if args.variant == "paper-shape":
         step = lambda: L.lapis_spmv_paper_shape(A.handle, w.alpha, x, w.beta, y)
     elif args.variant == "transpose":
         step = lambda: L.lapis_spmv_transpose(A.handle, w.alpha, x, w.beta, y)
+    elif args.variant == "transposed-handle":
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        At = A.transposed()
+        torch.cuda.synchronize()
+        create_ms = (time.perf_counter() - t0) * 1e3     # transposition + analysis of A^T
+        step = lambda: L.lapis_spmv(At.handle, w.alpha, x, w.beta, y)
     elif args.variant == "host-buffers":
         xv, yv = L.DualView(w.ncols, w.dtype), L.DualView(w.nrows, w.dtype)
         xv.host[:] = w.x

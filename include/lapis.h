@@ -16,7 +16,8 @@
  *   - every function returns a status code, never throws, aborts or prints;
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *
- * Row indices and column indices are 32-bit; nnz and nrows+1 must fit in int32.
+ * Row indices and column indices are 32-bit; nrows+1 must fit in int32 and nnz must not
+ * exceed LAPIS_MAX_NNZ.
  */
 #ifndef LAPIS_H
 #define LAPIS_H
@@ -88,6 +89,7 @@ extern "C" {
 #define LAPIS_STREAM_ROWS     32
 #define LAPIS_STREAM_MIN_NNZ  256
 #define LAPIS_SPLIT_BLOCK_BYTES 2097152   /* 2 MiB of x per column block */
+#define LAPIS_MAX_NNZ 2147418112        /* 2^31 - 2^16: entry ids plus a tile stay inside int32 */
 #define LAPIS_SPLIT_MAX_BLOCKS  32
 
 typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
@@ -97,7 +99,7 @@ typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
  * partition analysis (the per-row form of the Section 4.2 estimate) on it.
  *
  *   out        receives the handle; set to NULL on any error
- *   nrows, ncols, nnz   sizes, all >= 0; nnz and nrows+1 must fit in int32
+ *   nrows, ncols, nnz   sizes, all >= 0; nrows+1 must fit in int32, nnz <= LAPIS_MAX_NNZ
  *   d_rowptr   int32[nrows+1], d_rowptr[0] == 0, non-decreasing,
  *              d_rowptr[nrows] == nnz
  *   d_colidx   int32[nnz], 0 <= d_colidx[j] < ncols; columns inside a row need
@@ -152,6 +154,28 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
  */
 int lapis_spmv_transpose(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
                          void *hip_stream);
+
+/*
+ * lapis_csr_create_transpose - a handle for A^T (ncols x nrows) built on the device from the
+ * arrays of A as they are at the time of the call: the explicit form of the column-wise
+ * traversal of Section 4.2, for callers that apply A^T many times.  lapis_spmv / lapis_spmm on
+ * the new handle compute A^T x / A^T X with the same kernels and the same analysis as for any
+ * other matrix, with a fixed order of additions.
+ *
+ * The new handle OWNS its CSR arrays (device memory allocated here: (ncols+1 + nnz) int32 and
+ * nnz values, plus 8*nnz + 4*ncols bytes of temporaries during the call) and does not refer to
+ * A afterwards; later changes to A's values are not followed.  Inside row c of A^T the entries
+ * are ordered by (row of A, position inside that row), duplicates kept: the result of a serial
+ * row-by-row transposition, unique, so it can be compared bit for bit.
+ * Synchronises hip_stream.  Destroy with lapis_csr_destroy.
+ *
+ * lapis_csr_shape reports a handle's sizes and dtype (any out pointer may be NULL).
+ * lapis_csr_copy_arrays copies a handle's CSR arrays (borrowed or owned) to HOST buffers of
+ * nrows+1, nnz and nnz elements (any may be NULL); it synchronises the device.
+ */
+int lapis_csr_create_transpose(lapis_csr_t **out, const lapis_csr_t *A, void *hip_stream);
+int lapis_csr_shape(const lapis_csr_t *A, int64_t *nrows, int64_t *ncols, int64_t *nnz, int *dtype);
+int lapis_csr_copy_arrays(const lapis_csr_t *A, int32_t *h_rowptr, int32_t *h_colidx, void *h_vals);
 
 /*
  * lapis_spmv_paper_shape - the same product as lapis_spmv, computed with the

@@ -22,7 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
-    "lapis_spmv_transpose",
+    "lapis_spmv_transpose", "lapis_csr_create_transpose", "lapis_csr_shape", "lapis_csr_copy_arrays",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
     "lapis_dualview_sync_host", "lapis_dualview_copy_counts", "lapis_dualview_destroy",
@@ -57,6 +57,9 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
+        lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
+        lib.lapis_csr_copy_arrays.argtypes = [p, p, p, p]
         lib.lapis_paper_vector_length.argtypes = [i64, i64]
         lib.lapis_spmm.argtypes = [p, i64, f64, p, i64, f64, p, i64, p]
         lib.lapis_csr_destroy.argtypes = [p]
@@ -123,6 +126,30 @@ def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, strea
 
 def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
     _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_csr_create_transpose(A, stream=None):
+    """Returns the handle of A^T (it owns its arrays)."""
+    h = ctypes.c_void_p()
+    _check(load().lapis_csr_create_transpose(ctypes.byref(h), A, _stream(stream)))
+    return h
+
+
+def lapis_csr_shape(A):
+    """(nrows, ncols, nnz, dtype code) of a handle."""
+    n, m, z, d = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int()
+    _check(load().lapis_csr_shape(A, ctypes.byref(n), ctypes.byref(m), ctypes.byref(z), ctypes.byref(d)))
+    return n.value, m.value, z.value, d.value
+
+
+def lapis_csr_copy_arrays(A):
+    """Host copies (rowptr, colidx, vals) of a handle's CSR arrays."""
+    n, _, z, d = lapis_csr_shape(A)
+    rowptr = np.empty(n + 1, dtype=np.int32)
+    colidx = np.empty(z, dtype=np.int32)
+    vals = np.empty(z, dtype=np.float64 if d == LAPIS_F64 else np.float32)
+    _check(load().lapis_csr_copy_arrays(A, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data))
+    return rowptr, colidx, vals
 
 
 def lapis_spmv_transpose(A, alpha, d_x, beta, d_y, stream=None):

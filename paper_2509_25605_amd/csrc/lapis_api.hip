@@ -52,6 +52,9 @@ struct lapis_csr {
     const int32_t *rowptr = nullptr;
     const int32_t *colidx = nullptr;
     const void *vals = nullptr;
+    // arrays the handle owns (a transposed handle's CSR arrays); null when the arrays are borrowed
+    int32_t *own_rowptr = nullptr, *own_colidx = nullptr;
+    void *own_vals = nullptr;
     // level 1: stream chunks
     int32_t *d_stream_chunks = nullptr;  // [num_stream] chunk ids, class by class, ascending in a class
     int32_t h_stream_offset[kStreamClasses + 1] = {0};   // class boundaries in that list
@@ -136,6 +139,9 @@ void free_handle(lapis_csr *A)
     (void)hipFree(A->d_stream_chunks);
     (void)hipFree(A->d_cut);
     (void)hipFree(A->d_vsum);
+    (void)hipFree(A->own_rowptr);
+    (void)hipFree(A->own_colidx);
+    (void)hipFree(A->own_vals);
     free_set(A->rows);
     free_set(A->vrows);
     delete A;
@@ -316,6 +322,71 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     }
     build_short_plan(A->rows, split ? kNumBins - 3 : kShortBins - 1, &A->plan_rows);
     if (split) build_short_plan(A->vrows, kShortBins - 1, &A->plan_vrows);
+    return LAPIS_OK;
+}
+
+// CSR arrays of A^T into B->own_* (B's sizes are set): count, scan, fill, sort, gather.
+int build_transposed_arrays(const lapis_csr *A, lapis_csr *B, hipStream_t stream)
+{
+    const int64_t nt = B->nrows, nnz = A->nnz;      // rows of A^T = columns of A
+    const size_t esize = value_size(A);
+    if (int rc = device_alloc(&B->own_rowptr, sizeof(int32_t) * (size_t)(nt + 1))) return rc;
+    if (int rc = device_alloc(&B->own_colidx, sizeof(int32_t) * (size_t)nnz)) return rc;
+    {
+        char *v = nullptr;
+        if (int rc = device_alloc(&v, esize * (size_t)nnz)) return rc;
+        B->own_vals = v;
+    }
+    if (nnz == 0) {
+        LAPIS_HIP(hipMemsetAsync(B->own_rowptr, 0, sizeof(int32_t) * (size_t)(nt + 1), stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        return LAPIS_OK;
+    }
+    const int32_t scan_tiles = (int32_t)((nt + kScanTile - 1) / kScanTile);
+    const int64_t max_long = nnz / (kSortHalf + 1) + 1;
+    DeviceTemp count, tile_sums, keys, long_cols, num_long;
+    if (int rc = count.alloc(sizeof(int32_t) * (size_t)nt)) return rc;
+    if (int rc = tile_sums.alloc(sizeof(int32_t) * ((size_t)scan_tiles + 1))) return rc;
+    if (int rc = keys.alloc(sizeof(uint64_t) * (size_t)nnz)) return rc;
+    if (int rc = long_cols.alloc(sizeof(int32_t) * (size_t)max_long)) return rc;
+    if (int rc = num_long.alloc(sizeof(int32_t))) return rc;
+    int32_t *d_count = count.as<int32_t>();
+    LAPIS_HIP(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)nt, stream));
+    LAPIS_HIP(hipMemsetAsync(num_long.p, 0, sizeof(int32_t), stream));
+    int64_t cblocks = (nnz + kBlock - 1) / kBlock;
+    if (cblocks > 65536) cblocks = 65536;
+    column_count_kernel<<<dim3((uint32_t)cblocks), dim3(kBlock), 0, stream>>>((int32_t)nnz, A->colidx, d_count);
+    scan_tile_sums_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(nt, d_count, tile_sums.as<int32_t>());
+    scan_tile_offsets_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(scan_tiles, tile_sums.as<int32_t>());
+    scan_apply_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(nt, d_count, tile_sums.as<int32_t>(), scan_tiles,
+                                                                   B->own_rowptr);
+    LAPIS_HIP(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)nt, stream));     // now the cursors
+    const uint32_t entry_tiles = (uint32_t)((nnz + kScatterTile - 1) / kScatterTile);
+    transpose_fill_kernel<<<dim3(entry_tiles), dim3(kBlock), 0, stream>>>(
+        (int32_t)A->nrows, (int32_t)nnz, A->rowptr, A->colidx, B->own_rowptr, d_count, keys.as<uint64_t>(),
+        B->own_colidx);
+    const uint32_t sort_tiles = (uint32_t)((nnz + kSortHalf - 1) / kSortHalf);
+    transpose_sort_tiles_kernel<<<dim3(sort_tiles), dim3(kBlock), 0, stream>>>(
+        (int32_t)nt, (int32_t)nnz, B->own_rowptr, keys.as<uint64_t>(), B->own_colidx, long_cols.as<int32_t>(),
+        num_long.as<int32_t>());
+    LAPIS_HIP(hipGetLastError());
+    int32_t h_num_long = 0;
+    LAPIS_HIP(hipMemcpyAsync(&h_num_long, num_long.p, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    LAPIS_HIP(hipStreamSynchronize(stream));
+    if (h_num_long < 0 || h_num_long > max_long) return fail(LAPIS_ERR_DEVICE, "transposition: long column count out of range");
+    if (h_num_long > 0)
+        transpose_sort_long_kernel<<<dim3((uint32_t)h_num_long), dim3(kSortLongBlock), 0, stream>>>(
+            long_cols.as<int32_t>(), B->own_rowptr, keys.as<uint64_t>(), B->own_colidx);
+    int64_t gblocks = (nnz + kBlock - 1) / kBlock;
+    if (gblocks > 65536) gblocks = 65536;
+    if (A->dtype == LAPIS_F64)
+        transpose_gather_kernel<double><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)nnz, keys.as<uint64_t>(), static_cast<const double *>(A->vals), static_cast<double *>(B->own_vals));
+    else
+        transpose_gather_kernel<float><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)nnz, keys.as<uint64_t>(), static_cast<const float *>(A->vals), static_cast<float *>(B->own_vals));
+    LAPIS_HIP(hipGetLastError());
+    LAPIS_HIP(hipStreamSynchronize(stream));     // the temporaries are freed on return
     return LAPIS_OK;
 }
 
@@ -517,14 +588,53 @@ int copy_set(const BinnedSet &s, int32_t *h_bin_offset, int32_t *h_row_perm, int
 
 extern "C" {
 
+int lapis_csr_create_transpose(lapis_csr_t **out, const lapis_csr_t *A, void *hip_stream)
+{
+    if (!out) return fail(LAPIS_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lapis_csr *B = new (std::nothrow) lapis_csr();
+    if (!B) return fail(LAPIS_ERR_ALLOC, "host allocation failed");
+    B->nrows = A->ncols; B->ncols = A->nrows; B->nnz = A->nnz; B->dtype = A->dtype;
+    int rc = build_transposed_arrays(A, B, stream);
+    if (rc == LAPIS_OK) {
+        B->rowptr = B->own_rowptr; B->colidx = B->own_colidx; B->vals = B->own_vals;
+        rc = run_analysis(B, stream);
+    }
+    if (rc) { free_handle(B); return rc; }
+    *out = B;
+    return LAPIS_OK;
+}
+
+int lapis_csr_shape(const lapis_csr_t *A, int64_t *nrows, int64_t *ncols, int64_t *nnz, int *dtype)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (nrows) *nrows = A->nrows;
+    if (ncols) *ncols = A->ncols;
+    if (nnz) *nnz = A->nnz;
+    if (dtype) *dtype = A->dtype;
+    return LAPIS_OK;
+}
+
+int lapis_csr_copy_arrays(const lapis_csr_t *A, int32_t *h_rowptr, int32_t *h_colidx, void *h_vals)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_rowptr) LAPIS_HIP(hipMemcpy(h_rowptr, A->rowptr, sizeof(int32_t) * (size_t)(A->nrows + 1), hipMemcpyDeviceToHost));
+    if (h_colidx && A->nnz > 0) LAPIS_HIP(hipMemcpy(h_colidx, A->colidx, sizeof(int32_t) * (size_t)A->nnz, hipMemcpyDeviceToHost));
+    if (h_vals && A->nnz > 0) LAPIS_HIP(hipMemcpy(h_vals, A->vals, value_size(A) * (size_t)A->nnz, hipMemcpyDeviceToHost));
+    return LAPIS_OK;
+}
+
 int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nnz, const int32_t *d_rowptr,
                      const int32_t *d_colidx, const void *d_vals, int dtype, void *hip_stream)
 {
     if (!out) return fail(LAPIS_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (nrows < 0 || ncols < 0 || nnz < 0) return fail(LAPIS_ERR_INVALID_ARG, "negative size");
-    if (nnz > INT32_MAX || nrows + 1 > INT32_MAX || ncols > INT32_MAX)
-        return fail(LAPIS_ERR_INVALID_ARG, "nnz, nrows+1 and ncols must fit in int32");
+    if (nnz > LAPIS_MAX_NNZ || nrows + 1 > INT32_MAX || ncols > INT32_MAX)
+        return fail(LAPIS_ERR_INVALID_ARG, "nnz must not exceed 2^31 - 2^16; nrows+1 and ncols must fit in int32");
     if (dtype != LAPIS_F32 && dtype != LAPIS_F64) return fail(LAPIS_ERR_UNSUPPORTED, "dtype must be LAPIS_F32 or LAPIS_F64");
     if (!d_rowptr) return fail(LAPIS_ERR_INVALID_ARG, "d_rowptr is NULL");
     if (nnz > 0 && (!d_colidx || !d_vals)) return fail(LAPIS_ERR_INVALID_ARG, "d_colidx / d_vals is NULL with nnz > 0");

@@ -54,6 +54,19 @@ class CsrMatrix:
         B.lapis_spmm(self.handle, k, alpha, X, ldx, beta, Y, ldy, stream)
         return Y
 
+    def transposed(self, stream=None):
+        """A CsrMatrix for A^T whose handle owns its arrays (built on the device)."""
+        t = object.__new__(CsrMatrix)
+        t.handle = B.lapis_csr_create_transpose(self.handle, stream)
+        t.nrows, t.ncols, t.nnz = self.ncols, self.nrows, self.nnz
+        t.rowptr = t.colidx = t.vals = None
+        t.dtype = self.dtype
+        return t
+
+    def arrays(self):
+        """Host copies (rowptr, colidx, vals) of the handle's CSR arrays."""
+        return B.lapis_csr_copy_arrays(self.handle)
+
     def partition(self):
         return B.lapis_csr_copy_partition(self.handle)
 

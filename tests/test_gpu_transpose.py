@@ -7,7 +7,7 @@ import pytest
 
 import gen
 import oracle
-from helpers import DeviceCsr, assert_close, general_bound
+from helpers import DeviceCsr, assert_close, general_bound, literal_bound
 from test_gpu_parity import mixed_lengths, say
 
 pytestmark = pytest.mark.gpu
@@ -124,3 +124,94 @@ def test_transpose_full_workloads(cfg):
         check_transpose(dev, w.rowptr, w.colidx, w.vals, w.ncols, x, what=w.name)
     finally:
         dev.close()
+
+
+# ---- explicit transposition on the device -----------------------------------
+def check_transposed_handle(rowptr, colidx, vals, nrows, ncols, x=None, what=""):
+    """Arrays of the transposed handle are bit-identical to the oracle's transposition, its
+    partition to the oracle's partition of those arrays, and products on it match the oracle."""
+    dev = DeviceCsr(nrows, ncols, rowptr, colidx, vals)
+    t = dev.mat.transposed()
+    try:
+        ref = oracle.transpose(rowptr, colidx, vals, ncols)
+        got = t.arrays()
+        for name, g, r in zip(("rowptr", "colidx", "vals"), got, ref):
+            assert g.dtype == r.dtype and np.array_equal(g, r), f"{what}: transposed {name} differs"
+        part, pref = t.partition(), oracle.partition(ref[0])
+        for key in ("stream_chunks", "stream_offset", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+            assert np.array_equal(part[key], pref[key]), f"{what}: partition field {key} of the transposed handle differs"
+        if x is not None:
+            import torch
+            dx = torch.from_numpy(x).cuda()
+            dy = torch.full((ncols,), float("nan"), dtype=dx.dtype, device="cuda:0")
+            t.spmv(dx, dy)
+            torch.cuda.synchronize()
+            yref, absATx = oracle.spmv_transpose(rowptr, colidx, vals, ncols, x)
+            counts = np.bincount(colidx, minlength=ncols) if colidx.size else np.zeros(ncols, dtype=np.int64)
+            assert_close(dy.cpu().numpy(), yref, literal_bound(counts, absATx, vals.dtype), what)
+    finally:
+        t.close()
+        dev.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("n,ncols,longest,srt,dup", [
+    (1, 1, 1, True, False),
+    (5, 3, 3, True, False),
+    (257, 100, 100, True, False),
+    (4099, 5000, 700, False, False),
+    (20000, 777, 777, True, True),            # columns of about 2000 entries: the in-memory sort
+    (3001, 40000, 30000, True, False),
+    (30000, 1500, 1024, False, True),         # columns around the LDS / memory sort threshold
+])
+def test_transposed_handle_general_matrices(dtype, n, ncols, longest, srt, dup):
+    say(f"transposed handle n={n} ncols={ncols} longest={longest} {np.dtype(dtype).name}")
+    L = np.minimum(mixed_lengths(n, 33, longest), ncols)
+    if n < 10:
+        L = np.minimum(np.arange(n) % (longest + 1), ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 4322, dtype, sorted_cols=srt, allow_duplicates=dup)
+    x = gen.uniform(25, gen.STREAM_X, n).astype(dtype)
+    check_transposed_handle(rowptr, colidx, vals, n, ncols, x, what="general")
+
+
+def test_transposed_handle_degenerate_shapes():
+    say("transposed handle degenerate shapes")
+    z = np.zeros(0, dtype=np.int32)
+    check_transposed_handle(np.zeros(8, dtype=np.int32), z, np.zeros(0), 7, 11, np.ones(7), "no entries")
+    check_transposed_handle(np.zeros(1, dtype=np.int32), z, np.zeros(0), 0, 5, None, "no rows")
+    check_transposed_handle(np.zeros(4, dtype=np.int32), z, np.zeros(0), 3, 0, None, "no columns")
+    # one dense column of 5000 entries and one dense row: a single long column, sorted in memory
+    n, ncols = 5000, 3000
+    L = np.ones(n, dtype=np.int64)
+    L[17] = ncols
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 6, np.float64)
+    single = np.flatnonzero(np.diff(rowptr) == 1)
+    colidx[rowptr[single]] = 7                       # every one-entry row sits in column 7
+    check_transposed_handle(rowptr, colidx, vals, n, ncols, gen.uniform(26, gen.STREAM_X, n), "dense column")
+    # empty columns between occupied ones, entries only in the last rows
+    n, ncols = 4000, 100000
+    L = np.zeros(n, dtype=np.int64)
+    L[-3:] = 900
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 8, np.float32)
+    check_transposed_handle(rowptr, colidx, vals, n, ncols, gen.uniform(27, gen.STREAM_X, n).astype(np.float32), "sparse columns")
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_transposed_handle_full_workloads(cfg):
+    say(f"transposed handle workload {cfg} full size")
+    w = gen.workload(cfg)
+    x = gen.uniform(28, gen.STREAM_X, w.nrows).astype(w.vals.dtype)
+    check_transposed_handle(w.rowptr, w.colidx, w.vals, w.nrows, w.ncols, x, w.name)
+
+
+def test_transposing_twice_restores_sorted_matrices():
+    say("transposed handle twice")
+    w = gen.workload(4, {"n": 1 << 16, "cap": 20000})       # long rows become long columns on the way back
+    dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
+    t = dev.mat.transposed()
+    tt = t.transposed()
+    try:
+        for g, r in zip(tt.arrays(), (w.rowptr, w.colidx, w.vals)):
+            assert np.array_equal(g, r)
+    finally:
+        tt.close(); t.close(); dev.close()
