@@ -262,6 +262,35 @@ int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int
     return count;
 }
 
+/* Level 1b: 16-bit column offsets.  A stream chunk (class >= 1) is "narrow" if its largest
+ * and smallest column differ by at most 65535; chunk_base[c] is then its smallest column and
+ * col16[j] = colidx[j] - chunk_base[c] for its entries.  Every other chunk gets chunk_base -1 and
+ * its entries col16 0.  Returns the number of entries in narrow chunks; the compression is in
+ * use when that is at least half of all entries (and not zero).  chunk_base has
+ * ceil(nrows/chunk_rows) elements, col16 has rowptr[nrows]. */
+int64_t oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, int64_t chunk_rows,
+                       int64_t chunk_min_nnz, int32_t *chunk_base, uint16_t *col16)
+{
+    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows, narrow_entries = 0;
+    for (int64_t j = 0; j < rowptr[nrows]; ++j) col16[j] = 0;
+    for (int64_t c = 0; c < nchunks; ++c) {
+        chunk_base[c] = -1;
+        if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == 0) continue;
+        int64_t last = (c + 1) * chunk_rows < nrows ? (c + 1) * chunk_rows : nrows;
+        int64_t b = rowptr[c * chunk_rows], e = rowptr[last];
+        int32_t lo = colidx[b], hi = colidx[b];
+        for (int64_t j = b; j < e; ++j) {
+            if (colidx[j] < lo) lo = colidx[j];
+            if (colidx[j] > hi) hi = colidx[j];
+        }
+        if ((int64_t)hi - lo > 65535) continue;
+        chunk_base[c] = lo;
+        for (int64_t j = b; j < e; ++j) col16[j] = (uint16_t)(colidx[j] - lo);
+        narrow_entries += e - b;
+    }
+    return narrow_entries;
+}
+
 /* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and
  * row_perm[] (ids of the rows outside stream chunks, grouped by bin, ascending
  * inside each bin; bin_offset[num_bins] of them).  Returns through *num_long

@@ -60,6 +60,9 @@ struct lapis_csr {
     int32_t h_stream_offset[kStreamClasses + 1] = {0};   // class boundaries in that list
     int64_t num_chunks = 0, num_stream = 0;
     int64_t half_bandwidth = 0;          // max |column - row| over the entries
+    // level 1b: 16-bit column offsets of the stream chunks whose columns span less than 2^16
+    int32_t *d_chunk_base = nullptr;     // [num_chunks] smallest column of such a chunk, else -1; null: off
+    uint16_t *d_col16 = nullptr;         // [nnz rounded up to 4, + 4] colidx[j] - base of j's chunk
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -139,6 +142,8 @@ void free_handle(lapis_csr *A)
     (void)hipFree(A->d_stream_chunks);
     (void)hipFree(A->d_cut);
     (void)hipFree(A->d_vsum);
+    (void)hipFree(A->d_chunk_base);
+    (void)hipFree(A->d_col16);
     (void)hipFree(A->own_rowptr);
     (void)hipFree(A->own_colidx);
     (void)hipFree(A->own_vals);
@@ -421,7 +426,7 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
     const uint32_t padded = (waves + kXcds - 1) / kXcds * kXcds;
     const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
     spmv_stream_kernel<T, G, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-        (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx,
+        (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
         static_cast<const T *>(A->vals), x, y, a, b);
 }
 
@@ -525,7 +530,8 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         const uint32_t padded = (chunks + unit - 1) / unit * unit;
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC)
             spmm_stream_kernel<T, VEC, kStreamLanes, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx, vals,
+                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                A->d_chunk_base, A->d_col16, vals,
                 k, c0, X, ldx, Y, ldy, a, b);
     }
     if (n_rows_a > 0) {

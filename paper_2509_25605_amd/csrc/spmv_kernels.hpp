@@ -187,11 +187,23 @@ template <> struct StreamVec<double> { typedef double type __attribute__((ext_ve
 template <> struct StreamVec<float> { typedef float type __attribute__((ext_vector_type(4))); };
 typedef int32_t int4v __attribute__((ext_vector_type(4)));
 
+typedef uint16_t ushort4v __attribute__((ext_vector_type(4)));
+
+// Where a window's column indices come from: the matrix's 32-bit colidx, or (cbase >= 0) the
+// 16-bit offsets col16 from the chunk's smallest column cbase, which the analysis builds for
+// chunks whose columns span less than 2^16.  Both pointers are already advanced to the window.
+struct StreamCols {
+    const int32_t *__restrict__ c32;
+    const uint16_t *__restrict__ c16;     // 8-byte aligned at every multiple of 4 entries; padded past nnz
+    int32_t cbase;
+};
+
 // Copy the first n_vec (a multiple of 4, <= kStreamWindow) entries of the window to LDS with
-// NC 16-byte column loads and NV 16-byte value loads per lane.  Lanes past the end repeat the
-// last group: same address, same data, no extra memory traffic and no divergent control flow.
-template <typename T, int NC, int NV>
-__device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, const T *__restrict__ vw,
+// NC column loads (16 bytes, or 8 bytes of 16-bit offsets) and NV 16-byte value loads per lane.
+// Lanes past the end repeat the last group: same address, same data, no extra memory traffic
+// and no divergent control flow.
+template <typename T, int NC, int NV, bool C16>
+__device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__restrict__ vw,
                                             int lane, int n_vec, int32_t *s_col, T *s_val)
 {
     typedef typename StreamVec<T>::type vec_t;
@@ -199,12 +211,14 @@ __device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, cons
     const int last_c = n_vec - 4;
     const int last_v = n_vec - kPerVec;
     int4v cq[NC];
+    ushort4v cs[NC];
     vec_t vq[NV];
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
         int idx = i * (kWave * 4) + lane * 4;
         idx = idx < last_c ? idx : last_c;
-        cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cw + idx));
+        if constexpr (C16) cs[i] = __builtin_nontemporal_load(reinterpret_cast<const ushort4v *>(cols.c16 + idx));
+        else cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cols.c32 + idx));
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -216,7 +230,16 @@ __device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, cons
     for (int i = 0; i < NC; ++i) {
         int idx = i * (kWave * 4) + lane * 4;
         idx = idx < last_c ? idx : last_c;
-        *reinterpret_cast<int4v *>(s_col + idx) = cq[i];
+        if constexpr (C16) {
+            int4v c;
+            c.x = cols.cbase + (int32_t)cs[i].x;
+            c.y = cols.cbase + (int32_t)cs[i].y;
+            c.z = cols.cbase + (int32_t)cs[i].z;
+            c.w = cols.cbase + (int32_t)cs[i].w;
+            *reinterpret_cast<int4v *>(s_col + idx) = c;
+        } else {
+            *reinterpret_cast<int4v *>(s_col + idx) = cq[i];
+        }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -228,40 +251,52 @@ __device__ __forceinline__ void stream_fill(const int32_t *__restrict__ cw, cons
 
 // NC column loads cover NC*256 entries; the value loads needed for n_vec entries are either
 // NC*R or NC*R - 1 (R = value loads per 256 entries: 2 for double, 1 for float).
-template <typename T, int NC>
-__device__ __forceinline__ void stream_fill_pick(const int32_t *__restrict__ cw, const T *__restrict__ vw,
+template <typename T, int NC, bool C16>
+__device__ __forceinline__ void stream_fill_pick(const StreamCols cols, const T *__restrict__ vw,
                                                  int lane, int n_vec, int32_t *s_col, T *s_val)
 {
     constexpr int kPerLoad = kWave * (16 / (int)sizeof(T));   // entries per value load instruction
     constexpr int kFull = NC * (kWave * 4) / kPerLoad;
     if constexpr (kFull > 1 && kPerLoad < kWave * 4) {
         if (n_vec <= (kFull - 1) * kPerLoad) {
-            stream_fill<T, NC, kFull - 1>(cw, vw, lane, n_vec, s_col, s_val);
+            stream_fill<T, NC, kFull - 1, C16>(cols, vw, lane, n_vec, s_col, s_val);
             return;
         }
     }
-    stream_fill<T, NC, kFull>(cw, vw, lane, n_vec, s_col, s_val);
+    stream_fill<T, NC, kFull, C16>(cols, vw, lane, n_vec, s_col, s_val);
+}
+
+template <typename T, bool C16>
+__device__ __forceinline__ void stream_fill_by_size(const StreamCols cols, const T *__restrict__ vw,
+                                                    int lane, int n_vec, int32_t *s_col, T *s_val)
+{
+    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4, C16>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3, C16>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > kWave * 4) stream_fill_pick<T, 2, C16>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 0) stream_fill_pick<T, 1, C16>(cols, vw, lane, n_vec, s_col, s_val);
 }
 
 // Stage entries [w0, w1) of the matrix (w0 a multiple of 4, w1 - w0 <= kStreamWindow) in LDS:
-// 16-byte loads up to nnz4 (= nnz rounded down to a multiple of 4), the matrix's last nnz % 4
-// entries one by one.  Ends with a wavefront-level fence so every lane may read what others wrote.
+// vector loads up to nnz4 (= nnz rounded down to a multiple of 4), the matrix's last nnz % 4
+// entries one by one.  cbase >= 0: the columns are cbase + col16[j], else colidx[j] (col16 may
+// then be null).  Ends with a wavefront-level fence so every lane may read what others wrote.
 template <typename T>
 __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__ colidx,
+                                                     const uint16_t *__restrict__ col16, int32_t cbase,
                                                      const T *__restrict__ vals, int32_t w0, int32_t w1,
                                                      int32_t nnz4, int lane, int32_t *s_col, T *s_val)
 {
-    const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // 16-byte loads stop here
+    const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // vector loads stop here
     const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
-    const int32_t *__restrict__ cw = colidx + w0;
     const T *__restrict__ vw = vals + w0;
-    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > kWave * 4) stream_fill_pick<T, 2>(cw, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 0) stream_fill_pick<T, 1>(cw, vw, lane, n_vec, s_col, s_val);
+    if (cbase >= 0) stream_fill_by_size<T, true>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
+    else stream_fill_by_size<T, false>(StreamCols{colidx + w0, nullptr, 0}, vw, lane, n_vec, s_col, s_val);
     if (w0 + n_vec < w1) {                              // the matrix's last nnz % 4 entries
         const int32_t j = w0 + n_vec + lane;
-        if (j < w1) { s_col[j - w0] = colidx[j]; s_val[j - w0] = vals[j]; }
+        if (j < w1) {
+            s_col[j - w0] = cbase >= 0 ? cbase + (int32_t)col16[j] : colidx[j];
+            s_val[j - w0] = vals[j];
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -299,7 +334,8 @@ template <typename T, int G, bool XCD_REMAP, int UNR = kStreamUnroll>  // UNR mu
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
-    const int32_t *__restrict__ colidx, const T *__restrict__ vals, const T *__restrict__ x,
+    const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
+    const uint16_t *__restrict__ col16, const T *__restrict__ vals, const T *__restrict__ x,
     T *__restrict__ y, T alpha, T beta)
 {
     constexpr int kRowsPerWave = kWave / G;
@@ -315,6 +351,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     const int sub = lane % G;
     const uint32_t list_pos = id / kWavesPerChunk;
     const int64_t chunk = stream_chunks ? stream_chunks[list_pos] : (int64_t)list_pos;
+    const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
     const int64_t row = chunk * kStreamRows + (id % kWavesPerChunk) * kRowsPerWave + lane / G;
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
@@ -328,7 +365,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     // windows of kStreamWindow entries starting at a multiple of 4 (16-byte aligned loads)
     for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
-        stream_window_to_lds<T>(colidx, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
 
         // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
         const int32_t ub = (rb > w0 ? rb : w0) - w0;

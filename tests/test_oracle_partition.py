@@ -227,3 +227,68 @@ def test_split_matches_searchsorted():
     vlen = sp["cut"][S:] - sp["cut"][:-S]
     assert vlen.sum() == L[rows].sum() and np.all(vlen >= 0)
     assert np.array_equal(np.sort(sp["row_perm"]), np.arange(nb * S))
+
+
+# ---- level 1b: 16-bit column offsets of narrow stream chunks ----------------
+def _index16_brute(rowptr, colidx, part):
+    """Straight from the definition, chunk by chunk, with numpy min/max."""
+    n = rowptr.size - 1
+    nchunks = (n + oracle.STREAM_ROWS - 1) // oracle.STREAM_ROWS
+    base = np.full(nchunks, -1, dtype=np.int32)
+    col16 = np.zeros(colidx.size, dtype=np.uint16)
+    narrow = 0
+    for c in part["stream_chunks"]:
+        b, e = rowptr[c * oracle.STREAM_ROWS], rowptr[min((c + 1) * oracle.STREAM_ROWS, n)]
+        cols = colidx[b:e]
+        if int(cols.max()) - int(cols.min()) <= 65535:
+            base[c] = cols.min()
+            col16[b:e] = cols - cols.min()
+            narrow += e - b
+    return base, col16, narrow
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, None), (2, {"nx": 24, "ny": 24, "nz": 24}),
+                                       (3, {"n": 1 << 18}), (4, {"n": 1 << 15, "cap": 5000}),
+                                       (8, {"grid": 12})])
+def test_index16_matches_definition_and_reconstructs_columns(cfg, scale):
+    w = gen.workload(cfg, scale)
+    part = oracle.partition(w.rowptr)
+    got = oracle.index16(w.rowptr, w.colidx)
+    base, col16, narrow = _index16_brute(w.rowptr, w.colidx, part)
+    assert got["chunk_base"].dtype == np.int32 and got["col16"].dtype == np.uint16
+    assert np.array_equal(got["chunk_base"], base) and np.array_equal(got["col16"], col16)
+    assert got["narrow_entries"] == narrow and got["enabled"] == (narrow > 0 and 2 * narrow >= w.nnz)
+    # the point of the structure: base + offset gives back every column of a narrow chunk
+    chunk_of_entry = np.repeat(np.arange(w.nrows) // oracle.STREAM_ROWS, np.diff(w.rowptr))
+    b = got["chunk_base"][chunk_of_entry]
+    ok = b >= 0
+    assert np.array_equal(b[ok] + got["col16"][ok].astype(np.int64), w.colidx[ok])
+    assert np.all(got["col16"][~ok] == 0)
+
+
+def test_index16_threshold_is_65535():
+    """Two chunks of 32 rows x 8 entries; the second spans exactly 65535 / 65536 columns."""
+    n, per = 64, 8
+    rowptr = (np.arange(n + 1) * per).astype(np.int32)
+    for span, narrow in ((65535, True), (65536, False)):
+        colidx = np.tile(np.arange(per, dtype=np.int32), n)
+        colidx[32 * per:] += 1000
+        colidx[-1] = 1000 + span                  # largest column of chunk 1; its smallest is 1000
+        got = oracle.index16(rowptr, colidx)
+        assert got["chunk_base"][0] == 0
+        assert got["chunk_base"][1] == (1000 if narrow else -1)
+        assert got["col16"][-1] == (span if narrow else 0)
+        assert got["enabled"]                     # chunk 0 alone holds half of the entries
+
+
+def test_index16_off_without_stream_chunks_and_below_half():
+    rowptr = (np.arange(33) * 4).astype(np.int32)            # 128 entries: below the stream minimum
+    colidx = np.tile(np.arange(4, dtype=np.int32), 32)
+    got = oracle.index16(rowptr, colidx)
+    assert not got["enabled"] and np.all(got["chunk_base"] == -1) and got["narrow_entries"] == 0
+    # one narrow chunk of 256 entries and one wide chunk of 320 entries: 256 * 2 < 576
+    lens = np.concatenate([np.full(32, 8), np.full(32, 10)])
+    rowptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    colidx = np.concatenate([np.tile(np.arange(8), 32), np.tile(np.arange(10) * 10000, 32)]).astype(np.int32)
+    got = oracle.index16(rowptr, colidx)
+    assert got["chunk_base"].tolist() == [0, -1] and got["narrow_entries"] == 256 and not got["enabled"]
