@@ -253,6 +253,20 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
                          int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
                          int32_t *h_tile_nz);
 
+/*
+ * lapis_csr_copy_index16 - the 16-bit column offsets the analysis builds so that the stream
+ * kernels read 2 instead of 4 bytes of index per entry (an implementation choice of this
+ * library, not of the paper; exposed so that it can be compared bit for bit with a CPU
+ * reference).  A stream chunk whose largest and smallest column differ by at most 65535 gets
+ * chunk_base = its smallest column and col16[j] = colidx[j] - chunk_base for its entries; every
+ * other chunk has chunk_base -1 and col16 0.  The structure is kept (*enabled = 1) only if such
+ * chunks hold at least half of the matrix's entries; *narrow_entries is that count either way.
+ *   h_chunk_base  HOST int32[ceil(nrows / LAPIS_STREAM_ROWS)]   h_col16  HOST uint16[nnz]
+ * Both are written only when *enabled is 1; any pointer may be NULL.  Synchronises the device.
+ */
+int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int32_t *h_chunk_base,
+                           uint16_t *h_col16);
+
 /* max |column - row| over the matrix's entries, found by lapis_csr_create; lapis_spmm uses it to
  * decide how workgroups are dealt to the 8 XCDs (band-wide windows of X rows that overflow one
  * L2 are shared by all 8). */

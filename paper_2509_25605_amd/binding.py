@@ -22,6 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
+    "lapis_csr_copy_index16",
     "lapis_spmv_transpose", "lapis_csr_create_transpose", "lapis_csr_shape", "lapis_csr_copy_arrays",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
@@ -57,6 +58,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), p, p]
         lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
         lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
         lib.lapis_csr_copy_arrays.argtypes = [p, p, p, p]
@@ -126,6 +128,20 @@ def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, strea
 
 def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
     _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_csr_copy_index16(A):
+    """dict(enabled, narrow_entries, chunk_base, col16) of a handle (arrays None when not enabled)."""
+    n, _, z, _ = lapis_csr_shape(A)
+    on, narrow = ctypes.c_int(), ctypes.c_int64()
+    _check(load().lapis_csr_copy_index16(A, ctypes.byref(on), ctypes.byref(narrow), None, None))
+    out = {"enabled": bool(on.value), "narrow_entries": narrow.value, "chunk_base": None, "col16": None}
+    if on.value:
+        rows = lapis_partition_constants()["stream_rows"]
+        out["chunk_base"] = np.empty((n + rows - 1) // rows, dtype=np.int32)
+        out["col16"] = np.empty(z, dtype=np.uint16)
+        _check(load().lapis_csr_copy_index16(A, None, None, out["chunk_base"].ctypes.data, out["col16"].ctypes.data))
+    return out
 
 
 def lapis_csr_create_transpose(A, stream=None):

@@ -144,6 +144,59 @@ __global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t nu
     }
 }
 
+// Level 1b, one wavefront per chunk: chunk_base[c] = smallest column of stream chunk c if its
+// columns span at most 65535, else -1 (also for chunks that are not stream chunks);
+// *narrow_entries (0 on entry) += entries of the chunks that got a base.
+__global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                            const int32_t *__restrict__ chunk_flag,
+                                                            const int32_t *__restrict__ rowptr,
+                                                            const int32_t *__restrict__ colidx,
+                                                            int32_t *__restrict__ chunk_base,
+                                                            unsigned long long *__restrict__ narrow_entries)
+{
+    const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (c >= num_chunks) return;                       // whole wavefronts leave together
+    if (chunk_flag[c] == 0) {
+        if (lane == 0) chunk_base[c] = -1;
+        return;
+    }
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    const int32_t b = rowptr[first], e = rowptr[last];
+    int32_t hi = 0, lo_rev = 0;                        // lo_rev = INT32_MAX - smallest column
+    for (int32_t j = b + lane; j < e; j += kWave) {
+        const int32_t col = load_stream(colidx + j);
+        hi = max(hi, col);
+        lo_rev = max(lo_rev, INT32_MAX - col);
+    }
+    hi = wave_max_nonneg(hi);
+    const int32_t lo = INT32_MAX - wave_max_nonneg(lo_rev);
+    if (lane == 0) {
+        const bool narrow = e > b && hi - lo <= 65535;
+        chunk_base[c] = narrow ? lo : -1;
+        if (narrow) atomicAdd(narrow_entries, (unsigned long long)(e - b));
+    }
+}
+
+// col16[j] = colidx[j] - chunk_base[c] for the entries of the chunks with a base (col16 is 0 elsewhere)
+__global__ __launch_bounds__(kBlock) void col16_fill_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                            const int32_t *__restrict__ rowptr,
+                                                            const int32_t *__restrict__ colidx,
+                                                            const int32_t *__restrict__ chunk_base,
+                                                            uint16_t *__restrict__ col16)
+{
+    const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (c >= num_chunks) return;
+    const int32_t base = chunk_base[c];
+    if (base < 0) return;
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    const int32_t e = rowptr[last];
+    for (int32_t j = rowptr[first] + lane; j < e; j += kWave) col16[j] = (uint16_t)(load_stream(colidx + j) - base);
+}
+
 // Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped; chunk_flag
 // may be null); hist is bin-major: hist[bin*num_blocks + block].  row_begin[i] / row_end[i]
 // delimit row i: (rowptr, rowptr + 1) for the matrix's rows, the cut table for virtual rows.

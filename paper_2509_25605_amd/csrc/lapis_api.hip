@@ -63,6 +63,7 @@ struct lapis_csr {
     // level 1b: 16-bit column offsets of the stream chunks whose columns span less than 2^16
     int32_t *d_chunk_base = nullptr;     // [num_chunks] smallest column of such a chunk, else -1; null: off
     uint16_t *d_col16 = nullptr;         // [nnz rounded up to 4, + 4] colidx[j] - base of j's chunk
+    int64_t narrow_entries = 0;          // entries in the chunks that could get a base
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -287,6 +288,35 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         num_stream = A->h_stream_offset[kStreamClasses];
     }
     A->num_stream = num_stream;
+
+    // level 1b: 16-bit column offsets for the stream chunks with a narrow column span, kept only
+    // if those chunks hold at least half of the entries
+    if (num_stream > 0) {
+        DeviceTemp narrow;
+        if (int rc = narrow.alloc(sizeof(unsigned long long))) return rc;
+        if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
+        LAPIS_HIP(hipMemsetAsync(narrow.p, 0, sizeof(unsigned long long), stream));
+        const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
+        chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
+            A->d_chunk_base, narrow.as<unsigned long long>());
+        LAPIS_HIP(hipGetLastError());
+        unsigned long long h_narrow = 0;
+        LAPIS_HIP(hipMemcpyAsync(&h_narrow, narrow.p, sizeof(h_narrow), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipStreamSynchronize(stream));
+        A->narrow_entries = (int64_t)h_narrow;
+        if (h_narrow > 0 && 2 * h_narrow >= (unsigned long long)A->nnz) {
+            const size_t len = ((size_t)A->nnz + 3) / 4 * 4 + 4;
+            if (int rc = device_alloc(&A->d_col16, sizeof(uint16_t) * len)) return rc;
+            LAPIS_HIP(hipMemsetAsync(A->d_col16, 0, sizeof(uint16_t) * len, stream));
+            col16_fill_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+                (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16);
+            LAPIS_HIP(hipGetLastError());
+        } else {
+            (void)hipFree(A->d_chunk_base);
+            A->d_chunk_base = nullptr;
+        }
+    }
 
     // level 2: bins over the remaining rows
     A->rows.num_rows = n;
@@ -766,6 +796,22 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
     if (h_cut)
         LAPIS_HIP(hipMemcpy(h_cut, A->d_cut, sizeof(int32_t) * (size_t)((A->num_blocks + 1) * A->num_split), hipMemcpyDeviceToHost));
     return copy_set(A->vrows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);
+}
+
+int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int32_t *h_chunk_base,
+                           uint16_t *h_col16)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    const bool on = A->d_col16 != nullptr;
+    if (enabled) *enabled = on ? 1 : 0;
+    if (narrow_entries) *narrow_entries = A->narrow_entries;
+    if (!on) return LAPIS_OK;
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_chunk_base && A->num_chunks > 0)
+        LAPIS_HIP(hipMemcpy(h_chunk_base, A->d_chunk_base, sizeof(int32_t) * (size_t)A->num_chunks, hipMemcpyDeviceToHost));
+    if (h_col16 && A->nnz > 0)
+        LAPIS_HIP(hipMemcpy(h_col16, A->d_col16, sizeof(uint16_t) * (size_t)A->nnz, hipMemcpyDeviceToHost));
+    return LAPIS_OK;
 }
 
 int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth)

@@ -67,6 +67,10 @@ class CsrMatrix:
         """Host copies (rowptr, colidx, vals) of the handle's CSR arrays."""
         return B.lapis_csr_copy_arrays(self.handle)
 
+    def index16(self):
+        """The 16-bit column offsets of the narrow stream chunks (see lapis_csr_copy_index16)."""
+        return B.lapis_csr_copy_index16(self.handle)
+
     def partition(self):
         return B.lapis_csr_copy_partition(self.handle)
 

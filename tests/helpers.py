@@ -43,6 +43,7 @@ class DeviceCsr:
         dev = torch.device("cuda:0")
         self.nrows, self.ncols = nrows, ncols
         self.np_dtype = vals.dtype
+        self.h_rowptr, self.h_colidx = rowptr, colidx
         self.rowptr = torch.from_numpy(rowptr).to(dev)
         self.colidx = torch.from_numpy(colidx).to(dev) if colidx.size else torch.empty(0, dtype=torch.int32, device=dev)
         self.vals = torch.from_numpy(vals).to(dev) if vals.size else torch.empty(
@@ -95,6 +96,9 @@ class DeviceCsr:
 
     def partition(self):
         return self.mat.partition()
+
+    def index16(self):
+        return self.mat.index16()
 
     def split(self):
         return self.mat.split()

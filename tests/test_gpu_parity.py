@@ -24,12 +24,26 @@ def check_half_bandwidth(dev, rowptr, colidx):
     assert dev.L.lapis_csr_half_bandwidth(dev.mat.handle) == expect
 
 
+def check_index16(dev):
+    """The 16-bit column offsets of the handle against the oracle's, bit for bit."""
+    ref = oracle.index16(dev.h_rowptr, dev.h_colidx)
+    got = dev.index16()
+    assert got["enabled"] == ref["enabled"] and got["narrow_entries"] == ref["narrow_entries"]
+    if ref["enabled"]:
+        assert got["chunk_base"].dtype == np.int32 and got["col16"].dtype == np.uint16
+        assert np.array_equal(got["chunk_base"], ref["chunk_base"]), "chunk_base differs"
+        assert np.array_equal(got["col16"], ref["col16"]), "col16 differs"
+    return ref["enabled"]
+
+
 def check_partition(dev, rowptr):
     ref = oracle.partition(rowptr)
     got = dev.partition()
     for key in ("stream_chunks", "stream_offset", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
         assert got[key].dtype == np.int32
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
+    if rowptr is dev.h_rowptr or np.array_equal(rowptr, dev.h_rowptr):
+        check_index16(dev)
 
 
 def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):
@@ -313,6 +327,54 @@ def test_column_split_looks_only_at_the_split_rows():
         check_spmv(dev, rowptr, colidx, vals, x, what="one descent in a long row")
     finally:
         dev.close()
+
+
+def _banded_and_random(n, ncols, per_row, narrow_rows, seed, dtype):
+    """Rows [0, narrow_rows) get columns row, row+1, ... (a band); the rest keeps random columns."""
+    rowptr, colidx, vals = gen.random_csr(n, ncols, np.full(n, per_row), seed, dtype)
+    band = (np.arange(narrow_rows)[:, None] + np.arange(per_row)[None, :]) % ncols
+    colidx[: narrow_rows * per_row] = np.sort(band, axis=1).ravel().astype(np.int32)
+    return rowptr, colidx, vals
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("narrow_rows,expect_on", [(6400, True), (4480, True), (1600, False), (0, False)])
+def test_index16_mixed_narrow_and_wide_chunks(dtype, narrow_rows, expect_on):
+    """Chunks with 16-bit offsets and chunks with 32-bit columns in one launch (and the structure
+    dropped when the narrow chunks hold less than half of the entries)."""
+    say(f"index16 mixed narrow_rows={narrow_rows} {np.dtype(dtype).name}")
+    n, ncols = 6400, 1 << 20
+    rowptr, colidx, vals = _banded_and_random(n, ncols, 16, narrow_rows, 808, dtype)
+    x = gen.uniform(15, gen.STREAM_X, ncols).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        assert check_index16(dev) == expect_on
+        if expect_on:
+            base = dev.index16()["chunk_base"]
+            assert np.all(base[: narrow_rows // 32] >= 0) and np.all(base[narrow_rows // 32:] == -1)
+        check_spmv(dev, rowptr, colidx, vals, x, what="spmv")
+        X = gen.uniform(16, gen.STREAM_X, ncols * 8).astype(dtype).reshape(ncols, 8)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=8")
+    finally:
+        dev.close()
+
+
+def test_index16_last_entries_of_the_matrix():
+    """nnz % 4 = 1, 2, 3: the entries past the last vector load take the scalar path."""
+    for extra in (1, 2, 3):
+        say(f"index16 tail nnz%4={extra}")
+        n = 640
+        L = np.full(n, 12)
+        L[-1] = 12 + extra
+        rowptr, colidx, vals = gen.random_csr(n, 2000, L, 809, np.float64)
+        assert int(rowptr[-1]) % 4 == extra
+        dev = DeviceCsr(n, 2000, rowptr, colidx, vals)
+        try:
+            assert check_index16(dev)
+            check_spmv(dev, rowptr, colidx, vals, gen.uniform(17, gen.STREAM_X, 2000), what="tail")
+        finally:
+            dev.close()
 
 
 def test_workload4_wide_reduced():
