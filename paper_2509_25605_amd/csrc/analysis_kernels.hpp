@@ -146,18 +146,21 @@ __global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t nu
 
 // Level 1b, one wavefront per chunk: chunk_base[c] = smallest column of stream chunk c if its
 // columns span at most 65535, else -1 (also for chunks that are not stream chunks);
-// *narrow_entries (0 on entry) += entries of the chunks that got a base.
+// *narrow_entries (0 on entry) += entries of the chunks that got a base, and
+// narrow_chunks[class - 1] (0 on entry) += 1 for each of them.
 __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                             const int32_t *__restrict__ chunk_flag,
                                                             const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
                                                             int32_t *__restrict__ chunk_base,
-                                                            unsigned long long *__restrict__ narrow_entries)
+                                                            unsigned long long *__restrict__ narrow_entries,
+                                                            int32_t *__restrict__ narrow_chunks)
 {
     const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
     if (c >= num_chunks) return;                       // whole wavefronts leave together
-    if (chunk_flag[c] == 0) {
+    const int32_t cls = chunk_flag[c];
+    if (cls == 0) {
         if (lane == 0) chunk_base[c] = -1;
         return;
     }
@@ -175,7 +178,10 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
     if (lane == 0) {
         const bool narrow = e > b && hi - lo <= 65535;
         chunk_base[c] = narrow ? lo : -1;
-        if (narrow) atomicAdd(narrow_entries, (unsigned long long)(e - b));
+        if (narrow) {
+            atomicAdd(narrow_entries, (unsigned long long)(e - b));
+            atomicAdd(&narrow_chunks[cls - 1], 1);
+        }
     }
 }
 

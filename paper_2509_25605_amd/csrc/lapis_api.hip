@@ -62,8 +62,9 @@ struct lapis_csr {
     int64_t half_bandwidth = 0;          // max |column - row| over the entries
     // level 1b: 16-bit column offsets of the stream chunks whose columns span less than 2^16
     int32_t *d_chunk_base = nullptr;     // [num_chunks] smallest column of such a chunk, else -1; null: off
-    uint16_t *d_col16 = nullptr;         // [nnz rounded up to 4, + 4] colidx[j] - base of j's chunk
+    uint16_t *d_col16 = nullptr;         // [nnz rounded up to 8, + 8] colidx[j] - base of j's chunk
     int64_t narrow_entries = 0;          // entries in the chunks that could get a base
+    bool class_all16[kStreamClasses] = {false, false, false, false};   // every chunk of the class has a base
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -292,26 +293,33 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     // level 1b: 16-bit column offsets for the stream chunks with a narrow column span, kept only
     // if those chunks hold at least half of the entries
     if (num_stream > 0) {
+        struct NarrowCounts {
+            unsigned long long entries;
+            int32_t chunks[kStreamClasses];
+        } h_counts;
         DeviceTemp narrow;
-        if (int rc = narrow.alloc(sizeof(unsigned long long))) return rc;
+        if (int rc = narrow.alloc(sizeof(NarrowCounts))) return rc;
+        NarrowCounts *d_counts = narrow.as<NarrowCounts>();
         if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
-        LAPIS_HIP(hipMemsetAsync(narrow.p, 0, sizeof(unsigned long long), stream));
+        LAPIS_HIP(hipMemsetAsync(narrow.p, 0, sizeof(NarrowCounts), stream));
         const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
         chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
-            A->d_chunk_base, narrow.as<unsigned long long>());
+            A->d_chunk_base, &d_counts->entries, d_counts->chunks);
         LAPIS_HIP(hipGetLastError());
-        unsigned long long h_narrow = 0;
-        LAPIS_HIP(hipMemcpyAsync(&h_narrow, narrow.p, sizeof(h_narrow), hipMemcpyDeviceToHost, stream));
+        LAPIS_HIP(hipMemcpyAsync(&h_counts, narrow.p, sizeof(h_counts), hipMemcpyDeviceToHost, stream));
         LAPIS_HIP(hipStreamSynchronize(stream));
+        const unsigned long long h_narrow = h_counts.entries;
         A->narrow_entries = (int64_t)h_narrow;
         if (h_narrow > 0 && 2 * h_narrow >= (unsigned long long)A->nnz) {
-            const size_t len = ((size_t)A->nnz + 3) / 4 * 4 + 4;
+            const size_t len = ((size_t)A->nnz + 7) / 8 * 8 + 8;      // 16-byte loads may run past nnz
             if (int rc = device_alloc(&A->d_col16, sizeof(uint16_t) * len)) return rc;
             LAPIS_HIP(hipMemsetAsync(A->d_col16, 0, sizeof(uint16_t) * len, stream));
             col16_fill_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
                 (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16);
             LAPIS_HIP(hipGetLastError());
+            for (int cls = 1; cls <= kStreamClasses; ++cls)
+                A->class_all16[cls - 1] = h_counts.chunks[cls - 1] == A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
         } else {
             (void)hipFree(A->d_chunk_base);
             A->d_chunk_base = nullptr;
@@ -455,9 +463,14 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
     const uint32_t waves = (uint32_t)(count * (G / 2));
     const uint32_t padded = (waves + kXcds - 1) / kXcds * kXcds;
     const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
-    spmv_stream_kernel<T, G, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-        (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
-        static_cast<const T *>(A->vals), x, y, a, b);
+    if (A->class_all16[cls - 1])
+        spmv_stream_kernel<T, G, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
+            static_cast<const T *>(A->vals), x, y, a, b);
+    else
+        spmv_stream_kernel<T, G, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
+            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
+            static_cast<const T *>(A->vals), x, y, a, b);
 }
 
 // y (ncols values) = beta*y, then every entry of A adds alpha*vals[j]*x[row] into y[colidx[j]].

@@ -101,9 +101,9 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
         for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
 
-    for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform
+    for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
-        stream_window_to_lds<T>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, int32_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
         if (active) {
 #pragma unroll
             for (int p = 0; p < kPasses; ++p) {

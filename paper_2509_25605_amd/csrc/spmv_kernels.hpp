@@ -19,6 +19,8 @@
 //    second pass adds a row's tile sums in tile order, so every y[i] has one
 //    writer and the result does not depend on scheduling.
 #pragma once
+#include <type_traits>
+
 #include "device_utils.hpp"
 
 namespace lapis {
@@ -187,14 +189,14 @@ template <> struct StreamVec<double> { typedef double type __attribute__((ext_ve
 template <> struct StreamVec<float> { typedef float type __attribute__((ext_vector_type(4))); };
 typedef int32_t int4v __attribute__((ext_vector_type(4)));
 
-typedef uint16_t ushort4v __attribute__((ext_vector_type(4)));
+typedef uint16_t ushort8v __attribute__((ext_vector_type(8)));
 
 // Where a window's column indices come from: the matrix's 32-bit colidx, or (cbase >= 0) the
 // 16-bit offsets col16 from the chunk's smallest column cbase, which the analysis builds for
 // chunks whose columns span less than 2^16.  Both pointers are already advanced to the window.
 struct StreamCols {
     const int32_t *__restrict__ c32;
-    const uint16_t *__restrict__ c16;     // 8-byte aligned at every multiple of 4 entries; padded past nnz
+    const uint16_t *__restrict__ c16;     // window start a multiple of 8 entries (16 bytes); padded past nnz
     int32_t cbase;
 };
 
@@ -202,23 +204,35 @@ struct StreamCols {
 // NC column loads (16 bytes, or 8 bytes of 16-bit offsets) and NV 16-byte value loads per lane.
 // Lanes past the end repeat the last group: same address, same data, no extra memory traffic
 // and no divergent control flow.
-template <typename T, int NC, int NV, bool C16>
+template <typename T, int NC, int NV, bool C16, typename IDX>
 __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__restrict__ vw,
-                                            int lane, int n_vec, int32_t *s_col, T *s_val)
+                                            int lane, int n_vec, IDX *s_col, T *s_val)
 {
+    constexpr bool kRaw16 = sizeof(IDX) == 2;       // LDS keeps the 16-bit offsets as they are
+    static_assert(!kRaw16 || C16, "a 16-bit LDS window needs 16-bit offsets in memory");
     typedef typename StreamVec<T>::type vec_t;
     constexpr int kPerVec = 16 / sizeof(T);          // values per 16-byte load
     const int last_c = n_vec - 4;
     const int last_v = n_vec - kPerVec;
-    int4v cq[NC];
-    ushort4v cs[NC];
+    constexpr int NC8 = (NC + 1) / 2;               // 16-byte loads of 8 offsets cover 512 entries
+    const int last_c8 = ((n_vec + 7) & ~7) - 8;
+    int4v cq[C16 ? 1 : NC];
+    ushort8v cs[C16 ? NC8 : 1];
     vec_t vq[NV];
+    if constexpr (C16) {
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
-        int idx = i * (kWave * 4) + lane * 4;
-        idx = idx < last_c ? idx : last_c;
-        if constexpr (C16) cs[i] = __builtin_nontemporal_load(reinterpret_cast<const ushort4v *>(cols.c16 + idx));
-        else cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cols.c32 + idx));
+        for (int i = 0; i < NC8; ++i) {
+            int idx = i * (kWave * 8) + lane * 8;
+            idx = idx < last_c8 ? idx : last_c8;
+            cs[i] = __builtin_nontemporal_load(reinterpret_cast<const ushort8v *>(cols.c16 + idx));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            int idx = i * (kWave * 4) + lane * 4;
+            idx = idx < last_c ? idx : last_c;
+            cq[i] = __builtin_nontemporal_load(reinterpret_cast<const int4v *>(cols.c32 + idx));
+        }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -226,18 +240,28 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
         idx = idx < last_v ? idx : last_v;
         vq[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(vw + idx));
     }
+    if constexpr (C16) {
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
-        int idx = i * (kWave * 4) + lane * 4;
-        idx = idx < last_c ? idx : last_c;
-        if constexpr (C16) {
-            int4v c;
-            c.x = cols.cbase + (int32_t)cs[i].x;
-            c.y = cols.cbase + (int32_t)cs[i].y;
-            c.z = cols.cbase + (int32_t)cs[i].z;
-            c.w = cols.cbase + (int32_t)cs[i].w;
-            *reinterpret_cast<int4v *>(s_col + idx) = c;
-        } else {
+        for (int i = 0; i < NC8; ++i) {
+            int idx = i * (kWave * 8) + lane * 8;
+            idx = idx < last_c8 ? idx : last_c8;
+            if constexpr (kRaw16) {
+                *reinterpret_cast<ushort8v *>(s_col + idx) = cs[i];
+                continue;
+            }
+            int4v a, b;
+            a.x = cols.cbase + (int32_t)cs[i].s0; a.y = cols.cbase + (int32_t)cs[i].s1;
+            a.z = cols.cbase + (int32_t)cs[i].s2; a.w = cols.cbase + (int32_t)cs[i].s3;
+            b.x = cols.cbase + (int32_t)cs[i].s4; b.y = cols.cbase + (int32_t)cs[i].s5;
+            b.z = cols.cbase + (int32_t)cs[i].s6; b.w = cols.cbase + (int32_t)cs[i].s7;
+            *reinterpret_cast<int4v *>(s_col + idx) = a;
+            *reinterpret_cast<int4v *>(s_col + idx + 4) = b;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            int idx = i * (kWave * 4) + lane * 4;
+            idx = idx < last_c ? idx : last_c;
             *reinterpret_cast<int4v *>(s_col + idx) = cq[i];
         }
     }
@@ -251,50 +275,57 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
 
 // NC column loads cover NC*256 entries; the value loads needed for n_vec entries are either
 // NC*R or NC*R - 1 (R = value loads per 256 entries: 2 for double, 1 for float).
-template <typename T, int NC, bool C16>
+template <typename T, int NC, bool C16, typename IDX>
 __device__ __forceinline__ void stream_fill_pick(const StreamCols cols, const T *__restrict__ vw,
-                                                 int lane, int n_vec, int32_t *s_col, T *s_val)
+                                                 int lane, int n_vec, IDX *s_col, T *s_val)
 {
     constexpr int kPerLoad = kWave * (16 / (int)sizeof(T));   // entries per value load instruction
     constexpr int kFull = NC * (kWave * 4) / kPerLoad;
     if constexpr (kFull > 1 && kPerLoad < kWave * 4) {
         if (n_vec <= (kFull - 1) * kPerLoad) {
-            stream_fill<T, NC, kFull - 1, C16>(cols, vw, lane, n_vec, s_col, s_val);
+            stream_fill<T, NC, kFull - 1, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
             return;
         }
     }
-    stream_fill<T, NC, kFull, C16>(cols, vw, lane, n_vec, s_col, s_val);
+    stream_fill<T, NC, kFull, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
 }
 
-template <typename T, bool C16>
+template <typename T, bool C16, typename IDX>
 __device__ __forceinline__ void stream_fill_by_size(const StreamCols cols, const T *__restrict__ vw,
-                                                    int lane, int n_vec, int32_t *s_col, T *s_val)
+                                                    int lane, int n_vec, IDX *s_col, T *s_val)
 {
-    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4, C16>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3, C16>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > kWave * 4) stream_fill_pick<T, 2, C16>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 0) stream_fill_pick<T, 1, C16>(cols, vw, lane, n_vec, s_col, s_val);
+    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > kWave * 4) stream_fill_pick<T, 2, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 0) stream_fill_pick<T, 1, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
 }
 
-// Stage entries [w0, w1) of the matrix (w0 a multiple of 4, w1 - w0 <= kStreamWindow) in LDS:
+// Stage entries [w0, w1) of the matrix (w0 a multiple of 8, w1 - w0 <= kStreamWindow) in LDS:
 // vector loads up to nnz4 (= nnz rounded down to a multiple of 4), the matrix's last nnz % 4
 // entries one by one.  cbase >= 0: the columns are cbase + col16[j], else colidx[j] (col16 may
 // then be null).  Ends with a wavefront-level fence so every lane may read what others wrote.
-template <typename T>
+// With a 16-bit LDS window (IDX = uint16_t) the offsets are staged as they are and cbase must be >= 0.
+template <typename T, typename IDX>
 __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__ colidx,
                                                      const uint16_t *__restrict__ col16, int32_t cbase,
                                                      const T *__restrict__ vals, int32_t w0, int32_t w1,
-                                                     int32_t nnz4, int lane, int32_t *s_col, T *s_val)
+                                                     int32_t nnz4, int lane, IDX *s_col, T *s_val)
 {
+    constexpr bool kRaw16 = sizeof(IDX) == 2;
     const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;   // vector loads stop here
     const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
     const T *__restrict__ vw = vals + w0;
-    if (cbase >= 0) stream_fill_by_size<T, true>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
-    else stream_fill_by_size<T, false>(StreamCols{colidx + w0, nullptr, 0}, vw, lane, n_vec, s_col, s_val);
+    if constexpr (kRaw16) {
+        stream_fill_by_size<T, true, IDX>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
+    } else {
+        if (cbase >= 0) stream_fill_by_size<T, true, IDX>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
+        else stream_fill_by_size<T, false, IDX>(StreamCols{colidx + w0, nullptr, 0}, vw, lane, n_vec, s_col, s_val);
+    }
     if (w0 + n_vec < w1) {                              // the matrix's last nnz % 4 entries
         const int32_t j = w0 + n_vec + lane;
         if (j < w1) {
-            s_col[j - w0] = cbase >= 0 ? cbase + (int32_t)col16[j] : colidx[j];
+            if constexpr (kRaw16) s_col[j - w0] = col16[j];
+            else s_col[j - w0] = cbase >= 0 ? cbase + (int32_t)col16[j] : colidx[j];
             s_val[j - w0] = vals[j];
         }
     }
@@ -306,8 +337,9 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
 // B entries of this lane's share of a row: (column, value) pairs out of LDS, the B gathers of x
 // issued back to back, then the FMAs.  Lanes with fewer than u0 + B entries repeat their last
 // entry and discard the product (no divergent control flow).
-template <typename T, int B, int G>
-__device__ __forceinline__ T stream_batch(const int32_t *sc, const T *sv, int u0, int my_n, int last_u,
+// x is already advanced by the chunk's smallest column when the window holds 16-bit offsets.
+template <typename T, int B, int G, typename IDX>
+__device__ __forceinline__ T stream_batch(const IDX *sc, const T *sv, int u0, int my_n, int last_u,
                                           const T *__restrict__ x, T s)
 {
     int32_t cc[B];
@@ -315,7 +347,7 @@ __device__ __forceinline__ T stream_batch(const int32_t *sc, const T *sv, int u0
 #pragma unroll
     for (int t = 0; t < B; ++t) {
         const int u = (u0 + t < last_u ? u0 + t : last_u) * G;
-        cc[t] = sc[u];
+        cc[t] = (int32_t)sc[u];
         vv[t] = sv[u];
     }
 #pragma unroll
@@ -330,7 +362,9 @@ __device__ __forceinline__ T stream_batch(const int32_t *sc, const T *sv, int u0
 // stream_chunks lists the chunks of that class; nullptr means every chunk of the matrix.
 // colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a multiple of 4:
 // 16-byte loads never reach past it, the last nnz % 4 entries of the matrix are fetched one by one.
-template <typename T, int G, bool XCD_REMAP, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
+// ALL16: every chunk of this launch has 16-bit offsets (chunk_base >= 0); the LDS window then
+// keeps 2-byte offsets (10 instead of 12 KB per wavefront with doubles: more wavefronts per CU).
+template <typename T, int G, bool XCD_REMAP, bool ALL16 = false, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
@@ -342,8 +376,9 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     constexpr int kWavesPerChunk = kStreamRows / kRowsPerWave;
     static_assert(G >= 2 && G <= 16 && kWavesPerChunk * kRowsPerWave == kStreamRows, "G must be 2, 4, 8 or 16");
     static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
+    typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
-    __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
+    __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
 
     const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_waves) : blockIdx.x;
     if (id >= num_waves) return;
@@ -363,9 +398,9 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
 
     T s = T(0);
     // windows of kStreamWindow entries starting at a multiple of 4 (16-byte aligned loads)
-    for (int32_t w0 = base & ~3; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
+    for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
-        stream_window_to_lds<T>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
 
         // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
         const int32_t ub = (rb > w0 ? rb : w0) - w0;
@@ -373,24 +408,25 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
         const int my_n = (ue - ub - sub + G - 1) / G;                  // <= 0: nothing to do
         const int first = my_n > 0 ? ub + sub : 0;                     // idle lanes re-read entry 0
         const int last_u = my_n > 0 ? my_n - 1 : 0;
-        const int32_t *sc = s_col + first;
+        const idx_t *sc = s_col + first;
         const T *sv = s_val + first;
+        const T *xb = ALL16 ? x + cbase : x;
         // batches of UNR entries per lane; the last batch is cut to the longest share in the
         // wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane, not 16
         int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
         int u0 = 0;
 #pragma unroll 1
-        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch<T, UNR, G>(sc, sv, u0, my_n, last_u, x, s);
+        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s);
         switch ((rem + 1) / 2) {
         case 0: break;
-        case 1: s = stream_batch<T, 2, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 2: s = stream_batch<T, 4, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 3: s = stream_batch<T, 6, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 4: s = stream_batch<T, 8, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 5: s = stream_batch<T, 10, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 6: s = stream_batch<T, 12, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        case 7: s = stream_batch<T, 14, G>(sc, sv, u0, my_n, last_u, x, s); break;
-        default: s = stream_batch<T, UNR, G>(sc, sv, u0, my_n, last_u, x, s); break;
+        case 1: s = stream_batch<T, 2, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 2: s = stream_batch<T, 4, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 3: s = stream_batch<T, 6, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 4: s = stream_batch<T, 8, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 5: s = stream_batch<T, 10, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 6: s = stream_batch<T, 12, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 7: s = stream_batch<T, 14, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        default: s = stream_batch<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
