@@ -168,10 +168,15 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
     const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
     const int32_t b = rowptr[first], e = rowptr[last];
     int32_t hi = 0, lo_rev = 0;                        // lo_rev = INT32_MAX - smallest column
-    for (int32_t j = b + lane; j < e; j += kWave) {
-        const int32_t col = load_stream(colidx + j);
-        hi = max(hi, col);
-        lo_rev = max(lo_rev, INT32_MAX - col);
+    for (int32_t j = b + lane; j < e; j += 8 * kWave) {     // 8 loads in flight; past the end: the last entry again
+        int32_t col[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) col[q] = load_stream(colidx + (j + q * kWave < e ? j + q * kWave : e - 1));
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            hi = max(hi, col[q]);
+            lo_rev = max(lo_rev, INT32_MAX - col[q]);
+        }
     }
     hi = wave_max_nonneg(hi);
     const int32_t lo = INT32_MAX - wave_max_nonneg(lo_rev);
