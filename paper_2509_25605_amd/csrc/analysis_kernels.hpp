@@ -146,21 +146,18 @@ __global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t nu
 
 // Level 1b, one wavefront per chunk: chunk_base[c] = smallest column of stream chunk c if its
 // columns span at most 65535, else -1 (also for chunks that are not stream chunks);
-// *narrow_entries (0 on entry) += entries of the chunks that got a base, and
-// narrow_chunks[class - 1] (0 on entry) += 1 for each of them.
+// The totals are taken by narrow_count_kernel (one atomic per chunk on one address would
+// serialise: it cost 1 ms on 65 536 chunks).
 __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                             const int32_t *__restrict__ chunk_flag,
                                                             const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
-                                                            int32_t *__restrict__ chunk_base,
-                                                            unsigned long long *__restrict__ narrow_entries,
-                                                            int32_t *__restrict__ narrow_chunks)
+                                                            int32_t *__restrict__ chunk_base)
 {
     const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
     if (c >= num_chunks) return;                       // whole wavefronts leave together
-    const int32_t cls = chunk_flag[c];
-    if (cls == 0) {
+    if (chunk_flag[c] == 0) {
         if (lane == 0) chunk_base[c] = -1;
         return;
     }
@@ -183,11 +180,42 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
     if (lane == 0) {
         const bool narrow = e > b && hi - lo <= 65535;
         chunk_base[c] = narrow ? lo : -1;
-        if (narrow) {
-            atomicAdd(narrow_entries, (unsigned long long)(e - b));
-            atomicAdd(&narrow_chunks[cls - 1], 1);
-        }
     }
+}
+
+// One workgroup of kCompactBlock threads: *narrow_entries = entries of the chunks with a base,
+// narrow_chunks[k - 1] = how many of them are of class k.
+__global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nrows, int32_t num_chunks,
+                                                                     int32_t chunk_rows,
+                                                                     const int32_t *__restrict__ chunk_flag,
+                                                                     const int32_t *__restrict__ rowptr,
+                                                                     const int32_t *__restrict__ chunk_base,
+                                                                     unsigned long long *__restrict__ narrow_entries,
+                                                                     int32_t *__restrict__ narrow_chunks)
+{
+    __shared__ unsigned long long s_entries;
+    __shared__ int32_t s_chunks[kChunkClasses];
+    if (threadIdx.x == 0) s_entries = 0;
+    if (threadIdx.x < kChunkClasses) s_chunks[threadIdx.x] = 0;
+    __syncthreads();
+    unsigned long long entries = 0;
+    int32_t chunks[kChunkClasses] = {0, 0, 0, 0};
+    for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
+        if (chunk_base[c] < 0) continue;
+        const int64_t first = c * chunk_rows;
+        const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+        entries += (unsigned long long)(rowptr[last] - rowptr[first]);
+        const int32_t cls = chunk_flag[c];
+#pragma unroll
+        for (int k = 0; k < kChunkClasses; ++k) chunks[k] += (cls == k + 1);
+    }
+    if (entries) atomicAdd(&s_entries, entries);
+#pragma unroll
+    for (int k = 0; k < kChunkClasses; ++k)
+        if (chunks[k]) atomicAdd(&s_chunks[k], chunks[k]);
+    __syncthreads();
+    if (threadIdx.x == 0) *narrow_entries = s_entries;
+    if (threadIdx.x < kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
 }
 
 // col16[j] = colidx[j] - chunk_base[c] for the entries of the chunks with a base (col16 is 0 elsewhere)

@@ -301,11 +301,13 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         if (int rc = narrow.alloc(sizeof(NarrowCounts))) return rc;
         NarrowCounts *d_counts = narrow.as<NarrowCounts>();
         if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
-        LAPIS_HIP(hipMemsetAsync(narrow.p, 0, sizeof(NarrowCounts), stream));
         const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
         chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
-            A->d_chunk_base, &d_counts->entries, d_counts->chunks);
+            A->d_chunk_base);
+        narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
+            &d_counts->entries, d_counts->chunks);
         LAPIS_HIP(hipGetLastError());
         LAPIS_HIP(hipMemcpyAsync(&h_counts, narrow.p, sizeof(h_counts), hipMemcpyDeviceToHost, stream));
         LAPIS_HIP(hipStreamSynchronize(stream));
