@@ -99,11 +99,12 @@ def main():
     k = max(w.k, 1)
     y = (torch.from_numpy(w.y0).to(dev) if w.y0 is not None
          else torch.zeros(w.nrows * k, dtype=tdt, device=dev))
+    L.CsrMatrix(w.nrows, w.ncols, rowptr, colidx, vals).close()   # first call also loads the code object
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     A = L.CsrMatrix(w.nrows, w.ncols, rowptr, colidx, vals)
     torch.cuda.synchronize()
-    create_ms = (time.perf_counter() - t0) * 1e3
+    create_ms = (time.perf_counter() - t0) * 1e3                  # analysis of an already loaded library
 
     if args.variant != "tuned" and w.k != 0:
         sys.exit("bench.py: --variant applies to the SpMV workloads only")

@@ -120,6 +120,24 @@ int device_alloc(P **ptr, size_t bytes)
     return LAPIS_OK;
 }
 
+// Small device-to-host readback through a pinned staging buffer (a copy into pageable memory
+// costs a few hundred microseconds), followed by a stream synchronisation.  One buffer per host
+// thread, allocated on first use and kept for the life of the process.
+int read_back(void *dst, const void *d_src, size_t bytes, hipStream_t stream)
+{
+    constexpr size_t kStageBytes = 256;
+    thread_local void *stage = nullptr;
+    if (bytes > kStageBytes) return fail(LAPIS_ERR_DEVICE, "readback larger than the staging buffer");
+    if (!stage) {
+        hipError_t e = hipHostMalloc(&stage, kStageBytes, hipHostMallocDefault);
+        if (e != hipSuccess) { stage = nullptr; return fail_hip(e, "hipHostMalloc"); }
+    }
+    LAPIS_HIP(hipMemcpyAsync(stage, d_src, bytes, hipMemcpyDeviceToHost, stream));
+    LAPIS_HIP(hipStreamSynchronize(stream));
+    std::memcpy(dst, stage, bytes);
+    return LAPIS_OK;
+}
+
 // Frees on scope exit; for the temporaries of the analysis.
 struct DeviceTemp {
     void *p = nullptr;
@@ -192,9 +210,7 @@ int bin_row_set(BinnedSet *s, const int32_t *d_chunk_flag, size_t esize, hipStre
             (int32_t)n, s->row_begin, s->row_end, LAPIS_STREAM_ROWS, d_chunk_flag, num_blocks,
             hist.as<int32_t>(), s->d_row_perm);
         LAPIS_HIP(hipGetLastError());
-        LAPIS_HIP(hipMemcpyAsync(s->h_bin_offset, s->d_bin_offset, sizeof(int32_t) * (kNumBins + 1),
-                                 hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));   // hist is freed on return
+        if (int rc = read_back(s->h_bin_offset, s->d_bin_offset, sizeof(int32_t) * (kNumBins + 1), stream)) return rc;
     }
     s->num_binned = s->h_bin_offset[kNumBins];
 
@@ -206,8 +222,7 @@ int bin_row_set(BinnedSet *s, const int32_t *d_chunk_flag, size_t esize, hipStre
     if (m > 0) {
         long_scan_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(
             m, s->d_row_perm + s->h_bin_offset[kNumBins - 1], s->row_begin, s->row_end, s->d_long_off);
-        LAPIS_HIP(hipMemcpyAsync(&long_total, s->d_long_off + m, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (int rc = read_back(&long_total, s->d_long_off + m, sizeof(int32_t), stream)) return rc;
     } else {
         LAPIS_HIP(hipMemsetAsync(s->d_long_off, 0, sizeof(int32_t), stream));
     }
@@ -253,8 +268,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
             (int32_t)n, A->ncols, (int32_t)A->nnz, A->rowptr, A->colidx, d_flags);
         LAPIS_HIP(hipGetLastError());
         int32_t flags[kNumCheckFlags] = {0};
-        LAPIS_HIP(hipMemcpyAsync(flags, d_flags, sizeof(flags), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (int rc = read_back(flags, d_flags, sizeof(flags), stream)) return rc;
         if (flags[4]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr[0] must be 0 and rowptr[nrows] must equal nnz");
         if (flags[0]) return fail(LAPIS_ERR_INVALID_ARG, "rowptr is not non-decreasing");
         if (flags[1]) return fail(LAPIS_ERR_INVALID_ARG, "a column index is outside [0, ncols)");
@@ -283,9 +297,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         chunk_compact_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
             num_chunks, chunk_flag.as<int32_t>(), A->d_stream_chunks, offsets.as<int32_t>());
         LAPIS_HIP(hipGetLastError());
-        LAPIS_HIP(hipMemcpyAsync(A->h_stream_offset, offsets.as<int32_t>(), sizeof(int32_t) * (kStreamClasses + 1),
-                                 hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (int rc = read_back(A->h_stream_offset, offsets.as<int32_t>(), sizeof(int32_t) * (kStreamClasses + 1), stream)) return rc;
         num_stream = A->h_stream_offset[kStreamClasses];
     }
     A->num_stream = num_stream;
@@ -309,8 +321,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
             &d_counts->entries, d_counts->chunks);
         LAPIS_HIP(hipGetLastError());
-        LAPIS_HIP(hipMemcpyAsync(&h_counts, narrow.p, sizeof(h_counts), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (int rc = read_back(&h_counts, narrow.p, sizeof(h_counts), stream)) return rc;
         const unsigned long long h_narrow = h_counts.entries;
         A->narrow_entries = (int64_t)h_narrow;
         if (h_narrow > 0 && 2 * h_narrow >= (unsigned long long)A->nnz) {
@@ -346,8 +357,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         split_sorted_kernel<<<dim3(sblocks), dim3(kBlock), 0, stream>>>((int32_t)S, split_rows, A->rowptr,
                                                                         A->colidx, d_flags);
         int32_t unsorted = 0;
-        LAPIS_HIP(hipMemcpyAsync(&unsorted, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-        LAPIS_HIP(hipStreamSynchronize(stream));
+        if (int rc = read_back(&unsorted, d_flags, sizeof(int32_t), stream)) return rc;
         split = !unsorted;
     }
     if (split) {
@@ -416,8 +426,7 @@ int build_transposed_arrays(const lapis_csr *A, lapis_csr *B, hipStream_t stream
         num_long.as<int32_t>());
     LAPIS_HIP(hipGetLastError());
     int32_t h_num_long = 0;
-    LAPIS_HIP(hipMemcpyAsync(&h_num_long, num_long.p, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-    LAPIS_HIP(hipStreamSynchronize(stream));
+    if (int rc = read_back(&h_num_long, num_long.p, sizeof(int32_t), stream)) return rc;
     if (h_num_long < 0 || h_num_long > max_long) return fail(LAPIS_ERR_DEVICE, "transposition: long column count out of range");
     if (h_num_long > 0)
         transpose_sort_long_kernel<<<dim3((uint32_t)h_num_long), dim3(kSortLongBlock), 0, stream>>>(
