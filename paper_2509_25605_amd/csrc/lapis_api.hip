@@ -582,11 +582,19 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         }
         const uint32_t unit = xcd_block ? xcd_block * kXcds : kXcds;
         const uint32_t padded = (chunks + unit - 1) / unit * unit;
-        for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC)
-            spmm_stream_kernel<T, VEC, kStreamLanes, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                A->d_chunk_base, A->d_col16, vals,
-                k, c0, X, ldx, Y, ldy, a, b);
+        bool all16 = A->d_col16 != nullptr;                           // every stream chunk has 16-bit offsets
+        for (int cls = 1; cls <= kStreamClasses; ++cls)
+            all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
+        for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
+            if (all16)
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                    A->d_chunk_base, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+            else
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                    A->d_chunk_base, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+        }
     }
     if (n_rows_a > 0) {
         const uint32_t blocks = (uint32_t)(((int64_t)n_rows_a + kSlots - 1) / kSlots);

@@ -58,7 +58,8 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 // dealt to the XCDs block-cyclically, xcd_block chunks at a time (see xcd_block_cyclic_id).
 constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
-template <typename T, int VEC, int CL, bool XCD_REMAP>
+// ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
+template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
@@ -70,7 +71,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
     constexpr int kPasses = kStreamRows / kSlots;
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
-    __shared__ __attribute__((aligned(16))) int32_t s_col[kStreamWindow];
+    typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
+    __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
     __shared__ int32_t s_rp[kStreamRows + 1];
 
     const uint32_t id = !XCD_REMAP ? blockIdx.x
@@ -94,6 +96,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     const int32_t nnz4 = nnz & ~3;
     const int64_t col = c0 + (int64_t)l * VEC;
     const bool active = slot < kSlots && col < k;
+    const T *__restrict__ Xb = ALL16 ? X + (int64_t)cbase * ldx : X;     // offsets count from the chunk's base
 
     T acc[kPasses][VEC];
 #pragma unroll
@@ -103,7 +106,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
-        stream_window_to_lds<T, int32_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
         if (active) {
 #pragma unroll
             for (int p = 0; p < kPasses; ++p) {
@@ -122,12 +125,12 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
                     for (int t = 0; t < kSpmmUnroll; ++t) {
                         const int u = first + (u0 + t < last_u ? u0 + t : last_u);  // past the end: repeat
-                        cj[t] = s_col[u];
+                        cj[t] = (int32_t)s_col[u];
                         vj[t] = s_val[u];
                     }
 #pragma unroll
                     for (int t = 0; t < kSpmmUnroll; ++t)
-                        xv[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (int64_t)cj[t] * ldx + col);
+                        xv[t] = *reinterpret_cast<const Pack<T, VEC> *>(Xb + (int64_t)cj[t] * ldx + col);
 #pragma unroll
                     for (int t = 0; t < kSpmmUnroll; ++t)
 #pragma unroll
