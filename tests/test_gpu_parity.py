@@ -446,3 +446,8 @@ def test_workload_reduced(cfg):
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5, 8, 9])
 def test_workload_full_size(cfg):
     run_workload(cfg, None)
+
+
+def test_workload4_exponent_two_full_size():
+    """The labelled variant of workload 4 with Zipf exponent 2.0 (mean row length about 8)."""
+    run_workload(4, {"s": 2.0})
