@@ -582,7 +582,8 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         }
         const uint32_t unit = xcd_block ? xcd_block * kXcds : kXcds;
         const uint32_t padded = (chunks + unit - 1) / unit * unit;
-        bool all16 = A->d_col16 != nullptr;                           // every stream chunk has 16-bit offsets
+        // every stream chunk has 16-bit offsets, and offset * (bytes per row of X) fits in 32 bits
+        bool all16 = A->d_col16 != nullptr && ldx * (int64_t)sizeof(T) <= 0xffff;
         for (int cls = 1; cls <= kStreamClasses; ++cls)
             all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {

@@ -29,6 +29,9 @@ struct alignas(sizeof(T) * VEC) Pack {
     T v[VEC];
 };
 
+__device__ __forceinline__ double fused_madd(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float fused_madd(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
 template <typename T, int VEC>
 __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[VEC], int64_t col,
                                           int64_t k, T alpha, T beta)
@@ -96,7 +99,18 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     const int32_t nnz4 = nnz & ~3;
     const int64_t col = c0 + (int64_t)l * VEC;
     const bool active = slot < kSlots && col < k;
-    const T *__restrict__ Xb = ALL16 ? X + (int64_t)cbase * ldx : X;     // offsets count from the chunk's base
+    // Row c of X for this lane.  With 16-bit offsets (ALL16; the host guarantees a row of X is
+    // shorter than 64 KiB) the row is a 32-bit byte offset from the chunk's base row: one 24-bit
+    // multiply-add and a load with a scalar base; otherwise 64-bit pointer arithmetic.
+    const uint32_t row_bytes = (uint32_t)(ldx * (int64_t)sizeof(T));
+    auto x_row = [&](int32_t c) {
+        if constexpr (ALL16)
+            return *reinterpret_cast<const Pack<T, VEC> *>(
+                reinterpret_cast<const char *>(X + (int64_t)cbase * ldx) +
+                (__umul24((uint32_t)c, row_bytes) + (uint32_t)(col * (int64_t)sizeof(T))));
+        else
+            return *reinterpret_cast<const Pack<T, VEC> *>(X + (int64_t)c * ldx + col);
+    };
 
     T acc[kPasses][VEC];
 #pragma unroll
@@ -107,18 +121,53 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
         stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
-        if (active) {
 #pragma unroll
-            for (int p = 0; p < kPasses; ++p) {
-                const int r = p * kSlots + slot;
-                const int32_t rb = s_rp[r], re = s_rp[r + 1];
-                const int32_t ub = (rb > w0 ? rb : w0) - w0;
-                const int32_t ue = (re < w1 ? re : w1) - w0;
-                const int n = ue - ub;                                 // <= 0: row not in this window
-                const int first = n > 0 ? ub : 0;
-                const int last_u = n > 0 ? n - 1 : 0;
+        for (int p = 0; p < kPasses; ++p) {
+            const int r = active ? p * kSlots + slot : 0;
+            const int32_t rb = s_rp[r], re = s_rp[r + 1];
+            const int32_t ub = (rb > w0 ? rb : w0) - w0;
+            const int32_t ue = (re < w1 ? re : w1) - w0;
+            const int n = active ? ue - ub : 0;                        // <= 0: row not in this window
+            const int first = n > 0 ? ub : 0;
+            const int last_u = n > 0 ? n - 1 : 0;
+            const int n_all = wave_max_nonneg(n > 0 ? n : 0);          // every lane takes part
+            if (active) {
+                // While every lane in this branch still has B entries left (B = 16, then 8, 4, 2, 1),
+                // a batch of B runs without clamps or selects: LDS reads at immediate offsets, one
+                // address operation per row of X, fused multiply-adds.  What is left when the rows
+                // of the wavefront differ in length goes through the ragged batches below, which
+                // repeat a lane's last entry and discard the product.
+                int u0 = 0;
+                auto whole_batch = [&](auto batch) {
+                    constexpr int B = decltype(batch)::value;
+                    int32_t cj[B];
+                    T vj[B];
+                    Pack<T, VEC> xv[B];
+                    const idx_t *sc = s_col + first + u0;
+                    const T *sv = s_val + first + u0;
+#pragma unroll
+                    for (int t = 0; t < B; ++t) {
+                        cj[t] = (int32_t)sc[t];
+                        vj[t] = sv[t];
+                    }
+#pragma unroll
+                    for (int t = 0; t < B; ++t) xv[t] = x_row(cj[t]);
+#pragma unroll
+                    for (int t = 0; t < B; ++t)
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) acc[p][q] = fused_madd(vj[t], xv[t].v[q], acc[p][q]);
+                    u0 += B;
+                };
+                auto all_have = [&](int b) { return __builtin_amdgcn_ballot_w64(n - u0 < b) == 0; };
 #pragma unroll 1
-                for (int u0 = 0; u0 < n; u0 += kSpmmUnroll) {
+                while (all_have(kSpmmUnroll)) whole_batch(std::integral_constant<int, kSpmmUnroll>());
+                if (all_have(8)) whole_batch(std::integral_constant<int, 8>());
+                if (all_have(4)) whole_batch(std::integral_constant<int, 4>());
+                if (all_have(2)) whole_batch(std::integral_constant<int, 2>());
+                if (all_have(1)) whole_batch(std::integral_constant<int, 1>());
+#pragma unroll 1
+                for (; u0 < n_all; u0 += kSpmmUnroll) {
+                    if (u0 >= n) continue;
                     int32_t cj[kSpmmUnroll];
                     T vj[kSpmmUnroll];
                     Pack<T, VEC> xv[kSpmmUnroll];
@@ -129,8 +178,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                         vj[t] = s_val[u];
                     }
 #pragma unroll
-                    for (int t = 0; t < kSpmmUnroll; ++t)
-                        xv[t] = *reinterpret_cast<const Pack<T, VEC> *>(Xb + (int64_t)cj[t] * ldx + col);
+                    for (int t = 0; t < kSpmmUnroll; ++t) xv[t] = x_row(cj[t]);
 #pragma unroll
                     for (int t = 0; t < kSpmmUnroll; ++t)
 #pragma unroll
