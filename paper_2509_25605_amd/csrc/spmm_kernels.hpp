@@ -29,9 +29,6 @@ struct alignas(sizeof(T) * VEC) Pack {
     T v[VEC];
 };
 
-__device__ __forceinline__ double fused_madd(double a, double b, double c) { return __builtin_fma(a, b, c); }
-__device__ __forceinline__ float fused_madd(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
-
 template <typename T, int VEC>
 __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[VEC], int64_t col,
                                           int64_t k, T alpha, T beta)

@@ -337,24 +337,49 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
 // B entries of this lane's share of a row: (column, value) pairs out of LDS, the B gathers of x
 // issued back to back, then the FMAs.  Lanes with fewer than u0 + B entries repeat their last
 // entry and discard the product (no divergent control flow).
+__device__ __forceinline__ double fused_madd(double a, double b, double c) { return __builtin_fma(a, b, c); }
+__device__ __forceinline__ float fused_madd(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
+// B entries of this lane's share of a row: (column, value) pairs out of LDS, the B gathers of x
+// issued back to back, then the multiply-adds.  The first W of the B entries exist in every lane of
+// the wavefront (the caller knows the shortest share): they need no clamp and no select and use
+// FMAs.  For the others, lanes with fewer than u0 + B entries repeat their last entry and discard
+// the product (no divergent control flow).
 // x is already advanced by the chunk's smallest column when the window holds 16-bit offsets.
-template <typename T, int B, int G, typename IDX>
+template <typename T, int B, int W, int G, typename IDX>
 __device__ __forceinline__ T stream_batch(const IDX *sc, const T *sv, int u0, int my_n, int last_u,
                                           const T *__restrict__ x, T s)
 {
+    static_assert(W >= 0 && W <= B, "W counts leading entries of the batch");
     int32_t cc[B];
     T vv[B], xx[B];
 #pragma unroll
     for (int t = 0; t < B; ++t) {
-        const int u = (u0 + t < last_u ? u0 + t : last_u) * G;
+        const int u = (t < W ? u0 + t : (u0 + t < last_u ? u0 + t : last_u)) * G;
         cc[t] = (int32_t)sc[u];
         vv[t] = sv[u];
     }
 #pragma unroll
     for (int t = 0; t < B; ++t) xx[t] = x[cc[t]];
 #pragma unroll
-    for (int t = 0; t < B; ++t) s += (u0 + t < my_n) ? vv[t] * xx[t] : T(0);
+    for (int t = 0; t < B; ++t) {
+        if (t < W) s = fused_madd(vv[t], xx[t], s);
+        else s += (u0 + t < my_n) ? vv[t] * xx[t] : T(0);
+    }
     return s;
+}
+
+// The batch of B with as many unconditional leading entries as the shortest share allows:
+// all B, all but the last two (shares in a wavefront usually differ by at most one), or none.
+template <typename T, int B, int G, typename IDX>
+__device__ __forceinline__ T stream_batch_pick(const IDX *sc, const T *sv, int u0, int my_n, int last_u,
+                                               int shortest, const T *__restrict__ x, T s)
+{
+    if (shortest - u0 >= B) return stream_batch<T, B, B, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
+    if constexpr (B > 2) {
+        if (shortest - u0 >= B - 2) return stream_batch<T, B, B - 2, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
+    }
+    return stream_batch<T, B, 0, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
 }
 
 // One wavefront (= one workgroup) per 64/G consecutive rows of a stream chunk of the class with
@@ -414,19 +439,20 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
         // batches of UNR entries per lane; the last batch is cut to the longest share in the
         // wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane, not 16
         int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
+        const int shortest = kStreamWindow - wave_max_nonneg(kStreamWindow - (my_n > 0 ? my_n : 0));   // uniform
         int u0 = 0;
 #pragma unroll 1
-        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s);
+        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch_pick<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s);
         switch ((rem + 1) / 2) {
         case 0: break;
-        case 1: s = stream_batch<T, 2, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 2: s = stream_batch<T, 4, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 3: s = stream_batch<T, 6, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 4: s = stream_batch<T, 8, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 5: s = stream_batch<T, 10, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 6: s = stream_batch<T, 12, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        case 7: s = stream_batch<T, 14, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
-        default: s = stream_batch<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, xb, s); break;
+        case 1: s = stream_batch_pick<T, 2, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 2: s = stream_batch_pick<T, 4, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 3: s = stream_batch_pick<T, 6, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 4: s = stream_batch_pick<T, 8, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 5: s = stream_batch_pick<T, 10, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 6: s = stream_batch_pick<T, 12, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 7: s = stream_batch_pick<T, 14, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        default: s = stream_batch_pick<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
