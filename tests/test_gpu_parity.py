@@ -377,6 +377,30 @@ def test_index16_last_entries_of_the_matrix():
             dev.close()
 
 
+def test_spmm_row_lengths_and_wide_leading_dimension():
+    """Stream chunks with 16-bit offsets: rows of 16 / 24 / 27 / 33 entries exercise the whole
+    batches of 16, 8, 2 and 1 and the ragged remainder; a row of X longer than 64 KiB switches the
+    32-bit row offsets off."""
+    say("spmm batches and wide ldx")
+    n, ncols = 1280, 900
+    for lengths, tag in ((np.full(n, 16), "16"), (np.full(n, 24), "24"), (np.full(n, 27), "27"),
+                         (np.full(n, 33), "33"), (16 + (np.arange(n) * 7) % 20, "ragged 16..35")):
+        rowptr, colidx, vals = gen.random_csr(n, ncols, lengths, 4242, np.float64)
+        dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+        try:
+            assert check_index16(dev)
+            X = gen.uniform(18, gen.STREAM_X, ncols * 16).reshape(ncols, 16)
+            Y0 = gen.uniform(18, gen.STREAM_Y0, n * 16).reshape(n, 16)
+            check_spmm(dev, rowptr, colidx, vals, X, what=f"rows of {tag}")
+            check_spmm(dev, rowptr, colidx, vals, X, -0.5, 2.0, Y0, what=f"rows of {tag}, beta")
+            if tag == "27":
+                check_spmm(dev, rowptr, colidx, vals, X, what="ldx 8200", ldx=8200, ldy=20)
+                Xf = gen.uniform(19, gen.STREAM_X, ncols * 4).reshape(ncols, 4)
+                check_spmm(dev, rowptr, colidx, vals, Xf, what="k = 4")
+        finally:
+            dev.close()
+
+
 def test_workload4_wide_reduced():
     """Power-law rows over 2^21 columns: x = 8 MB of floats, so the column split is on."""
     run_workload(4, {"n": 1 << 21, "cap": 200000})
