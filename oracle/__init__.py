@@ -28,6 +28,8 @@ STREAM_ROWS = 32
 STREAM_MIN_NNZ = 256
 SPLIT_BLOCK_BYTES = 1 << 21   # target size of one column block of x
 SPLIT_MAX_BLOCKS = 32
+HUGE_ROW = 16384            # rows with more entries are cut at LDS-sized column blocks
+LDS_BLOCK_BYTES = 65536     # bytes of x one such block holds
 
 
 def build(force: bool = False) -> str:
@@ -211,30 +213,48 @@ def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SP
 
 
 def split_partition(rowptr, colidx, ncols, itemsize, part=None, wave=WAVE, long_threshold=LONG_THRESHOLD,
-                    tile_nnz=TILE_NNZ, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):
-    """Reference column split of the rows of the last two bins into virtual rows, and the bins /
-    tiles of those virtual rows.  Returns a dict; 'num_blocks' == 0 means the split is off (x
-    small, no such rows, or a split row with unsorted columns)."""
+                    tile_nnz=TILE_NNZ, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS,
+                    huge_row=HUGE_ROW, lds_block_bytes=LDS_BLOCK_BYTES):
+    """Reference column split of the rows of the last two bins.  Rows of more than huge_row
+    entries ('huge_rows', in row_perm order) are cut at the boundaries of column blocks that hold
+    lds_block_bytes of x ('fcut', num_fblocks blocks of fblock_width columns); the other rows
+    ('num_split_rows' of them, in row_perm order) are cut at the coarse blocks into virtual rows,
+    which get bins and tiles of their own.  Returns a dict; 'num_blocks' == 0 means the split is
+    off (x small, no such rows, or one of them with unsorted columns)."""
     part = part or partition(rowptr, wave, long_threshold, tile_nnz)
     nb_bins = part["num_bins"]
     off = part["bin_offset"]
-    split_rows = np.ascontiguousarray(part["row_perm"][off[nb_bins - 2]:off[nb_bins]])
-    S = split_rows.size
+    rows = np.ascontiguousarray(part["row_perm"][off[nb_bins - 2]:off[nb_bins]])
     nb, W = split_geometry(ncols, itemsize, block_bytes, max_blocks)
-    none = {"num_blocks": 0, "block_width": 0, "num_split_rows": 0}
-    if nb == 0 or S == 0:
+    none = {"num_blocks": 0, "block_width": 0, "num_split_rows": 0, "num_huge_rows": 0}
+    if nb == 0 or rows.size == 0:
         return none
-    cut = np.empty((nb + 1) * S, dtype=np.int32)
-    sorted_flag = ctypes.c_int32(0)
-    _load().oracle_split_cuts(_p(rowptr), _p(colidx), _p(split_rows), S, nb, W, _p(cut),
-                              ctypes.addressof(sorted_flag))
-    if not sorted_flag.value:
+    lengths = (rowptr[rows + 1] - rowptr[rows]).astype(np.int64)
+    split_rows = np.ascontiguousarray(rows[lengths <= huge_row])
+    huge_rows = np.ascontiguousarray(rows[lengths > huge_row])
+    S, H = split_rows.size, huge_rows.size
+    fW = lds_block_bytes // itemsize
+    nbf = -(-ncols // fW)
+    if (nb + 1) * S > 2 ** 31 - 1 or (nbf + 1) * H > 2 ** 31 - 1:
         return none
-    vlen = (cut[S:] - cut[:-S]).astype(np.int64)
+
+    def cuts(row_list, blocks, width):
+        out = np.empty((blocks + 1) * row_list.size, dtype=np.int32)
+        ok = ctypes.c_int32(1)
+        _load().oracle_split_cuts(_p(rowptr), _p(colidx), _p(row_list), row_list.size, blocks, width, _p(out),
+                                  ctypes.addressof(ok))
+        return out, bool(ok.value)
+
+    cut, ok1 = cuts(split_rows, nb, W)
+    fcut, ok2 = cuts(huge_rows, nbf, fW)
+    if not (ok1 and ok2):
+        return none
+    vlen = (cut[S:] - cut[:-S]).astype(np.int64) if S else np.zeros(0, dtype=np.int64)
     fake = np.zeros(vlen.size + 1, dtype=np.int32)      # only row lengths enter bins and tiles
     np.cumsum(vlen, out=fake[1:])
     vp = partition(fake, wave, long_threshold, tile_nnz, stream_rows=STREAM_ROWS, stream_min_nnz=2 ** 31 - 1)
     assert vp["stream_chunks"].size == 0
-    return {"num_blocks": nb, "block_width": W, "num_split_rows": S, "cut": cut,
+    return {"num_blocks": nb, "block_width": W, "num_split_rows": S, "split_rows": split_rows, "cut": cut,
             "bin_offset": vp["bin_offset"], "row_perm": vp["row_perm"], "long_off": vp["long_off"],
-            "tile_row": vp["tile_row"], "tile_nz": vp["tile_nz"]}
+            "tile_row": vp["tile_row"], "tile_nz": vp["tile_nz"],
+            "num_huge_rows": H, "huge_rows": huge_rows, "num_fblocks": nbf, "fblock_width": fW, "fcut": fcut}

@@ -218,6 +218,7 @@ def test_split_matches_searchsorted():
     sp = oracle.split_partition(rowptr, colidx, ncols, 8, part)
     nb, W, S = sp["num_blocks"], sp["block_width"], sp["num_split_rows"]
     rows = part["row_perm"][part["bin_offset"][8]:]          # rows above 64 entries outside stream chunks
+    assert sp["num_huge_rows"] == 0 and np.array_equal(sp["split_rows"], rows)
     assert (nb, W) == (4, 1 << 18) and S == rows.size and 0 < S <= (L > 64).sum()
     for r, row in enumerate(rows):
         cols = colidx[rowptr[row]:rowptr[row + 1]]
@@ -227,6 +228,58 @@ def test_split_matches_searchsorted():
     vlen = sp["cut"][S:] - sp["cut"][:-S]
     assert vlen.sum() == L[rows].sum() and np.all(vlen >= 0)
     assert np.array_equal(np.sort(sp["row_perm"]), np.arange(nb * S))
+
+
+def test_split_huge_rows_hand_worked():
+    """Threshold 70 entries and 32-byte LDS blocks (4 doubles) in a 30-column world: the row of 72
+    entries is 'huge' and cut at columns 0, 4, 8, ..., the row of 66 stays a split row."""
+    cols0 = np.sort(np.concatenate([np.arange(30), np.arange(30), np.arange(12)])).tolist()   # 72 entries
+    cols2 = np.sort(np.concatenate([np.arange(30), np.arange(30), np.arange(6)])).tolist()    # 66 entries
+    rowptr = np.array([0, 72, 74, 140], dtype=np.int32)
+    colidx = np.array(cols0 + [1, 2] + cols2, dtype=np.int32)
+    part = oracle.partition(rowptr)
+    sp = oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, huge_row=70, lds_block_bytes=32)
+    assert (sp["num_blocks"], sp["num_split_rows"], sp["num_huge_rows"]) == (3, 1, 1)
+    assert sp["split_rows"].tolist() == [2] and sp["huge_rows"].tolist() == [0]
+    assert (sp["num_fblocks"], sp["fblock_width"]) == (8, 4)
+    # row 0 holds columns 0..11 three times and 12..29 twice: 12 entries per block of 4 up to
+    # column 11, then 8 per block; the last block (28, 29) holds 4
+    assert np.diff(sp["fcut"]).tolist() == [12, 12, 12, 8, 8, 8, 8, 4]
+    assert sp["fcut"][0] == 0 and sp["fcut"][-1] == 72
+    # the split row alone: cuts at columns 10 and 20 of row 2 (entries 74..139)
+    assert sp["cut"].tolist() == [74, 74 + 26, 74 + 46, 140]
+    # an unsorted huge row switches everything off, as an unsorted split row does
+    colidx[2], colidx[3] = colidx[3], colidx[2]
+    assert colidx[2] > colidx[3]
+    assert oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, huge_row=70,
+                                  lds_block_bytes=32)["num_blocks"] == 0
+
+
+def test_split_huge_rows_match_searchsorted_on_power_law_rows():
+    w = gen.workload(4, {"n": 1 << 20, "cap": 100000})
+    part = oracle.partition(w.rowptr)
+    sp = oracle.split_partition(w.rowptr, w.colidx, w.ncols, 4, part)
+    L = np.diff(w.rowptr)
+    rows = part["row_perm"][part["bin_offset"][8]:]
+    assert sp["num_blocks"] > 0 and sp["num_huge_rows"] > 0
+    assert np.array_equal(sp["huge_rows"], rows[L[rows] > oracle.HUGE_ROW])
+    assert np.array_equal(sp["split_rows"], rows[L[rows] <= oracle.HUGE_ROW])
+    assert np.all(np.diff(sp["huge_rows"]) > 0)                       # all in the last bin: ascending ids
+    H, nbf, fW = sp["num_huge_rows"], sp["num_fblocks"], sp["fblock_width"]
+    assert fW == 16384 and nbf == -(-w.ncols // fW)
+    for h in (0, H // 2, H - 1):
+        row = sp["huge_rows"][h]
+        cols = w.colidx[w.rowptr[row]:w.rowptr[row + 1]]
+        expect = w.rowptr[row] + np.searchsorted(cols, np.arange(nbf + 1) * fW, side="left")
+        expect[-1] = w.rowptr[row + 1]
+        assert np.array_equal(sp["fcut"][h::H], expect)
+    # every entry of every row above 64 entries is owned exactly once
+    flen = sp["fcut"][H:] - sp["fcut"][:-H]
+    S = sp["num_split_rows"]
+    vlen = sp["cut"][S:] - sp["cut"][:-S]
+    assert flen.sum() == L[sp["huge_rows"]].sum() and vlen.sum() == L[sp["split_rows"]].sum()
+    assert np.all(flen >= 0) and np.all(vlen >= 0)
+    assert part["bin_offset"][8] == part["bin_offset"][10] - S - H
 
 
 # ---- level 1b: 16-bit column offsets of narrow stream chunks ----------------
