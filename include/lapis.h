@@ -74,13 +74,22 @@ extern "C" {
  * nb = min(LAPIS_SPLIT_MAX_BLOCKS, ceil(ncols / (LAPIS_SPLIT_BLOCK_BYTES / e)))
  * column blocks of width W = ceil(ncols / nb); the split is off when nb < 2,
  * when bins 8 and 9 are empty, or when one of their rows has decreasing
- * columns.  Let split_rows[0..S-1] be the rows of bins 8 and 9 in row_perm
- * order.  cut[b*S + r] is the first entry of row split_rows[r] whose column is
+ * columns.  Let split_rows[0..S-1] be the rows of bins 8 and 9 with at most
+ * LAPIS_HUGE_ROW entries, in row_perm order (the longer ones: level 3b below).
+ * cut[b*S + r] is the first entry of row split_rows[r] whose column is
  * >= b*W (b = 0..nb; cut[nb*S + r] is the row's end).  Virtual row v = b*S + r
  * owns the entries cut[v] .. cut[v+S]-1; the virtual rows are binned and tiled
  * by the level-2 rule (no stream chunks), processed block after block so that
  * the gathers of one column block stay cache resident, and each split row's nb
  * partial sums are added in ascending block order.
+ *
+ * Level 3b, for the rows of more than LAPIS_HUGE_ROW entries when the split is on:
+ * huge_rows[0..H-1] are those rows in row_perm order (all in bin 9, so ascending).  They are
+ * cut at column blocks that hold LAPIS_LDS_BLOCK_BYTES of x: nbf = ceil(ncols / Wf) blocks of
+ * Wf = LAPIS_LDS_BLOCK_BYTES / e columns; fcut[b*H + h] is the first entry of row huge_rows[h]
+ * whose column is >= b*Wf (b = 0..nbf; fcut[nbf*H + h] is the row's end).  A workgroup keeps
+ * one block of x in LDS while the pieces of all huge rows in that block stream by.  The split
+ * is also off when (nb+1)*S or (nbf+1)*H exceeds int32.
  */
 #define LAPIS_NUM_BINS        10
 #define LAPIS_WAVE            64
@@ -91,6 +100,8 @@ extern "C" {
 #define LAPIS_SPLIT_BLOCK_BYTES 2097152   /* 2 MiB of x per column block */
 #define LAPIS_MAX_NNZ 2147418112        /* 2^31 - 2^16: entry ids plus a tile stay inside int32 */
 #define LAPIS_SPLIT_MAX_BLOCKS  32
+#define LAPIS_HUGE_ROW 16384             /* rows with more entries are cut at LDS-sized column blocks */
+#define LAPIS_LDS_BLOCK_BYTES 65536      /* bytes of x one such block holds */
 
 typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
 
@@ -253,6 +264,13 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
                          int32_t *h_row_perm, int32_t *h_long_off, int32_t *h_tile_row,
                          int32_t *h_tile_nz);
 
+/* Level 3b.  lapis_csr_huge_sizes: *num_huge = H, *num_fblocks = nbf, *fblock_width = Wf (all 0
+ * when the split is off).  lapis_csr_copy_huge copies to HOST buffers (any may be NULL):
+ * h_split_rows int32[S], h_huge_rows int32[H], h_fcut int32[(nbf+1)*H]; LAPIS_ERR_INVALID_ARG
+ * when the split is off.  Synchronises the device. */
+int lapis_csr_huge_sizes(const lapis_csr_t *A, int64_t *num_huge, int64_t *num_fblocks, int64_t *fblock_width);
+int lapis_csr_copy_huge(const lapis_csr_t *A, int32_t *h_split_rows, int32_t *h_huge_rows, int32_t *h_fcut);
+
 /*
  * lapis_csr_copy_index16 - the 16-bit column offsets the analysis builds so that the stream
  * kernels read 2 instead of 4 bytes of index per entry (an implementation choice of this
@@ -274,8 +292,9 @@ int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth);
 
 /* The partition constants compiled into the library, in the order
  * {LAPIS_NUM_BINS, LAPIS_WAVE, LAPIS_LONG_THRESHOLD, LAPIS_TILE_NNZ,
- *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ, LAPIS_SPLIT_BLOCK_BYTES, LAPIS_SPLIT_MAX_BLOCKS}. */
-int lapis_partition_constants(int64_t h_out[8]);
+ *  LAPIS_STREAM_ROWS, LAPIS_STREAM_MIN_NNZ, LAPIS_SPLIT_BLOCK_BYTES, LAPIS_SPLIT_MAX_BLOCKS,
+ *  LAPIS_HUGE_ROW, LAPIS_LDS_BLOCK_BYTES}. */
+int lapis_partition_constants(int64_t h_out[10]);
 
 /* ---- host-side buffers with lazy synchronisation (after Section 4.3) ---------
  * A dual view pairs a pinned host buffer with a device buffer of the same size and keeps one

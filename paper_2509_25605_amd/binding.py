@@ -22,7 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
-    "lapis_csr_copy_index16",
+    "lapis_csr_copy_index16", "lapis_csr_huge_sizes", "lapis_csr_copy_huge",
     "lapis_spmv_transpose", "lapis_csr_create_transpose", "lapis_csr_shape", "lapis_csr_copy_arrays",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_csr_huge_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 3
+        lib.lapis_csr_copy_huge.argtypes = [p, p, p, p]
         lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), p, p]
         lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
         lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
@@ -198,11 +200,11 @@ def lapis_csr_partition_sizes(A):
 
 
 def lapis_partition_constants():
-    out = (ctypes.c_int64 * 8)()
+    out = (ctypes.c_int64 * 10)()
     _check(load().lapis_partition_constants(out))
     return {"num_bins": out[0], "wave": out[1], "long_threshold": out[2], "tile_nnz": out[3],
             "stream_rows": out[4], "stream_min_nnz": out[5], "split_block_bytes": out[6],
-            "split_max_blocks": out[7]}
+            "split_max_blocks": out[7], "huge_row": out[8], "lds_block_bytes": out[9]}
 
 
 def lapis_csr_copy_partition(A):
@@ -237,10 +239,16 @@ def lapis_csr_copy_split(A):
     """Host copies of the column split; {'num_blocks': 0, ...} when the split is off."""
     nb, W, S, nv, m, t = lapis_csr_split_sizes(A)
     if nb == 0:
-        return {"num_blocks": 0, "block_width": 0, "num_split_rows": 0}
+        return {"num_blocks": 0, "block_width": 0, "num_split_rows": 0, "num_huge_rows": 0}
     nbins = lapis_partition_constants()["num_bins"]
+    H, nbf, fW = (ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64())
+    _check(load().lapis_csr_huge_sizes(A, ctypes.byref(H), ctypes.byref(nbf), ctypes.byref(fW)))
+    H, nbf, fW = H.value, nbf.value, fW.value
     res = {
         "num_blocks": nb, "block_width": W, "num_split_rows": S,
+        "num_huge_rows": H, "num_fblocks": nbf, "fblock_width": fW,
+        "split_rows": np.empty(S, dtype=np.int32), "huge_rows": np.empty(H, dtype=np.int32),
+        "fcut": np.empty((nbf + 1) * H, dtype=np.int32),
         "cut": np.empty((nb + 1) * S, dtype=np.int32),
         "bin_offset": np.empty(nbins + 1, dtype=np.int32),
         "row_perm": np.empty(nv, dtype=np.int32),
@@ -251,6 +259,7 @@ def lapis_csr_copy_split(A):
     ptr = lambda a: a.ctypes.data_as(ctypes.c_void_p)
     _check(load().lapis_csr_copy_split(A, ptr(res["cut"]), ptr(res["bin_offset"]), ptr(res["row_perm"]),
                                        ptr(res["long_off"]), ptr(res["tile_row"]), ptr(res["tile_nz"])))
+    _check(load().lapis_csr_copy_huge(A, ptr(res["split_rows"]), ptr(res["huge_rows"]), ptr(res["fcut"])))
     return res
 
 

@@ -440,6 +440,47 @@ __global__ __launch_bounds__(kBlock) void split_sorted_kernel(int32_t S, const i
     if (bad) flag[0] = 1;
 }
 
+// One workgroup of kCompactBlock threads: the rows of the last two bins (rows[0..count), in
+// row_perm order) go, in that order, to split_rows if they have at most huge_row entries and to
+// huge_rows otherwise; counts[0], counts[1] = how many of each.
+__global__ __launch_bounds__(kCompactBlock) void split_rows_kernel(int32_t count, int32_t huge_row,
+                                                                   const int32_t *__restrict__ rows,
+                                                                   const int32_t *__restrict__ rowptr,
+                                                                   int32_t *__restrict__ split_rows,
+                                                                   int32_t *__restrict__ huge_rows,
+                                                                   int32_t *__restrict__ counts)
+{
+    constexpr int kWaves = kCompactBlock / kWave;
+    __shared__ int32_t s_wave[kWaves][2];
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    int32_t running[2] = {0, 0};
+    for (int64_t base = 0; base < count; base += kCompactBlock) {
+        const int64_t i = base + threadIdx.x;
+        int32_t row = 0, cls = -1;
+        if (i < count) {
+            row = rows[i];
+            cls = (rowptr[row + 1] - rowptr[row] > huge_row) ? 1 : 0;
+        }
+        const uint64_t m0 = __builtin_amdgcn_ballot_w64(cls == 0), m1 = __builtin_amdgcn_ballot_w64(cls == 1);
+        if (lane == 0) { s_wave[wave][0] = __popcll(m0); s_wave[wave][1] = __popcll(m1); }
+        __syncthreads();
+        int32_t before[2] = {running[0], running[1]};
+        for (int w = 0; w < kWaves; ++w) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int32_t n = s_wave[w][k];
+                if (w < wave) before[k] += n;
+                running[k] += n;
+            }
+        }
+        const uint64_t lower = (1ull << lane) - 1;
+        if (cls == 0) split_rows[before[0] + __popcll(m0 & lower)] = row;
+        if (cls == 1) huge_rows[before[1] + __popcll(m1 & lower)] = row;
+        __syncthreads();
+    }
+    if (threadIdx.x < 2) counts[threadIdx.x] = running[threadIdx.x];
+}
+
 // cut[b*S + r] = first entry j of row split_rows[r] with colidx[j] >= b*W; cut[nb*S + r] = row end.
 __global__ __launch_bounds__(kBlock) void split_cut_kernel(int32_t S, int32_t nb, int64_t W,
                                                            const int32_t *__restrict__ split_rows,

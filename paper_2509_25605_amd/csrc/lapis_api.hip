@@ -69,9 +69,15 @@ struct lapis_csr {
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
     int64_t num_blocks = 0, block_width = 0, num_split = 0;
+    int32_t *d_split_rows = nullptr;     // [num_split] rows of bins 8-9 with at most LAPIS_HUGE_ROW entries
     int32_t *d_cut = nullptr;            // [(num_blocks + 1) * num_split]
     void *d_vsum = nullptr;              // [num_blocks * num_split] of the value type
     BinnedSet vrows;
+    // rows of more than LAPIS_HUGE_ROW entries, cut at LDS-sized column blocks (only with the split on)
+    int64_t num_huge = 0, num_fblocks = 0, fblock_width = 0;
+    int32_t *d_huge_rows = nullptr;      // [num_huge]
+    int32_t *d_fcut = nullptr;           // [(num_fblocks + 1) * num_huge]
+    void *d_fsum = nullptr;              // [num_fblocks * num_huge] of the value type
     // launch plans for spmv_short_kernel
     ShortPlan plan_rows;       // bins 0..8 of `rows` (0..7 when the split is on)
     ShortPlan plan_vrows;      // bins 0..8 of `vrows`
@@ -161,6 +167,10 @@ void free_handle(lapis_csr *A)
     if (!A) return;
     (void)hipFree(A->d_stream_chunks);
     (void)hipFree(A->d_cut);
+    (void)hipFree(A->d_split_rows);
+    (void)hipFree(A->d_huge_rows);
+    (void)hipFree(A->d_fcut);
+    (void)hipFree(A->d_fsum);
     (void)hipFree(A->d_vsum);
     (void)hipFree(A->d_chunk_base);
     (void)hipFree(A->d_col16);
@@ -345,27 +355,44 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     A->rows.row_end = A->rowptr + 1;
     if (int rc = bin_row_set(&A->rows, chunk_flag.as<int32_t>(), esize, stream)) return rc;
 
-    // column split of the rows of the last two bins
+    // column split of the rows of the last two bins: rows above LAPIS_HUGE_ROW entries are cut at
+    // LDS-sized column blocks, the others at the coarse blocks into virtual rows
     int64_t nb = 0, W = 0;
     split_geometry(A->ncols, esize, &nb, &W);
-    const int64_t S = A->rows.h_bin_offset[kNumBins] - A->rows.h_bin_offset[kNumBins - 2];
-    bool split = nb > 0 && S > 0 && (nb + 1) * S <= INT32_MAX;
-    const int32_t *split_rows = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
-    if (split && !rows_sorted) {   // some row is unsorted: look at the split rows themselves
+    const int64_t R89 = A->rows.h_bin_offset[kNumBins] - A->rows.h_bin_offset[kNumBins - 2];
+    const int64_t fW = (int64_t)LAPIS_LDS_BLOCK_BYTES / (int64_t)esize;
+    const int64_t nbf = (A->ncols + fW - 1) / fW;
+    bool split = nb > 0 && R89 > 0;
+    const int32_t *rows89 = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
+    if (split && !rows_sorted) {   // some row is unsorted: look at these rows themselves
         LAPIS_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), stream));
-        const uint32_t sblocks = (uint32_t)(S < 65536 ? S : 65536);
-        split_sorted_kernel<<<dim3(sblocks), dim3(kBlock), 0, stream>>>((int32_t)S, split_rows, A->rowptr,
+        const uint32_t sblocks = (uint32_t)(R89 < 65536 ? R89 : 65536);
+        split_sorted_kernel<<<dim3(sblocks), dim3(kBlock), 0, stream>>>((int32_t)R89, rows89, A->rowptr,
                                                                         A->colidx, d_flags);
         int32_t unsorted = 0;
         if (int rc = read_back(&unsorted, d_flags, sizeof(int32_t), stream)) return rc;
         split = !unsorted;
     }
+    int64_t S = 0, H = 0;
+    if (split) {
+        if (int rc = device_alloc(&A->d_split_rows, sizeof(int32_t) * (size_t)R89)) return rc;
+        if (int rc = device_alloc(&A->d_huge_rows, sizeof(int32_t) * (size_t)R89)) return rc;
+        split_rows_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
+            (int32_t)R89, LAPIS_HUGE_ROW, rows89, A->rowptr, A->d_split_rows, A->d_huge_rows, d_flags);
+        LAPIS_HIP(hipGetLastError());
+        int32_t counts[2] = {0, 0};
+        if (int rc = read_back(counts, d_flags, sizeof(counts), stream)) return rc;
+        S = counts[0];
+        H = counts[1];
+        split = (nb + 1) * S <= INT32_MAX && (nbf + 1) * H <= INT32_MAX;
+    }
     if (split) {
         const int64_t cuts = (nb + 1) * S;
         if (int rc = device_alloc(&A->d_cut, sizeof(int32_t) * (size_t)cuts)) return rc;
         if (int rc = device_alloc(&A->d_vsum, esize * (size_t)(nb * S))) return rc;
-        split_cut_kernel<<<dim3((uint32_t)((cuts + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
-            (int32_t)S, (int32_t)nb, W, split_rows, A->rowptr, A->colidx, A->d_cut);
+        if (S > 0)
+            split_cut_kernel<<<dim3((uint32_t)((cuts + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+                (int32_t)S, (int32_t)nb, W, A->d_split_rows, A->rowptr, A->colidx, A->d_cut);
         LAPIS_HIP(hipGetLastError());
         A->num_blocks = nb;
         A->block_width = W;
@@ -374,6 +401,17 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         A->vrows.row_begin = A->d_cut;
         A->vrows.row_end = A->d_cut + S;
         if (int rc = bin_row_set(&A->vrows, nullptr, esize, stream)) return rc;
+        const int64_t fcuts = (nbf + 1) * H;
+        if (int rc = device_alloc(&A->d_fcut, sizeof(int32_t) * (size_t)fcuts)) return rc;
+        if (int rc = device_alloc(&A->d_fsum, esize * (size_t)(nbf * H))) return rc;
+        if (H > 0)
+            split_cut_kernel<<<dim3((uint32_t)((fcuts + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+                (int32_t)H, (int32_t)nbf, fW, A->d_huge_rows, A->rowptr, A->colidx, A->d_fcut);
+        LAPIS_HIP(hipGetLastError());
+        A->num_huge = H;
+        A->num_fblocks = nbf;
+        A->fblock_width = fW;
+        LAPIS_HIP(hipStreamSynchronize(stream));
     }
     build_short_plan(A->rows, split ? kNumBins - 3 : kShortBins - 1, &A->plan_rows);
     if (split) build_short_plan(A->vrows, kShortBins - 1, &A->plan_vrows);
@@ -504,6 +542,9 @@ int spmv_transpose_typed(const lapis_csr *A, double alpha, const void *d_x, doub
 }
 
 template <typename T>
+const T *vals_of(const lapis_csr *A) { return static_cast<const T *>(A->vals); }
+
+template <typename T>
 int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, hipStream_t stream)
 {
     const T a = (T)alpha, b = (T)beta;
@@ -519,9 +560,24 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
         // rows above 64 entries: their column-block pieces first, then one sum per row
         T *vsum = static_cast<T *>(A->d_vsum);
         launch_binned<T>(A, A->vrows, A->plan_vrows, true, x, vsum, T(1), T(0), stream);
-        const int32_t *split_rows = A->rows.d_row_perm + A->rows.h_bin_offset[kNumBins - 2];
-        split_combine_kernel<T><<<dim3((uint32_t)((A->num_split + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
-            (int32_t)A->num_split, (int32_t)A->num_blocks, split_rows, vsum, y, a, b);
+        if (A->num_split > 0)
+            split_combine_kernel<T><<<dim3((uint32_t)((A->num_split + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+                (int32_t)A->num_split, (int32_t)A->num_blocks, A->d_split_rows, vsum, y, a, b);
+        if (A->num_huge > 0) {
+            // rows above LAPIS_HUGE_ROW entries: pieces per LDS-sized block of x, then one sum per row
+            T *fsum = static_cast<T *>(A->d_fsum);
+            const int64_t H = A->num_huge, nbf = A->num_fblocks;
+            int64_t groups = (8 * 256 + nbf - 1) / nbf;                      // about 8 workgroups per CU in all
+            const int64_t most = (H + kLdsBlockWaves - 1) / kLdsBlockWaves;  // one piece per wavefront at least
+            if (groups > most) groups = most;
+            if (groups < 1) groups = 1;
+            if (groups > 65535) groups = 65535;
+            spmv_ldsblock_kernel<T><<<dim3((uint32_t)nbf, (uint32_t)groups), dim3(kLdsBlockThreads),
+                                      (size_t)LAPIS_LDS_BLOCK_BYTES, stream>>>(
+                (int32_t)H, (int32_t)A->fblock_width, A->ncols, A->d_fcut, A->colidx, vals_of<T>(A), x, fsum);
+            spmv_ldsblock_combine_kernel<T><<<dim3((uint32_t)((H + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(
+                (int32_t)H, (int32_t)nbf, A->d_huge_rows, fsum, y, a, b);
+        }
     }
     LAPIS_HIP(hipGetLastError());
     return LAPIS_OK;
@@ -826,9 +882,32 @@ int lapis_csr_copy_split(const lapis_csr_t *A, int32_t *h_cut, int32_t *h_bin_of
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
     if (A->num_blocks == 0) return fail(LAPIS_ERR_INVALID_ARG, "this matrix has no column split");
     LAPIS_HIP(hipDeviceSynchronize());
-    if (h_cut)
+    if (h_cut && A->num_split > 0)
         LAPIS_HIP(hipMemcpy(h_cut, A->d_cut, sizeof(int32_t) * (size_t)((A->num_blocks + 1) * A->num_split), hipMemcpyDeviceToHost));
     return copy_set(A->vrows, h_bin_offset, h_row_perm, h_long_off, h_tile_row, h_tile_nz);
+}
+
+int lapis_csr_huge_sizes(const lapis_csr_t *A, int64_t *num_huge, int64_t *num_fblocks, int64_t *fblock_width)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (num_huge) *num_huge = A->num_huge;
+    if (num_fblocks) *num_fblocks = A->num_fblocks;
+    if (fblock_width) *fblock_width = A->fblock_width;
+    return LAPIS_OK;
+}
+
+int lapis_csr_copy_huge(const lapis_csr_t *A, int32_t *h_split_rows, int32_t *h_huge_rows, int32_t *h_fcut)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->num_blocks == 0) return fail(LAPIS_ERR_INVALID_ARG, "this matrix has no column split");
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_split_rows && A->num_split > 0)
+        LAPIS_HIP(hipMemcpy(h_split_rows, A->d_split_rows, sizeof(int32_t) * (size_t)A->num_split, hipMemcpyDeviceToHost));
+    if (h_huge_rows && A->num_huge > 0)
+        LAPIS_HIP(hipMemcpy(h_huge_rows, A->d_huge_rows, sizeof(int32_t) * (size_t)A->num_huge, hipMemcpyDeviceToHost));
+    if (h_fcut && A->num_huge > 0)
+        LAPIS_HIP(hipMemcpy(h_fcut, A->d_fcut, sizeof(int32_t) * (size_t)((A->num_fblocks + 1) * A->num_huge), hipMemcpyDeviceToHost));
+    return LAPIS_OK;
 }
 
 int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int32_t *h_chunk_base,
@@ -854,7 +933,7 @@ int lapis_csr_half_bandwidth(const lapis_csr_t *A, int64_t *half_bandwidth)
     return LAPIS_OK;
 }
 
-int lapis_partition_constants(int64_t h_out[8])
+int lapis_partition_constants(int64_t h_out[10])
 {
     if (!h_out) return fail(LAPIS_ERR_INVALID_ARG, "h_out is NULL");
     h_out[0] = LAPIS_NUM_BINS;
@@ -865,6 +944,8 @@ int lapis_partition_constants(int64_t h_out[8])
     h_out[5] = LAPIS_STREAM_MIN_NNZ;
     h_out[6] = LAPIS_SPLIT_BLOCK_BYTES;
     h_out[7] = LAPIS_SPLIT_MAX_BLOCKS;
+    h_out[8] = LAPIS_HUGE_ROW;
+    h_out[9] = LAPIS_LDS_BLOCK_BYTES;
     return LAPIS_OK;
 }
 

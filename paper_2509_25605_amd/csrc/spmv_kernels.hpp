@@ -564,4 +564,77 @@ __global__ __launch_bounds__(kBlock) void spmv_long_fixup_kernel(
     if (lane == kWave - 1 && r < num_long) store_result(y, long_rows[r], s, alpha, beta);
 }
 
+// ---- huge rows: column blocks of x staged in LDS ---------------------------------
+// Rows above LAPIS_HUGE_ROW entries with ascending columns are cut at the boundaries of column
+// blocks that hold LAPIS_LDS_BLOCK_BYTES of x (fcut, H rows x (nbf + 1) cuts).  Workgroup
+// (b, g) copies block b of x into LDS once and then walks the pieces of its share of the rows:
+// a piece is a contiguous run of colidx / vals, read with coalesced loads, and its gathers of x
+// are LDS reads instead of one cache line per entry.  fsum[b*H + h] receives the piece's sum.
+constexpr int kLdsBlockThreads = 1024;
+constexpr int kLdsBlockWaves = kLdsBlockThreads / kWave;
+constexpr int kLdsBlockUnroll = 4;            // loads of 64 entries in flight per wavefront
+
+template <typename T>
+__global__ __launch_bounds__(kLdsBlockThreads) void spmv_ldsblock_kernel(
+    int32_t H, int32_t fblock_width, int64_t ncols, const int32_t *__restrict__ fcut,
+    const int32_t *__restrict__ colidx, const T *__restrict__ vals, const T *__restrict__ x,
+    T *__restrict__ fsum)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_raw[];
+    T *s_x = reinterpret_cast<T *>(s_raw);
+    const int32_t b = blockIdx.x;
+    const int64_t c0 = (int64_t)b * fblock_width;
+    const int32_t width = (int32_t)((ncols - c0 < fblock_width) ? ncols - c0 : fblock_width);
+    for (int32_t i = threadIdx.x; i < width; i += kLdsBlockThreads) s_x[i] = x[c0 + i];
+    __syncthreads();
+    const int lane = threadIdx.x % kWave;
+    const int32_t stride = kLdsBlockWaves * (int32_t)gridDim.y;
+    const int32_t *__restrict__ cut_lo = fcut + (int64_t)b * H;
+    const int32_t *__restrict__ cut_hi = cut_lo + H;
+    int32_t h = (int32_t)blockIdx.y * kLdsBlockWaves + (int32_t)(threadIdx.x / kWave);
+    int32_t jb = 0, je = 0;
+    if (h < H) { jb = cut_lo[h]; je = cut_hi[h]; }
+    while (h < H) {                                    // uniform per wavefront
+        const int32_t h_next = h + stride;
+        int32_t jb_next = 0, je_next = 0;
+        if (h_next < H) { jb_next = cut_lo[h_next]; je_next = cut_hi[h_next]; }   // on its way during the piece
+        T s = T(0);
+        for (int32_t j0 = jb; j0 < je; j0 += kLdsBlockUnroll * kWave) {
+            int32_t c[kLdsBlockUnroll];
+            T v[kLdsBlockUnroll];
+#pragma unroll
+            for (int q = 0; q < kLdsBlockUnroll; ++q) {
+                const int32_t j = j0 + q * kWave + lane;
+                const int32_t jc = j < je ? j : je - 1;                 // past the end: the last entry again
+                c[q] = load_stream(colidx + jc);
+                v[q] = load_stream(vals + jc);
+            }
+#pragma unroll
+            for (int q = 0; q < kLdsBlockUnroll; ++q) {
+                const T p = v[q] * s_x[c[q] - (int32_t)c0];
+                s += (j0 + q * kWave + lane < je) ? p : T(0);
+            }
+        }
+        s = group_sum<kWave>(s);
+        if (lane == kWave - 1) fsum[(int64_t)b * H + h] = s;
+        h = h_next; jb = jb_next; je = je_next;
+    }
+}
+
+// One wavefront per huge row: y[row] = alpha * (sum over the blocks of fsum[b*H + h]) + beta * y[row];
+// lanes stride the blocks in a fixed pattern, then a fixed reduction tree.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void spmv_ldsblock_combine_kernel(
+    int32_t H, int32_t nbf, const int32_t *__restrict__ huge_rows, const T *__restrict__ fsum,
+    T *__restrict__ y, T alpha, T beta)
+{
+    const int64_t h = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    T s = T(0);
+    if (h < H)
+        for (int32_t b = lane; b < nbf; b += kWave) s += fsum[(int64_t)b * H + h];
+    s = group_sum<kWave>(s);
+    if (lane == kWave - 1 && h < H) store_result(y, huge_rows[h], s, alpha, beta);
+}
+
 }  // namespace lapis

@@ -43,7 +43,9 @@ def test_header_constants_match_library_and_oracle(lib):
                  "long_threshold": macro("LAPIS_LONG_THRESHOLD"), "tile_nnz": macro("LAPIS_TILE_NNZ"),
                  "stream_rows": macro("LAPIS_STREAM_ROWS"), "stream_min_nnz": macro("LAPIS_STREAM_MIN_NNZ"),
                  "split_block_bytes": macro("LAPIS_SPLIT_BLOCK_BYTES"),
-                 "split_max_blocks": macro("LAPIS_SPLIT_MAX_BLOCKS")}
+                 "split_max_blocks": macro("LAPIS_SPLIT_MAX_BLOCKS"), "huge_row": macro("LAPIS_HUGE_ROW"),
+                 "lds_block_bytes": macro("LAPIS_LDS_BLOCK_BYTES")}
+    assert (c["huge_row"], c["lds_block_bytes"]) == (oracle.HUGE_ROW, oracle.LDS_BLOCK_BYTES)
     assert (c["split_block_bytes"], c["split_max_blocks"]) == (oracle.SPLIT_BLOCK_BYTES, oracle.SPLIT_MAX_BLOCKS)
     assert (c["num_bins"], c["wave"], c["long_threshold"], c["tile_nnz"], c["stream_rows"],
             c["stream_min_nnz"]) == (oracle.NUM_BINS, oracle.WAVE, oracle.LONG_THRESHOLD, oracle.TILE_NNZ,

@@ -51,12 +51,16 @@ def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):
     got = dev.split()
     if expect_on is not None:
         assert (ref["num_blocks"] > 0) == expect_on
-    for key in ("num_blocks", "block_width", "num_split_rows"):
+    for key in ("num_blocks", "block_width", "num_split_rows", "num_huge_rows"):
         assert got[key] == ref[key], f"split field {key} differs"
     if ref["num_blocks"]:
-        for key in ("cut", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
+        for key in ("num_fblocks", "fblock_width"):
+            assert got[key] == ref[key], f"split field {key} differs"
+        for key in ("split_rows", "huge_rows", "cut", "fcut", "bin_offset", "row_perm", "long_off", "tile_row",
+                    "tile_nz"):
             assert got[key].dtype == np.int32
             assert np.array_equal(got[key], ref[key]), f"split field {key} differs"
+    return ref
 
 
 def check_spmv(dev, rowptr, colidx, vals, x, alpha=1.0, beta=0.0, y0=None, literal=False, what="",
@@ -397,6 +401,37 @@ def test_spmm_row_lengths_and_wide_leading_dimension():
                 check_spmm(dev, rowptr, colidx, vals, X, what="ldx 8200", ldx=8200, ldy=20)
                 Xf = gen.uniform(19, gen.STREAM_X, ncols * 4).reshape(ncols, 4)
                 check_spmm(dev, rowptr, colidx, vals, Xf, what="k = 4")
+        finally:
+            dev.close()
+
+
+def test_spmv_huge_rows_lds_blocks():
+    """Rows above 16384 entries with the split on: pieces per 64 KiB block of x (one that ends
+    inside the last, partial block; empty pieces; a row that fills whole blocks)."""
+    say("huge rows")
+    for dtype, ncols in ((np.float32, (1 << 20) + 4321), (np.float64, (1 << 19) + 123)):
+        n = 700
+        L = mixed_lengths(n, 73, 3000)
+        L[3] = 20000
+        L[100] = 16385
+        L[101] = 16384                       # not huge: stays a split row
+        L[350] = min(ncols, 300000)
+        L[699] = 65536
+        rowptr, colidx, vals = gen.random_csr(n, ncols, L, 557, dtype)
+        # one huge row whose columns are one contiguous run: most of its blocks are empty
+        a = rowptr[100]
+        colidx[a:a + 16385] = np.arange(777, 777 + 16385, dtype=np.int32)
+        x = gen.uniform(29, gen.STREAM_X, ncols).astype(dtype)
+        y0 = gen.uniform(29, gen.STREAM_Y0, n).astype(dtype)
+        dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+        try:
+            check_partition(dev, rowptr)
+            ref = check_split(dev, rowptr, colidx, ncols, np.dtype(dtype).itemsize, expect_on=True)
+            assert ref["huge_rows"].tolist() == [3, 100, 350, 699]
+            check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+            check_spmv(dev, rowptr, colidx, vals, x, -1.5, 0.25, y0, what="alpha=-1.5 beta=0.25")
+            a1 = dev.spmv(x, 2.0, 0.0)
+            assert np.array_equal(a1, dev.spmv(x, 2.0, 0.0)), "two runs differ"
         finally:
             dev.close()
 
