@@ -25,14 +25,14 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # this script, each scaled by what the same counter reads for a plain 1 GiB device copy
 # (FETCH_SIZE x2.000, WRITE_SIZE x1.000).  Re-measure after a kernel change.
 MEASURED_TRAFFIC_BYTES = {
-    "stencil27_128x128x128_f64": 605.28e6,
-    "stencil27_128x128x128_f64_spmm_k16": 1136.92e6,
-    "table3_Elasticity3D_60_n648000_f64": 524.83e6,
+    "stencil27_128x128x128_f64": 605.55e6,
+    "stencil27_128x128x128_f64_spmm_k16": 1134.16e6,
+    "table3_Elasticity3D_60_n648000_f64": 525.03e6,
     "zipf1.8_cap200000_n8388608_f32": 10488.35e6,
 }
 DOMINANT_KERNEL = {
     "stencil27_128x128x128_f64": "spmv_stream_kernel<double, 2, true, true>",
-    "stencil27_128x128x128_f64_spmm_k16": "spmm_stream_kernel<double, 2, 8>",
+    "stencil27_128x128x128_f64_spmm_k16": "spmm_stream_kernel<double, 2, 8, true, true>",
     "table3_Elasticity3D_60_n648000_f64": "spmv_stream_kernel<double, 8, true, true>",
 }
 
