@@ -174,6 +174,7 @@ def main():
                "sample": f"full workload, best of {reps} serial passes ({best * 1e3:.1f} ms each; "
                          f"{flops / best / 1e9:.2f} GFLOP/s), 1 of {os.cpu_count()} host cores"}
 
+    traffic = MEASURED_TRAFFIC_BYTES.get(w.name) if args.variant == "tuned" else None
     out = {
         "metric": "CSR SpMV effective HBM GB/s (vals+colidx+rowptr+x+y bytes / time); "
                   "gflops and frac_hbm_peak alongside",
@@ -187,7 +188,9 @@ def main():
         "create_ms": round(create_ms, 3),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if args.variant == "tuned" else None,
+                     "traffic": traffic,
+                     # measured HBM bytes per launch / live kernel time: what the memory system really moved
+                     "traffic_rate_GBps": round(traffic / (kernel_ms * 1e-3) / 1e9, 2) if traffic else None,
                      "algorithmic_bytes": nbytes,
                      "kernel": (DOMINANT_KERNEL.get(w.name, "all kernels of the step") if args.variant == "tuned"
                                 else VARIANT_KERNEL[args.variant]),
