@@ -9,8 +9,9 @@
 //    rows.  The chunk's (column, value) pairs are streamed into LDS exactly as in
 //    the SpMV stream kernel; then 64/CL slots walk 64/CL rows at a time, reading
 //    each pair back as an LDS broadcast and one row of X with a 16-byte load per
-//    lane.  Consecutive rows sit in consecutive slots, so on banded matrices one
-//    load instruction reads consecutive rows of X.
+//    lane, in whole batches of 16 / 8 / 4 / 2 / 1 entries while all rows of the
+//    wavefront have that many left.  Consecutive rows sit in consecutive slots, so
+//    on banded matrices one load instruction reads consecutive rows of X.
 //  * spmm_rows_kernel (other rows of up to 64 entries): one slot per row.  The slot's
 //    lanes load CL consecutive (column, value) pairs of the row at once, park
 //    them in LDS, and every lane then reads them back one by one as LDS

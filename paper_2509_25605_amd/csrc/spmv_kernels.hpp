@@ -1,13 +1,14 @@
 // SpMV kernels for gfx950: y = alpha*A*x + beta*y with A in CSR (Section 6.2),
 // rows walked with the CSR loop nest of Section 4.2.
 //
-//  * spmv_stream_kernel: one wavefront per stream chunk (32 consecutive rows of
-//    at most 64 entries).  The chunk's entries are one contiguous range of the
-//    value / column arrays: the wavefront streams it with 16-byte non-temporal
-//    loads into LDS, then a group of 2 lanes per row walks the row out of LDS
-//    and gathers x.  Consecutive rows sit in consecutive lane groups, so for
-//    banded matrices (stencils, FEM) every gather instruction reads a nearly
-//    contiguous piece of x.
+//  * spmv_stream_kernel: one wavefront per 64/G consecutive rows of a stream chunk
+//    (32 consecutive rows; G = 2, 4, 8, 16 lanes per row by the chunk's class).
+//    The rows' entries are one contiguous range of the value / column arrays: the
+//    wavefront streams it with 16-byte non-temporal loads into LDS (16-bit column
+//    offsets instead of 32-bit columns where the analysis built them), then a
+//    group of G lanes per row walks the row out of LDS and gathers x.
+//    Consecutive rows sit in consecutive lane groups, so for banded matrices
+//    (stencils, FEM) every gather instruction reads a nearly contiguous piece of x.
 //  * spmv_short_kernel: one launch covers bins 0..8 of the row partition.  A
 //    group of G = 2^(bin-1) lanes owns a row, the lanes stride the row's
 //    entries (the ThreadVector level of Section 4.2 "Loop translation", with
@@ -18,6 +19,8 @@
 //    equal tiles of entries; a workgroup reduces one tile through LDS and a
 //    second pass adds a row's tile sums in tile order, so every y[i] has one
 //    writer and the result does not depend on scheduling.
+//  * spmv_ldsblock_kernel + spmv_ldsblock_combine_kernel: rows above LAPIS_HUGE_ROW
+//    entries, cut at column blocks of x that fit LDS; their gathers are LDS reads.
 #pragma once
 #include <type_traits>
 
@@ -422,7 +425,8 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     const int32_t nnz4 = nnz & ~3;
 
     T s = T(0);
-    // windows of kStreamWindow entries starting at a multiple of 4 (16-byte aligned loads)
+    // windows of kStreamWindow entries starting at a multiple of 8 (16-byte aligned loads of values,
+    // 32-bit columns and 16-bit offsets alike)
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
         stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
