@@ -432,8 +432,47 @@ def test_spmv_huge_rows_lds_blocks():
             check_spmv(dev, rowptr, colidx, vals, x, -1.5, 0.25, y0, what="alpha=-1.5 beta=0.25")
             a1 = dev.spmv(x, 2.0, 0.0)
             assert np.array_equal(a1, dev.spmv(x, 2.0, 0.0)), "two runs differ"
+            xn = x.copy()
+            xn[5], xn[ncols // 2], xn[ncols - 1] = np.inf, np.nan, -np.inf
+            with np.errstate(invalid="ignore", over="ignore"):
+                refn, _ = oracle.spmv(rowptr, colidx, vals, xn)
+                gotn = dev.spmv(xn)
+            assert np.array_equal(np.isnan(gotn), np.isnan(refn)) and np.array_equal(np.isinf(gotn), np.isinf(refn))
         finally:
             dev.close()
+
+
+def test_non_finite_values_propagate_like_the_reference():
+    """Inf and NaN in x, X and vals reach exactly the rows the serial evaluation says (padding
+    lanes repeat an entry and discard the product after the multiply, so they add nothing)."""
+    say("non-finite values")
+    n, ncols = 4000, 3000
+    L = mixed_lengths(n, 74, 5000)
+    L = np.minimum(L, ncols)
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 558, np.float64)
+    x = gen.uniform(30, gen.STREAM_X, ncols)
+    x[17] = np.inf
+    x[1234] = -np.inf
+    x[2999] = np.nan
+    vals[rowptr[500]] = np.inf                      # first entry of a row
+    vals[rowptr[2001] - 1] = np.nan                 # last entry of a row
+    X = gen.uniform(31, gen.STREAM_X, ncols * 16).reshape(ncols, 16)
+    X[17, 3] = np.inf
+    X[2999, :] = np.nan
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        with np.errstate(invalid="ignore", over="ignore"):
+            ref, _ = oracle.spmv(rowptr, colidx, vals, x)
+            got = dev.spmv(x)
+            assert np.array_equal(np.isnan(got), np.isnan(ref)), "NaN pattern differs (SpMV)"
+            assert np.array_equal(np.isposinf(got), np.isposinf(ref)) and np.array_equal(np.isneginf(got), np.isneginf(ref))
+            refm, _ = oracle.spmm(rowptr, colidx, vals, X)
+            gotm = dev.spmm(X)
+            assert np.array_equal(np.isnan(gotm), np.isnan(refm)), "NaN pattern differs (SpMM)"
+            assert np.array_equal(np.isposinf(gotm), np.isposinf(refm)) and np.array_equal(np.isneginf(gotm), np.isneginf(refm))
+        assert np.isnan(ref).sum() > 10 and np.isinf(ref).sum() > 10      # the case is not vacuous
+    finally:
+        dev.close()
 
 
 def test_workload4_wide_reduced():
