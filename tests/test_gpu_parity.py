@@ -475,6 +475,21 @@ def test_non_finite_values_propagate_like_the_reference():
         dev.close()
 
 
+def test_byte_offsets_beyond_4_gib():
+    """288^3 27-point stencil: 640.5 M entries, so the value array is 5.1 GB and byte offsets
+    into it pass 2^32 (and its chunks span more than 2^16 columns: 32-bit indices throughout)."""
+    w = gen.workload(2, {"nx": 288, "ny": 288, "nz": 288})
+    say(f"large {w.name} nnz={w.nnz}")
+    assert w.nnz * 8 > 2 ** 32
+    dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
+    try:
+        assert not dev.index16()["enabled"]
+        check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, literal=True, what=w.name)
+        check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, literal=True, what=w.name + " (paper shape)", paper_shape=True)
+    finally:
+        dev.close()
+
+
 def test_workload4_wide_reduced():
     """Power-law rows over 2^21 columns: x = 8 MB of floats, so the column split is on."""
     run_workload(4, {"n": 1 << 21, "cap": 200000})
