@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline workload); 6..9 = stand-ins for the paper's Table 3")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--scale", default=None,
+                    help="override size parameters of the workload's recipe, e.g. nx=288,ny=288,nz=288 "
+                         "(labelled in config.workload; the default sizes are the benchmark's)")
     ap.add_argument("--zipf-s", type=float, default=None,
                     help="workload 4 only: Zipf exponent (default 1.8; 2.0 gives the 'mean about 8' variant)")
     ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers"], default="tuned",
@@ -92,7 +95,14 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": nbytes, "bytes_written": nbytes}))
         return
 
-    w = gen.workload(args.config, {"s": args.zipf_s} if (args.zipf_s is not None and args.config == 4) else None)
+    scale = {}
+    if args.scale:
+        for item in args.scale.split(","):
+            key, val = item.split("=")
+            scale[key.strip()] = float(val) if "." in val else int(val)
+    if args.zipf_s is not None and args.config == 4:
+        scale["s"] = args.zipf_s
+    w = gen.workload(args.config, scale or None)
     tdt = torch.float64 if w.dtype == np.float64 else torch.float32
     rowptr = torch.from_numpy(w.rowptr).to(dev)
     colidx = torch.from_numpy(w.colidx).to(dev)

@@ -272,18 +272,25 @@ int lapis_csr_huge_sizes(const lapis_csr_t *A, int64_t *num_huge, int64_t *num_f
 int lapis_csr_copy_huge(const lapis_csr_t *A, int32_t *h_split_rows, int32_t *h_huge_rows, int32_t *h_fcut);
 
 /*
- * lapis_csr_copy_index16 - the 16-bit column offsets the analysis builds so that the stream
+ * lapis_csr_copy_index16 - the 16-bit column codes the analysis builds so that the stream
  * kernels read 2 instead of 4 bytes of index per entry (an implementation choice of this
  * library, not of the paper; exposed so that it can be compared bit for bit with a CPU
- * reference).  A stream chunk whose largest and smallest column differ by at most 65535 gets
- * chunk_base = its smallest column and col16[j] = colidx[j] - chunk_base for its entries; every
- * other chunk has chunk_base -1 and col16 0.  The structure is kept (*enabled = 1) only if such
- * chunks hold at least half of the matrix's entries; *narrow_entries is that count either way.
- *   h_chunk_base  HOST int32[ceil(nrows / LAPIS_STREAM_ROWS)]   h_col16  HOST uint16[nnz]
- * Both are written only when *enabled is 1; any pointer may be NULL.  Synchronises the device.
+ * reference).  For a stream chunk c:
+ *   narrow  (largest - smallest column <= 65535): chunk_base[c] = its smallest column,
+ *           col16[j] = colidx[j] - chunk_base[c];
+ *   framed  (not narrow, entries in at most 32 distinct frames; frame = column >> 11):
+ *           chunk_base[c] = -2, frame_table[32*c + k] = k-th smallest frame (the largest one
+ *           repeated above the count), col16[j] = (rank of the entry's frame << 11) |
+ *           (colidx[j] & 2047);
+ *   otherwise chunk_base[c] = -1, col16 0, frame_table 0 (also for chunks that do not stream).
+ * The structure is kept (*enabled = 1) only if narrow and framed chunks together hold at least
+ * half of the matrix's entries; *narrow_entries and *framed_entries are those counts either way.
+ *   h_chunk_base  HOST int32[C], C = ceil(nrows / LAPIS_STREAM_ROWS)
+ *   h_frame_table HOST int32[32*C]        h_col16  HOST uint16[nnz]
+ * The arrays are written only when *enabled is 1; any pointer may be NULL.  Synchronises the device.
  */
-int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int32_t *h_chunk_base,
-                           uint16_t *h_col16);
+int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int64_t *framed_entries,
+                           int32_t *h_chunk_base, int32_t *h_frame_table, uint16_t *h_col16);
 
 /* max |column - row| over the matrix's entries, found by lapis_csr_create; lapis_spmm uses it to
  * decide how workgroups are dealt to the 8 XCDs (band-wide windows of X rows that overflow one

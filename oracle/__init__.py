@@ -63,8 +63,8 @@ def _load():
         lib.oracle_partition_num_bins.restype = ctypes.c_int
         lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, p, p]
         lib.oracle_partition_stream_chunks.restype = i64
-        lib.oracle_index16.argtypes = [i64, p, p, i64, i64, p, p]
-        lib.oracle_index16.restype = i64
+        lib.oracle_index16.argtypes = [i64, p, p, i64, i64, p, p, p, p, p]
+        lib.oracle_index16.restype = None
         lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p]
         lib.oracle_partition_rows.restype = None
         lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
@@ -191,16 +191,24 @@ def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NN
 
 
 def index16(rowptr, colidx, stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_NNZ):
-    """16-bit column offsets of the narrow stream chunks: dict(enabled, chunk_base[num_chunks],
-    col16[nnz]); enabled when the narrow chunks hold at least half of the entries."""
+    """16-bit column codes of the stream chunks: dict(enabled, narrow_entries, framed_entries,
+    chunk_base[num_chunks] (>= 0: narrow chunk, its smallest column; -2: framed; -1: neither),
+    frame_table[32 * num_chunks], col16[nnz]); enabled when the narrow and framed chunks
+    together hold at least half of the entries."""
     assert rowptr.dtype == np.int32 and colidx.dtype == np.int32
     n = rowptr.size - 1
     nchunks = (n + stream_rows - 1) // stream_rows
     chunk_base = np.empty(nchunks, dtype=np.int32)
+    frame_table = np.empty(32 * nchunks, dtype=np.int32)
     col16 = np.empty(colidx.size, dtype=np.uint16)
-    narrow = _load().oracle_index16(n, _p(rowptr), _p(colidx), stream_rows, stream_min_nnz, _p(chunk_base), _p(col16))
-    return {"enabled": narrow > 0 and 2 * narrow >= colidx.size, "narrow_entries": narrow,
-            "chunk_base": chunk_base, "col16": col16}
+    scratch = np.empty(max(16 * stream_rows * stream_rows, 1), dtype=np.int32)   # rows of at most 2^4 * stream_rows entries
+    counts = np.zeros(2, dtype=np.int64)
+    _load().oracle_index16(n, _p(rowptr), _p(colidx), stream_rows, stream_min_nnz, _p(chunk_base),
+                           _p(frame_table), _p(col16), _p(scratch), _p(counts))
+    narrow, framed = int(counts[0]), int(counts[1])
+    return {"enabled": narrow + framed > 0 and 2 * (narrow + framed) >= colidx.size,
+            "narrow_entries": narrow, "framed_entries": framed,
+            "chunk_base": chunk_base, "frame_table": frame_table, "col16": col16}
 
 
 def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):

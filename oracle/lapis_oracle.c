@@ -33,6 +33,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 /* ---- SpMV, double matrix ------------------------------------------------ */
 void oracle_spmv_f64(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
@@ -262,19 +263,34 @@ int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int
     return count;
 }
 
-/* Level 1b: 16-bit column offsets.  A stream chunk (class >= 1) is "narrow" if its largest
- * and smallest column differ by at most 65535; chunk_base[c] is then its smallest column and
- * col16[j] = colidx[j] - chunk_base[c] for its entries.  Every other chunk gets chunk_base -1 and
- * its entries col16 0.  Returns the number of entries in narrow chunks; the compression is in
- * use when that is at least half of all entries (and not zero).  chunk_base has
- * ceil(nrows/chunk_rows) elements, col16 has rowptr[nrows]. */
-int64_t oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, int64_t chunk_rows,
-                       int64_t chunk_min_nnz, int32_t *chunk_base, uint16_t *col16)
+/* Level 1b: 16-bit column codes for the stream chunks (class >= 1).
+ *  - A chunk is "narrow" if its largest and smallest column differ by at most 65535:
+ *    chunk_base[c] = its smallest column, col16[j] = colidx[j] - chunk_base[c].
+ *  - Otherwise, with frames of 2048 columns (frame of a column = column >> 11), a chunk whose
+ *    entries touch at most 32 distinct frames is "framed": chunk_base[c] = -2,
+ *    frame_table[32*c + k] = its k-th smallest frame (k below the count; the largest frame
+ *    repeated above it), col16[j] = (k << 11) | (colidx[j] & 2047) with k the rank of the
+ *    entry's frame.
+ *  - Every other chunk: chunk_base -1, col16 0, frame_table 0.
+ * counts[0] = entries in narrow chunks, counts[1] = entries in framed chunks; the compression is
+ * in use when together they are at least half of all entries (and not zero).  chunk_base has
+ * ceil(nrows/chunk_rows) elements, frame_table 32 times as many, col16 has rowptr[nrows]. */
+static int cmp_i32(const void *a, const void *b)
 {
-    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows, narrow_entries = 0;
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+void oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, int64_t chunk_rows,
+                    int64_t chunk_min_nnz, int32_t *chunk_base, int32_t *frame_table, uint16_t *col16,
+                    int32_t *scratch, int64_t *counts)
+{
+    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
+    counts[0] = counts[1] = 0;
     for (int64_t j = 0; j < rowptr[nrows]; ++j) col16[j] = 0;
     for (int64_t c = 0; c < nchunks; ++c) {
         chunk_base[c] = -1;
+        for (int k = 0; k < 32; ++k) frame_table[32 * c + k] = 0;
         if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == 0) continue;
         int64_t last = (c + 1) * chunk_rows < nrows ? (c + 1) * chunk_rows : nrows;
         int64_t b = rowptr[c * chunk_rows], e = rowptr[last];
@@ -283,12 +299,29 @@ int64_t oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *coli
             if (colidx[j] < lo) lo = colidx[j];
             if (colidx[j] > hi) hi = colidx[j];
         }
-        if ((int64_t)hi - lo > 65535) continue;
-        chunk_base[c] = lo;
-        for (int64_t j = b; j < e; ++j) col16[j] = (uint16_t)(colidx[j] - lo);
-        narrow_entries += e - b;
+        if ((int64_t)hi - lo <= 65535) {
+            chunk_base[c] = lo;
+            for (int64_t j = b; j < e; ++j) col16[j] = (uint16_t)(colidx[j] - lo);
+            counts[0] += e - b;
+            continue;
+        }
+        /* distinct frames, ascending (scratch holds one int per entry of the chunk) */
+        for (int64_t j = b; j < e; ++j) scratch[j - b] = colidx[j] >> 11;
+        qsort(scratch, (size_t)(e - b), sizeof(int32_t), cmp_i32);
+        int64_t distinct = 0;
+        for (int64_t i = 0; i < e - b; ++i)
+            if (i == 0 || scratch[i] != scratch[i - 1]) scratch[distinct++] = scratch[i];
+        if (distinct > 32) continue;
+        chunk_base[c] = -2;
+        for (int k = 0; k < 32; ++k)
+            frame_table[32 * c + k] = scratch[k < distinct ? k : distinct - 1];
+        for (int64_t j = b; j < e; ++j) {
+            int k = 0;
+            while (frame_table[32 * c + k] != (colidx[j] >> 11)) ++k;
+            col16[j] = (uint16_t)((k << 11) | (colidx[j] & 2047));
+        }
+        counts[1] += e - b;
     }
-    return narrow_entries;
 }
 
 /* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and

@@ -60,7 +60,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_csr_huge_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 3
         lib.lapis_csr_copy_huge.argtypes = [p, p, p, p]
-        lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), p, p]
+        lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), p, p, p]
         lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
         lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
         lib.lapis_csr_copy_arrays.argtypes = [p, p, p, p]
@@ -133,16 +133,21 @@ def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
 
 
 def lapis_csr_copy_index16(A):
-    """dict(enabled, narrow_entries, chunk_base, col16) of a handle (arrays None when not enabled)."""
+    """dict(enabled, narrow_entries, framed_entries, chunk_base, frame_table, col16) of a handle
+    (arrays None when not enabled)."""
     n, _, z, _ = lapis_csr_shape(A)
-    on, narrow = ctypes.c_int(), ctypes.c_int64()
-    _check(load().lapis_csr_copy_index16(A, ctypes.byref(on), ctypes.byref(narrow), None, None))
-    out = {"enabled": bool(on.value), "narrow_entries": narrow.value, "chunk_base": None, "col16": None}
+    on, narrow, framed = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+    _check(load().lapis_csr_copy_index16(A, ctypes.byref(on), ctypes.byref(narrow), ctypes.byref(framed), None, None, None))
+    out = {"enabled": bool(on.value), "narrow_entries": narrow.value, "framed_entries": framed.value,
+           "chunk_base": None, "frame_table": None, "col16": None}
     if on.value:
         rows = lapis_partition_constants()["stream_rows"]
-        out["chunk_base"] = np.empty((n + rows - 1) // rows, dtype=np.int32)
+        chunks = (n + rows - 1) // rows
+        out["chunk_base"] = np.empty(chunks, dtype=np.int32)
+        out["frame_table"] = np.empty(32 * chunks, dtype=np.int32)
         out["col16"] = np.empty(z, dtype=np.uint16)
-        _check(load().lapis_csr_copy_index16(A, None, None, out["chunk_base"].ctypes.data, out["col16"].ctypes.data))
+        _check(load().lapis_csr_copy_index16(A, None, None, None, out["chunk_base"].ctypes.data,
+                                             out["frame_table"].ctypes.data, out["col16"].ctypes.data))
     return out
 
 

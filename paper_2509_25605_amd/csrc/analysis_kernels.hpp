@@ -183,57 +183,118 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
     }
 }
 
-// One workgroup of kCompactBlock threads: *narrow_entries = entries of the chunks with a base,
-// narrow_chunks[k - 1] = how many of them are of class k.
+// One workgroup of kCompactBlock threads: entries[0] = entries of the narrow chunks (chunk_base >= 0),
+// entries[1] = entries of the framed chunks (chunk_base == -2), narrow_chunks[k - 1] = how many
+// narrow chunks are of class k.
 __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nrows, int32_t num_chunks,
                                                                      int32_t chunk_rows,
                                                                      const int32_t *__restrict__ chunk_flag,
                                                                      const int32_t *__restrict__ rowptr,
                                                                      const int32_t *__restrict__ chunk_base,
-                                                                     unsigned long long *__restrict__ narrow_entries,
+                                                                     unsigned long long *__restrict__ entries_out,
                                                                      int32_t *__restrict__ narrow_chunks)
 {
-    __shared__ unsigned long long s_entries;
+    __shared__ unsigned long long s_entries[2];
     __shared__ int32_t s_chunks[kChunkClasses];
-    if (threadIdx.x == 0) s_entries = 0;
+    if (threadIdx.x < 2) s_entries[threadIdx.x] = 0;
     if (threadIdx.x < kChunkClasses) s_chunks[threadIdx.x] = 0;
     __syncthreads();
-    unsigned long long entries = 0;
+    unsigned long long entries = 0, framed = 0;
     int32_t chunks[kChunkClasses] = {0, 0, 0, 0};
     for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
-        if (chunk_base[c] < 0) continue;
+        const int32_t base = chunk_base[c];
+        if (base == -1) continue;
         const int64_t first = c * chunk_rows;
         const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
-        entries += (unsigned long long)(rowptr[last] - rowptr[first]);
+        const unsigned long long len = (unsigned long long)(rowptr[last] - rowptr[first]);
+        if (base == -2) { framed += len; continue; }
+        entries += len;
         const int32_t cls = chunk_flag[c];
 #pragma unroll
         for (int k = 0; k < kChunkClasses; ++k) chunks[k] += (cls == k + 1);
     }
-    if (entries) atomicAdd(&s_entries, entries);
+    if (entries) atomicAdd(&s_entries[0], entries);
+    if (framed) atomicAdd(&s_entries[1], framed);
 #pragma unroll
     for (int k = 0; k < kChunkClasses; ++k)
         if (chunks[k]) atomicAdd(&s_chunks[k], chunks[k]);
     __syncthreads();
-    if (threadIdx.x == 0) *narrow_entries = s_entries;
+    if (threadIdx.x < 2) entries_out[threadIdx.x] = s_entries[threadIdx.x];
     if (threadIdx.x < kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
 }
 
-// col16[j] = colidx[j] - chunk_base[c] for the entries of the chunks with a base (col16 is 0 elsewhere)
+// Frames of 2048 columns for the stream chunks that are not narrow (chunk_base == -1 on entry),
+// one wavefront per chunk: the distinct frames (column >> 11) are taken out smallest first; with
+// at most 32 of them the chunk becomes "framed": chunk_base = -2 and frame_table[32*c + k] = the
+// k-th smallest frame (the largest one repeated above the count).  frame_table must be 0 on entry.
+constexpr int kAnalysisFrameShift = 11;
+constexpr int kAnalysisFrameSlots = 32;
+__global__ __launch_bounds__(kBlock) void chunk_frames_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                              const int32_t *__restrict__ chunk_flag,
+                                                              const int32_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ colidx,
+                                                              int32_t *__restrict__ chunk_base,
+                                                              int32_t *__restrict__ frame_table)
+{
+    const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (c >= num_chunks) return;                       // whole wavefronts leave together
+    if (chunk_flag[c] == 0 || chunk_base[c] != -1) return;
+    const int64_t first = c * chunk_rows;
+    const int64_t last_row = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    const int32_t b = rowptr[first], e = rowptr[last_row];
+    int32_t last = -1, mine = 0, count = 0;
+    for (int k = 0; k <= kAnalysisFrameSlots; ++k) {
+        int32_t rev = 0;                               // INT32_MAX - (smallest frame above `last` seen by this lane)
+        for (int32_t j = b + lane; j < e; j += kWave) {
+            const int32_t f = colidx[j] >> kAnalysisFrameShift;
+            if (f > last) rev = max(rev, INT32_MAX - f);
+        }
+        rev = wave_max_nonneg(rev);
+        if (rev == 0) break;                           // no frame left
+        if (k == kAnalysisFrameSlots) { count = kAnalysisFrameSlots + 1; break; }
+        last = INT32_MAX - rev;
+        if (lane == k) mine = last;
+        count = k + 1;
+    }
+    if (count > kAnalysisFrameSlots) return;           // too scattered: stays -1
+    if (lane < kAnalysisFrameSlots) frame_table[c * kAnalysisFrameSlots + lane] = lane < count ? mine : last;
+    if (lane == 0) chunk_base[c] = -2;
+}
+
+// col16[j] for the entries of the narrow chunks (colidx[j] - chunk_base[c]) and of the framed
+// chunks ((rank of the entry's frame in the chunk's table) << 11 | (colidx[j] & 2047)); col16 is
+// 0 elsewhere.  One wavefront per chunk.
 __global__ __launch_bounds__(kBlock) void col16_fill_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                             const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
                                                             const int32_t *__restrict__ chunk_base,
+                                                            const int32_t *__restrict__ frame_table,
                                                             uint16_t *__restrict__ col16)
 {
     const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
     if (c >= num_chunks) return;
     const int32_t base = chunk_base[c];
-    if (base < 0) return;
+    if (base == -1) return;
     const int64_t first = c * chunk_rows;
     const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
     const int32_t e = rowptr[last];
-    for (int32_t j = rowptr[first] + lane; j < e; j += kWave) col16[j] = (uint16_t)(load_stream(colidx + j) - base);
+    if (base >= 0) {
+        for (int32_t j = rowptr[first] + lane; j < e; j += kWave) col16[j] = (uint16_t)(load_stream(colidx + j) - base);
+        return;
+    }
+    // framed: lane t < 32 keeps table entry t; the rank of a frame is the number of entries below it
+    const int32_t tab = frame_table[c * kAnalysisFrameSlots + (lane % kAnalysisFrameSlots)];
+    for (int32_t j0 = rowptr[first]; j0 < e; j0 += kWave) {           // uniform trip count: readlane needs all lanes
+        const int32_t j = j0 + lane;
+        const int32_t col = j < e ? load_stream(colidx + j) : 0;
+        const int32_t f = col >> kAnalysisFrameShift;
+        int32_t rank = 0;
+#pragma unroll
+        for (int t = 0; t < kAnalysisFrameSlots; ++t) rank += (__builtin_amdgcn_readlane(tab, t) < f);
+        if (j < e) col16[j] = (uint16_t)((rank << kAnalysisFrameShift) | (col & ((1 << kAnalysisFrameShift) - 1)));
+    }
 }
 
 // Pass 1: per-workgroup histogram of row bins (rows of flagged chunks are skipped; chunk_flag

@@ -63,7 +63,9 @@ struct lapis_csr {
     // level 1b: 16-bit column offsets of the stream chunks whose columns span less than 2^16
     int32_t *d_chunk_base = nullptr;     // [num_chunks] smallest column of such a chunk, else -1; null: off
     uint16_t *d_col16 = nullptr;         // [nnz rounded up to 8, + 8] colidx[j] - base of j's chunk
+    int32_t *d_frame_table = nullptr;    // [32 * num_chunks] frames of the framed chunks (chunk_base == -2)
     int64_t narrow_entries = 0;          // entries in the chunks that could get a base
+    int64_t framed_entries = 0;          // entries in the chunks that got a frame table instead
     bool class_all16[kStreamClasses] = {false, false, false, false};   // every chunk of the class has a base
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
@@ -174,6 +176,7 @@ void free_handle(lapis_csr *A)
     (void)hipFree(A->d_vsum);
     (void)hipFree(A->d_chunk_base);
     (void)hipFree(A->d_col16);
+    (void)hipFree(A->d_frame_table);
     (void)hipFree(A->own_rowptr);
     (void)hipFree(A->own_colidx);
     (void)hipFree(A->own_vals);
@@ -316,7 +319,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     // if those chunks hold at least half of the entries
     if (num_stream > 0) {
         struct NarrowCounts {
-            unsigned long long entries;
+            unsigned long long entries[2];      // in narrow chunks, in framed chunks
             int32_t chunks[kStreamClasses];
         } h_counts;
         DeviceTemp narrow;
@@ -324,28 +327,37 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         NarrowCounts *d_counts = narrow.as<NarrowCounts>();
         if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
         const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
+        if (int rc = device_alloc(&A->d_frame_table, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots)) return rc;
+        LAPIS_HIP(hipMemsetAsync(A->d_frame_table, 0, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots, stream));
         chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
             A->d_chunk_base);
+        chunk_frames_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
+            A->d_chunk_base, A->d_frame_table);
         narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
-            &d_counts->entries, d_counts->chunks);
+            d_counts->entries, d_counts->chunks);
         LAPIS_HIP(hipGetLastError());
         if (int rc = read_back(&h_counts, narrow.p, sizeof(h_counts), stream)) return rc;
-        const unsigned long long h_narrow = h_counts.entries;
-        A->narrow_entries = (int64_t)h_narrow;
+        const unsigned long long h_narrow = h_counts.entries[0] + h_counts.entries[1];
+        A->narrow_entries = (int64_t)h_counts.entries[0];
+        A->framed_entries = (int64_t)h_counts.entries[1];
         if (h_narrow > 0 && 2 * h_narrow >= (unsigned long long)A->nnz) {
             const size_t len = ((size_t)A->nnz + 7) / 8 * 8 + 8;      // 16-byte loads may run past nnz
             if (int rc = device_alloc(&A->d_col16, sizeof(uint16_t) * len)) return rc;
             LAPIS_HIP(hipMemsetAsync(A->d_col16, 0, sizeof(uint16_t) * len, stream));
             col16_fill_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
-                (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16);
+                (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
+                A->d_col16);
             LAPIS_HIP(hipGetLastError());
             for (int cls = 1; cls <= kStreamClasses; ++cls)
                 A->class_all16[cls - 1] = h_counts.chunks[cls - 1] == A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
         } else {
             (void)hipFree(A->d_chunk_base);
+            (void)hipFree(A->d_frame_table);
             A->d_chunk_base = nullptr;
+            A->d_frame_table = nullptr;
         }
     }
 
@@ -514,12 +526,12 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
     const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
     if (A->class_all16[cls - 1])
         spmv_stream_kernel<T, G, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
-            static_cast<const T *>(A->vals), x, y, a, b);
+            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
+            A->d_col16, static_cast<const T *>(A->vals), x, y, a, b);
     else
         spmv_stream_kernel<T, G, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
-            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_col16,
-            static_cast<const T *>(A->vals), x, y, a, b);
+            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
+            A->d_col16, static_cast<const T *>(A->vals), x, y, a, b);
 }
 
 // y (ncols values) = beta*y, then every entry of A adds alpha*vals[j]*x[row] into y[colidx[j]].
@@ -646,11 +658,11 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
             if (all16)
                 spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
                     (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                    A->d_chunk_base, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+                    A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
             else
                 spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
                     (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                    A->d_chunk_base, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+                    A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
         }
     }
     if (n_rows_a > 0) {
@@ -910,17 +922,20 @@ int lapis_csr_copy_huge(const lapis_csr_t *A, int32_t *h_split_rows, int32_t *h_
     return LAPIS_OK;
 }
 
-int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int32_t *h_chunk_base,
-                           uint16_t *h_col16)
+int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int64_t *framed_entries,
+                           int32_t *h_chunk_base, int32_t *h_frame_table, uint16_t *h_col16)
 {
     if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
     const bool on = A->d_col16 != nullptr;
     if (enabled) *enabled = on ? 1 : 0;
     if (narrow_entries) *narrow_entries = A->narrow_entries;
+    if (framed_entries) *framed_entries = A->framed_entries;
     if (!on) return LAPIS_OK;
     LAPIS_HIP(hipDeviceSynchronize());
     if (h_chunk_base && A->num_chunks > 0)
         LAPIS_HIP(hipMemcpy(h_chunk_base, A->d_chunk_base, sizeof(int32_t) * (size_t)A->num_chunks, hipMemcpyDeviceToHost));
+    if (h_frame_table && A->num_chunks > 0)
+        LAPIS_HIP(hipMemcpy(h_frame_table, A->d_frame_table, sizeof(int32_t) * (size_t)A->num_chunks * kFrameSlots, hipMemcpyDeviceToHost));
     if (h_col16 && A->nnz > 0)
         LAPIS_HIP(hipMemcpy(h_col16, A->d_col16, sizeof(uint16_t) * (size_t)A->nnz, hipMemcpyDeviceToHost));
     return LAPIS_OK;

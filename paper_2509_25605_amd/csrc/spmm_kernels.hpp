@@ -65,7 +65,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     uint32_t xcd_block, const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
-    const uint16_t *__restrict__ col16, const T *__restrict__ vals, int64_t k,
+    const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16,
+    const T *__restrict__ vals, int64_t k,
     int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
 {
     static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
     __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
     __shared__ int32_t s_rp[kStreamRows + 1];
+    __shared__ int32_t s_tab[ALL16 ? 1 : kFrameSlots];
 
     const uint32_t id = !XCD_REMAP ? blockIdx.x
                         : xcd_block ? xcd_block_cyclic_id(blockIdx.x, xcd_block)
@@ -86,6 +88,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
     const int64_t row0 = chunk * kStreamRows;
     const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
+    if constexpr (!ALL16) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
     if (lane <= kStreamRows) {
         const int64_t r = row0 + lane;
         s_rp[lane] = rowptr[r < nrows ? r : nrows];     // rows past the end: empty
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
-        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
             const int r = active ? p * kSlots + slot : 0;

@@ -201,18 +201,33 @@ struct StreamCols {
     const int32_t *__restrict__ c32;
     const uint16_t *__restrict__ c16;     // window start a multiple of 8 entries (16 bytes); padded past nnz
     int32_t cbase;
+    const int32_t *tab;                   // LDS: the chunk's frame table (framed chunks only)
 };
+
+// How a chunk's columns are stored: 32-bit colidx; 16-bit offsets from the chunk's smallest
+// column (chunk_base >= 0); or 16-bit codes (slot << 11) | (column & 2047) with a per-chunk table
+// of up to 32 frames of 2048 columns (chunk_base == kChunkFramed).
+constexpr int kCols32 = 0, kColsNarrow = 1, kColsFramed = 2;
+constexpr int32_t kChunkFramed = -2;
+constexpr int kFrameShift = 11, kFrameSlots = 32;
+constexpr int32_t kFrameMask = (1 << kFrameShift) - 1;
+
+__device__ __forceinline__ int32_t framed_column(const int32_t *tab, uint16_t code)
+{
+    return (tab[code >> kFrameShift] << kFrameShift) | ((int32_t)code & kFrameMask);
+}
 
 // Copy the first n_vec (a multiple of 4, <= kStreamWindow) entries of the window to LDS with
 // NC column loads (16 bytes, or 8 bytes of 16-bit offsets) and NV 16-byte value loads per lane.
 // Lanes past the end repeat the last group: same address, same data, no extra memory traffic
 // and no divergent control flow.
-template <typename T, int NC, int NV, bool C16, typename IDX>
+template <typename T, int NC, int NV, int KIND, typename IDX>
 __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__restrict__ vw,
                                             int lane, int n_vec, IDX *s_col, T *s_val)
 {
+    constexpr bool C16 = KIND != kCols32;
     constexpr bool kRaw16 = sizeof(IDX) == 2;       // LDS keeps the 16-bit offsets as they are
-    static_assert(!kRaw16 || C16, "a 16-bit LDS window needs 16-bit offsets in memory");
+    static_assert(!kRaw16 || KIND == kColsNarrow, "a 16-bit LDS window needs 16-bit offsets in memory");
     typedef typename StreamVec<T>::type vec_t;
     constexpr int kPerVec = 16 / sizeof(T);          // values per 16-byte load
     const int last_c = n_vec - 4;
@@ -253,10 +268,17 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
                 continue;
             }
             int4v a, b;
-            a.x = cols.cbase + (int32_t)cs[i].s0; a.y = cols.cbase + (int32_t)cs[i].s1;
-            a.z = cols.cbase + (int32_t)cs[i].s2; a.w = cols.cbase + (int32_t)cs[i].s3;
-            b.x = cols.cbase + (int32_t)cs[i].s4; b.y = cols.cbase + (int32_t)cs[i].s5;
-            b.z = cols.cbase + (int32_t)cs[i].s6; b.w = cols.cbase + (int32_t)cs[i].s7;
+            if constexpr (KIND == kColsFramed) {
+                a.x = framed_column(cols.tab, cs[i].s0); a.y = framed_column(cols.tab, cs[i].s1);
+                a.z = framed_column(cols.tab, cs[i].s2); a.w = framed_column(cols.tab, cs[i].s3);
+                b.x = framed_column(cols.tab, cs[i].s4); b.y = framed_column(cols.tab, cs[i].s5);
+                b.z = framed_column(cols.tab, cs[i].s6); b.w = framed_column(cols.tab, cs[i].s7);
+            } else {
+                a.x = cols.cbase + (int32_t)cs[i].s0; a.y = cols.cbase + (int32_t)cs[i].s1;
+                a.z = cols.cbase + (int32_t)cs[i].s2; a.w = cols.cbase + (int32_t)cs[i].s3;
+                b.x = cols.cbase + (int32_t)cs[i].s4; b.y = cols.cbase + (int32_t)cs[i].s5;
+                b.z = cols.cbase + (int32_t)cs[i].s6; b.w = cols.cbase + (int32_t)cs[i].s7;
+            }
             *reinterpret_cast<int4v *>(s_col + idx) = a;
             *reinterpret_cast<int4v *>(s_col + idx + 4) = b;
         }
@@ -278,7 +300,7 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
 
 // NC column loads cover NC*256 entries; the value loads needed for n_vec entries are either
 // NC*R or NC*R - 1 (R = value loads per 256 entries: 2 for double, 1 for float).
-template <typename T, int NC, bool C16, typename IDX>
+template <typename T, int NC, int KIND, typename IDX>
 __device__ __forceinline__ void stream_fill_pick(const StreamCols cols, const T *__restrict__ vw,
                                                  int lane, int n_vec, IDX *s_col, T *s_val)
 {
@@ -286,21 +308,21 @@ __device__ __forceinline__ void stream_fill_pick(const StreamCols cols, const T 
     constexpr int kFull = NC * (kWave * 4) / kPerLoad;
     if constexpr (kFull > 1 && kPerLoad < kWave * 4) {
         if (n_vec <= (kFull - 1) * kPerLoad) {
-            stream_fill<T, NC, kFull - 1, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+            stream_fill<T, NC, kFull - 1, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
             return;
         }
     }
-    stream_fill<T, NC, kFull, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    stream_fill<T, NC, kFull, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
 }
 
-template <typename T, bool C16, typename IDX>
+template <typename T, int KIND, typename IDX>
 __device__ __forceinline__ void stream_fill_by_size(const StreamCols cols, const T *__restrict__ vw,
                                                     int lane, int n_vec, IDX *s_col, T *s_val)
 {
-    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > kWave * 4) stream_fill_pick<T, 2, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
-    else if (n_vec > 0) stream_fill_pick<T, 1, C16, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    if (n_vec > 3 * kWave * 4) stream_fill_pick<T, 4, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 2 * kWave * 4) stream_fill_pick<T, 3, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > kWave * 4) stream_fill_pick<T, 2, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
+    else if (n_vec > 0) stream_fill_pick<T, 1, KIND, IDX>(cols, vw, lane, n_vec, s_col, s_val);
 }
 
 // Stage entries [w0, w1) of the matrix (w0 a multiple of 8, w1 - w0 <= kStreamWindow) in LDS:
@@ -308,9 +330,12 @@ __device__ __forceinline__ void stream_fill_by_size(const StreamCols cols, const
 // entries one by one.  cbase >= 0: the columns are cbase + col16[j], else colidx[j] (col16 may
 // then be null).  Ends with a wavefront-level fence so every lane may read what others wrote.
 // With a 16-bit LDS window (IDX = uint16_t) the offsets are staged as they are and cbase must be >= 0.
+// cbase == kChunkFramed: the codes are expanded through the chunk's frame table s_tab (LDS, filled
+// and fenced by the caller).
 template <typename T, typename IDX>
 __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__ colidx,
                                                      const uint16_t *__restrict__ col16, int32_t cbase,
+                                                     const int32_t *s_tab,
                                                      const T *__restrict__ vals, int32_t w0, int32_t w1,
                                                      int32_t nnz4, int lane, IDX *s_col, T *s_val)
 {
@@ -319,16 +344,18 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
     const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
     const T *__restrict__ vw = vals + w0;
     if constexpr (kRaw16) {
-        stream_fill_by_size<T, true, IDX>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
+        stream_fill_by_size<T, kColsNarrow, IDX>(StreamCols{nullptr, col16 + w0, cbase, nullptr}, vw, lane, n_vec, s_col, s_val);
     } else {
-        if (cbase >= 0) stream_fill_by_size<T, true, IDX>(StreamCols{nullptr, col16 + w0, cbase}, vw, lane, n_vec, s_col, s_val);
-        else stream_fill_by_size<T, false, IDX>(StreamCols{colidx + w0, nullptr, 0}, vw, lane, n_vec, s_col, s_val);
+        if (cbase >= 0) stream_fill_by_size<T, kColsNarrow, IDX>(StreamCols{nullptr, col16 + w0, cbase, nullptr}, vw, lane, n_vec, s_col, s_val);
+        else if (cbase == kChunkFramed) stream_fill_by_size<T, kColsFramed, IDX>(StreamCols{nullptr, col16 + w0, 0, s_tab}, vw, lane, n_vec, s_col, s_val);
+        else stream_fill_by_size<T, kCols32, IDX>(StreamCols{colidx + w0, nullptr, 0, nullptr}, vw, lane, n_vec, s_col, s_val);
     }
     if (w0 + n_vec < w1) {                              // the matrix's last nnz % 4 entries
         const int32_t j = w0 + n_vec + lane;
         if (j < w1) {
             if constexpr (kRaw16) s_col[j - w0] = col16[j];
-            else s_col[j - w0] = cbase >= 0 ? cbase + (int32_t)col16[j] : colidx[j];
+            else s_col[j - w0] = cbase >= 0 ? cbase + (int32_t)col16[j]
+                                 : cbase == kChunkFramed ? framed_column(s_tab, col16[j]) : colidx[j];
             s_val[j - w0] = vals[j];
         }
     }
@@ -337,9 +364,18 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// B entries of this lane's share of a row: (column, value) pairs out of LDS, the B gathers of x
-// issued back to back, then the FMAs.  Lanes with fewer than u0 + B entries repeat their last
-// entry and discard the product (no divergent control flow).
+// The frame table of a framed chunk into LDS (32 ints per wavefront), fenced for the wavefront.
+__device__ __forceinline__ void load_frame_table(const int32_t *__restrict__ frame_table, int64_t chunk,
+                                                 int32_t cbase, int lane, int32_t *s_tab)
+{
+    if (cbase == kChunkFramed) {
+        if (lane < kFrameSlots) s_tab[lane] = frame_table[chunk * kFrameSlots + lane];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
 __device__ __forceinline__ double fused_madd(double a, double b, double c) { return __builtin_fma(a, b, c); }
 __device__ __forceinline__ float fused_madd(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 
@@ -397,8 +433,8 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
-    const uint16_t *__restrict__ col16, const T *__restrict__ vals, const T *__restrict__ x,
-    T *__restrict__ y, T alpha, T beta)
+    const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16,
+    const T *__restrict__ vals, const T *__restrict__ x, T *__restrict__ y, T alpha, T beta)
 {
     constexpr int kRowsPerWave = kWave / G;
     constexpr int kWavesPerChunk = kStreamRows / kRowsPerWave;
@@ -407,6 +443,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
+    __shared__ int32_t s_tab[ALL16 ? 1 : kFrameSlots];
 
     const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_waves) : blockIdx.x;
     if (id >= num_waves) return;
@@ -415,6 +452,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     const uint32_t list_pos = id / kWavesPerChunk;
     const int64_t chunk = stream_chunks ? stream_chunks[list_pos] : (int64_t)list_pos;
     const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
+    if constexpr (!ALL16) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
     const int64_t row = chunk * kStreamRows + (id % kWavesPerChunk) * kRowsPerWave + lane / G;
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
@@ -429,7 +467,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     // 32-bit columns and 16-bit offsets alike)
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
-        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 
         // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
         const int32_t ub = (rb > w0 ? rb : w0) - w0;

@@ -29,9 +29,11 @@ def check_index16(dev):
     ref = oracle.index16(dev.h_rowptr, dev.h_colidx)
     got = dev.index16()
     assert got["enabled"] == ref["enabled"] and got["narrow_entries"] == ref["narrow_entries"]
+    assert got["framed_entries"] == ref["framed_entries"]
     if ref["enabled"]:
         assert got["chunk_base"].dtype == np.int32 and got["col16"].dtype == np.uint16
         assert np.array_equal(got["chunk_base"], ref["chunk_base"]), "chunk_base differs"
+        assert np.array_equal(got["frame_table"], ref["frame_table"]), "frame_table differs"
         assert np.array_equal(got["col16"], ref["col16"]), "col16 differs"
     return ref["enabled"]
 
@@ -364,6 +366,41 @@ def test_index16_mixed_narrow_and_wide_chunks(dtype, narrow_rows, expect_on):
         dev.close()
 
 
+def test_index16_framed_chunks():
+    """Stencil planes of 200 x 200: chunks span 2*(200^2 + 201) columns, far beyond 2^16, but touch
+    only 9 runs of columns: frame tables.  Also a matrix mixing narrow, framed and plain chunks."""
+    say("index16 framed")
+    w = gen.workload(2, {"nx": 200, "ny": 200, "nz": 12})
+    dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
+    try:
+        check_partition(dev, w.rowptr)
+        assert check_index16(dev) and dev.index16()["framed_entries"] > 0
+        check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, literal=True, what="stencil 200x200x12")
+        X = gen.uniform(32, gen.STREAM_X, w.ncols * 16).reshape(w.ncols, 16)
+        check_spmm(dev, w.rowptr, w.colidx, w.vals, X, what="spmm k=16")
+    finally:
+        dev.close()
+    for dtype in (np.float64, np.float32):
+        n, ncols, per = 9600, 1 << 22, 16
+        rowptr, colidx, vals = _banded_and_random(n, ncols, per, 3200, 810, dtype)   # rows 0..3199 narrow
+        # rows 3200..6399: four clusters of four columns far apart (4 frames per row, few per chunk)
+        r = np.arange(3200, 6400)
+        clusters = (np.arange(4)[None, :, None] * 700001 + (r[:, None, None] // 64) * 2048 + np.arange(4)[None, None, :])
+        colidx[3200 * per:6400 * per] = np.sort(clusters.reshape(3200, per) % ncols, axis=1).ravel().astype(np.int32)
+        x = gen.uniform(33, gen.STREAM_X, ncols).astype(dtype)
+        dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+        try:
+            check_partition(dev, rowptr)
+            assert check_index16(dev)
+            base = dev.index16()["chunk_base"]
+            assert np.all(base[:100] >= 0) and np.all(base[100:200] == -2) and np.all(base[200:] == -1)
+            check_spmv(dev, rowptr, colidx, vals, x, what="mixed kinds")
+            X = gen.uniform(34, gen.STREAM_X, ncols * 4).astype(dtype).reshape(ncols, 4)
+            check_spmm(dev, rowptr, colidx, vals, X, what="mixed kinds spmm k=4")
+        finally:
+            dev.close()
+
+
 def test_index16_last_entries_of_the_matrix():
     """nnz % 4 = 1, 2, 3: the entries past the last vector load take the scalar path."""
     for extra in (1, 2, 3):
@@ -477,13 +514,14 @@ def test_non_finite_values_propagate_like_the_reference():
 
 def test_byte_offsets_beyond_4_gib():
     """288^3 27-point stencil: 640.5 M entries, so the value array is 5.1 GB and byte offsets
-    into it pass 2^32 (and its chunks span more than 2^16 columns: 32-bit indices throughout)."""
+    into it pass 2^32 (and its chunks span more than 2^16 columns: framed 16-bit codes)."""
     w = gen.workload(2, {"nx": 288, "ny": 288, "nz": 288})
     say(f"large {w.name} nnz={w.nnz}")
     assert w.nnz * 8 > 2 ** 32
     dev = DeviceCsr(w.nrows, w.ncols, w.rowptr, w.colidx, w.vals)
     try:
-        assert not dev.index16()["enabled"]
+        got = dev.mat.index16()
+        assert got["enabled"] and got["framed_entries"] > 0.9 * w.nnz
         check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, literal=True, what=w.name)
         check_spmv(dev, w.rowptr, w.colidx, w.vals, w.x, literal=True, what=w.name + " (paper shape)", paper_shape=True)
     finally:

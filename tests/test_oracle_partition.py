@@ -284,12 +284,13 @@ def test_split_huge_rows_match_searchsorted_on_power_law_rows():
 
 # ---- level 1b: 16-bit column offsets of narrow stream chunks ----------------
 def _index16_brute(rowptr, colidx, part):
-    """Straight from the definition, chunk by chunk, with numpy min/max."""
+    """Straight from the definition, chunk by chunk, with numpy min / max / unique."""
     n = rowptr.size - 1
     nchunks = (n + oracle.STREAM_ROWS - 1) // oracle.STREAM_ROWS
     base = np.full(nchunks, -1, dtype=np.int32)
+    table = np.zeros(32 * nchunks, dtype=np.int32)
     col16 = np.zeros(colidx.size, dtype=np.uint16)
-    narrow = 0
+    narrow = framed = 0
     for c in part["stream_chunks"]:
         b, e = rowptr[c * oracle.STREAM_ROWS], rowptr[min((c + 1) * oracle.STREAM_ROWS, n)]
         cols = colidx[b:e]
@@ -297,26 +298,72 @@ def _index16_brute(rowptr, colidx, part):
             base[c] = cols.min()
             col16[b:e] = cols - cols.min()
             narrow += e - b
-    return base, col16, narrow
+            continue
+        frames = np.unique(cols >> 11)
+        if frames.size <= 32:
+            base[c] = -2
+            table[32 * c:32 * c + 32] = frames[-1]
+            table[32 * c:32 * c + frames.size] = frames
+            col16[b:e] = (np.searchsorted(frames, cols >> 11) << 11) | (cols & 2047)
+            framed += e - b
+    return base, table, col16, narrow, framed
+
+
+def _decode_index16(rowptr, got):
+    """Columns back from the codes: base + offset, or frame_table[code >> 11] * 2048 + (code & 2047)."""
+    n = rowptr.size - 1
+    chunk_of_entry = np.repeat(np.arange(n) // oracle.STREAM_ROWS, np.diff(rowptr))
+    b = got["chunk_base"][chunk_of_entry].astype(np.int64)
+    code = got["col16"].astype(np.int64)
+    frame = got["frame_table"][32 * chunk_of_entry + (code >> 11)].astype(np.int64)
+    cols = np.where(b >= 0, b + code, frame * 2048 + (code & 2047))
+    return cols, b
 
 
 @pytest.mark.parametrize("cfg,scale", [(1, None), (2, {"nx": 24, "ny": 24, "nz": 24}),
+                                       (2, {"nx": 200, "ny": 200, "nz": 6}),
                                        (3, {"n": 1 << 18}), (4, {"n": 1 << 15, "cap": 5000}),
                                        (8, {"grid": 12})])
 def test_index16_matches_definition_and_reconstructs_columns(cfg, scale):
     w = gen.workload(cfg, scale)
     part = oracle.partition(w.rowptr)
     got = oracle.index16(w.rowptr, w.colidx)
-    base, col16, narrow = _index16_brute(w.rowptr, w.colidx, part)
+    base, table, col16, narrow, framed = _index16_brute(w.rowptr, w.colidx, part)
     assert got["chunk_base"].dtype == np.int32 and got["col16"].dtype == np.uint16
     assert np.array_equal(got["chunk_base"], base) and np.array_equal(got["col16"], col16)
-    assert got["narrow_entries"] == narrow and got["enabled"] == (narrow > 0 and 2 * narrow >= w.nnz)
-    # the point of the structure: base + offset gives back every column of a narrow chunk
-    chunk_of_entry = np.repeat(np.arange(w.nrows) // oracle.STREAM_ROWS, np.diff(w.rowptr))
-    b = got["chunk_base"][chunk_of_entry]
-    ok = b >= 0
-    assert np.array_equal(b[ok] + got["col16"][ok].astype(np.int64), w.colidx[ok])
+    assert np.array_equal(got["frame_table"], table)
+    assert (got["narrow_entries"], got["framed_entries"]) == (narrow, framed)
+    assert got["enabled"] == (narrow + framed > 0 and 2 * (narrow + framed) >= w.nnz)
+    # the point of the structure: every column of a narrow or framed chunk comes back from its code
+    cols, b = _decode_index16(w.rowptr, got)
+    ok = b != -1
+    assert np.array_equal(cols[ok], w.colidx[ok])
     assert np.all(got["col16"][~ok] == 0)
+    if cfg == 2 and scale["nx"] == 200:
+        assert framed > narrow                     # 200 x 200 planes: interior chunks span 2*(200^2+201) columns
+
+
+def test_index16_frames_hand_worked():
+    """One chunk of 32 rows x 8 entries: columns 0..3 and 100000..100003 in every row: two frames
+    (0 and 48); a second chunk touching 33 frames is left alone."""
+    n, per = 64, 8
+    rowptr = (np.arange(n + 1) * per).astype(np.int32)
+    row_a = np.array([0, 1, 2, 3, 100000, 100001, 100002, 100003], dtype=np.int32)
+    chunk_b = (np.arange(32 * per) % 33 * 2048 + 5).astype(np.int32)          # 33 distinct frames
+    colidx = np.concatenate([np.tile(row_a, 32), np.sort(chunk_b.reshape(32, per), axis=1).ravel()]).astype(np.int32)
+    got = oracle.index16(rowptr, colidx)
+    assert got["chunk_base"].tolist() == [-2, -1]
+    assert got["frame_table"][:32].tolist() == [0] + [48] * 31 and np.all(got["frame_table"][32:] == 0)
+    assert got["col16"][:8].tolist() == [0, 1, 2, 3, 2048 + 100000 % 2048, 2048 + 100001 % 2048,
+                                          2048 + 100002 % 2048, 2048 + 100003 % 2048]
+    assert np.all(got["col16"][256:] == 0)
+    assert (got["narrow_entries"], got["framed_entries"], got["enabled"]) == (0, 256, True)
+    # 32 frames is still fine
+    chunk_c = (np.arange(32 * per) % 32 * 4096 + 7).astype(np.int32)
+    colidx[256:] = np.sort(chunk_c.reshape(32, per), axis=1).ravel()
+    got = oracle.index16(rowptr, colidx)
+    assert got["chunk_base"].tolist() == [-2, -2]
+    assert got["frame_table"][32:].tolist() == list(range(0, 64, 2))
 
 
 def test_index16_threshold_is_65535():
@@ -329,8 +376,8 @@ def test_index16_threshold_is_65535():
         colidx[-1] = 1000 + span                  # largest column of chunk 1; its smallest is 1000
         got = oracle.index16(rowptr, colidx)
         assert got["chunk_base"][0] == 0
-        assert got["chunk_base"][1] == (1000 if narrow else -1)
-        assert got["col16"][-1] == (span if narrow else 0)
+        assert got["chunk_base"][1] == (1000 if narrow else -2)       # not narrow: two frames, 0 and 32
+        assert got["col16"][-1] == (span if narrow else (1 << 11) | ((1000 + span) & 2047))
         assert got["enabled"]                     # chunk 0 alone holds half of the entries
 
 
@@ -339,9 +386,11 @@ def test_index16_off_without_stream_chunks_and_below_half():
     colidx = np.tile(np.arange(4, dtype=np.int32), 32)
     got = oracle.index16(rowptr, colidx)
     assert not got["enabled"] and np.all(got["chunk_base"] == -1) and got["narrow_entries"] == 0
-    # one narrow chunk of 256 entries and one wide chunk of 320 entries: 256 * 2 < 576
+    # one narrow chunk of 256 entries and one chunk of 320 entries over 40 frames: 256 * 2 < 576
     lens = np.concatenate([np.full(32, 8), np.full(32, 10)])
     rowptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-    colidx = np.concatenate([np.tile(np.arange(8), 32), np.tile(np.arange(10) * 10000, 32)]).astype(np.int32)
+    wide = np.sort(((np.arange(32)[:, None] * 10 + np.arange(10)[None, :]) % 40) * 10000, axis=1)
+    colidx = np.concatenate([np.tile(np.arange(8), 32), wide.ravel()]).astype(np.int32)
     got = oracle.index16(rowptr, colidx)
     assert got["chunk_base"].tolist() == [0, -1] and got["narrow_entries"] == 256 and not got["enabled"]
+    assert got["framed_entries"] == 0
