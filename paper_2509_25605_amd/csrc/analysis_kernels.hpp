@@ -184,8 +184,8 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
 }
 
 // One workgroup of kCompactBlock threads: entries[0] = entries of the narrow chunks (chunk_base >= 0),
-// entries[1] = entries of the framed chunks (chunk_base == -2), narrow_chunks[k - 1] = how many
-// narrow chunks are of class k.
+// entries[1] = entries of the framed chunks (chunk_base == -2), narrow_chunks[k - 1] /
+// narrow_chunks[kChunkClasses + k - 1] = how many narrow / framed chunks are of class k.
 __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nrows, int32_t num_chunks,
                                                                      int32_t chunk_rows,
                                                                      const int32_t *__restrict__ chunk_flag,
@@ -195,32 +195,34 @@ __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nro
                                                                      int32_t *__restrict__ narrow_chunks)
 {
     __shared__ unsigned long long s_entries[2];
-    __shared__ int32_t s_chunks[kChunkClasses];
+    __shared__ int32_t s_chunks[2 * kChunkClasses];
     if (threadIdx.x < 2) s_entries[threadIdx.x] = 0;
-    if (threadIdx.x < kChunkClasses) s_chunks[threadIdx.x] = 0;
+    if (threadIdx.x < 2 * kChunkClasses) s_chunks[threadIdx.x] = 0;
     __syncthreads();
     unsigned long long entries = 0, framed = 0;
-    int32_t chunks[kChunkClasses] = {0, 0, 0, 0};
+    int32_t chunks[2 * kChunkClasses] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
         const int32_t base = chunk_base[c];
         if (base == -1) continue;
         const int64_t first = c * chunk_rows;
         const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
         const unsigned long long len = (unsigned long long)(rowptr[last] - rowptr[first]);
-        if (base == -2) { framed += len; continue; }
-        entries += len;
         const int32_t cls = chunk_flag[c];
+        if (base == -2) framed += len; else entries += len;
 #pragma unroll
-        for (int k = 0; k < kChunkClasses; ++k) chunks[k] += (cls == k + 1);
+        for (int k = 0; k < kChunkClasses; ++k) {
+            chunks[k] += (cls == k + 1 && base >= 0);
+            chunks[kChunkClasses + k] += (cls == k + 1 && base == -2);
+        }
     }
     if (entries) atomicAdd(&s_entries[0], entries);
     if (framed) atomicAdd(&s_entries[1], framed);
 #pragma unroll
-    for (int k = 0; k < kChunkClasses; ++k)
+    for (int k = 0; k < 2 * kChunkClasses; ++k)
         if (chunks[k]) atomicAdd(&s_chunks[k], chunks[k]);
     __syncthreads();
     if (threadIdx.x < 2) entries_out[threadIdx.x] = s_entries[threadIdx.x];
-    if (threadIdx.x < kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
+    if (threadIdx.x < 2 * kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
 }
 
 // Frames of 2048 columns for the stream chunks that are not narrow (chunk_base == -1 on entry),

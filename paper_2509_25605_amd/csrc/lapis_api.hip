@@ -67,6 +67,8 @@ struct lapis_csr {
     int64_t narrow_entries = 0;          // entries in the chunks that could get a base
     int64_t framed_entries = 0;          // entries in the chunks that got a frame table instead
     bool class_all16[kStreamClasses] = {false, false, false, false};   // every chunk of the class has a base
+    bool class_allframed[kStreamClasses] = {false, false, false, false};   // every chunk of the class is framed
+    bool class_allcoded[kStreamClasses] = {false, false, false, false};    // every chunk is one or the other
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -320,7 +322,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     if (num_stream > 0) {
         struct NarrowCounts {
             unsigned long long entries[2];      // in narrow chunks, in framed chunks
-            int32_t chunks[kStreamClasses];
+            int32_t chunks[2 * kStreamClasses]; // narrow chunks per class, then framed chunks per class
         } h_counts;
         DeviceTemp narrow;
         if (int rc = narrow.alloc(sizeof(NarrowCounts))) return rc;
@@ -351,8 +353,12 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
                 (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
                 A->d_col16);
             LAPIS_HIP(hipGetLastError());
-            for (int cls = 1; cls <= kStreamClasses; ++cls)
-                A->class_all16[cls - 1] = h_counts.chunks[cls - 1] == A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
+            for (int cls = 1; cls <= kStreamClasses; ++cls) {
+                const int32_t size = A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
+                A->class_all16[cls - 1] = h_counts.chunks[cls - 1] == size;
+                A->class_allframed[cls - 1] = h_counts.chunks[kStreamClasses + cls - 1] == size;
+                A->class_allcoded[cls - 1] = h_counts.chunks[cls - 1] + h_counts.chunks[kStreamClasses + cls - 1] == size;
+            }
         } else {
             (void)hipFree(A->d_chunk_base);
             (void)hipFree(A->d_frame_table);
@@ -524,14 +530,15 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
     const uint32_t waves = (uint32_t)(count * (G / 2));
     const uint32_t padded = (waves + kXcds - 1) / kXcds * kXcds;
     const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
-    if (A->class_all16[cls - 1])
-        spmv_stream_kernel<T, G, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
-            A->d_col16, static_cast<const T *>(A->vals), x, y, a, b);
-    else
-        spmv_stream_kernel<T, G, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
-            (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base, A->d_frame_table,
-            A->d_col16, static_cast<const T *>(A->vals), x, y, a, b);
+#define LAPIS_STREAM_LAUNCH(RAW)                                                                             \
+    spmv_stream_kernel<T, G, true, RAW><<<dim3(padded), dim3(kWave), 0, stream>>>(                            \
+        (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base,        \
+        A->d_frame_table, A->d_col16, static_cast<const T *>(A->vals), x, y, a, b)
+    if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);
+    else if (A->class_allframed[cls - 1]) LAPIS_STREAM_LAUNCH(kColsFramed);
+    else if (A->class_allcoded[cls - 1]) LAPIS_STREAM_LAUNCH(kColsEither);
+    else LAPIS_STREAM_LAUNCH(kCols32);
+#undef LAPIS_STREAM_LAUNCH
 }
 
 // y (ncols values) = beta*y, then every entry of A adds alpha*vals[j]*x[row] into y[colidx[j]].

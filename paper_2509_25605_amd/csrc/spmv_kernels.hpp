@@ -207,7 +207,7 @@ struct StreamCols {
 // How a chunk's columns are stored: 32-bit colidx; 16-bit offsets from the chunk's smallest
 // column (chunk_base >= 0); or 16-bit codes (slot << 11) | (column & 2047) with a per-chunk table
 // of up to 32 frames of 2048 columns (chunk_base == kChunkFramed).
-constexpr int kCols32 = 0, kColsNarrow = 1, kColsFramed = 2;
+constexpr int kCols32 = 0, kColsNarrow = 1, kColsFramed = 2, kColsEither = 3;   // kColsEither: narrow or framed, per chunk
 constexpr int32_t kChunkFramed = -2;
 constexpr int kFrameShift = 11, kFrameSlots = 32;
 constexpr int32_t kFrameMask = (1 << kFrameShift) - 1;
@@ -385,9 +385,11 @@ __device__ __forceinline__ float fused_madd(float a, float b, float c) { return 
 // FMAs.  For the others, lanes with fewer than u0 + B entries repeat their last entry and discard
 // the product (no divergent control flow).
 // x is already advanced by the chunk's smallest column when the window holds 16-bit offsets.
-template <typename T, int B, int W, int G, typename IDX>
+// RAW == kColsFramed: the window holds raw frame codes, expanded here through the table `tab`;
+// RAW == kColsEither: offsets from cbase if cbase >= 0 (wave-uniform), else frame codes.
+template <typename T, int B, int W, int G, typename IDX, int RAW>
 __device__ __forceinline__ T stream_batch(const IDX *sc, const T *sv, int u0, int my_n, int last_u,
-                                          const T *__restrict__ x, T s)
+                                          const T *__restrict__ x, const int32_t *tab, int32_t cbase, T s)
 {
     static_assert(W >= 0 && W <= B, "W counts leading entries of the batch");
     int32_t cc[B];
@@ -397,6 +399,18 @@ __device__ __forceinline__ T stream_batch(const IDX *sc, const T *sv, int u0, in
         const int u = (t < W ? u0 + t : (u0 + t < last_u ? u0 + t : last_u)) * G;
         cc[t] = (int32_t)sc[u];
         vv[t] = sv[u];
+    }
+    if constexpr (RAW == kColsFramed) {
+#pragma unroll
+        for (int t = 0; t < B; ++t) cc[t] = framed_column(tab, (uint16_t)cc[t]);
+    } else if constexpr (RAW == kColsEither) {
+        if (cbase >= 0) {
+#pragma unroll
+            for (int t = 0; t < B; ++t) cc[t] += cbase;
+        } else {
+#pragma unroll
+            for (int t = 0; t < B; ++t) cc[t] = framed_column(tab, (uint16_t)cc[t]);
+        }
     }
 #pragma unroll
     for (int t = 0; t < B; ++t) xx[t] = x[cc[t]];
@@ -410,15 +424,17 @@ __device__ __forceinline__ T stream_batch(const IDX *sc, const T *sv, int u0, in
 
 // The batch of B with as many unconditional leading entries as the shortest share allows:
 // all B, all but the last two (shares in a wavefront usually differ by at most one), or none.
-template <typename T, int B, int G, typename IDX>
+template <typename T, int B, int G, typename IDX, int RAW>
 __device__ __forceinline__ T stream_batch_pick(const IDX *sc, const T *sv, int u0, int my_n, int last_u,
-                                               int shortest, const T *__restrict__ x, T s)
+                                               int shortest, const T *__restrict__ x, const int32_t *tab,
+                                               int32_t cbase, T s)
 {
-    if (shortest - u0 >= B) return stream_batch<T, B, B, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
+    if (shortest - u0 >= B) return stream_batch<T, B, B, G, IDX, RAW>(sc, sv, u0, my_n, last_u, x, tab, cbase, s);
     if constexpr (B > 2) {
-        if (shortest - u0 >= B - 2) return stream_batch<T, B, B - 2, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
+        if (shortest - u0 >= B - 2)
+            return stream_batch<T, B, B - 2, G, IDX, RAW>(sc, sv, u0, my_n, last_u, x, tab, cbase, s);
     }
-    return stream_batch<T, B, 0, G, IDX>(sc, sv, u0, my_n, last_u, x, s);
+    return stream_batch<T, B, 0, G, IDX, RAW>(sc, sv, u0, my_n, last_u, x, tab, cbase, s);
 }
 
 // One wavefront (= one workgroup) per 64/G consecutive rows of a stream chunk of the class with
@@ -426,9 +442,12 @@ __device__ __forceinline__ T stream_batch_pick(const IDX *sc, const T *sv, int u
 // stream_chunks lists the chunks of that class; nullptr means every chunk of the matrix.
 // colidx and vals must be 16-byte aligned.  nnz4 = nnz rounded down to a multiple of 4:
 // 16-byte loads never reach past it, the last nnz % 4 entries of the matrix are fetched one by one.
-// ALL16: every chunk of this launch has 16-bit offsets (chunk_base >= 0); the LDS window then
-// keeps 2-byte offsets (10 instead of 12 KB per wavefront with doubles: more wavefronts per CU).
-template <typename T, int G, bool XCD_REMAP, bool ALL16 = false, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
+// RAW == kColsNarrow: every chunk of this launch is narrow (chunk_base >= 0); RAW == kColsFramed:
+// every chunk is framed.  The LDS window then keeps the 2-byte offsets / codes as they are (10
+// instead of 12 KB per wavefront with doubles: more wavefronts per CU) and they are expanded
+// when x is gathered.  RAW == kColsEither: every chunk is one or the other.  RAW == kCols32: any
+// mix, 32-bit columns in the window.
+template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
@@ -440,10 +459,10 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     constexpr int kWavesPerChunk = kStreamRows / kRowsPerWave;
     static_assert(G >= 2 && G <= 16 && kWavesPerChunk * kRowsPerWave == kStreamRows, "G must be 2, 4, 8 or 16");
     static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
-    typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
+    typedef typename std::conditional<RAW != kCols32, uint16_t, int32_t>::type idx_t;
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
-    __shared__ int32_t s_tab[ALL16 ? 1 : kFrameSlots];
+    __shared__ int32_t s_tab[RAW == kColsNarrow ? 1 : kFrameSlots];
 
     const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_waves) : blockIdx.x;
     if (id >= num_waves) return;
@@ -452,7 +471,7 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     const uint32_t list_pos = id / kWavesPerChunk;
     const int64_t chunk = stream_chunks ? stream_chunks[list_pos] : (int64_t)list_pos;
     const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
-    if constexpr (!ALL16) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
+    if constexpr (RAW != kColsNarrow) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
     const int64_t row = chunk * kStreamRows + (id % kWavesPerChunk) * kRowsPerWave + lane / G;
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
@@ -477,24 +496,24 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
         const int last_u = my_n > 0 ? my_n - 1 : 0;
         const idx_t *sc = s_col + first;
         const T *sv = s_val + first;
-        const T *xb = ALL16 ? x + cbase : x;
+        const T *xb = RAW == kColsNarrow ? x + cbase : x;
         // batches of UNR entries per lane; the last batch is cut to the longest share in the
         // wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane, not 16
         int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
         const int shortest = kStreamWindow - wave_max_nonneg(kStreamWindow - (my_n > 0 ? my_n : 0));   // uniform
         int u0 = 0;
 #pragma unroll 1
-        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch_pick<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s);
+        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch_pick<T, UNR, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s);
         switch ((rem + 1) / 2) {
         case 0: break;
-        case 1: s = stream_batch_pick<T, 2, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 2: s = stream_batch_pick<T, 4, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 3: s = stream_batch_pick<T, 6, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 4: s = stream_batch_pick<T, 8, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 5: s = stream_batch_pick<T, 10, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 6: s = stream_batch_pick<T, 12, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        case 7: s = stream_batch_pick<T, 14, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
-        default: s = stream_batch_pick<T, UNR, G, idx_t>(sc, sv, u0, my_n, last_u, shortest, xb, s); break;
+        case 1: s = stream_batch_pick<T, 2, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 2: s = stream_batch_pick<T, 4, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 3: s = stream_batch_pick<T, 6, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 4: s = stream_batch_pick<T, 8, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 5: s = stream_batch_pick<T, 10, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 6: s = stream_batch_pick<T, 12, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        case 7: s = stream_batch_pick<T, 14, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        default: s = stream_batch_pick<T, UNR, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
