@@ -69,6 +69,11 @@ extern "C" {
  * tiles of LAPIS_TILE_NNZ entries; LAPIS_LONG_THRESHOLD >= LAPIS_TILE_NNZ, so a
  * tile touches at most two rows.
  *
+ * Demotion: when x is far larger than a level-2 cache (nb >= 2 in level 3 below), a chunk
+ * that would stream but whose columns are neither narrow nor framed (see
+ * lapis_csr_copy_index16) and that has a row of more than LAPIS_WAVE entries does not stream:
+ * its rows are binned like those of any class-0 chunk.
+ *
  * Level 3, column split (lapis_spmv only), for the rows of bins 8 and 9 when x
  * is far larger than a level-2 cache.  With e the size of a value in bytes:
  * nb = min(LAPIS_SPLIT_MAX_BLOCKS, ceil(ncols / (LAPIS_SPLIT_BLOCK_BYTES / e)))

@@ -61,11 +61,13 @@ def _load():
             getattr(lib, name).restype = None
         lib.oracle_partition_num_bins.argtypes = [i64]
         lib.oracle_partition_num_bins.restype = ctypes.c_int
-        lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, p, p]
+        lib.oracle_partition_stream_chunks.argtypes = [i64, p, i64, i64, p, p, p]
+        lib.oracle_demoted_chunks.argtypes = [i64, p, i64, i64, i64, p, p]
+        lib.oracle_demoted_chunks.restype = None
         lib.oracle_partition_stream_chunks.restype = i64
         lib.oracle_index16.argtypes = [i64, p, p, i64, i64, p, p, p, p, p]
         lib.oracle_index16.restype = None
-        lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p]
+        lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p, p]
         lib.oracle_partition_rows.restype = None
         lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
         lib.oracle_partition_tiles.restype = None
@@ -155,19 +157,38 @@ def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):
     return Y, absAX
 
 
+def demoted_chunks(rowptr, colidx, ncols, itemsize, wave=WAVE, stream_rows=STREAM_ROWS,
+                   stream_min_nnz=STREAM_MIN_NNZ):
+    """uint8 per chunk: 1 for the chunks that would stream but are demoted to the bins (x far
+    larger than an L2, columns neither narrow nor framed, a row above `wave` entries)."""
+    n = rowptr.size - 1
+    nchunks = (n + stream_rows - 1) // stream_rows
+    out = np.zeros(nchunks, dtype=np.uint8)
+    if split_geometry(ncols, itemsize)[0] == 0 or nchunks == 0:
+        return out
+    base = index16(rowptr, colidx, stream_rows, stream_min_nnz)["chunk_base"]
+    _load().oracle_demoted_chunks(n, _p(rowptr), stream_rows, stream_min_nnz, wave, _p(base), _p(out))
+    return out
+
+
 def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NNZ,
-              stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_NNZ):
+              stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_NNZ, colidx=None, ncols=None, itemsize=None):
     """Reference row partition.  Returns a dict with stream_chunks[] (class by class),
     stream_offset[5], bin_offset[num_bins+1],
-    row_perm[rows outside stream chunks], long_off[m+1], tile_row[T+1], tile_nz[T+1]."""
+    row_perm[rows outside stream chunks], long_off[m+1], tile_row[T+1], tile_nz[T+1].
+    With colidx, ncols and itemsize the chunks of demoted_chunks() do not stream (the library
+    always knows the columns; without them the partition is the one of the row lengths alone)."""
     assert rowptr.dtype == np.int32 and rowptr.flags.c_contiguous
     lib = _load()
     n = rowptr.size - 1
     nb = lib.oracle_partition_num_bins(wave)
     nchunks = (n + stream_rows - 1) // stream_rows
+    demoted = None
+    if colidx is not None:
+        demoted = demoted_chunks(rowptr, colidx, ncols, itemsize, wave, stream_rows, stream_min_nnz)
     stream_chunks = np.empty(nchunks, dtype=np.int32)
     stream_offset = np.zeros(5, dtype=np.int32)
-    ns = lib.oracle_partition_stream_chunks(n, _p(rowptr), stream_rows, stream_min_nnz,
+    ns = lib.oracle_partition_stream_chunks(n, _p(rowptr), stream_rows, stream_min_nnz, _p(demoted),
                                             _p(stream_chunks), _p(stream_offset))
     stream_chunks = stream_chunks[:ns].copy()
     bin_offset = np.zeros(nb + 1, dtype=np.int32)
@@ -175,7 +196,7 @@ def partition(rowptr, wave=WAVE, long_threshold=LONG_THRESHOLD, tile_nnz=TILE_NN
     m = ctypes.c_int64(0)
     T = ctypes.c_int64(0)
     lib.oracle_partition_rows(n, _p(rowptr), wave, long_threshold, tile_nnz, stream_rows,
-                              stream_min_nnz, _p(bin_offset), _p(row_perm),
+                              stream_min_nnz, _p(demoted), _p(bin_offset), _p(row_perm),
                               ctypes.addressof(m), ctypes.addressof(T))
     m, T = m.value, T.value
     row_perm = row_perm[:bin_offset[nb]].copy()
@@ -229,7 +250,7 @@ def split_partition(rowptr, colidx, ncols, itemsize, part=None, wave=WAVE, long_
     ('num_split_rows' of them, in row_perm order) are cut at the coarse blocks into virtual rows,
     which get bins and tiles of their own.  Returns a dict; 'num_blocks' == 0 means the split is
     off (x small, no such rows, or one of them with unsorted columns)."""
-    part = part or partition(rowptr, wave, long_threshold, tile_nnz)
+    part = part or partition(rowptr, wave, long_threshold, tile_nnz, colidx=colidx, ncols=ncols, itemsize=itemsize)
     nb_bins = part["num_bins"]
     off = part["bin_offset"]
     rows = np.ascontiguousarray(part["row_perm"][off[nb_bins - 2]:off[nb_bins]])

@@ -226,7 +226,7 @@ int oracle_partition_num_bins(int64_t wave)
     return bin_of_length(wave + 1, wave, wave + 1) + 2;
 }
 
-static int chunk_class(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
+static int chunk_class_plain(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
                        int64_t chunk_min_nnz)
 {
     int64_t first = c * chunk_rows;
@@ -245,18 +245,27 @@ static int chunk_class(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t 
     return by_length;
 }
 
+/* The class a chunk finally has: a chunk listed in `demoted` (may be NULL: none) is not a stream
+ * chunk whatever its rows look like (see oracle_demoted_chunks). */
+static int chunk_class(int64_t c, int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
+                       int64_t chunk_min_nnz, const uint8_t *demoted)
+{
+    if (demoted && demoted[c]) return 0;
+    return chunk_class_plain(c, nrows, rowptr, chunk_rows, chunk_min_nnz);
+}
+
 /* Pass 0: stream_chunks[] (caller provides ceil(nrows/chunk_rows) slots) and
  * stream_offset[5]; returns the number of stream chunks. */
 int64_t oracle_partition_stream_chunks(int64_t nrows, const int32_t *rowptr, int64_t chunk_rows,
-                                       int64_t chunk_min_nnz, int32_t *stream_chunks,
-                                       int32_t *stream_offset)
+                                       int64_t chunk_min_nnz, const uint8_t *demoted,
+                                       int32_t *stream_chunks, int32_t *stream_offset)
 {
     int64_t count = 0;
     int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
     for (int k = 1; k <= 4; ++k) {
         stream_offset[k - 1] = (int32_t)count;
         for (int64_t c = 0; c < nchunks; ++c)
-            if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == k)
+            if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz, demoted) == k)
                 stream_chunks[count++] = (int32_t)c;
     }
     stream_offset[4] = (int32_t)count;
@@ -291,7 +300,7 @@ void oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
     for (int64_t c = 0; c < nchunks; ++c) {
         chunk_base[c] = -1;
         for (int k = 0; k < 32; ++k) frame_table[32 * c + k] = 0;
-        if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == 0) continue;
+        if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz, NULL) == 0) continue;
         int64_t last = (c + 1) * chunk_rows < nrows ? (c + 1) * chunk_rows : nrows;
         int64_t b = rowptr[c * chunk_rows], e = rowptr[last];
         int32_t lo = colidx[b], hi = colidx[b];
@@ -324,6 +333,24 @@ void oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
     }
 }
 
+/* When x is far larger than a level-2 cache (the caller checks that: the column split's own
+ * condition), a chunk that would stream although its columns are neither narrow nor framed
+ * (chunk_base[c] == -1 from oracle_index16) and that has a row of more than `wave` entries is
+ * demoted: its rows go to the bins, where the column split orders their gathers.
+ * demoted[c] = 1 for those chunks, 0 otherwise. */
+void oracle_demoted_chunks(int64_t nrows, const int32_t *rowptr, int64_t chunk_rows, int64_t chunk_min_nnz,
+                           int64_t wave, const int32_t *chunk_base, uint8_t *demoted)
+{
+    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
+    for (int64_t c = 0; c < nchunks; ++c) {
+        demoted[c] = 0;
+        if (chunk_class_plain(c, nrows, rowptr, chunk_rows, chunk_min_nnz) == 0 || chunk_base[c] != -1) continue;
+        int64_t last = (c + 1) * chunk_rows < nrows ? (c + 1) * chunk_rows : nrows;
+        for (int64_t i = c * chunk_rows; i < last; ++i)
+            if (rowptr[i + 1] - rowptr[i] > wave) demoted[c] = 1;
+    }
+}
+
 /* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and
  * row_perm[] (ids of the rows outside stream chunks, grouped by bin, ascending
  * inside each bin; bin_offset[num_bins] of them).  Returns through *num_long
@@ -331,13 +358,13 @@ void oracle_index16(int64_t nrows, const int32_t *rowptr, const int32_t *colidx,
  * tiles T = ceil(total long nnz / tile_nnz). */
 void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
                            int64_t long_threshold, int64_t tile_nnz, int64_t chunk_rows,
-                           int64_t chunk_min_nnz, int32_t *bin_offset, int32_t *row_perm,
+                           int64_t chunk_min_nnz, const uint8_t *demoted, int32_t *bin_offset, int32_t *row_perm,
                            int64_t *num_long, int64_t *num_tiles)
 {
     int nb = oracle_partition_num_bins(wave);
     for (int b = 0; b <= nb; ++b) bin_offset[b] = 0;
     for (int64_t i = 0; i < nrows; ++i) {
-        if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz)) continue;
+        if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz, demoted)) continue;
         bin_offset[bin_of_length(rowptr[i + 1] - rowptr[i], wave, long_threshold) + 1] += 1;
     }
     for (int b = 0; b < nb; ++b) bin_offset[b + 1] += bin_offset[b];
@@ -346,7 +373,7 @@ void oracle_partition_rows(int64_t nrows, const int32_t *rowptr, int64_t wave,
         int64_t at = bin_offset[b];
         for (int64_t i = 0; i < nrows; ++i) {
             int64_t L = rowptr[i + 1] - rowptr[i];
-            if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz)) continue;
+            if (chunk_class(i / chunk_rows, nrows, rowptr, chunk_rows, chunk_min_nnz, demoted)) continue;
             if (bin_of_length(L, wave, long_threshold) != b) continue;
             row_perm[at++] = (int32_t)i;
             if (b == nb - 1) long_nnz += L;

@@ -144,6 +144,26 @@ __global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t nu
     }
 }
 
+// flag[c] = 0 for every stream chunk that is neither narrow nor framed (chunk_base == -1) and has a
+// row of more than `wave` entries: its rows go to the bins instead.
+__global__ __launch_bounds__(kBlock) void chunk_demote_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                              int32_t wave, const int32_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ chunk_base,
+                                                              int32_t *__restrict__ flag)
+{
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c >= num_chunks || flag[c] == 0 || chunk_base[c] != -1) return;
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    int32_t prev = rowptr[first], longest = 0;
+    for (int64_t i = first + 1; i <= last; ++i) {
+        const int32_t cur = rowptr[i];
+        longest = (cur - prev > longest) ? cur - prev : longest;
+        prev = cur;
+    }
+    if (longest > wave) flag[c] = 0;
+}
+
 // Level 1b, one wavefront per chunk: chunk_base[c] = smallest column of stream chunk c if its
 // columns span at most 65535, else -1 (also for chunks that are not stream chunks);
 // The totals are taken by narrow_count_kernel (one atomic per chunk on one address would

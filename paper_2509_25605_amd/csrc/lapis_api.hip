@@ -303,9 +303,41 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     if (int rc = chunk_flag.alloc(sizeof(int32_t) * (size_t)num_chunks)) return rc;
     if (int rc = device_alloc(&A->d_stream_chunks, sizeof(int32_t) * (size_t)num_chunks)) return rc;
     int32_t num_stream = 0;
+    bool index16 = false;
+    struct NarrowCounts {
+        unsigned long long entries[2];      // in narrow chunks, in framed chunks
+        int32_t chunks[2 * kStreamClasses]; // narrow chunks per class, then framed chunks per class
+    } h_counts = {};
     if (n > 0) {
         chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, chunk_flag.as<int32_t>());
+
+        // level 1b: 16-bit column codes for the stream chunks that are narrow or framed, kept only if
+        // those chunks hold at least half of the entries
+        DeviceTemp narrow;
+        if (int rc = narrow.alloc(sizeof(NarrowCounts))) return rc;
+        NarrowCounts *d_counts = narrow.as<NarrowCounts>();
+        if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
+        if (int rc = device_alloc(&A->d_frame_table, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots)) return rc;
+        LAPIS_HIP(hipMemsetAsync(A->d_frame_table, 0, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots, stream));
+        const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
+        chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
+            A->d_chunk_base);
+        chunk_frames_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
+            A->d_chunk_base, A->d_frame_table);
+        // when x is far larger than an L2 (the column split's own condition), a chunk with rows above
+        // 64 entries whose columns are neither narrow nor framed is better off in the bins, where
+        // the column split orders its gathers: it stops being a stream chunk
+        int64_t nb0 = 0, W0 = 0;
+        split_geometry(A->ncols, esize, &nb0, &W0);
+        if (nb0 > 0)
+            chunk_demote_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+                (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, LAPIS_WAVE, A->rowptr, A->d_chunk_base, chunk_flag.as<int32_t>());
+        narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
+            d_counts->entries, d_counts->chunks);
         static_assert(kChunkClasses == kStreamClasses, "one list per stream class");
         DeviceTemp offsets;
         if (int rc = offsets.alloc(sizeof(int32_t) * (kStreamClasses + 1))) return rc;
@@ -314,38 +346,12 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         LAPIS_HIP(hipGetLastError());
         if (int rc = read_back(A->h_stream_offset, offsets.as<int32_t>(), sizeof(int32_t) * (kStreamClasses + 1), stream)) return rc;
         num_stream = A->h_stream_offset[kStreamClasses];
-    }
-    A->num_stream = num_stream;
-
-    // level 1b: 16-bit column offsets for the stream chunks with a narrow column span, kept only
-    // if those chunks hold at least half of the entries
-    if (num_stream > 0) {
-        struct NarrowCounts {
-            unsigned long long entries[2];      // in narrow chunks, in framed chunks
-            int32_t chunks[2 * kStreamClasses]; // narrow chunks per class, then framed chunks per class
-        } h_counts;
-        DeviceTemp narrow;
-        if (int rc = narrow.alloc(sizeof(NarrowCounts))) return rc;
-        NarrowCounts *d_counts = narrow.as<NarrowCounts>();
-        if (int rc = device_alloc(&A->d_chunk_base, sizeof(int32_t) * (size_t)num_chunks)) return rc;
-        const uint32_t wblocks = (uint32_t)((num_chunks + kWavesPerBlock - 1) / kWavesPerBlock);
-        if (int rc = device_alloc(&A->d_frame_table, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots)) return rc;
-        LAPIS_HIP(hipMemsetAsync(A->d_frame_table, 0, sizeof(int32_t) * (size_t)num_chunks * kFrameSlots, stream));
-        chunk_span_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
-            A->d_chunk_base);
-        chunk_frames_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
-            A->d_chunk_base, A->d_frame_table);
-        narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
-            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
-            d_counts->entries, d_counts->chunks);
-        LAPIS_HIP(hipGetLastError());
         if (int rc = read_back(&h_counts, narrow.p, sizeof(h_counts), stream)) return rc;
-        const unsigned long long h_narrow = h_counts.entries[0] + h_counts.entries[1];
+        const unsigned long long coded = h_counts.entries[0] + h_counts.entries[1];
         A->narrow_entries = (int64_t)h_counts.entries[0];
         A->framed_entries = (int64_t)h_counts.entries[1];
-        if (h_narrow > 0 && 2 * h_narrow >= (unsigned long long)A->nnz) {
+        index16 = coded > 0 && 2 * coded >= (unsigned long long)A->nnz;
+        if (index16) {
             const size_t len = ((size_t)A->nnz + 7) / 8 * 8 + 8;      // 16-byte loads may run past nnz
             if (int rc = device_alloc(&A->d_col16, sizeof(uint16_t) * len)) return rc;
             LAPIS_HIP(hipMemsetAsync(A->d_col16, 0, sizeof(uint16_t) * len, stream));
@@ -359,12 +365,14 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
                 A->class_allframed[cls - 1] = h_counts.chunks[kStreamClasses + cls - 1] == size;
                 A->class_allcoded[cls - 1] = h_counts.chunks[cls - 1] + h_counts.chunks[kStreamClasses + cls - 1] == size;
             }
-        } else {
-            (void)hipFree(A->d_chunk_base);
-            (void)hipFree(A->d_frame_table);
-            A->d_chunk_base = nullptr;
-            A->d_frame_table = nullptr;
         }
+    }
+    A->num_stream = num_stream;
+    if (!index16) {
+        (void)hipFree(A->d_chunk_base);
+        (void)hipFree(A->d_frame_table);
+        A->d_chunk_base = nullptr;
+        A->d_frame_table = nullptr;
     }
 
     // level 2: bins over the remaining rows

@@ -39,13 +39,13 @@ def check_index16(dev):
 
 
 def check_partition(dev, rowptr):
-    ref = oracle.partition(rowptr)
+    assert rowptr is dev.h_rowptr or np.array_equal(rowptr, dev.h_rowptr)
+    ref = oracle.partition(rowptr, colidx=dev.h_colidx, ncols=dev.ncols, itemsize=np.dtype(dev.np_dtype).itemsize)
     got = dev.partition()
     for key in ("stream_chunks", "stream_offset", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
         assert got[key].dtype == np.int32
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
-    if rowptr is dev.h_rowptr or np.array_equal(rowptr, dev.h_rowptr):
-        check_index16(dev)
+    check_index16(dev)
 
 
 def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):

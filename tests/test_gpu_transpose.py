@@ -137,7 +137,7 @@ def check_transposed_handle(rowptr, colidx, vals, nrows, ncols, x=None, what="")
         got = t.arrays()
         for name, g, r in zip(("rowptr", "colidx", "vals"), got, ref):
             assert g.dtype == r.dtype and np.array_equal(g, r), f"{what}: transposed {name} differs"
-        part, pref = t.partition(), oracle.partition(ref[0])
+        part, pref = t.partition(), oracle.partition(ref[0], colidx=ref[1], ncols=nrows, itemsize=vals.itemsize)
         for key in ("stream_chunks", "stream_offset", "bin_offset", "row_perm", "long_off", "tile_row", "tile_nz"):
             assert np.array_equal(part[key], pref[key]), f"{what}: partition field {key} of the transposed handle differs"
         if x is not None:

@@ -394,3 +394,62 @@ def test_index16_off_without_stream_chunks_and_below_half():
     got = oracle.index16(rowptr, colidx)
     assert got["chunk_base"].tolist() == [0, -1] and got["narrow_entries"] == 256 and not got["enabled"]
     assert got["framed_entries"] == 0
+
+
+# ---- demotion of stream chunks whose gathers would have no locality ----------
+def test_demoted_chunks_rule():
+    """Four chunks of 32 rows over 2^20 double columns (x = 8 MiB: the split's condition holds):
+    0: rows of 16 scattered columns (wide, but no row above 64)   -> streams
+    1: one row of 100 scattered columns, 31 rows of 8              -> demoted
+    2: one row of 100 consecutive columns (narrow), 31 rows of 8   -> streams
+    3: one row of 100 columns in 4 far-apart clusters (framed)     -> streams"""
+    ncols = 1 << 20
+    rng = np.random.default_rng(3)
+    rows = []
+    for c in range(4):
+        for r in range(32):
+            if c == 0:
+                rows.append(np.sort(rng.choice(ncols, 16, replace=False)))
+            elif r == 0 and c == 1:
+                rows.append(np.sort(rng.choice(ncols, 100, replace=False)))
+            elif r == 0 and c == 2:
+                rows.append(5000 + np.arange(100))
+            elif r == 0 and c == 3:
+                rows.append(np.sort(np.concatenate([k * 200000 + np.arange(25) for k in range(4)])))
+            else:
+                rows.append(5000 + c + np.arange(8))
+    rowptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int32)
+    colidx = np.concatenate(rows).astype(np.int32)
+    plain = oracle.partition(rowptr)
+    assert plain["stream_chunks"].size == 4
+    base = oracle.index16(rowptr, colidx)["chunk_base"]
+    assert base[0] == -1 and base[1] == -1 and base[2] >= 0 and base[3] == -2
+    dem = oracle.demoted_chunks(rowptr, colidx, ncols, 8)
+    assert dem.tolist() == [0, 1, 0, 0]
+    part = oracle.partition(rowptr, colidx=colidx, ncols=ncols, itemsize=8)
+    assert sorted(part["stream_chunks"].tolist()) == [0, 2, 3]
+    assert np.array_equal(np.sort(part["row_perm"]), np.arange(32, 64))       # the demoted chunk's rows are binned
+    assert part["bin_offset"][8] == 31 and part["bin_offset"][9] == 32        # 31 rows of 8 (bin 4), one of 100 (bin 8)
+    # x of 2 MiB or less: nothing is demoted
+    assert oracle.demoted_chunks(rowptr, np.minimum(colidx, (1 << 18) - 1), 1 << 18, 8).sum() == 0
+    # the codes are those of the undemoted view: a demoted chunk had none anyway
+    again = oracle.index16(rowptr, colidx)
+    assert np.array_equal(again["chunk_base"], base)
+
+
+def test_demotion_on_power_law_rows():
+    w = gen.workload(4, {"n": 1 << 20, "cap": 100000})
+    plain = oracle.partition(w.rowptr)
+    part = oracle.partition(w.rowptr, colidx=w.colidx, ncols=w.ncols, itemsize=4)
+    dem = oracle.demoted_chunks(w.rowptr, w.colidx, w.ncols, 4)
+    assert dem.sum() > 0
+    assert np.array_equal(np.setdiff1d(plain["stream_chunks"], part["stream_chunks"]), np.flatnonzero(dem))
+    L = np.diff(w.rowptr)
+    for c in np.flatnonzero(dem)[:50]:
+        assert L[c * 32:(c + 1) * 32].max() > 64
+    for c in part["stream_chunks"][:2000]:
+        cols = w.colidx[w.rowptr[c * 32]:w.rowptr[min((c + 1) * 32, w.nrows)]]
+        coded = int(cols.max()) - int(cols.min()) <= 65535 or np.unique(cols >> 11).size <= 32
+        assert coded or L[c * 32:(c + 1) * 32].max() <= 64
+    assert part["bin_offset"][-1] == plain["bin_offset"][-1] + sum(
+        min(32, w.nrows - c * 32) for c in np.flatnonzero(dem))
