@@ -40,7 +40,7 @@ extern "C" {
 #define LAPIS_F64 1
 
 /* ---- row partition constants ---------------------------------------------
- * The analysis pass has two levels.
+ * The levels of the analysis pass.
  *
  * Level 1, stream chunks.  Rows are taken in chunks of LAPIS_STREAM_ROWS
  * consecutive rows (chunk c = rows c*LAPIS_STREAM_ROWS ...).  With M the longest
