@@ -28,7 +28,7 @@ MEASURED_TRAFFIC_BYTES = {
     "stencil27_128x128x128_f64": 605.55e6,
     "stencil27_128x128x128_f64_spmm_k16": 1134.16e6,
     "table3_Elasticity3D_60_n648000_f64": 525.03e6,
-    "zipf1.8_cap200000_n8388608_f32": 10488.35e6,
+    "zipf1.8_cap200000_n8388608_f32": 9123.35e6,
 }
 DOMINANT_KERNEL = {
     "stencil27_128x128x128_f64": "spmv_stream_kernel<double, 2, true, true>",
