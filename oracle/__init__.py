@@ -30,6 +30,9 @@ SPLIT_BLOCK_BYTES = 1 << 21   # target size of one column block of x
 SPLIT_MAX_BLOCKS = 32
 HUGE_ROW = 16384            # rows with more entries are cut at LDS-sized column blocks
 LDS_BLOCK_BYTES = 65536     # bytes of x one such block holds
+PATTERN_MAX_ROW = 128        # longest row a patterned chunk may have
+PATTERN_SLOTS = 8            # distinct row patterns per chunk at most
+PATTERN_TABLE = 512          # diagonals in a chunk's pattern table at most
 
 
 def build(force: bool = False) -> str:
@@ -67,6 +70,8 @@ def _load():
         lib.oracle_partition_stream_chunks.restype = i64
         lib.oracle_index16.argtypes = [i64, p, p, i64, i64, p, p, p, p, p]
         lib.oracle_index16.restype = None
+        lib.oracle_row_patterns.argtypes = [i64, p, p, i64, i64, p, i64, i64, i64, p, p, p, p]
+        lib.oracle_row_patterns.restype = None
         lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p, p]
         lib.oracle_partition_rows.restype = None
         lib.oracle_partition_tiles.argtypes = [p, i64, p, i64, i64, p, p, p]
@@ -230,6 +235,34 @@ def index16(rowptr, colidx, stream_rows=STREAM_ROWS, stream_min_nnz=STREAM_MIN_N
     return {"enabled": narrow + framed > 0 and 2 * (narrow + framed) >= colidx.size,
             "narrow_entries": narrow, "framed_entries": framed,
             "chunk_base": chunk_base, "frame_table": frame_table, "col16": col16}
+
+
+def row_patterns(rowptr, colidx, ncols=None, itemsize=None, wave=WAVE, stream_rows=STREAM_ROWS,
+                 stream_min_nnz=STREAM_MIN_NNZ, max_row=PATTERN_MAX_ROW, max_patterns=PATTERN_SLOTS,
+                 max_table=PATTERN_TABLE):
+    """Row patterns of the stream chunks: dict(enabled, entries, pat_off[num_chunks + 1],
+    row_pat[nrows] (uint16), pool[pat_off[-1]]): row i of a patterned chunk c has the columns
+    i + pool[pat_off[c] + row_pat[i] + k].  With ncols and itemsize the demoted chunks are
+    left out, as in partition().  enabled when the patterned chunks hold at least half of
+    the entries."""
+    assert rowptr.dtype == np.int32 and colidx.dtype == np.int32
+    assert max_table <= 4096 and max_patterns <= 64
+    n = rowptr.size - 1
+    nchunks = (n + stream_rows - 1) // stream_rows
+    demoted = None
+    if ncols is not None:
+        demoted = demoted_chunks(rowptr, colidx, ncols, itemsize, wave, stream_rows, stream_min_nnz)
+    pat_off = np.zeros(nchunks + 1, dtype=np.int32)
+    row_pat = np.zeros(n, dtype=np.uint16)
+    entries = ctypes.c_int64(0)
+    args = (n, _p(rowptr), _p(colidx), stream_rows, stream_min_nnz, _p(demoted), max_row, max_patterns,
+            max_table, _p(pat_off), _p(row_pat))
+    _load().oracle_row_patterns(*args, None, ctypes.addressof(entries))
+    pool = np.zeros(int(pat_off[-1]), dtype=np.int32)
+    _load().oracle_row_patterns(*args, _p(pool), ctypes.addressof(entries))
+    e = int(entries.value)
+    return {"enabled": e > 0 and 2 * e >= colidx.size, "entries": e, "pat_off": pat_off,
+            "row_pat": row_pat, "pool": pool}
 
 
 def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):

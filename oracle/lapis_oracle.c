@@ -351,6 +351,70 @@ void oracle_demoted_chunks(int64_t nrows, const int32_t *rowptr, int64_t chunk_r
     }
 }
 
+/* Level 1c: row patterns of the stream chunks (final class >= 1).
+ * The pattern of a non-empty row i is the list of its diagonals colidx[j] - i in stored order.
+ * Going through the rows of a chunk in ascending order, every pattern not seen before in the
+ * chunk is appended to the chunk's table; row_pat[i] = where the pattern of row i starts in
+ * that table (0 for empty rows).  A chunk is "patterned" when no row has more than max_row
+ * entries, at most max_patterns patterns were needed, the table has at most max_table
+ * diagonals and twice the table length does not exceed the chunk's entry count; otherwise its
+ * table is empty and row_pat is 0 for its rows.
+ * pat_off[0 .. nchunks] = exclusive scan of the table lengths (pat_off[c+1] == pat_off[c] for
+ * chunks without patterns); pool (may be NULL to get the sizes only) receives the tables back
+ * to back.  *entries = number of matrix entries in patterned chunks.
+ * Reconstruction: colidx[rowptr[i] + k] == i + pool[pat_off[c] + row_pat[i] + k]. */
+void oracle_row_patterns(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, int64_t chunk_rows,
+                         int64_t chunk_min_nnz, const uint8_t *demoted, int64_t max_row, int64_t max_patterns,
+                         int64_t max_table, int32_t *pat_off, uint16_t *row_pat, int32_t *pool,
+                         int64_t *entries)
+{
+    int64_t nchunks = (nrows + chunk_rows - 1) / chunk_rows;
+    int32_t table[4096];
+    int64_t start[64], length[64];
+    *entries = 0;
+    pat_off[0] = 0;
+    for (int64_t i = 0; i < nrows; ++i) row_pat[i] = 0;
+    for (int64_t c = 0; c < nchunks; ++c) {
+        pat_off[c + 1] = pat_off[c];
+        if (chunk_class(c, nrows, rowptr, chunk_rows, chunk_min_nnz, demoted) == 0) continue;
+        int64_t first = c * chunk_rows;
+        int64_t last = first + chunk_rows < nrows ? first + chunk_rows : nrows;
+        int64_t P = 0, L = 0;
+        int ok = 1;
+        for (int64_t i = first; i < last && ok; ++i) {
+            int64_t b = rowptr[i], len = rowptr[i + 1] - b;
+            if (len == 0) continue;
+            if (len > max_row) { ok = 0; break; }
+            int64_t found = -1;
+            for (int64_t p = 0; p < P && found < 0; ++p) {
+                if (length[p] != len) continue;
+                int same = 1;
+                for (int64_t k = 0; k < len; ++k)
+                    if (table[start[p] + k] != colidx[b + k] - (int32_t)i) same = 0;
+                if (same) found = p;
+            }
+            if (found < 0) {
+                if (P == max_patterns || L + len > max_table) { ok = 0; break; }
+                start[P] = L;
+                length[P] = len;
+                for (int64_t k = 0; k < len; ++k) table[L + k] = colidx[b + k] - (int32_t)i;
+                found = P++;
+                L += len;
+            }
+            row_pat[i] = (uint16_t)start[found];
+        }
+        int64_t chunk_entries = rowptr[last] - rowptr[first];
+        if (!ok || 2 * L > chunk_entries) {
+            for (int64_t i = first; i < last; ++i) row_pat[i] = 0;
+            continue;
+        }
+        if (pool)
+            for (int64_t t = 0; t < L; ++t) pool[pat_off[c] + t] = table[t];
+        pat_off[c + 1] = pat_off[c] + (int32_t)L;
+        *entries += chunk_entries;
+    }
+}
+
 /* Pass 1: bin_offset[num_bins+1] (exclusive scan of per-bin row counts) and
  * row_perm[] (ids of the rows outside stream chunks, grouped by bin, ascending
  * inside each bin; bin_offset[num_bins] of them).  Returns through *num_long

@@ -453,3 +453,148 @@ def test_demotion_on_power_law_rows():
         assert coded or L[c * 32:(c + 1) * 32].max() <= 64
     assert part["bin_offset"][-1] == plain["bin_offset"][-1] + sum(
         min(32, w.nrows - c * 32) for c in np.flatnonzero(dem))
+
+
+# ---- level 1c: row patterns ---------------------------------------------------
+def _csr_from_rows(rows):
+    rowptr = np.zeros(len(rows) + 1, dtype=np.int32)
+    np.cumsum([len(r) for r in rows], out=rowptr[1:])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    return rowptr, colidx
+
+
+def _banded(n, half):
+    return [[j for j in range(i - half, i + half + 1) if 0 <= j < n] for i in range(n)]
+
+
+def _columns_from_patterns(rowptr, got):
+    """Columns back from the patterns (-1 where the chunk has none): row + pool[pat_off + row_pat + k]."""
+    n = rowptr.size - 1
+    L = np.diff(rowptr)
+    row_of_entry = np.repeat(np.arange(n, dtype=np.int64), L)
+    k = np.arange(rowptr[-1], dtype=np.int64) - np.repeat(rowptr[:-1].astype(np.int64), L)
+    chunk = row_of_entry // oracle.STREAM_ROWS
+    has = (got["pat_off"][1:] > got["pat_off"][:-1])[chunk]
+    at = got["pat_off"][chunk].astype(np.int64) + got["row_pat"][row_of_entry] + k
+    cols = np.full(rowptr[-1], -1, dtype=np.int64)
+    cols[has] = row_of_entry[has] + got["pool"][at[has]]
+    return cols, has
+
+
+def test_row_patterns_hand_worked_band():
+    # 9 diagonals, 64 rows: chunk 0 needs the four cut-off patterns of rows 0-3 (5, 6, 7, 8 entries)
+    # and the full one; chunk 1 the full one and the four cut-off ones of rows 60-63
+    rowptr, colidx = _csr_from_rows(_banded(64, 4))
+    got = oracle.row_patterns(rowptr, colidx)
+    assert got["pat_off"].tolist() == [0, 35, 70]
+    assert got["row_pat"][:6].tolist() == [0, 5, 11, 18, 26, 26] and np.all(got["row_pat"][4:32] == 26)
+    assert got["pool"][:35].tolist() == (list(range(0, 5)) + list(range(-1, 5)) + list(range(-2, 5))
+                                        + list(range(-3, 5)) + list(range(-4, 5)))
+    assert np.all(got["row_pat"][32:60] == 0) and got["row_pat"][60:].tolist() == [9, 17, 24, 30]
+    assert got["pool"][35:].tolist() == (list(range(-4, 5)) + list(range(-4, 4)) + list(range(-4, 3))
+                                        + list(range(-4, 2)) + list(range(-4, 1)))
+    assert got["entries"] == colidx.size and got["enabled"]
+    assert got["row_pat"].dtype == np.uint16 and got["pool"].dtype == np.int32
+
+
+def test_row_patterns_first_appearance_order_and_prefixes():
+    # A B A C(prefix of A) in the first rows; the stored order of a row matters (unsorted, duplicates)
+    n = 32
+    A = [0, 3, 1, 1, 7, 9, 12, 15, 2]
+    B = [5, 4, 3, 2, 1, 0, 6, 7, 8]
+    C = A[:8]
+    pats = [A, B, A, C] + [A] * (n - 4)
+    rows = [[i + d for d in p] for i, p in enumerate(pats)]
+    rowptr, colidx = _csr_from_rows(rows)
+    got = oracle.row_patterns(rowptr, colidx)
+    assert got["pat_off"].tolist() == [0, 26]
+    assert got["row_pat"][:5].tolist() == [0, 9, 0, 18, 0]
+    assert got["pool"].tolist() == A + B + C
+
+
+def test_row_patterns_limits():
+    base = list(range(9))
+
+    def chunk_with(patterns):
+        rows = [[i + d for d in patterns[i % len(patterns)]] for i in range(32)]
+        return _csr_from_rows(rows)
+
+    eight = [base[:-1] + [20 + p] for p in range(8)]
+    nine = eight + [base[:-1] + [40]]
+    assert oracle.row_patterns(*chunk_with(eight))["pat_off"].tolist() == [0, 72]
+    got = oracle.row_patterns(*chunk_with(nine))                       # a ninth pattern: none at all
+    assert got["pat_off"].tolist() == [0, 0] and not got["row_pat"].any() and got["entries"] == 0 and not got["enabled"]
+    # table of exactly 512 diagonals fits (8 patterns of 64), 513 do not
+    wide = [[q * 100 + t for t in range(64)] for q in range(8)]
+    assert oracle.row_patterns(*chunk_with(wide))["pat_off"].tolist() == [0, 512]
+    wider = [w[:] for w in wide]
+    wider[7] = wider[7] + [999]
+    assert oracle.row_patterns(*chunk_with(wider))["pat_off"].tolist() == [0, 0]
+    # a row of 128 entries is allowed, 129 is not (one pattern, 4 rows of it make 512 >= 256 entries)
+    for length, expect in ((128, [0, 128]), (129, [0, 0])):
+        rows = [list(range(i, i + length)) if i < 4 else [] for i in range(32)]
+        assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == expect
+    # the table must pay for itself: 8 rows, all different, 40 entries each: 2 * 320 > 320
+    rows = [[i + 3 * t + (t == 39) * i for t in range(40)] for i in range(8)]
+    assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == [0, 0]
+    # exactly twice the table: two patterns, each used twice
+    rows = [[i + t * (1 + i % 2) for t in range(64)] for i in range(4)]
+    assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == [0, 128]
+    # chunks below the stream minimum (255 entries) have no patterns
+    rows = [list(range(i, i + 8)) for i in range(31)] + [list(range(31, 38))]
+    assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == [0, 0]
+
+
+def test_row_patterns_of_the_27_point_stencil_are_its_neighbour_offsets():
+    nx, ny, nz = 32, 6, 5                                               # one grid line per chunk
+    w = gen.workload(2, {"nx": nx, "ny": ny, "nz": nz})
+    got = oracle.row_patterns(w.rowptr, w.colidx)
+    assert got["enabled"] and got["entries"] == w.nnz
+    lens = np.diff(got["pat_off"])
+    for z in range(nz):
+        for y in range(ny):
+            c = z * ny + y
+            dz = [d for d in (-1, 0, 1) if 0 <= z + d < nz]
+            dy = [d for d in (-1, 0, 1) if 0 <= y + d < ny]
+            left = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (0, 1)]
+            mid = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (-1, 0, 1)]
+            right = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (-1, 0)]
+            assert lens[c] == len(left) + len(mid) + len(right)
+            assert got["pool"][got["pat_off"][c]:got["pat_off"][c + 1]].tolist() == left + mid + right
+            rp = got["row_pat"][32 * c:32 * c + 32]
+            assert rp[0] == 0 and np.all(rp[1:31] == len(left)) and rp[31] == len(left) + len(mid)
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, None), (2, {"nx": 24, "ny": 24, "nz": 24}),
+                                       (2, {"nx": 50, "ny": 7, "nz": 9}),
+                                       (3, {"n": 1 << 14}), (4, {"n": 1 << 15, "cap": 5000}),
+                                       (7, {"scale": 0.01}), (8, {"grid": 12})])
+def test_row_patterns_reconstruct_columns_and_are_minimal(cfg, scale):
+    w = gen.workload(cfg, scale)
+    got = oracle.row_patterns(w.rowptr, w.colidx, w.ncols, w.vals.dtype.itemsize)
+    cols, has = _columns_from_patterns(w.rowptr, got)
+    assert np.array_equal(cols[has], w.colidx[has])
+    assert got["entries"] == int(has.sum())
+    part = oracle.partition(w.rowptr, colidx=w.colidx, ncols=w.ncols, itemsize=w.vals.dtype.itemsize)
+    streams = set(part["stream_chunks"].tolist())
+    L = np.diff(w.rowptr)
+    for c in range(got["pat_off"].size - 1):
+        rows = range(32 * c, min(32 * c + 32, w.nrows))
+        pats = {tuple((w.colidx[w.rowptr[i]:w.rowptr[i + 1]] - i).tolist()) for i in rows if L[i]}
+        size = sum(len(p) for p in pats)
+        entries = int(w.rowptr[rows[-1] + 1] - w.rowptr[rows[0]])
+        fits = (c in streams and len(pats) <= 8 and size <= 512 and 2 * size <= entries
+                and max(L[i] for i in rows) <= 128)
+        assert got["pat_off"][c + 1] - got["pat_off"][c] == (size if fits else 0), c
+        if fits:      # equal rows share a start, different rows do not
+            starts = {}
+            for i in rows:
+                if L[i]:
+                    starts.setdefault(int(got["row_pat"][i]), set()).add(tuple((w.colidx[w.rowptr[i]:w.rowptr[i + 1]] - i).tolist()))
+            assert len(starts) == len(pats) and all(len(v) == 1 for v in starts.values())
+        else:
+            assert not got["row_pat"][rows[0]:rows[-1] + 1].any()
+    if cfg in (1, 3, 4):      # 5-point chunks are below the stream minimum; random columns repeat nothing
+        assert not got["enabled"]
+    if cfg == 2:              # everything but a last chunk below the stream minimum
+        assert got["enabled"] and got["entries"] >= w.nnz - 255
