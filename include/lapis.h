@@ -107,6 +107,9 @@ extern "C" {
 #define LAPIS_SPLIT_MAX_BLOCKS  32
 #define LAPIS_HUGE_ROW 16384             /* rows with more entries are cut at LDS-sized column blocks */
 #define LAPIS_LDS_BLOCK_BYTES 65536      /* bytes of x one such block holds */
+#define LAPIS_PATTERN_MAX_ROW 128        /* longest row a patterned chunk may have (lapis_csr_copy_patterns) */
+#define LAPIS_PATTERN_SLOTS 8            /* distinct row patterns per chunk at most */
+#define LAPIS_PATTERN_TABLE 512          /* diagonals in a chunk's pattern table at most */
 
 typedef struct lapis_csr lapis_csr_t;   /* opaque handle */
 
@@ -296,6 +299,30 @@ int lapis_csr_copy_huge(const lapis_csr_t *A, int32_t *h_split_rows, int32_t *h_
  */
 int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_entries, int64_t *framed_entries,
                            int32_t *h_chunk_base, int32_t *h_frame_table, uint16_t *h_col16);
+
+/*
+ * lapis_csr_copy_patterns - the row patterns the analysis finds in the stream chunks (an
+ * implementation choice of this library, not of the paper; exposed so that it can be compared
+ * bit for bit with a CPU reference).  Matrices of regular grids repeat the same list of
+ * diagonals (column - row, in stored order) row after row; where the rows of a chunk share a
+ * few such lists, lapis_spmv reads no column index per entry at all for that chunk.
+ * For a stream chunk c (after the demotion above), going through its rows in ascending order,
+ * every list not met before in the chunk is appended to the chunk's table, and row_pat[i] is
+ * where the list of row i starts in that table (0 for empty rows).  The chunk is patterned if no
+ * row has more than LAPIS_PATTERN_MAX_ROW entries, at most LAPIS_PATTERN_SLOTS lists were needed,
+ * the table has at most LAPIS_PATTERN_TABLE diagonals and twice its length does not exceed the
+ * chunk's entries; otherwise its table is empty and row_pat is 0 for its rows.
+ * pat_off[0..C] (C = ceil(nrows / LAPIS_STREAM_ROWS)) is the exclusive scan of the table lengths
+ * and pool holds the tables back to back, so that for a row i of a patterned chunk c
+ *   colidx[rowptr[i] + k] == i + pool[pat_off[c] + row_pat[i] + k].
+ * The structure is kept (*enabled = 1) only if the patterned chunks hold at least half of the
+ * matrix's entries; *pattern_entries is that count and *pool_size = pat_off[C] either way.
+ *   h_pat_off HOST int32[C + 1]    h_row_pat HOST uint16[nrows]    h_pool HOST int32[*pool_size]
+ * The arrays are written only when *enabled is 1; any pointer may be NULL (call once for
+ * *pool_size, then again with the buffers).  Synchronises the device.
+ */
+int lapis_csr_copy_patterns(const lapis_csr_t *A, int *enabled, int64_t *pattern_entries, int64_t *pool_size,
+                            int32_t *h_pat_off, uint16_t *h_row_pat, int32_t *h_pool);
 
 /* max |column - row| over the matrix's entries, found by lapis_csr_create; lapis_spmm uses it to
  * decide how workgroups are dealt to the 8 XCDs (band-wide windows of X rows that overflow one

@@ -22,7 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
-    "lapis_csr_copy_index16", "lapis_csr_huge_sizes", "lapis_csr_copy_huge",
+    "lapis_csr_copy_index16", "lapis_csr_copy_patterns", "lapis_csr_huge_sizes", "lapis_csr_copy_huge",
     "lapis_spmv_transpose", "lapis_csr_create_transpose", "lapis_csr_shape", "lapis_csr_copy_arrays",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
@@ -61,6 +61,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_huge_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 3
         lib.lapis_csr_copy_huge.argtypes = [p, p, p, p]
         lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), p, p, p]
+        lib.lapis_csr_copy_patterns.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), p, p, p]
         lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
         lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
         lib.lapis_csr_copy_arrays.argtypes = [p, p, p, p]
@@ -148,6 +149,23 @@ def lapis_csr_copy_index16(A):
         out["col16"] = np.empty(z, dtype=np.uint16)
         _check(load().lapis_csr_copy_index16(A, None, None, None, out["chunk_base"].ctypes.data,
                                              out["frame_table"].ctypes.data, out["col16"].ctypes.data))
+    return out
+
+
+def lapis_csr_copy_patterns(A):
+    """dict(enabled, entries, pat_off, row_pat, pool) of a handle (arrays None when not enabled)."""
+    n, _, _, _ = lapis_csr_shape(A)
+    on, entries, pool = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+    _check(load().lapis_csr_copy_patterns(A, ctypes.byref(on), ctypes.byref(entries), ctypes.byref(pool), None, None, None))
+    out = {"enabled": bool(on.value), "entries": entries.value, "pool_size": pool.value,
+           "pat_off": None, "row_pat": None, "pool": None}
+    if on.value:
+        rows = lapis_partition_constants()["stream_rows"]
+        out["pat_off"] = np.empty((n + rows - 1) // rows + 1, dtype=np.int32)
+        out["row_pat"] = np.empty(n, dtype=np.uint16)
+        out["pool"] = np.empty(pool.value, dtype=np.int32)
+        _check(load().lapis_csr_copy_patterns(A, None, None, None, out["pat_off"].ctypes.data,
+                                              out["row_pat"].ctypes.data, out["pool"].ctypes.data))
     return out
 
 

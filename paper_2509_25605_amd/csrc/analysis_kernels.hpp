@@ -204,45 +204,63 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
 }
 
 // One workgroup of kCompactBlock threads: entries[0] = entries of the narrow chunks (chunk_base >= 0),
-// entries[1] = entries of the framed chunks (chunk_base == -2), narrow_chunks[k - 1] /
-// narrow_chunks[kChunkClasses + k - 1] = how many narrow / framed chunks are of class k.
+// entries[1] = entries of the framed chunks (chunk_base == -2), entries[2] = entries of the
+// patterned stream chunks (pat_len > 0), entries[3] = sum of their table lengths,
+// entries[4 + k - 1] / entries[4 + kChunkClasses + k - 1] = the last two for class k alone;
+// narrow_chunks[q * kChunkClasses + k - 1] = how many chunks of class k are narrow (q = 0), framed
+// (1), patterned (2), patterned or narrow or framed (3).
 __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nrows, int32_t num_chunks,
                                                                      int32_t chunk_rows,
                                                                      const int32_t *__restrict__ chunk_flag,
                                                                      const int32_t *__restrict__ rowptr,
                                                                      const int32_t *__restrict__ chunk_base,
+                                                                     const int32_t *__restrict__ pat_len,
                                                                      unsigned long long *__restrict__ entries_out,
                                                                      int32_t *__restrict__ narrow_chunks)
 {
-    __shared__ unsigned long long s_entries[2];
-    __shared__ int32_t s_chunks[2 * kChunkClasses];
-    if (threadIdx.x < 2) s_entries[threadIdx.x] = 0;
-    if (threadIdx.x < 2 * kChunkClasses) s_chunks[threadIdx.x] = 0;
+    constexpr int kTotals = 4 + 2 * kChunkClasses;
+    __shared__ unsigned long long s_entries[kTotals];
+    __shared__ int32_t s_chunks[4 * kChunkClasses];
+    if (threadIdx.x < kTotals) s_entries[threadIdx.x] = 0;
+    if (threadIdx.x < 4 * kChunkClasses) s_chunks[threadIdx.x] = 0;
     __syncthreads();
-    unsigned long long entries = 0, framed = 0;
-    int32_t chunks[2 * kChunkClasses] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long entries = 0, framed = 0, patterned = 0, table = 0;
+    unsigned long long cls_entries[kChunkClasses] = {0, 0, 0, 0}, cls_table[kChunkClasses] = {0, 0, 0, 0};
+    int32_t chunks[4 * kChunkClasses] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
         const int32_t base = chunk_base[c];
-        if (base == -1) continue;
+        const int32_t cls = chunk_flag[c];
+        const int32_t plen = cls != 0 ? pat_len[c] : 0;
+        if (base == -1 && plen == 0) continue;
         const int64_t first = c * chunk_rows;
         const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
         const unsigned long long len = (unsigned long long)(rowptr[last] - rowptr[first]);
-        const int32_t cls = chunk_flag[c];
-        if (base == -2) framed += len; else entries += len;
+        if (base == -2) framed += len; else if (base >= 0) entries += len;
+        if (plen > 0) { patterned += len; table += (unsigned long long)plen; }
 #pragma unroll
         for (int k = 0; k < kChunkClasses; ++k) {
+            if (cls == k + 1 && plen > 0) { cls_entries[k] += len; cls_table[k] += (unsigned long long)plen; }
             chunks[k] += (cls == k + 1 && base >= 0);
             chunks[kChunkClasses + k] += (cls == k + 1 && base == -2);
+            chunks[2 * kChunkClasses + k] += (cls == k + 1 && plen > 0);
+            chunks[3 * kChunkClasses + k] += (cls == k + 1 && (plen > 0 || base != -1));
         }
     }
     if (entries) atomicAdd(&s_entries[0], entries);
     if (framed) atomicAdd(&s_entries[1], framed);
+    if (patterned) atomicAdd(&s_entries[2], patterned);
+    if (table) atomicAdd(&s_entries[3], table);
 #pragma unroll
-    for (int k = 0; k < 2 * kChunkClasses; ++k)
+    for (int k = 0; k < kChunkClasses; ++k) {
+        if (cls_entries[k]) atomicAdd(&s_entries[4 + k], cls_entries[k]);
+        if (cls_table[k]) atomicAdd(&s_entries[4 + kChunkClasses + k], cls_table[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < 4 * kChunkClasses; ++k)
         if (chunks[k]) atomicAdd(&s_chunks[k], chunks[k]);
     __syncthreads();
-    if (threadIdx.x < 2) entries_out[threadIdx.x] = s_entries[threadIdx.x];
-    if (threadIdx.x < 2 * kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
+    if (threadIdx.x < kTotals) entries_out[threadIdx.x] = s_entries[threadIdx.x];
+    if (threadIdx.x < 4 * kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
 }
 
 // Frames of 2048 columns for the stream chunks that are not narrow (chunk_base == -1 on entry),
@@ -316,6 +334,95 @@ __global__ __launch_bounds__(kBlock) void col16_fill_kernel(int32_t nrows, int32
 #pragma unroll
         for (int t = 0; t < kAnalysisFrameSlots; ++t) rank += (__builtin_amdgcn_readlane(tab, t) < f);
         if (j < e) col16[j] = (uint16_t)((rank << kAnalysisFrameShift) | (col & ((1 << kAnalysisFrameShift) - 1)));
+    }
+}
+
+// Level 1c, one wavefront per chunk: the row patterns of a stream chunk.  The pattern of a
+// non-empty row i is the list of its diagonals colidx[j] - i in stored order; going through the
+// rows in ascending order every pattern not met before in the chunk is appended to the chunk's
+// table (LDS here), and row_pat[i] = where the pattern of row i starts in it (0 for empty rows).
+// pat_len[c] = length of the table if no row has more than kPatternMaxRow entries, at most
+// kPatternSlots patterns were needed, the table has at most kPatternTableSize diagonals and
+// twice its length does not exceed the chunk's entries; otherwise 0 (and row_pat 0 for the
+// chunk's rows).  Chunks that do not stream get 0 as well.  chunk_rows <= 64.
+constexpr int kPatternMaxRow = 128, kPatternSlots = 8, kPatternTableSize = 512;
+__global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                                const int32_t *__restrict__ chunk_flag,
+                                                                const int32_t *__restrict__ rowptr,
+                                                                const int32_t *__restrict__ colidx,
+                                                                int32_t *__restrict__ pat_len,
+                                                                uint16_t *__restrict__ row_pat)
+{
+    static_assert(kPatternMaxRow == 2 * kWave, "two entries of a row per lane");
+    __shared__ int32_t s_table[kWavesPerBlock][kPatternTableSize];
+    const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (c >= num_chunks) return;                       // whole wavefronts leave together
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    int32_t *tab = s_table[threadIdx.x / kWave];
+    int32_t p_start[kPatternSlots], p_len[kPatternSlots];
+#pragma unroll
+    for (int p = 0; p < kPatternSlots; ++p) { p_start[p] = 0; p_len[p] = 0; }
+    int32_t P = 0, L = 0, mine = 0;
+    bool ok = chunk_flag[c] != 0;
+    for (int64_t r = first; r < last && ok; ++r) {     // uniform
+        const int32_t b = rowptr[r], len = rowptr[r + 1] - b;
+        if (len == 0) continue;
+        if (len > kPatternMaxRow) { ok = false; break; }
+        const int32_t d0 = lane < len ? colidx[b + lane] - (int32_t)r : 0;
+        const int32_t d1 = lane + kWave < len ? colidx[b + kWave + lane] - (int32_t)r : 0;
+        int32_t found = -1;
+#pragma unroll
+        for (int p = 0; p < kPatternSlots; ++p) {
+            if (found < 0 && p < P && p_len[p] == len) {
+                const bool same = (lane >= len || tab[p_start[p] + lane] == d0) &&
+                                  (lane + kWave >= len || tab[p_start[p] + kWave + lane] == d1);
+                if (__ballot(!same) == 0) found = p_start[p];
+            }
+        }
+        if (found < 0) {
+            if (P == kPatternSlots || L + len > kPatternTableSize) { ok = false; break; }
+            if (lane < len) tab[L + lane] = d0;
+            if (lane + kWave < len) tab[L + kWave + lane] = d1;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int p = 0; p < kPatternSlots; ++p)
+                if (p == P) { p_start[p] = L; p_len[p] = len; }
+            found = L;
+            P += 1;
+            L += len;
+        }
+        if (lane == (int)(r - first)) mine = found;
+    }
+    const int32_t entries = rowptr[last] - rowptr[first];
+    if (!ok || 2 * L > entries) { L = 0; mine = 0; }
+    if (lane == 0) pat_len[c] = L;
+    if (first + lane < last) row_pat[first + lane] = (uint16_t)mine;
+}
+
+// The tables of the patterned chunks back to back: pool[pat_off[c] + row_pat[i] + k] = diagonal
+// of the k-th entry of row i.  Equal rows write equal values.  One wavefront per chunk.
+__global__ __launch_bounds__(kBlock) void pattern_pool_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
+                                                              const int32_t *__restrict__ rowptr,
+                                                              const int32_t *__restrict__ colidx,
+                                                              const int32_t *__restrict__ pat_off,
+                                                              const uint16_t *__restrict__ row_pat,
+                                                              int32_t *__restrict__ pool)
+{
+    const int64_t c = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (c >= num_chunks) return;
+    const int32_t off = pat_off[c];
+    if (pat_off[c + 1] == off) return;
+    const int64_t first = c * chunk_rows;
+    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
+    for (int64_t r = first; r < last; ++r) {
+        const int32_t b = rowptr[r], len = rowptr[r + 1] - b;
+        const int32_t at = off + (int32_t)row_pat[r];
+        for (int32_t k = lane; k < len; k += kWave) pool[at + k] = colidx[b + k] - (int32_t)r;
     }
 }
 

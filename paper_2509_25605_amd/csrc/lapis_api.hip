@@ -69,6 +69,14 @@ struct lapis_csr {
     bool class_all16[kStreamClasses] = {false, false, false, false};   // every chunk of the class has a base
     bool class_allframed[kStreamClasses] = {false, false, false, false};   // every chunk of the class is framed
     bool class_allcoded[kStreamClasses] = {false, false, false, false};    // every chunk is one or the other
+    // level 1c: row patterns (kept when the patterned chunks hold at least half of the entries)
+    int32_t *d_pat_off = nullptr;        // [num_chunks + 1] exclusive scan of the chunks' table lengths
+    uint16_t *d_row_pat = nullptr;       // [nrows] start of the row's pattern in its chunk's table
+    int32_t *d_pat_pool = nullptr;       // the tables back to back
+    int64_t pattern_entries = 0;         // entries in patterned chunks
+    int64_t pattern_pool = 0;            // diagonals in the pool
+    bool class_allpattern[kStreamClasses] = {false, false, false, false};  // every chunk of the class is patterned
+    bool class_pattern16[kStreamClasses] = {false, false, false, false};   // ... is patterned, narrow or framed
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -179,6 +187,9 @@ void free_handle(lapis_csr *A)
     (void)hipFree(A->d_chunk_base);
     (void)hipFree(A->d_col16);
     (void)hipFree(A->d_frame_table);
+    (void)hipFree(A->d_pat_off);
+    (void)hipFree(A->d_row_pat);
+    (void)hipFree(A->d_pat_pool);
     (void)hipFree(A->own_rowptr);
     (void)hipFree(A->own_colidx);
     (void)hipFree(A->own_vals);
@@ -305,9 +316,11 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     int32_t num_stream = 0;
     bool index16 = false;
     struct NarrowCounts {
-        unsigned long long entries[2];      // in narrow chunks, in framed chunks
-        int32_t chunks[2 * kStreamClasses]; // narrow chunks per class, then framed chunks per class
+        unsigned long long entries[4 + 2 * kStreamClasses];   // in narrow, framed, patterned chunks; pool size;
+                                                              // then the last two per class
+        int32_t chunks[4 * kStreamClasses]; // per class: narrow, framed, patterned, any of the three
     } h_counts = {};
+    bool patterns = false;
     if (n > 0) {
         chunk_flag_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, min_nnz, A->rowptr, chunk_flag.as<int32_t>());
@@ -335,9 +348,19 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         if (nb0 > 0)
             chunk_demote_kernel<<<dim3((uint32_t)((num_chunks + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
                 (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, LAPIS_WAVE, A->rowptr, A->d_chunk_base, chunk_flag.as<int32_t>());
+        // level 1c: row patterns of the chunks that still stream
+        static_assert(LAPIS_STREAM_ROWS <= kWave && LAPIS_PATTERN_MAX_ROW == kPatternMaxRow &&
+                      LAPIS_PATTERN_SLOTS == kPatternSlots && LAPIS_PATTERN_TABLE == kPatternTableSize &&
+                      kPatternTableSize == kPatternTable, "pattern limits of the header, the analysis and the kernels");
+        DeviceTemp pat_len;
+        if (int rc = pat_len.alloc(sizeof(int32_t) * (size_t)num_chunks)) return rc;
+        if (int rc = device_alloc(&A->d_row_pat, sizeof(uint16_t) * (size_t)n)) return rc;
+        chunk_patterns_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
+            pat_len.as<int32_t>(), A->d_row_pat);
         narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
-            d_counts->entries, d_counts->chunks);
+            pat_len.as<int32_t>(), d_counts->entries, d_counts->chunks);
         static_assert(kChunkClasses == kStreamClasses, "one list per stream class");
         DeviceTemp offsets;
         if (int rc = offsets.alloc(sizeof(int32_t) * (kStreamClasses + 1))) return rc;
@@ -351,6 +374,36 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         A->narrow_entries = (int64_t)h_counts.entries[0];
         A->framed_entries = (int64_t)h_counts.entries[1];
         index16 = coded > 0 && 2 * coded >= (unsigned long long)A->nnz;
+        A->pattern_entries = (int64_t)h_counts.entries[2];
+        A->pattern_pool = (int64_t)h_counts.entries[3];
+        patterns = h_counts.entries[2] > 0 && 2 * h_counts.entries[2] >= (unsigned long long)A->nnz;
+        if (patterns) {
+            const int32_t scan_tiles = (int32_t)((num_chunks + kScanTile - 1) / kScanTile);
+            DeviceTemp tile_sums;
+            if (int rc = tile_sums.alloc(sizeof(int32_t) * ((size_t)scan_tiles + 1))) return rc;
+            if (int rc = device_alloc(&A->d_pat_off, sizeof(int32_t) * ((size_t)num_chunks + 1))) return rc;
+            if (int rc = device_alloc(&A->d_pat_pool, sizeof(int32_t) * (size_t)A->pattern_pool)) return rc;
+            scan_tile_sums_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(num_chunks, pat_len.as<int32_t>(),
+                                                                                 tile_sums.as<int32_t>());
+            scan_tile_offsets_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(scan_tiles, tile_sums.as<int32_t>());
+            scan_apply_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(num_chunks, pat_len.as<int32_t>(),
+                                                                             tile_sums.as<int32_t>(), scan_tiles, A->d_pat_off);
+            pattern_pool_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+                (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_pat_off, A->d_row_pat, A->d_pat_pool);
+            LAPIS_HIP(hipGetLastError());
+            LAPIS_HIP(hipStreamSynchronize(stream));       // pat_len and tile_sums are released on return
+            for (int cls = 1; cls <= kStreamClasses; ++cls) {
+                const int32_t size = A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
+                // each of the class's 2^(cls-1) wavefronts per chunk loads the chunk's whole table (4
+                // bytes a diagonal) instead of its share of 2-byte codes: worth it while that is at most
+                // half as much
+                const unsigned long long waves = 1ull << (cls - 1);
+                const bool pays = 4 * waves * h_counts.entries[4 + kStreamClasses + cls - 1] <= h_counts.entries[4 + cls - 1];
+                A->class_allpattern[cls - 1] = pays && h_counts.chunks[2 * kStreamClasses + cls - 1] == size;
+                A->class_pattern16[cls - 1] = pays && index16 && h_counts.chunks[2 * kStreamClasses + cls - 1] > 0 &&
+                                              h_counts.chunks[3 * kStreamClasses + cls - 1] == size;
+            }
+        }
         if (index16) {
             const size_t len = ((size_t)A->nnz + 7) / 8 * 8 + 8;      // 16-byte loads may run past nnz
             if (int rc = device_alloc(&A->d_col16, sizeof(uint16_t) * len)) return rc;
@@ -368,6 +421,10 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         }
     }
     A->num_stream = num_stream;
+    if (!patterns) {
+        (void)hipFree(A->d_row_pat);
+        A->d_row_pat = nullptr;
+    }
     if (!index16) {
         (void)hipFree(A->d_chunk_base);
         (void)hipFree(A->d_frame_table);
@@ -541,8 +598,11 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
 #define LAPIS_STREAM_LAUNCH(RAW)                                                                             \
     spmv_stream_kernel<T, G, true, RAW><<<dim3(padded), dim3(kWave), 0, stream>>>(                            \
         (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base,        \
-        A->d_frame_table, A->d_col16, static_cast<const T *>(A->vals), x, y, a, b)
-    if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);
+        A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},              \
+        static_cast<const T *>(A->vals), x, y, a, b)
+    if (A->class_allpattern[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPattern);
+    else if (A->class_pattern16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPatternOr16);
+    else if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);
     else if (A->class_allframed[cls - 1]) LAPIS_STREAM_LAUNCH(kColsFramed);
     else if (A->class_allcoded[cls - 1]) LAPIS_STREAM_LAUNCH(kColsEither);
     else LAPIS_STREAM_LAUNCH(kCols32);
@@ -953,6 +1013,25 @@ int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_e
         LAPIS_HIP(hipMemcpy(h_frame_table, A->d_frame_table, sizeof(int32_t) * (size_t)A->num_chunks * kFrameSlots, hipMemcpyDeviceToHost));
     if (h_col16 && A->nnz > 0)
         LAPIS_HIP(hipMemcpy(h_col16, A->d_col16, sizeof(uint16_t) * (size_t)A->nnz, hipMemcpyDeviceToHost));
+    return LAPIS_OK;
+}
+
+int lapis_csr_copy_patterns(const lapis_csr_t *A, int *enabled, int64_t *pattern_entries, int64_t *pool_size,
+                            int32_t *h_pat_off, uint16_t *h_row_pat, int32_t *h_pool)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    const bool on = A->d_pat_off != nullptr;
+    if (enabled) *enabled = on ? 1 : 0;
+    if (pattern_entries) *pattern_entries = A->pattern_entries;
+    if (pool_size) *pool_size = A->pattern_pool;
+    if (!on) return LAPIS_OK;
+    LAPIS_HIP(hipDeviceSynchronize());
+    if (h_pat_off)
+        LAPIS_HIP(hipMemcpy(h_pat_off, A->d_pat_off, sizeof(int32_t) * ((size_t)A->num_chunks + 1), hipMemcpyDeviceToHost));
+    if (h_row_pat && A->nrows > 0)
+        LAPIS_HIP(hipMemcpy(h_row_pat, A->d_row_pat, sizeof(uint16_t) * (size_t)A->nrows, hipMemcpyDeviceToHost));
+    if (h_pool && A->pattern_pool > 0)
+        LAPIS_HIP(hipMemcpy(h_pool, A->d_pat_pool, sizeof(int32_t) * (size_t)A->pattern_pool, hipMemcpyDeviceToHost));
     return LAPIS_OK;
 }
 

@@ -208,6 +208,12 @@ struct StreamCols {
 // column (chunk_base >= 0); or 16-bit codes (slot << 11) | (column & 2047) with a per-chunk table
 // of up to 32 frames of 2048 columns (chunk_base == kChunkFramed).
 constexpr int kCols32 = 0, kColsNarrow = 1, kColsFramed = 2, kColsEither = 3;   // kColsEither: narrow or framed, per chunk
+// A patterned chunk needs no columns per entry at all: equal rows of the chunk share one list
+// of diagonals (column - row) in the chunk's pattern table, and a row only knows where its list
+// starts.  kColsPattern: every chunk of the launch is patterned; kColsPatternOr16: patterned, or
+// else narrow or framed.  kColsNone: a window of values only.
+constexpr int kColsPattern = 4, kColsPatternOr16 = 5, kColsNone = -1;
+constexpr int kPatternTable = 512;                   // diagonals in a chunk's pattern table at most
 constexpr int32_t kChunkFramed = -2;
 constexpr int kFrameShift = 11, kFrameSlots = 32;
 constexpr int32_t kFrameMask = (1 << kFrameShift) - 1;
@@ -225,7 +231,7 @@ template <typename T, int NC, int NV, int KIND, typename IDX>
 __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__restrict__ vw,
                                             int lane, int n_vec, IDX *s_col, T *s_val)
 {
-    constexpr bool C16 = KIND != kCols32;
+    constexpr bool C16 = KIND != kCols32 && KIND != kColsNone;
     constexpr bool kRaw16 = sizeof(IDX) == 2;       // LDS keeps the 16-bit offsets as they are
     static_assert(!kRaw16 || KIND == kColsNarrow, "a 16-bit LDS window needs 16-bit offsets in memory");
     typedef typename StreamVec<T>::type vec_t;
@@ -244,7 +250,7 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
             idx = idx < last_c8 ? idx : last_c8;
             cs[i] = __builtin_nontemporal_load(reinterpret_cast<const ushort8v *>(cols.c16 + idx));
         }
-    } else {
+    } else if constexpr (KIND != kColsNone) {
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
             int idx = i * (kWave * 4) + lane * 4;
@@ -282,7 +288,7 @@ __device__ __forceinline__ void stream_fill(const StreamCols cols, const T *__re
             *reinterpret_cast<int4v *>(s_col + idx) = a;
             *reinterpret_cast<int4v *>(s_col + idx + 4) = b;
         }
-    } else {
+    } else if constexpr (KIND != kColsNone) {
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
             int idx = i * (kWave * 4) + lane * 4;
@@ -364,6 +370,25 @@ __device__ __forceinline__ void stream_window_to_lds(const int32_t *__restrict__
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The values alone of entries [w0, w1) into LDS (patterned chunks keep no columns per entry);
+// same alignment rules and the same closing fence as stream_window_to_lds.
+template <typename T>
+__device__ __forceinline__ void stream_values_to_lds(const T *__restrict__ vals, int32_t w0, int32_t w1,
+                                                     int32_t nnz4, int lane, T *s_val)
+{
+    const int32_t vec_end = w1 < nnz4 ? ((w1 + 3) & ~3) : nnz4;
+    const int n_vec = vec_end > w0 ? vec_end - w0 : 0;
+    stream_fill_by_size<T, kColsNone, int32_t>(StreamCols{nullptr, nullptr, 0, nullptr}, vals + w0, lane, n_vec,
+                                               nullptr, s_val);
+    if (w0 + n_vec < w1) {
+        const int32_t j = w0 + n_vec + lane;
+        if (j < w1) s_val[j - w0] = vals[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // The frame table of a framed chunk into LDS (32 ints per wavefront), fenced for the wavefront.
 __device__ __forceinline__ void load_frame_table(const int32_t *__restrict__ frame_table, int64_t chunk,
                                                  int32_t cbase, int lane, int32_t *s_tab)
@@ -437,6 +462,35 @@ __device__ __forceinline__ T stream_batch_pick(const IDX *sc, const T *sv, int u
     return stream_batch<T, B, 0, G, IDX, RAW>(sc, sv, u0, my_n, last_u, x, tab, cbase, s);
 }
 
+// One lane's share of a row out of a staged window: my_n entries (<= 0: none) at sc[u * G] /
+// sv[u * G], u = 0 .. my_n - 1, in batches of UNR gathers.  The last batch is cut to the longest
+// share in the wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane,
+// not 16.  All lanes of the wavefront must call this together.
+template <typename T, int G, typename IDX, int RAW, int UNR>
+__device__ __forceinline__ T stream_share(const IDX *sc, const T *sv, int my_n, const T *__restrict__ xb,
+                                          const int32_t *s_tab, int32_t cbase, T s)
+{
+    static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
+    const int last_u = my_n > 0 ? my_n - 1 : 0;
+    int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
+    const int shortest = kStreamWindow - wave_max_nonneg(kStreamWindow - (my_n > 0 ? my_n : 0));   // uniform
+    int u0 = 0;
+#pragma unroll 1
+    for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch_pick<T, UNR, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s);
+    switch ((rem + 1) / 2) {
+    case 0: break;
+    case 1: s = stream_batch_pick<T, 2, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 2: s = stream_batch_pick<T, 4, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 3: s = stream_batch_pick<T, 6, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 4: s = stream_batch_pick<T, 8, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 5: s = stream_batch_pick<T, 10, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 6: s = stream_batch_pick<T, 12, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    case 7: s = stream_batch_pick<T, 14, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    default: s = stream_batch_pick<T, UNR, G, IDX, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+    }
+    return s;
+}
+
 // One wavefront (= one workgroup) per 64/G consecutive rows of a stream chunk of the class with
 // G lanes per row (G = 2, 4, 8, 16: a chunk of 32 rows is shared by G/2 wavefronts).
 // stream_chunks lists the chunks of that class; nullptr means every chunk of the matrix.
@@ -446,23 +500,35 @@ __device__ __forceinline__ T stream_batch_pick(const IDX *sc, const T *sv, int u
 // every chunk is framed.  The LDS window then keeps the 2-byte offsets / codes as they are (10
 // instead of 12 KB per wavefront with doubles: more wavefronts per CU) and they are expanded
 // when x is gathered.  RAW == kColsEither: every chunk is one or the other.  RAW == kCols32: any
-// mix, 32-bit columns in the window.
-template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll>  // UNR must be 16 (see the switch)
+// mix, 32-bit columns in the window.  RAW == kColsPattern: every chunk is patterned
+// (pat_off[chunk + 1] > pat_off[chunk]): only the values are streamed, the chunk's table of
+// diagonals (pool + pat_off[chunk]) takes the window's place in LDS and row_pat[row] says where
+// the row's list starts in it.  RAW == kColsPatternOr16: patterned, else narrow or framed.
+struct StreamPatterns {
+    const int32_t *__restrict__ pat_off;     // [num_chunks + 1]
+    const uint16_t *__restrict__ row_pat;    // [nrows]
+    const int32_t *__restrict__ pool;
+};
+
+template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll>  // UNR must be 16
 __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
-    const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16,
+    const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16, const StreamPatterns pats,
     const T *__restrict__ vals, const T *__restrict__ x, T *__restrict__ y, T alpha, T beta)
 {
     constexpr int kRowsPerWave = kWave / G;
     constexpr int kWavesPerChunk = kStreamRows / kRowsPerWave;
     static_assert(G >= 2 && G <= 16 && kWavesPerChunk * kRowsPerWave == kStreamRows, "G must be 2, 4, 8 or 16");
-    static_assert(UNR == 16, "the last-batch switch below enumerates even sizes up to 16");
+    constexpr bool kHasPatterns = RAW == kColsPattern || RAW == kColsPatternOr16;
+    constexpr int kShareMode = RAW == kColsPatternOr16 ? kColsEither : RAW;       // how the 16-bit window is read
     typedef typename std::conditional<RAW != kCols32, uint16_t, int32_t>::type idx_t;
+    static_assert(kPatternTable * sizeof(int32_t) == kStreamWindow * sizeof(uint16_t), "the table takes the window's place");
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
-    __shared__ int32_t s_tab[RAW == kColsNarrow ? 1 : kFrameSlots];
+    __shared__ int32_t s_tab[(RAW == kColsNarrow || RAW == kColsPattern) ? 1 : kFrameSlots];
+    int32_t *s_pat = reinterpret_cast<int32_t *>(s_col);
 
     const uint32_t id = XCD_REMAP ? xcd_contiguous_id(blockIdx.x, padded_waves) : blockIdx.x;
     if (id >= num_waves) return;
@@ -470,12 +536,36 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     const int sub = lane % G;
     const uint32_t list_pos = id / kWavesPerChunk;
     const int64_t chunk = stream_chunks ? stream_chunks[list_pos] : (int64_t)list_pos;
-    const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
-    if constexpr (RAW != kColsNarrow) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
     const int64_t row = chunk * kStreamRows + (id % kWavesPerChunk) * kRowsPerWave + lane / G;
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
     const int32_t p0 = rowptr[row_c], p1 = rowptr[row_c + 1];
+    int32_t pat_begin = 0, pat_len = 0, pat_start = 0;
+    if constexpr (kHasPatterns) {
+        pat_begin = pats.pat_off[chunk];
+        pat_len = pats.pat_off[chunk + 1] - pat_begin;                  // wave-uniform
+        pat_start = pats.row_pat[row_c];
+    }
+    const bool patterned = RAW == kColsPattern || (RAW == kColsPatternOr16 && pat_len > 0);
+    int32_t cbase = -1;                                                 // wave-uniform
+    if constexpr (RAW != kColsPattern) {
+        cbase = chunk_base ? chunk_base[chunk] : -1;
+        if constexpr (RAW != kColsNarrow) {
+            if (!patterned) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
+        }
+    }
+    if (patterned) {
+        // the table is written once and read by every window of this wavefront's rows; all of
+        // its loads are issued before the first is stored
+        constexpr int kLoads = kPatternTable / kWave;
+        int32_t d[kLoads];
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i)
+            if (i == 0 || i * kWave < pat_len) d[i] = (i * kWave + lane < pat_len) ? pats.pool[pat_begin + i * kWave + lane] : 0;
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i)
+            if (i == 0 || i * kWave < pat_len) s_pat[i * kWave + lane] = d[i];
+    }
     const int32_t rb = row_ok ? p0 : p1, re = p1;      // rows past the end: empty range
     const int32_t base = __builtin_amdgcn_readfirstlane(rb);
     const int32_t end = __builtin_amdgcn_readlane(re, kWave - 1);
@@ -486,34 +576,23 @@ __global__ __launch_bounds__(kWave) void spmv_stream_kernel(
     // 32-bit columns and 16-bit offsets alike)
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform; one trip unless
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;  // rows are dense
-        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
+        if (patterned) stream_values_to_lds<T>(vals, w0, w1, nnz4, lane, s_val);
+        else stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 
         // this lane's share of its row inside the window: entries ub+sub, ub+sub+G, ...
         const int32_t ub = (rb > w0 ? rb : w0) - w0;
         const int32_t ue = (re < w1 ? re : w1) - w0;
         const int my_n = (ue - ub - sub + G - 1) / G;                  // <= 0: nothing to do
         const int first = my_n > 0 ? ub + sub : 0;                     // idle lanes re-read entry 0
-        const int last_u = my_n > 0 ? my_n - 1 : 0;
-        const idx_t *sc = s_col + first;
-        const T *sv = s_val + first;
-        const T *xb = RAW == kColsNarrow ? x + cbase : x;
-        // batches of UNR entries per lane; the last batch is cut to the longest share in the
-        // wavefront (rounded up to even), so rows of 27 entries issue 14 gathers per lane, not 16
-        int rem = wave_max_nonneg(my_n > 0 ? my_n : 0);
-        const int shortest = kStreamWindow - wave_max_nonneg(kStreamWindow - (my_n > 0 ? my_n : 0));   // uniform
-        int u0 = 0;
-#pragma unroll 1
-        for (; rem > UNR; rem -= UNR, u0 += UNR) s = stream_batch_pick<T, UNR, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s);
-        switch ((rem + 1) / 2) {
-        case 0: break;
-        case 1: s = stream_batch_pick<T, 2, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 2: s = stream_batch_pick<T, 4, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 3: s = stream_batch_pick<T, 6, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 4: s = stream_batch_pick<T, 8, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 5: s = stream_batch_pick<T, 10, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 6: s = stream_batch_pick<T, 12, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        case 7: s = stream_batch_pick<T, 14, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
-        default: s = stream_batch_pick<T, UNR, G, idx_t, RAW>(sc, sv, u0, my_n, last_u, shortest, xb, s_tab, cbase, s); break;
+        if (patterned) {
+            // the diagonals of the row's pattern from where this window cuts into the row; idle
+            // lanes read the table's first diagonal and gather x[0]
+            const int32_t *sc = s_pat + (my_n > 0 ? pat_start + (ub + w0 - rb) + sub : 0);
+            const T *xb = my_n > 0 ? x + row_c : x - s_pat[0];
+            s = stream_share<T, G, int32_t, kCols32, UNR>(sc, s_val + first, my_n, xb, nullptr, 0, s);
+        } else {
+            const T *xb = RAW == kColsNarrow ? x + cbase : x;
+            s = stream_share<T, G, idx_t, kShareMode, UNR>(s_col + first, s_val + first, my_n, xb, s_tab, cbase, s);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();

@@ -71,6 +71,10 @@ class CsrMatrix:
         """The 16-bit column offsets of the narrow stream chunks (see lapis_csr_copy_index16)."""
         return B.lapis_csr_copy_index16(self.handle)
 
+    def patterns(self):
+        """The row patterns of the stream chunks (see lapis_csr_copy_patterns)."""
+        return B.lapis_csr_copy_patterns(self.handle)
+
     def partition(self):
         return B.lapis_csr_copy_partition(self.handle)
 

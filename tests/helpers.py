@@ -100,6 +100,9 @@ class DeviceCsr:
     def index16(self):
         return self.mat.index16()
 
+    def patterns(self):
+        return self.mat.patterns()
+
     def split(self):
         return self.mat.split()
 

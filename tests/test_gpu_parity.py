@@ -38,6 +38,20 @@ def check_index16(dev):
     return ref["enabled"]
 
 
+def check_patterns(dev):
+    """The row patterns of the handle against the oracle's, bit for bit."""
+    ref = oracle.row_patterns(dev.h_rowptr, dev.h_colidx, dev.ncols, np.dtype(dev.np_dtype).itemsize)
+    got = dev.patterns()
+    assert got["enabled"] == ref["enabled"] and got["entries"] == ref["entries"]
+    assert got["pool_size"] == ref["pool"].size
+    if ref["enabled"]:
+        assert got["pat_off"].dtype == np.int32 and got["row_pat"].dtype == np.uint16
+        assert np.array_equal(got["pat_off"], ref["pat_off"]), "pat_off differs"
+        assert np.array_equal(got["row_pat"], ref["row_pat"]), "row_pat differs"
+        assert np.array_equal(got["pool"], ref["pool"]), "pattern pool differs"
+    return ref["enabled"]
+
+
 def check_partition(dev, rowptr):
     assert rowptr is dev.h_rowptr or np.array_equal(rowptr, dev.h_rowptr)
     ref = oracle.partition(rowptr, colidx=dev.h_colidx, ncols=dev.ncols, itemsize=np.dtype(dev.np_dtype).itemsize)
@@ -46,6 +60,7 @@ def check_partition(dev, rowptr):
         assert got[key].dtype == np.int32
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
     check_index16(dev)
+    check_patterns(dev)
 
 
 def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):
@@ -399,6 +414,96 @@ def test_index16_framed_chunks():
             check_spmm(dev, rowptr, colidx, vals, X, what="mixed kinds spmm k=4")
         finally:
             dev.close()
+
+
+def _rows_from_diagonals(n, lists, seed, dtype, empty=()):
+    """CSR whose row i has the columns i + d for d in lists[i % len(lists)] (stored in that order);
+    rows in `empty` have no entries."""
+    rows = [[] if i in empty else [i + d for d in lists[i % len(lists)]] for i in range(n)]
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum([len(r) for r in rows], out=rowptr[1:])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    vals = gen.uniform(seed, gen.STREAM_VALUES, colidx.size).astype(dtype)
+    return rowptr, colidx, vals
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("kind", ["band9", "band81", "band120", "three_lists", "unsorted_dups", "holes"])
+def test_row_patterns_every_chunk_patterned(kind, dtype):
+    """Matrices whose stream chunks all have row patterns: the kernels read no column per entry."""
+    say(f"row patterns {kind} {np.dtype(dtype).name}")
+    n = 3211                                            # ragged last chunk of 11 rows
+    empty = ()
+    if kind.startswith("band"):
+        lists = [list(range(int(kind[4:])))]
+    elif kind == "three_lists":
+        lists = [list(range(0, 54, 2)), list(range(1, 37, 2)) + [900], list(range(27))]
+    elif kind == "unsorted_dups":
+        lists = [[5, 0, 5, 2, 700, 3, 3, 1, 64, 9, 8, 7], [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]]
+    else:
+        lists = [list(range(40))]
+        empty = set(range(0, 40)) | set(range(100, 131)) | {n - 1, n - 3}     # a chunk starting with empty rows
+    ncols = n + 1000
+    rowptr, colidx, vals = _rows_from_diagonals(n, lists, 911, dtype, empty)
+    x = gen.uniform(912, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(912, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        got = dev.patterns()
+        assert got["enabled"]
+        streams = dev.partition()["stream_chunks"]
+        assert streams.size > 0 and np.all(np.diff(got["pat_off"])[streams] > 0)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, -0.25, 2.0, y0, what="alpha=-0.25 beta=2")
+        X = gen.uniform(913, gen.STREAM_X, ncols * 4).astype(dtype).reshape(ncols, 4)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=4")
+    finally:
+        dev.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("others", ["narrow", "framed", "plain", "few_patterned"])
+def test_row_patterns_beside_other_chunks(others, dtype):
+    """Patterned chunks in one launch with chunks that have 16-bit codes, and matrices where a
+    class also holds chunks with neither (the patterns are then left unused for that class)."""
+    say(f"row patterns beside {others} {np.dtype(dtype).name}")
+    n, per = 6400, 16
+    patterned_rows = 1600 if others == "few_patterned" else 4480
+    ncols = 1 << 22
+    rowptr, colidx, vals = gen.random_csr(n, ncols, np.full(n, per), 915, dtype)
+    r = np.arange(n)
+    # rows below patterned_rows: one list of 16 diagonals; above: random columns near the diagonal
+    # (narrow), in four far clusters (framed), or anywhere (neither)
+    colidx[: patterned_rows * per] = (r[:patterned_rows, None] + 3 * np.arange(per)[None, :]).ravel().astype(np.int32)
+    rest = r[patterned_rows:]
+    if others in ("narrow", "few_patterned"):
+        jitter = (gen.uniform(916, 5, rest.size * per, 0.0, 1.0) * 3000).astype(np.int64).reshape(rest.size, per)
+        colidx[patterned_rows * per:] = np.sort(rest[:, None] + jitter, axis=1).ravel().astype(np.int32)
+    elif others == "framed":
+        jitter = (gen.uniform(916, 5, rest.size * per, 0.0, 1.0) * 500).astype(np.int64).reshape(rest.size, 4, 4)
+        clusters = np.arange(4)[None, :, None] * 900001 + (rest[:, None, None] // 64) * 2048 + jitter
+        colidx[patterned_rows * per:] = np.sort(clusters.reshape(rest.size, per), axis=1).ravel().astype(np.int32)
+    x = gen.uniform(917, gen.STREAM_X, ncols).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        got = dev.patterns()
+        assert got["enabled"] == (others != "few_patterned")
+        assert got["entries"] == patterned_rows * per
+        if got["enabled"]:
+            lens = np.diff(got["pat_off"])
+            assert np.all(lens[: patterned_rows // 32] == per) and not lens[patterned_rows // 32:].any()
+        base = dev.index16()["chunk_base"]
+        if others == "framed":
+            assert np.all(base[patterned_rows // 32:] == -2)
+        elif others == "plain":
+            assert np.all(base[patterned_rows // 32:] == -1)
+        check_spmv(dev, rowptr, colidx, vals, x, what="spmv")
+        X = gen.uniform(918, gen.STREAM_X, ncols * 8).astype(dtype).reshape(ncols, 8)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=8")
+    finally:
+        dev.close()
 
 
 def test_index16_last_entries_of_the_matrix():
