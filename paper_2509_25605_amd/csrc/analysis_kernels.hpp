@@ -404,7 +404,7 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
 }
 
 // The tables of the patterned chunks back to back: pool[pat_off[c] + row_pat[i] + k] = diagonal
-// of the k-th entry of row i.  Equal rows write equal values.  One wavefront per chunk.
+// of the k-th entry of row i.  One wavefront per chunk; chunk_rows <= 64.
 __global__ __launch_bounds__(kBlock) void pattern_pool_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                               const int32_t *__restrict__ rowptr,
                                                               const int32_t *__restrict__ colidx,
@@ -417,12 +417,27 @@ __global__ __launch_bounds__(kBlock) void pattern_pool_kernel(int32_t nrows, int
     if (c >= num_chunks) return;
     const int32_t off = pat_off[c];
     if (pat_off[c + 1] == off) return;
-    const int64_t first = c * chunk_rows;
-    const int64_t last = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
-    for (int64_t r = first; r < last; ++r) {
-        const int32_t b = rowptr[r], len = rowptr[r + 1] - b;
-        const int32_t at = off + (int32_t)row_pat[r];
-        for (int32_t k = lane; k < len; k += kWave) pool[at + k] = colidx[b + k] - (int32_t)r;
+    // only the first row with each list writes it: lane r looks after row first + r
+    const int64_t first = c * (int64_t)chunk_rows;
+    const int64_t r = first + lane;
+    const bool has_row = lane < chunk_rows && r < nrows;
+    const int32_t b = has_row ? rowptr[r] : 0;
+    const int32_t len = has_row ? rowptr[r + 1] - b : 0;
+    const int32_t start = has_row ? (int32_t)row_pat[r] : 0;
+    bool writer = len > 0;
+    for (int t = 0; t < chunk_rows; ++t) {             // uniform
+        const int32_t t_start = __builtin_amdgcn_readlane(start, t);
+        const int32_t t_len = __builtin_amdgcn_readlane(len, t);
+        if (t < lane && t_len > 0 && t_start == start) writer = false;
+    }
+    unsigned long long todo = __ballot(writer);
+    while (todo) {                                     // uniform: at most kPatternSlots rows
+        const int t = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int32_t t_b = __builtin_amdgcn_readlane(b, t);
+        const int32_t t_len = __builtin_amdgcn_readlane(len, t);
+        const int32_t at = off + __builtin_amdgcn_readlane(start, t);
+        for (int32_t k = lane; k < t_len; k += kWave) pool[at + k] = colidx[t_b + k] - (int32_t)(first + t);
     }
 }
 
