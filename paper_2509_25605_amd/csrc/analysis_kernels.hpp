@@ -80,67 +80,94 @@ __global__ __launch_bounds__(kBlock) void chunk_flag_kernel(int32_t nrows, int32
     flag[c] = cls;
 }
 
-// Pass 0b (one workgroup of kCompactBlock threads): list = the chunk ids of class 1, then of
-// class 2, ... each class ascending; offset[k] = position of the first chunk of class k+1,
-// offset[kChunkClasses] = number of listed chunks.  flag holds values 0..kChunkClasses.
+// Pass 0b, three launches (histogram per block of kCompactBlock chunks, scan, ordered scatter):
+// list = the chunk ids of class 1, then of class 2, ... each class ascending; offset[k] =
+// position of the first chunk of class k+1, offset[kChunkClasses] = number of listed chunks.
+// flag holds values 0..kChunkClasses.
 constexpr int kChunkClasses = 4;
 constexpr int kCompactBlock = 1024;
+// Step 1 of 3: hist[b * kChunkClasses + k - 1] = how many of the chunks b * kCompactBlock ..
+// (b + 1) * kCompactBlock - 1 are of class k.
+__global__ __launch_bounds__(kCompactBlock) void chunk_class_hist_kernel(int32_t num_chunks,
+                                                                         const int32_t *__restrict__ flag,
+                                                                         int32_t *__restrict__ hist)
+{
+    __shared__ int32_t s_count[kChunkClasses];
+    if (threadIdx.x < kChunkClasses) s_count[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t c = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
+    const int32_t f = (c < num_chunks) ? flag[c] : 0;
+#pragma unroll
+    for (int k = 0; k < kChunkClasses; ++k) {
+        const uint64_t m = __builtin_amdgcn_ballot_w64(f == k + 1);
+        if (threadIdx.x % kWave == 0 && m) atomicAdd(&s_count[k], (int32_t)__popcll(m));
+    }
+    __syncthreads();
+    if (threadIdx.x < kChunkClasses) hist[(int64_t)blockIdx.x * kChunkClasses + threadIdx.x] = s_count[threadIdx.x];
+}
+
+// Step 2 of 3, one workgroup: offset[0 .. kChunkClasses] = where each class's list starts in
+// `list` (and the total), and hist[b * kChunkClasses + k - 1] becomes where the class-k chunks of
+// block b go: the class's start plus the class-k chunks of the blocks before b.
+__global__ __launch_bounds__(kCompactBlock) void chunk_class_scan_kernel(int32_t num_blocks, int32_t *__restrict__ hist,
+                                                                         int32_t *__restrict__ offset)
+{
+    __shared__ int32_t s_part[kCompactBlock];
+    __shared__ int32_t s_total[kChunkClasses + 1];
+    const int tid = threadIdx.x;
+    const int32_t per = (num_blocks + kCompactBlock - 1) / kCompactBlock;
+    const int32_t b0 = tid * per, b1 = (b0 + per < num_blocks) ? b0 + per : num_blocks;
+    if (tid == 0) s_total[0] = 0;
+    for (int k = 0; k < kChunkClasses; ++k) {
+        int32_t sum = 0;
+        for (int32_t b = b0; b < b1; ++b) sum += hist[(int64_t)b * kChunkClasses + k];
+        __syncthreads();
+        s_part[tid] = sum;
+        __syncthreads();
+        for (int d = 1; d < kCompactBlock; d *= 2) {
+            const int32_t other = tid >= d ? s_part[tid - d] : 0;
+            __syncthreads();
+            s_part[tid] += other;
+            __syncthreads();
+        }
+        if (tid == kCompactBlock - 1) s_total[k + 1] = s_total[k] + s_part[tid];
+        __syncthreads();
+        int32_t at = s_total[k] + s_part[tid] - sum;       // exclusive prefix of this thread's blocks
+        for (int32_t b = b0; b < b1; ++b) {
+            const int32_t n = hist[(int64_t)b * kChunkClasses + k];
+            hist[(int64_t)b * kChunkClasses + k] = at;
+            at += n;
+        }
+    }
+    __syncthreads();
+    if (tid <= kChunkClasses) offset[tid] = s_total[tid];
+}
+
+// Step 3 of 3: list[] = the chunks of class 1, then class 2, ..., each ascending; start[] is
+// the hist[] that step 2 left.  Ballots give the position inside the wavefront, LDS the counts
+// of the wavefronts before it.
 __global__ __launch_bounds__(kCompactBlock) void chunk_compact_kernel(int32_t num_chunks,
                                                                       const int32_t *__restrict__ flag,
-                                                                      int32_t *__restrict__ list,
-                                                                      int32_t *__restrict__ offset)
+                                                                      const int32_t *__restrict__ start,
+                                                                      int32_t *__restrict__ list)
 {
     constexpr int kWaves = kCompactBlock / kWave;
-    __shared__ int32_t s_base[kChunkClasses + 1];
     __shared__ int32_t s_wave[kWaves][kChunkClasses];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    if (threadIdx.x <= kChunkClasses) s_base[threadIdx.x] = 0;
-    __syncthreads();
-    // class totals
-    int32_t cnt[kChunkClasses] = {0, 0, 0, 0};
-    for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
-        const int32_t f = flag[c];
+    const int64_t c = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x;
+    const int32_t f = (c < num_chunks) ? flag[c] : 0;
+    uint64_t mine = 0;
 #pragma unroll
-        for (int k = 0; k < kChunkClasses; ++k) cnt[k] += (f == k + 1);
-    }
-#pragma unroll
-    for (int k = 0; k < kChunkClasses; ++k)
-        if (cnt[k]) atomicAdd(&s_base[k + 1], cnt[k]);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int k = 1; k <= kChunkClasses; ++k) s_base[k] += s_base[k - 1];
-        for (int k = 0; k <= kChunkClasses; ++k) offset[k] = s_base[k];
+    for (int k = 0; k < kChunkClasses; ++k) {
+        const uint64_t m = __builtin_amdgcn_ballot_w64(f == k + 1);
+        if (lane == 0) s_wave[wave][k] = __popcll(m);
+        if (f == k + 1) mine = m;
     }
     __syncthreads();
-    int32_t running[kChunkClasses];
-#pragma unroll
-    for (int k = 0; k < kChunkClasses; ++k) running[k] = s_base[k];
-    // ordered scatter: ballots give the position inside the wavefront, LDS the counts of the others
-    for (int64_t base = 0; base < num_chunks; base += kCompactBlock) {
-        const int64_t c = base + threadIdx.x;
-        const int32_t f = (c < num_chunks) ? flag[c] : 0;
-        uint64_t mine = 0;
-#pragma unroll
-        for (int k = 0; k < kChunkClasses; ++k) {
-            const uint64_t m = __builtin_amdgcn_ballot_w64(f == k + 1);
-            if (lane == 0) s_wave[wave][k] = __popcll(m);
-            if (f == k + 1) mine = m;
-        }
-        __syncthreads();
-        int32_t before = 0;
-#pragma unroll
-        for (int k = 0; k < kChunkClasses; ++k) {
-            int32_t all = 0;
-            for (int w = 0; w < kWaves; ++w) {
-                const int32_t n = s_wave[w][k];
-                if (w < wave && f == k + 1) before += n;
-                all += n;
-            }
-            if (f == k + 1) before += running[k];
-            running[k] += all;
-        }
-        if (f) list[before + __popcll(mine & ((1ull << lane) - 1))] = (int32_t)c;
-        __syncthreads();
+    if (f) {
+        int32_t before = start[(int64_t)blockIdx.x * kChunkClasses + f - 1];
+        for (int w = 0; w < wave; ++w) before += s_wave[w][f - 1];
+        list[before + __popcll(mine & ((1ull << lane) - 1))] = (int32_t)c;
     }
 }
 
@@ -203,7 +230,8 @@ __global__ __launch_bounds__(kBlock) void chunk_span_kernel(int32_t nrows, int32
     }
 }
 
-// One workgroup of kCompactBlock threads: entries[0] = entries of the narrow chunks (chunk_base >= 0),
+// Totals over the chunks, added to entries_out / narrow_chunks (zero on entry; any number of
+// workgroups of kCompactBlock threads): entries[0] = entries of the narrow chunks (chunk_base >= 0),
 // entries[1] = entries of the framed chunks (chunk_base == -2), entries[2] = entries of the
 // patterned stream chunks (pat_len > 0), entries[3] = sum of their table lengths,
 // entries[4 + k - 1] / entries[4 + kChunkClasses + k - 1] = the last two for class k alone;
@@ -227,7 +255,7 @@ __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nro
     unsigned long long entries = 0, framed = 0, patterned = 0, table = 0;
     unsigned long long cls_entries[kChunkClasses] = {0, 0, 0, 0}, cls_table[kChunkClasses] = {0, 0, 0, 0};
     int32_t chunks[4 * kChunkClasses] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-    for (int64_t c = threadIdx.x; c < num_chunks; c += kCompactBlock) {
+    for (int64_t c = (int64_t)blockIdx.x * kCompactBlock + threadIdx.x; c < num_chunks; c += (int64_t)gridDim.x * kCompactBlock) {
         const int32_t base = chunk_base[c];
         const int32_t cls = chunk_flag[c];
         const int32_t plen = cls != 0 ? pat_len[c] : 0;
@@ -259,8 +287,8 @@ __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nro
     for (int k = 0; k < 4 * kChunkClasses; ++k)
         if (chunks[k]) atomicAdd(&s_chunks[k], chunks[k]);
     __syncthreads();
-    if (threadIdx.x < kTotals) entries_out[threadIdx.x] = s_entries[threadIdx.x];
-    if (threadIdx.x < 4 * kChunkClasses) narrow_chunks[threadIdx.x] = s_chunks[threadIdx.x];
+    if (threadIdx.x < kTotals && s_entries[threadIdx.x]) atomicAdd(&entries_out[threadIdx.x], s_entries[threadIdx.x]);
+    if (threadIdx.x < 4 * kChunkClasses && s_chunks[threadIdx.x]) atomicAdd(&narrow_chunks[threadIdx.x], s_chunks[threadIdx.x]);
 }
 
 // Frames of 2048 columns for the stream chunks that are not narrow (chunk_base == -1 on entry),
@@ -344,7 +372,7 @@ __global__ __launch_bounds__(kBlock) void col16_fill_kernel(int32_t nrows, int32
 // pat_len[c] = length of the table if no row has more than kPatternMaxRow entries, at most
 // kPatternSlots patterns were needed, the table has at most kPatternTableSize diagonals and
 // twice its length does not exceed the chunk's entries; otherwise 0 (and row_pat 0 for the
-// chunk's rows).  Chunks that do not stream get 0 as well.  chunk_rows <= 64.
+// chunk's rows).  Chunks that do not stream get 0 as well.  chunk_rows divides 64.
 constexpr int kPatternMaxRow = 128, kPatternSlots = 8, kPatternTableSize = 512;
 __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                                 const int32_t *__restrict__ chunk_flag,
@@ -366,10 +394,36 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
     for (int p = 0; p < kPatternSlots; ++p) { p_start[p] = 0; p_len[p] = 0; }
     int32_t P = 0, L = 0, mine = 0;
     bool ok = chunk_flag[c] != 0;
-    for (int64_t r = first; r < last && ok; ++r) {     // uniform
-        const int32_t b = rowptr[r], len = rowptr[r + 1] - b;
-        if (len == 0) continue;
-        if (len > kPatternMaxRow) { ok = false; break; }
+    // Most rows repeat the row before them (its columns shifted by one).  That is settled first
+    // for all rows at once, kWave / chunk_rows lanes per row striding its entries; only the rows
+    // that differ from their predecessor go through the comparison with the stored lists below,
+    // the others take their predecessor's answer (the same list, so the same place in the table).
+    const int per_row = kWave / chunk_rows;
+    const int64_t r_mine = first + lane / per_row;
+    const bool has_row = ok && lane / per_row < chunk_rows && r_mine < last;
+    const int32_t b_mine = has_row ? rowptr[r_mine] : 0;
+    const int32_t len_mine = has_row ? rowptr[r_mine + 1] - b_mine : 0;
+    const int32_t b_prev = (has_row && r_mine > first) ? rowptr[r_mine - 1] : b_mine;
+    bool repeats = has_row && r_mine > first && len_mine > 0 && b_mine - b_prev == len_mine;
+    const int32_t longest = wave_max_nonneg(len_mine);
+    if (longest > kPatternMaxRow) ok = false;
+    if (ok) {
+        for (int32_t k = lane % per_row; k < longest; k += per_row)
+            if (repeats && k < len_mine) repeats = colidx[b_mine + k] - colidx[b_prev + k] == 1;
+    }
+    // bit r of `search`: row first + r has entries and does not repeat its predecessor
+    unsigned long long search = 0;
+    {
+        const unsigned long long differs = __ballot(has_row && len_mine > 0 && !repeats);   // per lane
+        for (int r = 0; r < chunk_rows; ++r)
+            if ((differs >> (r * per_row)) & ((1ull << per_row) - 1)) search |= 1ull << r;
+    }
+    const unsigned long long nonempty_lanes = __ballot(has_row && len_mine > 0);
+    for (unsigned long long todo = ok ? search : 0; todo != 0 && ok; todo &= todo - 1) {     // uniform
+        const int t = __builtin_ctzll(todo);
+        const int64_t r = first + t;
+        const int32_t b = __builtin_amdgcn_readlane(b_mine, t * per_row);
+        const int32_t len = __builtin_amdgcn_readlane(len_mine, t * per_row);
         const int32_t d0 = lane < len ? colidx[b + lane] - (int32_t)r : 0;
         const int32_t d1 = lane + kWave < len ? colidx[b + kWave + lane] - (int32_t)r : 0;
         int32_t found = -1;
@@ -395,12 +449,21 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
             P += 1;
             L += len;
         }
-        if (lane == (int)(r - first)) mine = found;
+        if (lane == t) mine = found;
+    }
+    // lane r < chunk_rows answers for row first + r: a row that repeats its predecessor takes the
+    // answer of the nearest searched row below it; empty rows keep 0
+    {
+        const bool my_nonempty = lane < chunk_rows && ((nonempty_lanes >> (lane * per_row)) & 1);
+        const unsigned long long below = lane < chunk_rows ? (search & ((2ull << lane) - 1)) : 0;
+        const int src = below ? 63 - __builtin_clzll(below) : 0;
+        const int32_t taken = __shfl(mine, src, kWave);
+        mine = (my_nonempty && below) ? taken : 0;
     }
     const int32_t entries = rowptr[last] - rowptr[first];
     if (!ok || 2 * L > entries) { L = 0; mine = 0; }
     if (lane == 0) pat_len[c] = L;
-    if (first + lane < last) row_pat[first + lane] = (uint16_t)mine;
+    if (lane < chunk_rows && first + lane < last) row_pat[first + lane] = (uint16_t)mine;
 }
 
 // The tables of the patterned chunks back to back: pool[pat_off[c] + row_pat[i] + k] = diagonal
@@ -574,54 +637,120 @@ __global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t 
 }
 
 
-// One pass over the structure, entry-parallel (each entry finds its row by bisection of rowptr
-// inside the row range of its tile of kCheckTile consecutive entries).  flags must be 0 on entry:
+// The structure check works on tiles of kCheckTile consecutive entries.  tile_first[t] = the row
+// that holds entry t * kCheckTile: the largest r in [0, nrows) with rowptr[r] <= t * kCheckTile
+// (rows before it that start at the same entry are empty), for t = 0 .. num_tiles - 1, and
+// tile_first[num_tiles] = nrows - 1.  One thread per tile; with a rowptr that is not monotone
+// the result is some row id in [0, nrows) all the same.
+constexpr int kCheckTile = kBlock * 8;
+constexpr int kNumCheckFlags = 5;
+__global__ __launch_bounds__(kBlock) void check_tile_rows_kernel(int32_t nrows, int64_t num_tiles,
+                                                                 const int32_t *__restrict__ rowptr,
+                                                                 int32_t *__restrict__ tile_first)
+{
+    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t > num_tiles) return;
+    int32_t lo = 0, hi = nrows - 1;
+    if (t == num_tiles) lo = hi;
+    const int64_t j = t * kCheckTile;
+    while (lo < hi) {
+        const int32_t mid = lo + (hi - lo + 1) / 2;
+        if (rowptr[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    tile_first[t] = lo;
+}
+
+// One pass over the structure, entry-parallel.  A workgroup takes a tile of kCheckTile entries:
+// the rows that start inside the tile leave their id at their first entry's slot in LDS, a
+// running maximum over the slots gives every entry its row (no search per entry), then each
+// thread checks its entries.  flags must be 0 on entry:
 //   flags[0] = 1 if rowptr decreases somewhere     flags[1] = 1 if a column is outside [0, ncols)
 //   flags[2] = max |column - row| over the entries (the half bandwidth)
 //   flags[3] = 1 if some row has a column smaller than its predecessor
 //   flags[4] = 1 if rowptr[0] != 0 or rowptr[nrows] != nnz
 // With flags[0] or flags[4] set, flags[2] and flags[3] are meaningless (every access stays in
-// bounds all the same: row ids stay in [0, nrows) and entry ids in [0, nnz)).  nrows >= 1.
-constexpr int kCheckTile = kBlock * 8;
-constexpr int kNumCheckFlags = 5;
+// bounds all the same: row ids stay in [0, nrows), entry ids in [0, nnz) and LDS slots inside
+// the tile).  nrows >= 1; tile_first comes from check_tile_rows_kernel.
 __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, int64_t ncols, int32_t nnz,
                                                                  const int32_t *__restrict__ rowptr,
                                                                  const int32_t *__restrict__ colidx,
+                                                                 const int32_t *__restrict__ tile_first,
                                                                  int32_t *__restrict__ flags)
 {
+    constexpr int kPer = kCheckTile / kBlock;
+    __shared__ int32_t s_row[kCheckTile + 1];
+    __shared__ int32_t s_scan[kBlock];
     bool bad_row = false, bad_col = false, unsorted = false;
     int32_t best = 0;
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += stride)
         bad_row |= rowptr[i + 1] < rowptr[i];
     if (blockIdx.x == 0 && threadIdx.x == 0 && (rowptr[0] != 0 || rowptr[nrows] != nnz)) flags[4] = 1;
-    // largest row id r in [lo, hi] with rowptr[r] <= j (rows before it that start at the same
-    // entry are empty)
-    auto row_of = [&](int32_t j, int32_t lo, int32_t hi) {
-        while (lo < hi) {
-            const int32_t mid = lo + (hi - lo + 1) / 2;
-            if (rowptr[mid] <= j) lo = mid; else hi = mid - 1;
+    const int tid = threadIdx.x;
+    for (int64_t t = blockIdx.x; t * kCheckTile < nnz; t += gridDim.x) {
+        const int32_t j0 = (int32_t)(t * kCheckTile);
+        const int32_t j1 = (int32_t)((t * kCheckTile + kCheckTile < nnz) ? t * kCheckTile + kCheckTile : nnz);
+        const int32_t first = tile_first[t], next = tile_first[t + 1];
+        __syncthreads();                               // the previous tile's slots are no longer read
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) s_row[i * kBlock + tid] = first;
+        if (tid == 0) s_row[kCheckTile] = next;        // the row of entry j1, for the tile's last entry
+        __syncthreads();
+        // rows first+1 .. next start at an entry in (j0, j1] (when rowptr is monotone)
+        for (int64_t r = (int64_t)first + 1 + tid; r <= next; r += kBlock) {
+            const int32_t at = rowptr[r];
+            if (at > j0 && at < j1) atomicMax(&s_row[at - j0], (int32_t)r);
         }
-        return lo;
-    };
-    for (int64_t t0 = (int64_t)blockIdx.x * kCheckTile; t0 < nnz; t0 += (int64_t)gridDim.x * kCheckTile) {
-        const int32_t j0 = (int32_t)t0;
-        const int32_t j1 = (int32_t)((t0 + kCheckTile < nnz) ? t0 + kCheckTile : nnz);
-        const int32_t first = row_of(j0, 0, nrows - 1), last = row_of(j1 - 1, first, nrows - 1);
-        for (int32_t j = j0 + (int32_t)threadIdx.x; j < j1; j += kBlock) {
-            const int32_t r = row_of(j, first, last);
-            const int32_t c = colidx[j];
-            bad_col |= (c < 0) | (c >= ncols);
-            const int64_t d = (int64_t)c - r;
-            const int64_t ad = d < 0 ? -d : d;
-            best = max(best, (int32_t)(ad < INT32_MAX ? ad : INT32_MAX));
-            if (j + 1 < nnz && j + 1 < rowptr[r + 1]) unsorted |= c > colidx[j + 1];
+        __syncthreads();
+        // running maximum over the slots: thread tid owns slots tid*kPer .. tid*kPer+kPer-1
+        int32_t v[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            v[i] = s_row[tid * kPer + i];
+            if (i > 0) v[i] = max(v[i], v[i - 1]);
+        }
+        s_scan[tid] = v[kPer - 1];
+        __syncthreads();
+        for (int d = 1; d < kBlock; d *= 2) {
+            const int32_t other = tid >= d ? s_scan[tid - d] : 0;
+            __syncthreads();
+            s_scan[tid] = max(s_scan[tid], other);
+            __syncthreads();
+        }
+        const int32_t before = tid > 0 ? s_scan[tid - 1] : 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) s_row[tid * kPer + i] = max(v[i], before);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int32_t pos = i * kBlock + tid;
+            const int32_t j = j0 + pos;
+            if (j < j1) {
+                const int32_t r = s_row[pos];
+                const int32_t c = load_stream(colidx + j);
+                bad_col |= (c < 0) | (c >= ncols);
+                const int64_t d = (int64_t)c - r;
+                const int64_t ad = d < 0 ? -d : d;
+                best = max(best, (int32_t)(ad < INT32_MAX ? ad : INT32_MAX));
+                // the next entry belongs to the same row: its slot (the tile's last entry: the next
+                // tile's first row) holds the same row id
+                const int32_t r_next = s_row[pos + 1 < j1 - j0 ? pos + 1 : kCheckTile];
+                if (j + 1 < nnz && r_next == r) unsorted |= c > colidx[j + 1];
+            }
         }
     }
     if (bad_row) flags[0] = 1;
     if (bad_col) flags[1] = 1;
-    if (best > 0) atomicMax(&flags[2], best);
     if (unsorted) flags[3] = 1;
+    // one atomic per workgroup: atomics of many wavefronts on one address are served one by one
+    best = wave_max_nonneg(best);
+    __syncthreads();
+    if (tid % kWave == 0) s_scan[tid / kWave] = best;
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < kWavesPerBlock; ++w) best = max(best, s_scan[w]);
+        if (best > 0) atomicMax(&flags[2], best);
+    }
 }
 
 // ---- column split of the rows above kWave entries ---------------------------

@@ -289,9 +289,14 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     bool rows_sorted = false;
     if (n > 0) {
         int64_t vblocks = ((n > A->nnz ? n : A->nnz) + kCheckTile - 1) / kCheckTile;
-        if (vblocks > 16384) vblocks = 16384;
+        if (vblocks > 2048) vblocks = 2048;          // 8 per CU; each ends with one atomic on the same word
+        const int64_t check_tiles = (A->nnz + kCheckTile - 1) / kCheckTile;
+        DeviceTemp tile_first;
+        if (int rc = tile_first.alloc(sizeof(int32_t) * ((size_t)check_tiles + 1))) return rc;
+        check_tile_rows_kernel<<<dim3((uint32_t)((check_tiles + 1 + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+            (int32_t)n, check_tiles, A->rowptr, tile_first.as<int32_t>());
         structure_check_kernel<<<dim3((uint32_t)vblocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)n, A->ncols, (int32_t)A->nnz, A->rowptr, A->colidx, d_flags);
+            (int32_t)n, A->ncols, (int32_t)A->nnz, A->rowptr, A->colidx, tile_first.as<int32_t>(), d_flags);
         LAPIS_HIP(hipGetLastError());
         int32_t flags[kNumCheckFlags] = {0};
         if (int rc = read_back(flags, d_flags, sizeof(flags), stream)) return rc;
@@ -358,14 +363,23 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         chunk_patterns_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->colidx,
             pat_len.as<int32_t>(), A->d_row_pat);
-        narrow_count_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
+        LAPIS_HIP(hipMemsetAsync(d_counts, 0, sizeof(NarrowCounts), stream));
+        const uint32_t count_blocks = (uint32_t)((num_chunks + 4 * kCompactBlock - 1) / (4 * kCompactBlock));
+        narrow_count_kernel<<<dim3(count_blocks < 256 ? count_blocks : 256), dim3(kCompactBlock), 0, stream>>>(
             (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, chunk_flag.as<int32_t>(), A->rowptr, A->d_chunk_base,
             pat_len.as<int32_t>(), d_counts->entries, d_counts->chunks);
         static_assert(kChunkClasses == kStreamClasses, "one list per stream class");
         DeviceTemp offsets;
         if (int rc = offsets.alloc(sizeof(int32_t) * (kStreamClasses + 1))) return rc;
-        chunk_compact_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(
-            num_chunks, chunk_flag.as<int32_t>(), A->d_stream_chunks, offsets.as<int32_t>());
+        const int32_t compact_blocks = (num_chunks + kCompactBlock - 1) / kCompactBlock;
+        DeviceTemp class_hist;
+        if (int rc = class_hist.alloc(sizeof(int32_t) * (size_t)compact_blocks * kChunkClasses)) return rc;
+        chunk_class_hist_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
+            num_chunks, chunk_flag.as<int32_t>(), class_hist.as<int32_t>());
+        chunk_class_scan_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(compact_blocks, class_hist.as<int32_t>(),
+                                                                             offsets.as<int32_t>());
+        chunk_compact_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
+            num_chunks, chunk_flag.as<int32_t>(), class_hist.as<int32_t>(), A->d_stream_chunks);
         LAPIS_HIP(hipGetLastError());
         if (int rc = read_back(A->h_stream_offset, offsets.as<int32_t>(), sizeof(int32_t) * (kStreamClasses + 1), stream)) return rc;
         num_stream = A->h_stream_offset[kStreamClasses];
