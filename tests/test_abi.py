@@ -50,6 +50,11 @@ def test_header_constants_match_library_and_oracle(lib):
     assert (c["num_bins"], c["wave"], c["long_threshold"], c["tile_nnz"], c["stream_rows"],
             c["stream_min_nnz"]) == (oracle.NUM_BINS, oracle.WAVE, oracle.LONG_THRESHOLD, oracle.TILE_NNZ,
                                      oracle.STREAM_ROWS, oracle.STREAM_MIN_NNZ)
+    # the row-pattern limits are compile-time constants of the library (a static_assert ties its
+    # kernels to the header); the oracle keeps its own copies
+    assert macro("LAPIS_PATTERN_MAX_ROW") == oracle.PATTERN_MAX_ROW
+    assert macro("LAPIS_PATTERN_SLOTS") == oracle.PATTERN_SLOTS
+    assert macro("LAPIS_PATTERN_TABLE") == oracle.PATTERN_TABLE
 
 
 def _create(lib, nrows, ncols, nnz, rowptr, colidx, vals, dtype, out=True):
