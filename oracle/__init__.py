@@ -70,6 +70,9 @@ def _load():
         lib.oracle_partition_stream_chunks.restype = i64
         lib.oracle_index16.argtypes = [i64, p, p, i64, i64, p, p, p, p, p]
         lib.oracle_index16.restype = None
+        for name in ("oracle_batched_gemm_f64", "oracle_batched_gemm_f32"):
+            getattr(lib, name).argtypes = [i64, i64, i64, i64, ctypes.c_double, p, p, ctypes.c_double, p, p, p]
+            getattr(lib, name).restype = None
         lib.oracle_row_patterns.argtypes = [i64, p, p, i64, i64, p, i64, i64, i64, p, p, p, p]
         lib.oracle_row_patterns.restype = None
         lib.oracle_partition_rows.argtypes = [i64, p, i64, i64, i64, i64, i64, p, p, p, p, p]
@@ -160,6 +163,25 @@ def spmm(rowptr, colidx, vals, X, alpha=1.0, beta=0.0, Y0=None):
     fn(n, k, _p(rowptr), _p(colidx), _p(vals), _p(X), ldx, float(alpha), float(beta),
        _p(Y0) if beta != 0.0 else None, _p(Y), k, _p(absAX))
     return Y, absAX
+
+
+def batched_gemm(A, B, alpha=1.0, beta=0.0, C0=None):
+    """Returns (C, absAB): C[b] = alpha*A[b]@B[b] + beta*C0[b] in A.dtype for A (batch, m, k) and
+    B (batch, k, n), and sum_l |A[b,i,l]||B[b,l,j]| in float64."""
+    assert A.ndim == 3 and B.ndim == 3 and A.shape[0] == B.shape[0] and A.shape[2] == B.shape[1]
+    assert A.dtype == B.dtype and A.dtype in (np.float32, np.float64)
+    batch, m, k = A.shape
+    n = B.shape[2]
+    A = np.ascontiguousarray(A)
+    B = np.ascontiguousarray(B)
+    if beta != 0.0:
+        assert C0 is not None and C0.shape == (batch, m, n)
+        C0 = np.ascontiguousarray(C0, dtype=A.dtype)
+    C = np.empty((batch, m, n), dtype=A.dtype)
+    absAB = np.empty((batch, m, n), dtype=np.float64)
+    fn = _load().oracle_batched_gemm_f64 if A.dtype == np.float64 else _load().oracle_batched_gemm_f32
+    fn(batch, m, n, k, float(alpha), _p(A), _p(B), float(beta), _p(C0) if beta != 0.0 else None, _p(C), _p(absAB))
+    return C, absAB
 
 
 def demoted_chunks(rowptr, colidx, ncols, itemsize, wave=WAVE, stream_rows=STREAM_ROWS,

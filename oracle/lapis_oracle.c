@@ -134,6 +134,49 @@ void oracle_transpose(int64_t nrows, int64_t ncols, const int32_t *rowptr, const
     tptr[0] = 0;
 }
 
+/* ---- Batched GEMM (Section 5, the batched kernel the paper lowers with the batch dimension
+ * vectorised): for every b < batch, C[b] = alpha * A[b] * B[b] + beta * C0[b] with A[b] m x k,
+ * B[b] k x n, C[b] m x n, each matrix row-major and the matrices of an operand back to back.
+ * The plain definition: one dot product per element, summed left to right in double (f32
+ * operands promoted, the result rounded once).  absAB (may be NULL) receives sum |a||b| for the
+ * tolerance.  beta == 0: C0 is not read. ---------------------------------------------------- */
+void oracle_batched_gemm_f64(int64_t batch, int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                             const double *B, double beta, const double *C0, double *C, double *absAB)
+{
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                double s = 0.0, t = 0.0;
+                for (int64_t l = 0; l < k; ++l) {
+                    double x = A[(b * m + i) * k + l], y = B[(b * k + l) * n + j];
+                    s += x * y;
+                    t += fabs(x) * fabs(y);
+                }
+                int64_t at = (b * m + i) * n + j;
+                C[at] = (beta == 0.0) ? alpha * s : alpha * s + beta * C0[at];
+                if (absAB) absAB[at] = t;
+            }
+}
+
+void oracle_batched_gemm_f32(int64_t batch, int64_t m, int64_t n, int64_t k, double alpha, const float *A,
+                             const float *B, double beta, const float *C0, float *C, double *absAB)
+{
+    for (int64_t b = 0; b < batch; ++b)
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                double s = 0.0, t = 0.0;
+                for (int64_t l = 0; l < k; ++l) {
+                    double x = (double)A[(b * m + i) * k + l], y = (double)B[(b * k + l) * n + j];
+                    s += x * y;
+                    t += fabs(x) * fabs(y);
+                }
+                int64_t at = (b * m + i) * n + j;
+                double r = (beta == 0.0) ? alpha * s : alpha * s + beta * (double)C0[at];
+                C[at] = (float)r;
+                if (absAB) absAB[at] = t;
+            }
+}
+
 /* ---- SpMM: Y = alpha*A*X + beta*Y0, X, Y0, Y row-major with leading
  * dimensions ldx, ldy (Y0 and Y share ldy); absAX is nrows*k contiguous.
  * Column c is by definition the SpMV with column c of X. ------------------- */
