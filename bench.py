@@ -50,6 +50,59 @@ VARIANT_KERNEL = {"paper-shape": "spmv_vector_kernel", "transpose": "transpose_s
                   "host-buffers": "all kernels and copies of the step"}
 
 
+def batched_gemm_bench(args, scale, torch, gen, L, dev):
+    """One step = one lapis_batched_gemm over the whole batch; bytes = A + B + C once each."""
+    batch, m = int(scale.get("batch", 1 << 20)), int(scale.get("m", 8))
+    n, k = int(scale.get("n", m)), int(scale.get("k", m))
+    dt = np.float32 if scale.get("f32") else np.float64
+    A = gen.uniform(20250925, gen.STREAM_VALUES, batch * m * k).reshape(batch, m, k).astype(dt)
+    B = gen.uniform(20250925, gen.STREAM_X, batch * k * n).reshape(batch, k, n).astype(dt)
+    dA, dB = torch.from_numpy(A).to(dev), torch.from_numpy(B).to(dev)
+    dC = torch.zeros((batch, m, n), dtype=dA.dtype, device=dev)
+    code = L.LAPIS_F64 if dt == np.float64 else L.LAPIS_F32
+    step = lambda: L.lapis_batched_gemm(batch, m, n, k, 1.0, dA, dB, 0.0, dC, code)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    stop.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - wall0) * 1e3 / args.steps
+    kernel_ms = start.elapsed_time(stop) / args.steps
+    nbytes = batch * (m * k + k * n + m * n) * A.itemsize
+    flops = 2.0 * batch * m * n * k
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        sample = min(batch, max(1, int(2e8 / (m * n * k))))      # about a second per pass
+        best, spent, reps = float("inf"), 0.0, 0
+        while spent < args.cpu_seconds or reps < 3:
+            t = time.perf_counter()
+            oracle.batched_gemm(A[:sample], B[:sample])
+            d = time.perf_counter() - t
+            best, spent, reps = min(best, d), spent + d, reps + 1
+        cpu = {"value": round(nbytes * (sample / batch) / best / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {sample} of {batch} products, best of {reps} serial passes ({best * 1e3:.1f} ms each), "
+                         f"1 of {os.cpu_count()} host cores"}
+    achieved = nbytes / (kernel_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "batched GEMM effective HBM GB/s (A+B+C bytes / time); gflops alongside",
+        "value": round(nbytes / (ms_per_step * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64" if dt == np.float64 else "f32", "data": "synthetic",
+        "config": {"workload": f"batched_gemm_{batch}x{m}x{n}x{k}_{'f64' if dt == np.float64 else 'f32'}",
+                   "bytes_per_step": nbytes, "variant": "batched-gemm"},
+        "gflops": round(flops / (ms_per_step * 1e-3) / 1e9, 2),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
+                     "kernel": "batched_gemm_kernel", "kernel_ms": round(kernel_ms, 6)},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,12 +116,15 @@ def main():
                          "(labelled in config.workload; the default sizes are the benchmark's)")
     ap.add_argument("--zipf-s", type=float, default=None,
                     help="workload 4 only: Zipf exponent (default 1.8; 2.0 gives the 'mean about 8' variant)")
-    ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers"], default="tuned",
+    ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers",
+                                          "batched-gemm"], default="tuned",
                     help="paper-shape: the single-vector-length kernel of the paper's loop mapping; "
                          "transpose: y = alpha*A^T*x + beta*y (column-wise traversal, atomics); transposed-handle: "
                          "the same product through a handle for A^T built on the device; host-buffers: the "
                          "product on lazily synchronised host buffers with x rewritten on the host and y "
-                         "read back every step (PCIe-inclusive rate, never the headline value)")
+                         "read back every step (PCIe-inclusive rate, never the headline value); batched-gemm: "
+                         "lapis_batched_gemm on 2^20 products of 8 x 8 doubles (--scale batch=,m=,n=,k=,f32=1 "
+                         "to change that), a workload of its own, --config is ignored")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -100,6 +156,9 @@ def main():
         for item in args.scale.split(","):
             key, val = item.split("=")
             scale[key.strip()] = float(val) if "." in val else int(val)
+    if args.variant == "batched-gemm":
+        batched_gemm_bench(args, scale, torch, gen, L, dev)
+        return
     if args.zipf_s is not None and args.config == 4:
         scale["s"] = args.zipf_s
     w = gen.workload(args.config, scale or None)

@@ -371,6 +371,26 @@ int lapis_dualview_destroy(lapis_dualview_t *v);
 int lapis_spmv_dualview(const lapis_csr_t *A, double alpha, lapis_dualview_t *x, double beta,
                         lapis_dualview_t *y, void *hip_stream);
 
+/*
+ * lapis_batched_gemm - C[b] = alpha * A[b] * B[b] + beta * C[b] for b = 0 .. batch-1, many small
+ * dense products (Section 5 of the paper: the batched kernel, for which the batch dimension is
+ * the one to vectorise because the matrices themselves are small).
+ *   d_A  DEVICE [batch][m][k], d_B  DEVICE [batch][k][n], d_C  DEVICE [batch][m][n], values of
+ *        `dtype` (LAPIS_F32 / LAPIS_F64), every matrix row-major and the matrices of an operand
+ *        back to back (a contiguous (batch, rows, cols) tensor); borrowed for the call; C must
+ *        not overlap A or B
+ *   1 <= m, n, k <= LAPIS_BATCHED_MAX_DIM; batch >= 0 (0: nothing is done, pointers may be NULL)
+ *   alpha, beta are rounded to dtype; beta == 0: C is write-only (NaN or Inf in old C does not
+ *   propagate)
+ * Every element is one dot product summed over l = 0 .. k-1 in that order, in dtype.
+ * Asynchronous on hip_stream (NULL = default stream): no allocation, no copy, no host
+ * synchronisation.  Errors: LAPIS_ERR_INVALID_ARG (sizes out of range, NULL operand with
+ * batch > 0), LAPIS_ERR_UNSUPPORTED (dtype), LAPIS_ERR_DEVICE (launch failure).
+ */
+#define LAPIS_BATCHED_MAX_DIM 32
+int lapis_batched_gemm(int64_t batch, int32_t m, int32_t n, int32_t k, double alpha, const void *d_A,
+                       const void *d_B, double beta, void *d_C, int dtype, void *hip_stream);
+
 /* Text of the most recent error on the calling thread ("" if none).  The
  * pointer stays valid until the next failing call on that thread. */
 const char *lapis_last_error(void);

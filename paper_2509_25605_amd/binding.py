@@ -28,6 +28,7 @@ EXPORTS = [
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
     "lapis_dualview_sync_host", "lapis_dualview_copy_counts", "lapis_dualview_destroy",
     "lapis_spmv_dualview",
+    "lapis_batched_gemm",
     "lapis_last_error",
 ]
 
@@ -84,6 +85,7 @@ def load() -> ctypes.CDLL:
             getattr(lib, name).argtypes = [p, p]
         lib.lapis_dualview_copy_counts.argtypes = [p, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         lib.lapis_spmv_dualview.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_batched_gemm.argtypes = [i64, i32, i32, i32, f64, p, p, f64, p, i32, p]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
         lib.lapis_dualview_host.restype = p
@@ -209,6 +211,13 @@ def lapis_paper_vector_length(nrows, nnz):
 def lapis_spmm(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream=None):
     _check(load().lapis_spmm(A, k, float(alpha), _addr(d_X), ldx, float(beta), _addr(d_Y), ldy,
                              _stream(stream)))
+
+
+def lapis_batched_gemm(batch, m, n, k, alpha, d_A, d_B, beta, d_C, dtype, stream=None):
+    """C[b] = alpha*A[b]@B[b] + beta*C[b] on contiguous device tensors (batch, m, k), (batch, k, n),
+    (batch, m, n); dtype is LAPIS_F32 or LAPIS_F64."""
+    _check(load().lapis_batched_gemm(batch, m, n, k, float(alpha), _addr(d_A), _addr(d_B), float(beta),
+                                     _addr(d_C), dtype, _stream(stream)))
 
 
 def lapis_csr_destroy(A):

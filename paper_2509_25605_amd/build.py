@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblapis_mi355x.so")
-SOURCES = ["lapis_api.hip", "dualview.hip"]
+SOURCES = ["lapis_api.hip", "dualview.hip", "batched_gemm.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instructions are kept off for every HIP translation unit
