@@ -7,7 +7,7 @@
 // One wavefront = one workgroup takes E consecutive batch entries (E a power of two, as many as
 // fit in its LDS tile).  Their A and B matrices are one contiguous piece of memory each, which
 // the wavefront streams into LDS with coalesced loads; P = 64 / E lanes then share one entry and
-// each lane computes strips of 4 consecutive elements of a row of C out of LDS.  The kernel is
+// each lane computes strips of 16 bytes (2 doubles, 4 floats) of a row of C out of LDS.  The kernel is
 // bound by HBM (2 m n k flops for (m k + k n + m n [+ m n]) values), so everything is arranged
 // around wide, contiguous global accesses.  Contracts of the entry point are in include/lapis.h.
 #include <hip/hip_runtime.h>
@@ -22,9 +22,11 @@
 namespace lapis {
 
 constexpr int kGemmMaxDim = LAPIS_BATCHED_MAX_DIM;
-// LDS tile of a wavefront: one entry of the largest size must fit, (2 * 32 * 32 + 1) doubles
-constexpr int kGemmTileBytes = (2 * kGemmMaxDim * kGemmMaxDim + 1) * 8;
-constexpr int kGemmStrip = 4;                        // consecutive elements of a row of C per work item
+// LDS tile of a wavefront: one entry of the largest size must fit ((2 * 32 * 32 + 1) doubles), and
+// 16 entries of 8 x 8 doubles with their padding; 9 wavefronts per CU
+constexpr int kGemmTileBytes = 2080 * 8;
+static_assert(kGemmTileBytes >= (2 * kGemmMaxDim * kGemmMaxDim + 1) * 8, "one entry of the largest size must fit");
+constexpr int kGemmMaxVec = (kGemmTileBytes / 16 + kWave - 1) / kWave;      // 16-byte loads per lane and tile
 
 // floor(g / d) for 0 <= g < 2^20 and 1 <= d (inv = 1.0f / d): the float estimate is off by at
 // most one either way
@@ -36,13 +38,43 @@ __device__ __forceinline__ uint32_t small_div(uint32_t g, uint32_t d, float inv)
     return q;
 }
 
-// stride: LDS elements per entry (m*k + k*n, plus one if that is even: an odd stride keeps the
-// lanes of different entries on different banks); entries_per_wave = E.
+// `count` consecutive elements from src into the tile: element g goes to entry g / d at offset
+// shift + g % d; 4 loads in flight per lane (the path for tiles that are not full or not aligned)
 template <typename T>
+__device__ __forceinline__ void stage_scalar(const T *__restrict__ src, uint32_t count, uint32_t d, uint32_t shift,
+                                             int stride, int lane, T *s_tile)
+{
+    const float inv = 1.0f / (float)d;
+    for (uint32_t g0 = 0; g0 < count; g0 += 4 * kWave) {         // uniform
+        T v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t g = g0 + q * kWave + lane;
+            v[q] = load_stream(src + (g < count ? g : count - 1));
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t g = g0 + q * kWave + lane;
+            if (g < count) {
+                const uint32_t e = small_div(g, d, inv);
+                s_tile[e * stride + shift + (g - e * d)] = v[q];
+            }
+        }
+    }
+}
+
+// stride: LDS elements per entry (m*k + k*n, plus one if that is even: an odd stride keeps the
+// lanes of different entries on different banks); entries_per_wave = E.  VEC: the A and B pieces
+// of a full tile are multiples of 16 bytes and A, B are 16-byte aligned.  VECC: every strip of C
+// is 16 bytes at a 16-byte aligned address (C aligned, n a multiple of the strip).
+// RB: rows of C per work item (a b value read from LDS serves RB products).
+template <typename T, bool VEC, bool VECC, int RB>
 __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     int64_t batch, int m, int n, int k, int entries_per_wave, int stride, T alpha, const T *__restrict__ A,
     const T *__restrict__ B, T beta, T *__restrict__ C)
 {
+    constexpr int kGemmStrip = 16 / (int)sizeof(T);                // elements of a row of C per work item
+    typedef T vec_t __attribute__((ext_vector_type(16 / sizeof(T))));
     __shared__ __attribute__((aligned(16))) T s_tile[kGemmTileBytes / sizeof(T)];
     const int lane = threadIdx.x;
     const int E = entries_per_wave;
@@ -52,83 +84,118 @@ __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     const uint32_t mk = (uint32_t)(m * k), kn = (uint32_t)(k * n), mn = (uint32_t)(m * n);
 
     // stream the tile's A and B matrices into LDS: element g of the contiguous piece belongs to
-    // entry g / mk (g / kn); 4 loads in flight per lane
-    {
-        const T *__restrict__ src = A + b0 * mk;
-        const uint32_t count = (uint32_t)here * mk;
-        const float inv = 1.0f / (float)mk;
-        for (uint32_t g0 = 0; g0 < count; g0 += 4 * kWave) {         // uniform
-            T v[4];
+    // entry g / mk (g / kn)
+    if (VEC && here == E) {
+        // a full tile whose pieces are multiples of 16 bytes at 16-byte aligned addresses (the host
+        // checked): every 16-byte load of the tile is issued before the first value is stored
+        constexpr int kPer = 16 / (int)sizeof(T);
+        const uint32_t va = (uint32_t)E * mk / kPer, vb = (uint32_t)E * kn / kPer;
+        const vec_t *__restrict__ src_a = reinterpret_cast<const vec_t *>(A + b0 * mk);
+        const vec_t *__restrict__ src_b = reinterpret_cast<const vec_t *>(B + b0 * kn);
+        const float inv_a = 1.0f / (float)mk, inv_b = 1.0f / (float)kn;
+        const bool whole_a = mk % kPer == 0, whole_b = kn % kPer == 0;       // uniform
+        vec_t v[kGemmMaxVec];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t g = g0 + q * kWave + lane;
-                v[q] = load_stream(src + (g < count ? g : count - 1));
+        for (int q = 0; q < kGemmMaxVec; ++q) {
+            if ((uint32_t)(q * kWave) < va + vb) {                     // uniform
+                uint32_t h = q * kWave + lane;
+                h = h < va + vb ? h : va + vb - 1;
+                v[q] = __builtin_nontemporal_load(h < va ? src_a + h : src_b + (h - va));
             }
+        }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t g = g0 + q * kWave + lane;
-                if (g < count) {
-                    const uint32_t e = small_div(g, mk, inv);
-                    s_tile[e * stride + (g - e * mk)] = v[q];
+        for (int q = 0; q < kGemmMaxVec; ++q) {
+            if ((uint32_t)(q * kWave) < va + vb) {
+                const uint32_t h = q * kWave + lane;
+                if (h < va + vb) {
+                    const bool in_a = h < va;
+                    const uint32_t d = in_a ? mk : kn, first = (in_a ? h : h - va) * kPer;
+                    const float inv = in_a ? inv_a : inv_b;
+                    const uint32_t shift = in_a ? 0 : mk;
+                    if (whole_a && whole_b) {              // a vector never straddles two entries
+                        const uint32_t e = small_div(first, d, inv);
+                        T *dst = s_tile + e * stride + shift + (first - e * d);
+#pragma unroll
+                        for (int t = 0; t < kPer; ++t) dst[t] = v[q][t];
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < kPer; ++t) {
+                            const uint32_t g = first + t;
+                            const uint32_t e = small_div(g, d, inv);
+                            s_tile[e * stride + shift + (g - e * d)] = v[q][t];
+                        }
+                    }
                 }
             }
         }
-    }
-    {
-        const T *__restrict__ src = B + b0 * kn;
-        const uint32_t count = (uint32_t)here * kn;
-        const float inv = 1.0f / (float)kn;
-        for (uint32_t g0 = 0; g0 < count; g0 += 4 * kWave) {         // uniform
-            T v[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t g = g0 + q * kWave + lane;
-                v[q] = load_stream(src + (g < count ? g : count - 1));
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t g = g0 + q * kWave + lane;
-                if (g < count) {
-                    const uint32_t e = small_div(g, kn, inv);
-                    s_tile[e * stride + mk + (g - e * kn)] = v[q];
-                }
-            }
-        }
+    } else {
+        stage_scalar(A + b0 * mk, (uint32_t)here * mk, mk, 0u, stride, lane, s_tile);
+        stage_scalar(B + b0 * kn, (uint32_t)here * kn, kn, mk, stride, lane, s_tile);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    // lane (e, p): work items p, p + P, ... of entry e; item w = (row i, strip of 4 columns)
+    // lane (e, p): work items p, p + P, ... of entry e; item w = (block of RB rows, strip of 16
+    // bytes of them)
     const int e = lane / P, p = lane % P;
     if (e >= here) return;
     const int strips = (n + kGemmStrip - 1) / kGemmStrip;
-    const int items = m * strips;
+    const int items = ((m + RB - 1) / RB) * strips;
     const float inv_strips = 1.0f / (float)strips;
     const T *a_lds = s_tile + e * stride;
     const T *b_lds = a_lds + mk;
     T *__restrict__ c_out = C + (b0 + e) * mn;
     for (int w = p; w < items; w += P) {
-        const int i = (int)small_div((uint32_t)w, (uint32_t)strips, inv_strips);
-        const int j0 = (w - i * strips) * kGemmStrip;
-        // columns past n repeat column n - 1 and are not stored
+        const int ib = (int)small_div((uint32_t)w, (uint32_t)strips, inv_strips);
+        const int i0 = ib * RB;
+        const int j0 = (w - ib * strips) * kGemmStrip;
+        // rows past m repeat row m - 1, columns past n column n - 1; neither is stored
         int col[kGemmStrip];
 #pragma unroll
         for (int q = 0; q < kGemmStrip; ++q) col[q] = j0 + q < n ? j0 + q : n - 1;
-        T acc[kGemmStrip];
+        const T *a_row[RB];
 #pragma unroll
-        for (int q = 0; q < kGemmStrip; ++q) acc[q] = T(0);
-        const T *a_row = a_lds + i * k;
+        for (int r = 0; r < RB; ++r) a_row[r] = a_lds + (i0 + r < m ? i0 + r : m - 1) * k;
+        T acc[RB][kGemmStrip];
+#pragma unroll
+        for (int r = 0; r < RB; ++r)
+#pragma unroll
+            for (int q = 0; q < kGemmStrip; ++q) acc[r][q] = T(0);
         for (int l = 0; l < k; ++l) {
-            const T a = a_row[l];
             const T *b_row = b_lds + l * n;
+            T bv[kGemmStrip];
 #pragma unroll
-            for (int q = 0; q < kGemmStrip; ++q) acc[q] += a * b_row[col[q]];
+            for (int q = 0; q < kGemmStrip; ++q) bv[q] = b_row[col[q]];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const T a = a_row[r][l];
+#pragma unroll
+                for (int q = 0; q < kGemmStrip; ++q) acc[r][q] += a * bv[q];
+            }
         }
-        T *dst = c_out + i * n + j0;
 #pragma unroll
-        for (int q = 0; q < kGemmStrip; ++q) {
-            if (j0 + q < n) dst[q] = beta == T(0) ? alpha * acc[q] : alpha * acc[q] + beta * dst[q];
+        for (int r = 0; r < RB; ++r) {
+            if (i0 + r < m) {
+                T *dst = c_out + (i0 + r) * n + j0;
+                if constexpr (VECC) {
+                    vec_t out;
+                    if (beta == T(0)) {
+#pragma unroll
+                        for (int q = 0; q < kGemmStrip; ++q) out[q] = alpha * acc[r][q];
+                    } else {
+                        const vec_t old = *reinterpret_cast<const vec_t *>(dst);
+#pragma unroll
+                        for (int q = 0; q < kGemmStrip; ++q) out[q] = alpha * acc[r][q] + beta * old[q];
+                    }
+                    *reinterpret_cast<vec_t *>(dst) = out;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < kGemmStrip; ++q) {
+                        if (j0 + q < n) dst[q] = beta == T(0) ? alpha * acc[r][q] : alpha * acc[r][q] + beta * dst[q];
+                    }
+                }
+            }
         }
     }
 }
@@ -144,9 +211,28 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
     while (E > 1 && E * stride > capacity) E /= 2;
     const int64_t tiles = (batch + E - 1) / E;
     if (tiles > INT32_MAX) return fail(LAPIS_ERR_INVALID_ARG, "lapis_batched_gemm: batch is too large");
-    batched_gemm_kernel<T><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(
-        batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,
-        static_cast<T *>(C));
+    const bool vec = reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0 &&
+                     ((size_t)E * m * k * sizeof(T)) % 16 == 0 && ((size_t)E * k * n * sizeof(T)) % 16 == 0;
+    const int strip = 16 / (int)sizeof(T);
+    const bool vecc = reinterpret_cast<uintptr_t>(C) % 16 == 0 && n % strip == 0;
+    // blocks of 4 rows per work item when that still leaves every lane of an entry an item
+    const int P = kWave / E;
+    const bool blocked = ((m + 3) / 4) * ((n + strip - 1) / strip) >= P;
+#define LAPIS_GEMM_LAUNCH(VEC, VECC, RB)                                                                        \
+    batched_gemm_kernel<T, VEC, VECC, RB><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(                   \
+        batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,     \
+        static_cast<T *>(C))
+#define LAPIS_GEMM_PICK(VEC, VECC)                       \
+    do {                                                 \
+        if (blocked) LAPIS_GEMM_LAUNCH(VEC, VECC, 4);    \
+        else LAPIS_GEMM_LAUNCH(VEC, VECC, 1);            \
+    } while (0)
+    if (vec && vecc) LAPIS_GEMM_PICK(true, true);
+    else if (vec) LAPIS_GEMM_PICK(true, false);
+    else if (vecc) LAPIS_GEMM_PICK(false, true);
+    else LAPIS_GEMM_PICK(false, false);
+#undef LAPIS_GEMM_PICK
+#undef LAPIS_GEMM_LAUNCH
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return fail(LAPIS_ERR_DEVICE, std::string("lapis_batched_gemm: ") + hipGetErrorString(err));
     return LAPIS_OK;
