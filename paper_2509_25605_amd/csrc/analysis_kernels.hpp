@@ -643,7 +643,7 @@ __global__ __launch_bounds__(kBlock) void tile_search_kernel(int32_t m, int64_t 
 // tile_first[num_tiles] = nrows - 1.  One thread per tile; with a rowptr that is not monotone
 // the result is some row id in [0, nrows) all the same.
 constexpr int kCheckTile = kBlock * 8;
-constexpr int kNumCheckFlags = 5;
+constexpr int kNumCheckFlags = 6;
 __global__ __launch_bounds__(kBlock) void check_tile_rows_kernel(int32_t nrows, int64_t num_tiles,
                                                                  const int32_t *__restrict__ rowptr,
                                                                  int32_t *__restrict__ tile_first)
@@ -668,7 +668,8 @@ __global__ __launch_bounds__(kBlock) void check_tile_rows_kernel(int32_t nrows, 
 //   flags[2] = max |column - row| over the entries (the half bandwidth)
 //   flags[3] = 1 if some row has a column smaller than its predecessor
 //   flags[4] = 1 if rowptr[0] != 0 or rowptr[nrows] != nnz
-// With flags[0] or flags[4] set, flags[2] and flags[3] are meaningless (every access stays in
+//   flags[5] = number of entries followed, in their row, by the next column (runs of columns)
+// With flags[0] or flags[4] set, flags[2], flags[3] and flags[5] are meaningless (every access stays in
 // bounds all the same: row ids stay in [0, nrows), entry ids in [0, nnz) and LDS slots inside
 // the tile).  nrows >= 1; tile_first comes from check_tile_rows_kernel.
 __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, int64_t ncols, int32_t nnz,
@@ -681,7 +682,7 @@ __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, 
     __shared__ int32_t s_row[kCheckTile + 1];
     __shared__ int32_t s_scan[kBlock];
     bool bad_row = false, bad_col = false, unsorted = false;
-    int32_t best = 0;
+    int32_t best = 0, in_runs = 0;                     // in_runs: per wavefront (ballot counts)
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < nrows; i += stride)
         bad_row |= rowptr[i + 1] < rowptr[i];
@@ -725,6 +726,7 @@ __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, 
         for (int i = 0; i < kPer; ++i) {
             const int32_t pos = i * kBlock + tid;
             const int32_t j = j0 + pos;
+            bool continues = false;
             if (j < j1) {
                 const int32_t r = s_row[pos];
                 const int32_t c = load_stream(colidx + j);
@@ -735,8 +737,13 @@ __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, 
                 // the next entry belongs to the same row: its slot (the tile's last entry: the next
                 // tile's first row) holds the same row id
                 const int32_t r_next = s_row[pos + 1 < j1 - j0 ? pos + 1 : kCheckTile];
-                if (j + 1 < nnz && r_next == r) unsorted |= c > colidx[j + 1];
+                if (j + 1 < nnz && r_next == r) {
+                    const int32_t c_next = colidx[j + 1];
+                    unsorted |= c > c_next;
+                    continues = c_next == c + 1;
+                }
             }
+            in_runs += (int32_t)__popcll(__ballot(continues));
         }
     }
     if (bad_row) flags[0] = 1;
@@ -750,6 +757,14 @@ __global__ __launch_bounds__(kBlock) void structure_check_kernel(int32_t nrows, 
     if (tid == 0) {
         for (int w = 1; w < kWavesPerBlock; ++w) best = max(best, s_scan[w]);
         if (best > 0) atomicMax(&flags[2], best);
+    }
+    __syncthreads();
+    if (tid % kWave == 0) s_scan[tid / kWave] = in_runs;
+    __syncthreads();
+    if (tid == 0) {
+        int32_t total = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) total += s_scan[w];
+        if (total > 0) atomicAdd(&flags[5], total);
     }
 }
 

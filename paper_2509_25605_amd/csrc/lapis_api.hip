@@ -69,6 +69,7 @@ struct lapis_csr {
     bool class_all16[kStreamClasses] = {false, false, false, false};   // every chunk of the class has a base
     bool class_allframed[kStreamClasses] = {false, false, false, false};   // every chunk of the class is framed
     bool class_allcoded[kStreamClasses] = {false, false, false, false};    // every chunk is one or the other
+    bool scattered_columns = false;      // few entries continue a run of consecutive columns (see launch_stream)
     // level 1c: row patterns (kept when the patterned chunks hold at least half of the entries)
     int32_t *d_pat_off = nullptr;        // [num_chunks + 1] exclusive scan of the chunks' table lengths
     uint16_t *d_row_pat = nullptr;       // [nrows] start of the row's pattern in its chunk's table
@@ -305,6 +306,9 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
         if (flags[1]) return fail(LAPIS_ERR_INVALID_ARG, "a column index is outside [0, ncols)");
         A->half_bandwidth = flags[2];
         rows_sorted = !flags[3];
+        // entries whose successor in the row is the next column: below a quarter of the entries the
+        // gathers of a chunk mostly touch a cache line each
+        A->scattered_columns = A->nnz > 0 && 4 * (int64_t)flags[5] < A->nnz;
     } else if (A->nnz != 0) {
         return fail(LAPIS_ERR_INVALID_ARG, "nnz must be 0 when nrows is 0");
     }
@@ -614,6 +618,20 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
         (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base,        \
         A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},              \
         static_cast<const T *>(A->vals), x, y, a, b)
+    // With scattered columns every gather is a cache line of its own and the time goes into L1
+    // misses: the wavefronts of a chunk then run as one workgroup, on one CU, where the lines one
+    // of them fetched serve the others (stand-ins 7 and 9: 143 -> 137 us, 309 -> 291 us).  Where
+    // columns come in runs the same grouping costs time (Elasticity3D stand-in 94 -> 107 us).
+    if constexpr (G >= 4) {
+        if (A->scattered_columns && A->class_all16[cls - 1] && !A->class_allpattern[cls - 1] && !A->class_pattern16[cls - 1]) {
+            const uint32_t groups = (uint32_t)count, pgroups = (groups + kXcds - 1) / kXcds * kXcds;
+            spmv_stream_kernel<T, G, true, kColsNarrow, kStreamUnroll, true><<<dim3(pgroups), dim3(kWave * (G / 2)), 0, stream>>>(
+                (int32_t)A->nrows, (int32_t)A->nnz, waves, pgroups, list, A->rowptr, A->colidx, A->d_chunk_base,
+                A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},
+                static_cast<const T *>(A->vals), x, y, a, b);
+            return;
+        }
+    }
     if (A->class_allpattern[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPattern);
     else if (A->class_pattern16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPatternOr16);
     else if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);
