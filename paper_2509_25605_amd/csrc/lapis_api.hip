@@ -5,6 +5,7 @@
 
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -622,16 +623,21 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
     // misses: the wavefronts of a chunk then run as one workgroup, on one CU, where the lines one
     // of them fetched serve the others (stand-ins 7 and 9: 143 -> 137 us, 309 -> 291 us).  Where
     // columns come in runs the same grouping costs time (Elasticity3D stand-in 94 -> 107 us).
-    if constexpr (G >= 4) {
-        if (A->scattered_columns && A->class_all16[cls - 1] && !A->class_allpattern[cls - 1] && !A->class_pattern16[cls - 1]) {
-            const uint32_t groups = (uint32_t)count, pgroups = (groups + kXcds - 1) / kXcds * kXcds;
-            spmv_stream_kernel<T, G, true, kColsNarrow, kStreamUnroll, true><<<dim3(pgroups), dim3(kWave * (G / 2)), 0, stream>>>(
-                (int32_t)A->nrows, (int32_t)A->nnz, waves, pgroups, list, A->rowptr, A->colidx, A->d_chunk_base,
-                A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},
-                static_cast<const T *>(A->vals), x, y, a, b);
+#define LAPIS_STREAM_GROUPED(GWV)                                                                            \
+    do {                                                                                                     \
+        const uint32_t groups = (waves + (GWV) - 1) / (GWV), pgroups = (groups + kXcds - 1) / kXcds * kXcds;  \
+        spmv_stream_kernel<T, G, true, kColsNarrow, kStreamUnroll, GWV><<<dim3(pgroups), dim3(kWave * (GWV)), 0, stream>>>( \
+            (int32_t)A->nrows, (int32_t)A->nnz, waves, pgroups, list, A->rowptr, A->colidx, A->d_chunk_base,   \
+            A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},          \
+            static_cast<const T *>(A->vals), x, y, a, b);                                                     \
+    } while (0)
+    if (A->scattered_columns && A->class_all16[cls - 1] && !A->class_allpattern[cls - 1] && !A->class_pattern16[cls - 1]) {
+        if constexpr (G >= 4) {      // neighbouring one-wavefront chunks (G == 2) gain nothing from it
+            LAPIS_STREAM_GROUPED(G / 2);
             return;
         }
     }
+#undef LAPIS_STREAM_GROUPED
     if (A->class_allpattern[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPattern);
     else if (A->class_pattern16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPatternOr16);
     else if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);

@@ -510,8 +510,8 @@ struct StreamPatterns {
     const int32_t *__restrict__ pool;
 };
 
-template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll, bool GROUP = false>  // UNR must be 16
-__global__ __launch_bounds__(GROUP ? kWave * (kStreamRows * G / kWave) : kWave) void spmv_stream_kernel(
+template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll, int GW = 1>  // UNR must be 16
+__global__ __launch_bounds__(kWave * GW) void spmv_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_waves, uint32_t padded_waves,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
@@ -525,15 +525,15 @@ __global__ __launch_bounds__(GROUP ? kWave * (kStreamRows * G / kWave) : kWave) 
     constexpr int kShareMode = RAW == kColsPatternOr16 ? kColsEither : RAW;       // how the 16-bit window is read
     typedef typename std::conditional<RAW != kCols32, uint16_t, int32_t>::type idx_t;
     static_assert(kPatternTable * sizeof(int32_t) == kStreamWindow * sizeof(uint16_t), "the table takes the window's place");
-    // GROUP: the kWavesPerChunk wavefronts of a chunk form one workgroup.  They share nothing but
-    // the CU and its L1, which pays when every gather touches a cache line of its own (the
-    // wavefronts of a chunk gather from the same neighbourhood of x); padded_waves then counts
-    // workgroups.
-    constexpr int kGroup = GROUP ? kWavesPerChunk : 1;
+    // GW > 1: GW wavefronts with consecutive ids (the wavefronts of one chunk, or of neighbouring
+    // chunks) form one workgroup.  They share nothing but the CU and its L1, which pays when every
+    // gather touches a cache line of its own (they gather from the same neighbourhood of x);
+    // padded_waves then counts workgroups.
+    constexpr int kGroup = GW;
     __shared__ __attribute__((aligned(16))) T s_val_all[kGroup][kStreamWindow];
     __shared__ __attribute__((aligned(16))) idx_t s_col_all[kGroup][kStreamWindow];
     __shared__ int32_t s_tab_all[kGroup][(RAW == kColsNarrow || RAW == kColsPattern) ? 1 : kFrameSlots];
-    const int wave_in_group = GROUP ? threadIdx.x / kWave : 0;
+    const int wave_in_group = GW > 1 ? threadIdx.x / kWave : 0;
     T *s_val = s_val_all[wave_in_group];
     idx_t *s_col = s_col_all[wave_in_group];
     int32_t *s_tab = s_tab_all[wave_in_group];
