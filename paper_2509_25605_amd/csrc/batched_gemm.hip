@@ -67,12 +67,16 @@ __device__ __forceinline__ void stage_scalar(const T *__restrict__ src, uint32_t
 // lanes of different entries on different banks); entries_per_wave = E.  VEC: the A and B pieces
 // of a full tile are multiples of 16 bytes and A, B are 16-byte aligned.  VECC: every strip of C
 // is 16 bytes at a 16-byte aligned address (C aligned, n a multiple of the strip).
-// RB: rows of C per work item (a b value read from LDS serves RB products).
-template <typename T, bool VEC, bool VECC, int RB>
+// RB: rows of C per work item (a b value read from LDS serves RB products).  DIM > 0: m = n = k =
+// DIM is known at compile time (loops unroll, divisions become multiplications, LDS offsets
+// immediates); 0: the sizes are the run-time arguments.
+template <typename T, bool VEC, bool VECC, int RB, int DIM = 0>
 __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
-    int64_t batch, int m, int n, int k, int entries_per_wave, int stride, T alpha, const T *__restrict__ A,
-    const T *__restrict__ B, T beta, T *__restrict__ C)
+    int64_t batch, int m_arg, int n_arg, int k_arg, int entries_per_wave, int stride_arg, T alpha,
+    const T *__restrict__ A, const T *__restrict__ B, T beta, T *__restrict__ C)
 {
+    const int m = DIM ? DIM : m_arg, n = DIM ? DIM : n_arg, k = DIM ? DIM : k_arg;
+    const int stride = DIM ? (2 * DIM * DIM + 1) : stride_arg;
     constexpr int kGemmStrip = 16 / (int)sizeof(T);                // elements of a row of C per work item
     typedef T vec_t __attribute__((ext_vector_type(16 / sizeof(T))));
     __shared__ __attribute__((aligned(16))) T s_tile[kGemmTileBytes / sizeof(T)];
@@ -113,7 +117,7 @@ __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
                     const float inv = in_a ? inv_a : inv_b;
                     const uint32_t shift = in_a ? 0 : mk;
                     if (whole_a && whole_b) {              // a vector never straddles two entries
-                        const uint32_t e = small_div(first, d, inv);
+                        const uint32_t e = DIM ? first / (uint32_t)(DIM * DIM) : small_div(first, d, inv);
                         T *dst = s_tile + e * stride + shift + (first - e * d);
 #pragma unroll
                         for (int t = 0; t < kPer; ++t) dst[t] = v[q][t];
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     const T *b_lds = a_lds + mk;
     T *__restrict__ c_out = C + (b0 + e) * mn;
     for (int w = p; w < items; w += P) {
-        const int ib = (int)small_div((uint32_t)w, (uint32_t)strips, inv_strips);
+        const int ib = DIM ? w / (DIM / kGemmStrip) : (int)small_div((uint32_t)w, (uint32_t)strips, inv_strips);
         const int i0 = ib * RB;
         const int j0 = (w - ib * strips) * kGemmStrip;
         // rows past m repeat row m - 1, columns past n column n - 1; neither is stored
@@ -227,10 +231,19 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
         if (blocked) LAPIS_GEMM_LAUNCH(VEC, VECC, 4);    \
         else LAPIS_GEMM_LAUNCH(VEC, VECC, 1);            \
     } while (0)
-    if (vec && vecc) LAPIS_GEMM_PICK(true, true);
+    const bool cube = m == n && n == k && vec && vecc && blocked;
+#define LAPIS_GEMM_CUBE(D)                                                                                      \
+    batched_gemm_kernel<T, true, true, 4, D><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(                \
+        batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,     \
+        static_cast<T *>(C))
+    if (cube && m == 4) LAPIS_GEMM_CUBE(4);
+    else if (cube && m == 8) LAPIS_GEMM_CUBE(8);
+    else if (cube && m == 16) LAPIS_GEMM_CUBE(16);       // (32: the unrolled nest is slower than the loop)
+    else if (vec && vecc) LAPIS_GEMM_PICK(true, true);
     else if (vec) LAPIS_GEMM_PICK(true, false);
     else if (vecc) LAPIS_GEMM_PICK(false, true);
     else LAPIS_GEMM_PICK(false, false);
+#undef LAPIS_GEMM_CUBE
 #undef LAPIS_GEMM_PICK
 #undef LAPIS_GEMM_LAUNCH
     const hipError_t err = hipGetLastError();
