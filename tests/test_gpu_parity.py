@@ -506,6 +506,37 @@ def test_row_patterns_beside_other_chunks(others, dtype):
         dev.close()
 
 
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("per_row,half_band", [(12, 700), (40, 900), (81, 1000), (200, 600), (300, 1000), (12, 1100)])
+def test_spmv_scattered_columns_in_a_narrow_band(per_row, half_band, dtype):
+    """Random columns inside a band around the diagonal: every gather its own cache line, the
+    columns of a chunk inside a window that fits LDS (or just not: the last case in doubles)."""
+    say(f"band per_row={per_row} half_band={half_band} {np.dtype(dtype).name}")
+    n = 4000 + 13
+    ncols = n
+    L = np.full(n, per_row, dtype=np.int64)
+    L[5] = 0
+    L[64:96] = 0                                        # an empty chunk
+    L[n - 40:n - 20] = 0                                # empty rows in the last chunks
+    rowptr, colidx, vals = gen.random_csr(n, ncols, L, 921, dtype)
+    u = gen.uniform(922, 5, int(rowptr[-1]), 0.0, 1.0)
+    rows = np.repeat(np.arange(n, dtype=np.int64), L)
+    lo = np.clip(rows - half_band, 0, ncols - 2 * half_band - 1)
+    cols = lo + (u * (2 * half_band)).astype(np.int64)
+    order = np.lexsort((cols, rows))                    # ascending inside a row (duplicates stay)
+    colidx[:] = cols[order].astype(np.int32)
+    x = gen.uniform(923, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(923, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        assert dev.partition()["stream_chunks"].size > 0
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, 1.5, -0.5, y0, what="alpha=1.5 beta=-0.5")
+    finally:
+        dev.close()
+
+
 def test_index16_last_entries_of_the_matrix():
     """nnz % 4 = 1, 2, 3: the entries past the last vector load take the scalar path."""
     for extra in (1, 2, 3):
