@@ -46,6 +46,7 @@ def algorithmic_bytes(w):
 
 
 VARIANT_KERNEL = {"paper-shape": "spmv_vector_kernel", "transpose": "transpose_scatter_kernel",
+                  "graph": "all kernels of the step, replayed from a HIP graph",
                   "transposed-handle": "all kernels of the step",
                   "host-buffers": "all kernels and copies of the step"}
 
@@ -120,14 +121,16 @@ def main():
     ap.add_argument("--zipf-s", type=float, default=None,
                     help="workload 4 only: Zipf exponent (default 1.8; 2.0 gives the 'mean about 8' variant)")
     ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers",
-                                          "batched-gemm"], default="tuned",
+                                          "batched-gemm", "graph"], default="tuned",
                     help="paper-shape: the single-vector-length kernel of the paper's loop mapping; "
                          "transpose: y = alpha*A^T*x + beta*y (column-wise traversal, atomics); transposed-handle: "
                          "the same product through a handle for A^T built on the device; host-buffers: the "
                          "product on lazily synchronised host buffers with x rewritten on the host and y "
                          "read back every step (PCIe-inclusive rate, never the headline value); batched-gemm: "
                          "lapis_batched_gemm on 2^20 products of 8 x 8 doubles (--scale batch=,m=,n=,k=,f32=1 "
-                         "to change that), a workload of its own, --config is ignored")
+                         "to change that), a workload of its own, --config is ignored; graph: the tuned product "
+                         "recorded 50 times into a HIP graph and replayed (what a launch-bound caller such as "
+                         "workload 1 gains; --steps is rounded to a multiple of 50)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size instead (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -205,6 +208,21 @@ def main():
             xv.modify_host()                     # the caller rewrote x on the host
             L.lapis_spmv_dualview(A.handle, w.alpha, xv, w.beta, yv)
             yv.sync_host()                       # and reads y on the host
+    elif args.variant == "graph":
+        per_graph = 50
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(per_graph):
+                L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
+        args.steps = max(per_graph, args.steps // per_graph * per_graph)
+        replays = iter(range(10 ** 9))
+        step = lambda: graph.replay() if next(replays) % per_graph == 0 else None
     elif w.k == 0:
         step = lambda: L.lapis_spmv(A.handle, w.alpha, x, w.beta, y)
     else:
