@@ -738,3 +738,73 @@ def test_workload_full_size(cfg):
 def test_workload4_exponent_two_full_size():
     """The labelled variant of workload 4 with Zipf exponent 2.0 (mean row length about 8)."""
     run_workload(4, {"s": 2.0})
+
+
+# ---------------------------------------------------------------------------
+# seeded sweep over structures: sections of a matrix built in different ways, so that patterned,
+# narrow, framed and plain chunks, grouped and single wavefronts, bins and tiles meet in one handle
+# ---------------------------------------------------------------------------
+def _section(kind, r0, r1, ncols, seed):
+    """Rows r0..r1-1 as lists of columns."""
+    n = r1 - r0
+    u = gen.uniform(seed, 9, n * 8 + 8, 0.0, 1.0)
+    rows = []
+    if kind == "stencil":                                # a few diagonals, every row the same list
+        diags = sorted(set(int(d) for d in (np.floor(u[:9] * 400) - 200)))
+        rows = [[min(max(i + d, 0), ncols - 1) for d in diags] for i in range(r0, r1)]
+    elif kind == "band":                                 # a dense band of varying width
+        w = 3 + int(u[0] * 90)
+        rows = [[min(i + d, ncols - 1) for d in range(w)] for i in range(r0, r1)]
+    elif kind == "short":                                # 0-6 random columns
+        for k, i in enumerate(range(r0, r1)):
+            m = int(u[k] * 7)
+            rows.append(sorted(int(c) for c in np.floor(gen.uniform(seed + i, 10, m, 0.0, 1.0) * ncols)))
+    elif kind == "jitter":                               # 20-150 columns scattered near the diagonal
+        for k, i in enumerate(range(r0, r1)):
+            m = 20 + int(u[k] * 130)
+            c = i + np.floor(gen.uniform(seed + i, 11, m, 0.0, 1.0) * 3000).astype(np.int64) - 1500
+            rows.append(sorted(int(v) for v in np.clip(c, 0, ncols - 1)))
+    elif kind == "wide":                                 # 10-40 columns anywhere, unsorted
+        for k, i in enumerate(range(r0, r1)):
+            m = 10 + int(u[k] * 30)
+            rows.append([int(c) for c in np.floor(gen.uniform(seed + i, 12, m, 0.0, 1.0) * ncols)])
+    else:                                                # "long": one row of a few thousand entries among short ones
+        for k, i in enumerate(range(r0, r1)):
+            m = 5000 + int(u[0] * 3000) if k == n // 2 else 3
+            rows.append(sorted(int(c) for c in np.floor(gen.uniform(seed + i, 13, m, 0.0, 1.0) * ncols)))
+    return rows
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_structure_sweep(seed):
+    kinds = ["stencil", "band", "short", "jitter", "wide", "long"]
+    pick = gen.uniform(4000 + seed, 1, 16, 0.0, 1.0)
+    dtype = np.float64 if seed % 2 == 0 else np.float32
+    ncols = [3000, 70000, 1 << 20][seed % 3]
+    sections, r = [], 0
+    for t in range(3 + seed % 3):
+        length = 32 * (2 + int(pick[t] * 20)) + (int(pick[t + 8] * 31) if t % 2 else 0)
+        sections.append((kinds[int(pick[t + 4] * len(kinds)) % len(kinds)], r, r + length))
+        r += length
+    n = r
+    say(f"sweep seed={seed} n={n} ncols={ncols} {np.dtype(dtype).name} " + " ".join(k for k, _, _ in sections))
+    rows = []
+    for k, a, b in sections:
+        rows += _section(k, a, b, ncols, 5000 + 97 * seed + a)
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum([len(x) for x in rows], out=rowptr[1:])
+    colidx = np.array([c for x in rows for c in x], dtype=np.int32)
+    vals = gen.uniform(6000 + seed, gen.STREAM_VALUES, colidx.size).astype(dtype)
+    x = gen.uniform(6000 + seed, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(6000 + seed, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        check_half_bandwidth(dev, rowptr, colidx)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, -2.0, 0.75, y0, what="alpha=-2 beta=0.75")
+        k = 1 + seed % 5 * 4
+        X = gen.uniform(6100 + seed, gen.STREAM_X, ncols * k).astype(dtype).reshape(ncols, k)
+        check_spmm(dev, rowptr, colidx, vals, X, what=f"spmm k={k}")
+    finally:
+        dev.close()
