@@ -23,7 +23,7 @@ namespace lapis {
 
 constexpr int kGemmMaxDim = LAPIS_BATCHED_MAX_DIM;
 // LDS tile of a wavefront: one entry of the largest size must fit ((2 * 32 * 32 + 1) doubles), and
-// 16 entries of 8 x 8 doubles with their padding; 9 wavefronts per CU
+// 16 entries of 8 x 8 doubles with their padding (9 wavefronts per CU at that size)
 constexpr int kGemmTileBytes = 2080 * 8;
 static_assert(kGemmTileBytes >= (2 * kGemmMaxDim * kGemmMaxDim + 1) * 8, "one entry of the largest size must fit");
 constexpr int kGemmMaxVec = (kGemmTileBytes / 16 + kWave - 1) / kWave;      // 16-byte loads per lane and tile
@@ -70,7 +70,7 @@ __device__ __forceinline__ void stage_scalar(const T *__restrict__ src, uint32_t
 // RB: rows of C per work item (a b value read from LDS serves RB products).  DIM > 0: m = n = k =
 // DIM is known at compile time (loops unroll, divisions become multiplications, LDS offsets
 // immediates); 0: the sizes are the run-time arguments.
-template <typename T, bool VEC, bool VECC, int RB, int DIM = 0>
+template <typename T, bool VEC, bool VECC, int RB, int DIM = 0, bool DYN = false>
 __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     int64_t batch, int m_arg, int n_arg, int k_arg, int entries_per_wave, int stride_arg, T alpha,
     const T *__restrict__ A, const T *__restrict__ B, T beta, T *__restrict__ C)
@@ -79,7 +79,11 @@ __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     const int stride = DIM ? (2 * DIM * DIM + 1) : stride_arg;
     constexpr int kGemmStrip = 16 / (int)sizeof(T);                // elements of a row of C per work item
     typedef T vec_t __attribute__((ext_vector_type(16 / sizeof(T))));
-    __shared__ __attribute__((aligned(16))) T s_tile[kGemmTileBytes / sizeof(T)];
+    // DYN: the launch sizes the tile to E * stride values, so tiny products leave room for more
+    // wavefronts per CU; otherwise a fixed tile, whose addresses the compiler knows
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_tile_bytes[];
+    __shared__ __attribute__((aligned(16))) T s_tile_fixed[DYN ? 1 : kGemmTileBytes / sizeof(T)];
+    T *s_tile = DYN ? reinterpret_cast<T *>(s_tile_bytes) : s_tile_fixed;
     const int lane = threadIdx.x;
     const int E = entries_per_wave;
     const int P = kWave / E;
@@ -214,6 +218,8 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
     int E = kWave;
     while (E > 1 && E * stride > capacity) E /= 2;
     const int64_t tiles = (batch + E - 1) / E;
+    const size_t lds_bytes = ((size_t)E * stride * sizeof(T) + 15) / 16 * 16;
+    const bool tiny = lds_bytes <= 8192;          // at least twice the wavefronts per CU of the fixed tile
     if (tiles > INT32_MAX) return fail(LAPIS_ERR_INVALID_ARG, "lapis_batched_gemm: batch is too large");
     const bool vec = reinterpret_cast<uintptr_t>(A) % 16 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0 &&
                      ((size_t)E * m * k * sizeof(T)) % 16 == 0 && ((size_t)E * k * n * sizeof(T)) % 16 == 0;
@@ -223,9 +229,16 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
     const int P = kWave / E;
     const bool blocked = ((m + 3) / 4) * ((n + strip - 1) / strip) >= P;
 #define LAPIS_GEMM_LAUNCH(VEC, VECC, RB)                                                                        \
-    batched_gemm_kernel<T, VEC, VECC, RB><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(                   \
-        batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,     \
-        static_cast<T *>(C))
+    do {                                                                                                        \
+        if (tiny)                                                                                               \
+            batched_gemm_kernel<T, VEC, VECC, RB, 0, true><<<dim3((uint32_t)tiles), dim3(kWave), lds_bytes, stream>>>( \
+                batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B),      \
+                (T)beta, static_cast<T *>(C));                                                                  \
+        else                                                                                                    \
+            batched_gemm_kernel<T, VEC, VECC, RB><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(           \
+                batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B),      \
+                (T)beta, static_cast<T *>(C));                                                                  \
+    } while (0)
 #define LAPIS_GEMM_PICK(VEC, VECC)                       \
     do {                                                 \
         if (blocked) LAPIS_GEMM_LAUNCH(VEC, VECC, 4);    \
@@ -236,7 +249,10 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
     batched_gemm_kernel<T, true, true, 4, D><<<dim3((uint32_t)tiles), dim3(kWave), 0, stream>>>(                \
         batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,     \
         static_cast<T *>(C))
-    if (cube && m == 4) LAPIS_GEMM_CUBE(4);
+    if (cube && m == 4)
+        batched_gemm_kernel<T, true, true, 4, 4, true><<<dim3((uint32_t)tiles), dim3(kWave), lds_bytes, stream>>>(
+            batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,
+            static_cast<T *>(C));
     else if (cube && m == 8) LAPIS_GEMM_CUBE(8);
     else if (cube && m == 16) LAPIS_GEMM_CUBE(16);       // (32: the unrolled nest is slower than the loop)
     else if (vec && vecc) LAPIS_GEMM_PICK(true, true);
