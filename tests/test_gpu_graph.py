@@ -49,3 +49,43 @@ def test_spmv_in_a_graph_replays_like_eager(cfg, scale):
             A.spmv(x, eager, 1.0, 0.0)
             torch.cuda.synchronize()
             assert torch.equal(eager, y), f"replay {rep} is not bitwise the eager result"
+
+
+def test_spmm_and_batched_gemm_in_a_graph():
+    _say("graph capture spmm + batched gemm")
+    w = gen.workload(5, {"nx": 20, "ny": 12, "nz": 9, "k": 16})
+    rowptr, colidx, vals = (torch.from_numpy(a).cuda() for a in (w.rowptr, w.colidx, w.vals))
+    X = torch.from_numpy(np.ascontiguousarray(w.x)).cuda()
+    Y = torch.zeros(w.nrows, 16, dtype=torch.float64, device="cuda")
+    batch, m = 300, 6
+    A = gen.uniform(81, 1, batch * m * m).reshape(batch, m, m)
+    B = gen.uniform(81, 2, batch * m * m).reshape(batch, m, m)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.zeros(batch, m, m, dtype=torch.float64, device="cuda")
+    with L.CsrMatrix(w.nrows, w.ncols, rowptr, colidx, vals) as M:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            M.spmm(X, Y)
+            L.lapis_batched_gemm(batch, m, m, m, 1.0, dA, dB, 0.0, dC, L.LAPIS_F64)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            M.spmm(X, Y)
+            L.lapis_batched_gemm(batch, m, m, m, 1.0, dA, dB, 0.0, dC, L.LAPIS_F64)
+        for rep in range(3):
+            Xh = gen.uniform(800 + rep, gen.STREAM_X, w.ncols * 16).reshape(w.ncols, 16)
+            X.copy_(torch.from_numpy(Xh))
+            Ah = gen.uniform(810 + rep, 1, batch * m * m).reshape(batch, m, m)
+            dA.copy_(torch.from_numpy(Ah))
+            Y.fill_(float("nan"))
+            dC.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ref, absAX = oracle.spmm(w.rowptr, w.colidx, w.vals, Xh)
+            tol = 8.0 * np.diff(w.rowptr)[:, None] * 2.0 ** -53 * absAX
+            assert np.all(np.abs(Y.cpu().numpy() - ref) <= tol), f"spmm replay {rep} differs"
+            refC, absAB = oracle.batched_gemm(Ah, B)
+            assert np.all(np.abs(dC.cpu().numpy() - refC) <= 8.0 * (m + 2) * 2.0 ** -53 * absAB), f"gemm replay {rep} differs"
