@@ -116,3 +116,23 @@ def test_paper_vector_length_on_table3(lib, golden_dir):
     assert L.lapis_paper_vector_length(10, 41) == 8
     assert L.lapis_paper_vector_length(1, 10 ** 9) == 64
     assert L.lapis_paper_vector_length(0, 0) == 1
+
+
+def test_header_is_plain_c_and_declares_what_the_library_exports(tmp_path):
+    """include/lapis.h compiles as C99 on its own, and a C program that takes the address of every
+    declared function links against the library (no call is made: no GPU needed)."""
+    import subprocess
+    text = open(os.path.join(ROOT, "include", "lapis.h")).read()
+    names = sorted(set(re.findall(r"\b(lapis_[a-z0-9_]+)\s*\(", text)) - {"lapis_csr_t", "lapis_dualview_t"})
+    assert set(names) == set(binding.EXPORTS)
+    src = tmp_path / "client.c"
+    src.write_text('#include "lapis.h"\n#include <stdio.h>\ntypedef void (*fn_t)(void);\nint main(void) {\n    fn_t f[] = {'
+                   + ", ".join(f"(fn_t){n}" for n in names)
+                   + "};\n    printf(\"%d\\n\", (int)(sizeof f / sizeof f[0]));\n    return f[0] == 0;\n}\n")
+    exe = tmp_path / "client"
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+           "-L", lib_dir, "-l:" + os.path.basename(binding.LIB_PATH), "-Wl,-rpath," + lib_dir,
+           "-Wl,--allow-shlib-undefined"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
