@@ -11,6 +11,7 @@
 #include <string>
 
 #include "transpose_kernels.hpp"
+#include "radix_transpose_kernels.hpp"
 #include "internal.hpp"
 #include "../../include/lapis.h"
 #include "analysis_kernels.hpp"
@@ -537,48 +538,64 @@ int build_transposed_arrays(const lapis_csr *A, lapis_csr *B, hipStream_t stream
         LAPIS_HIP(hipStreamSynchronize(stream));
         return LAPIS_OK;
     }
-    const int32_t scan_tiles = (int32_t)((nt + kScanTile - 1) / kScanTile);
-    const int64_t max_long = nnz / (kSortHalf + 1) + 1;
-    DeviceTemp count, tile_sums, keys, long_cols, num_long;
-    if (int rc = count.alloc(sizeof(int32_t) * (size_t)nt)) return rc;
+    // stable radix sort of (column, entry id) by column, 8 bits per pass
+    int bits = 1;
+    while (bits < 31 && ((int64_t)1 << bits) < nt) ++bits;
+    const int passes = (bits + kRadixBits - 1) / kRadixBits;
+    const int32_t num_waves = (int32_t)((nnz + kRadixPerWave - 1) / kRadixPerWave);
+    const int64_t counts = (int64_t)kRadixDigits * num_waves;
+    const int32_t scan_tiles = (int32_t)((counts + kScanTile - 1) / kScanTile);
+    const int64_t check_tiles = (nnz + kCheckTile - 1) / kCheckTile;
+    // two pairs of buffers take turns; the arrays of A^T itself serve as the second pair (they
+    // are written last, from the first pair, which therefore has to hold the last pass's output)
+    DeviceTemp keys_t, vals_t, count, offset, tile_sums, entry_row, tile_first;
+    if (int rc = keys_t.alloc(sizeof(int32_t) * (size_t)nnz)) return rc;
+    if (int rc = vals_t.alloc(sizeof(int32_t) * (size_t)nnz)) return rc;
+    int32_t *const keys_pair[2] = {keys_t.as<int32_t>(), static_cast<int32_t *>(B->own_vals)};
+    int32_t *const vals_pair[2] = {vals_t.as<int32_t>(), B->own_colidx};
+    if (int rc = count.alloc(sizeof(int32_t) * (size_t)counts)) return rc;
+    if (int rc = offset.alloc(sizeof(int32_t) * ((size_t)counts + 1))) return rc;
     if (int rc = tile_sums.alloc(sizeof(int32_t) * ((size_t)scan_tiles + 1))) return rc;
-    if (int rc = keys.alloc(sizeof(uint64_t) * (size_t)nnz)) return rc;
-    if (int rc = long_cols.alloc(sizeof(int32_t) * (size_t)max_long)) return rc;
-    if (int rc = num_long.alloc(sizeof(int32_t))) return rc;
-    int32_t *d_count = count.as<int32_t>();
-    LAPIS_HIP(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)nt, stream));
-    LAPIS_HIP(hipMemsetAsync(num_long.p, 0, sizeof(int32_t), stream));
-    int64_t cblocks = (nnz + kBlock - 1) / kBlock;
-    if (cblocks > 65536) cblocks = 65536;
-    column_count_kernel<<<dim3((uint32_t)cblocks), dim3(kBlock), 0, stream>>>((int32_t)nnz, A->colidx, d_count);
-    scan_tile_sums_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(nt, d_count, tile_sums.as<int32_t>());
-    scan_tile_offsets_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(scan_tiles, tile_sums.as<int32_t>());
-    scan_apply_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(nt, d_count, tile_sums.as<int32_t>(), scan_tiles,
-                                                                   B->own_rowptr);
-    LAPIS_HIP(hipMemsetAsync(d_count, 0, sizeof(int32_t) * (size_t)nt, stream));     // now the cursors
-    const uint32_t entry_tiles = (uint32_t)((nnz + kScatterTile - 1) / kScatterTile);
-    transpose_fill_kernel<<<dim3(entry_tiles), dim3(kBlock), 0, stream>>>(
-        (int32_t)A->nrows, (int32_t)nnz, A->rowptr, A->colidx, B->own_rowptr, d_count, keys.as<uint64_t>(),
-        B->own_colidx);
-    const uint32_t sort_tiles = (uint32_t)((nnz + kSortHalf - 1) / kSortHalf);
-    transpose_sort_tiles_kernel<<<dim3(sort_tiles), dim3(kBlock), 0, stream>>>(
-        (int32_t)nt, (int32_t)nnz, B->own_rowptr, keys.as<uint64_t>(), B->own_colidx, long_cols.as<int32_t>(),
-        num_long.as<int32_t>());
-    LAPIS_HIP(hipGetLastError());
-    int32_t h_num_long = 0;
-    if (int rc = read_back(&h_num_long, num_long.p, sizeof(int32_t), stream)) return rc;
-    if (h_num_long < 0 || h_num_long > max_long) return fail(LAPIS_ERR_DEVICE, "transposition: long column count out of range");
-    if (h_num_long > 0)
-        transpose_sort_long_kernel<<<dim3((uint32_t)h_num_long), dim3(kSortLongBlock), 0, stream>>>(
-            long_cols.as<int32_t>(), B->own_rowptr, keys.as<uint64_t>(), B->own_colidx);
+    if (int rc = entry_row.alloc(sizeof(int32_t) * (size_t)nnz)) return rc;
+    if (int rc = tile_first.alloc(sizeof(int32_t) * ((size_t)check_tiles + 1))) return rc;
+    const uint32_t wave_blocks = (uint32_t)((num_waves + kWavesPerBlock - 1) / kWavesPerBlock);
+    const int32_t *keys_in = A->colidx, *vals_in = nullptr;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = pass * kRadixBits;
+        const int to = (passes - 1 - pass) % 2;         // the last pass writes pair 0
+        int32_t *keys_out = keys_pair[to], *vals_out = vals_pair[to];
+        radix_count_kernel<<<dim3(wave_blocks), dim3(kBlock), 0, stream>>>((int32_t)nnz, num_waves, shift, keys_in,
+                                                                          count.as<int32_t>());
+        scan_tile_sums_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(counts, count.as<int32_t>(),
+                                                                             tile_sums.as<int32_t>());
+        scan_tile_offsets_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(scan_tiles, tile_sums.as<int32_t>());
+        scan_apply_kernel<<<dim3(scan_tiles), dim3(kBlock), 0, stream>>>(counts, count.as<int32_t>(), tile_sums.as<int32_t>(),
+                                                                         scan_tiles, offset.as<int32_t>());
+        radix_scatter_kernel<<<dim3(wave_blocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)nnz, num_waves, shift, keys_in, vals_in, offset.as<int32_t>(), keys_out, vals_out);
+        keys_in = keys_out;
+        vals_in = vals_out;
+    }
+    int64_t pblocks = (nnz + 1 + kBlock - 1) / kBlock;
+    if (pblocks > 65536) pblocks = 65536;
+    sorted_keys_to_ptr_kernel<<<dim3((uint32_t)pblocks), dim3(kBlock), 0, stream>>>((int32_t)nnz, (int32_t)nt, keys_in,
+                                                                                    B->own_rowptr);
+    // the row of every entry of A, then rows and values in sorted order
+    check_tile_rows_kernel<<<dim3((uint32_t)((check_tiles + 1 + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
+        (int32_t)A->nrows, check_tiles, A->rowptr, tile_first.as<int32_t>());
+    int64_t rblocks = check_tiles < 8192 ? check_tiles : 8192;
+    entry_rows_kernel<<<dim3((uint32_t)rblocks), dim3(kBlock), 0, stream>>>((int32_t)nnz, A->rowptr, tile_first.as<int32_t>(),
+                                                                            entry_row.as<int32_t>());
     int64_t gblocks = (nnz + kBlock - 1) / kBlock;
     if (gblocks > 65536) gblocks = 65536;
     if (A->dtype == LAPIS_F64)
-        transpose_gather_kernel<double><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)nnz, keys.as<uint64_t>(), static_cast<const double *>(A->vals), static_cast<double *>(B->own_vals));
+        transpose_gather_sorted_kernel<double><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)nnz, vals_in, entry_row.as<int32_t>(), static_cast<const double *>(A->vals), B->own_colidx,
+            static_cast<double *>(B->own_vals));
     else
-        transpose_gather_kernel<float><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
-            (int32_t)nnz, keys.as<uint64_t>(), static_cast<const float *>(A->vals), static_cast<float *>(B->own_vals));
+        transpose_gather_sorted_kernel<float><<<dim3((uint32_t)gblocks), dim3(kBlock), 0, stream>>>(
+            (int32_t)nnz, vals_in, entry_row.as<int32_t>(), static_cast<const float *>(A->vals), B->own_colidx,
+            static_cast<float *>(B->own_vals));
     LAPIS_HIP(hipGetLastError());
     LAPIS_HIP(hipStreamSynchronize(stream));     // the temporaries are freed on return
     return LAPIS_OK;

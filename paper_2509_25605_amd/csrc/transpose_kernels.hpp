@@ -98,21 +98,7 @@ __global__ __launch_bounds__(kBlock) void transpose_scatter_kernel(int32_t nrows
     }
 }
 
-// ---- explicit transposition: the CSR arrays of A^T, built on the device ------
-// count the entries of every column -> exclusive scan gives tptr -> every entry takes a slot of
-// its column with an atomic cursor (any order) and leaves the key (column, entry id) and its row
-// -> the slots of each column are sorted by entry id, which is the order of a serial row-by-row
-// transposition (unique, duplicates included) -> values are gathered through the entry ids.
-// Columns of at most kSortHalf entries are sorted in LDS, several columns per workgroup; longer
-// ones by one workgroup each in memory.
-
-// count[c] = entries in column c; count must be 0 on entry
-__global__ __launch_bounds__(kBlock) void column_count_kernel(int32_t nnz, const int32_t *__restrict__ colidx,
-                                                              int32_t *__restrict__ count)
-{
-    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < nnz; j += (int64_t)gridDim.x * kBlock)
-        atomicAdd(&count[load_stream(colidx + j)], 1);
-}
+// ---- exclusive scan of ints (used by the radix sort of the explicit transposition) ------
 
 // Exclusive scan of n ints in three launches: per-tile sums, scan of the sums by one workgroup,
 // per-tile scan with the tile's offset.  out has n + 1 elements (out[n] = total).
@@ -186,159 +172,6 @@ __global__ __launch_bounds__(kBlock) void scan_apply_kernel(int64_t n, const int
         prefix += v[q];
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) out[n] = tile_offset[num_tiles];
-}
-
-// Every entry j (row r, column c) takes slot p = tptr[c] + (cursor[c]++) and leaves
-// key[p] = (c << 32) | j and trow[p] = r.  cursor must be 0 on entry.  Same tiling as the scatter.
-__global__ __launch_bounds__(kBlock) void transpose_fill_kernel(int32_t nrows, int32_t nnz,
-                                                                const int32_t *__restrict__ rowptr,
-                                                                const int32_t *__restrict__ colidx,
-                                                                const int32_t *__restrict__ tptr,
-                                                                int32_t *__restrict__ cursor,
-                                                                uint64_t *__restrict__ key, int32_t *__restrict__ trow)
-{
-    __shared__ int32_t s_start[kScatterRowsInLds];
-    __shared__ int32_t s_range[2];
-    const int32_t j0 = (int32_t)blockIdx.x * kScatterTile;
-    const int32_t j1 = (nnz - j0 > kScatterTile) ? j0 + kScatterTile : nnz;
-    const TileRows rows = stage_tile_rows(s_start, s_range, j0, j1, nrows, rowptr);
-#pragma unroll
-    for (int k = 0; k < kScatterPerThread; ++k) {
-        const int32_t j = j0 + k * kBlock + (int32_t)threadIdx.x;
-        if (j < j1) {
-            const int32_t c = load_stream(colidx + j);
-            const int32_t p = tptr[c] + atomicAdd(&cursor[c], 1);
-            key[p] = ((uint64_t)(uint32_t)c << 32) | (uint32_t)j;
-            trow[p] = tile_row_of(rows, s_start, rowptr, j);
-        }
-    }
-}
-
-constexpr int kSortHalf = 1024;             // longest column sorted in LDS; also the slot range per workgroup
-constexpr int kSortTile = 2 * kSortHalf;    // most slots one workgroup can meet
-constexpr uint64_t kSortPad = ~0ull;
-
-// first column c in [0, ncols] with tptr[c] >= p   (tptr[ncols] = nnz >= p)
-__device__ __forceinline__ int32_t first_column_starting_at_or_after(const int32_t *__restrict__ tptr,
-                                                                     int32_t ncols, int32_t p)
-{
-    int32_t lo = 0, hi = ncols;
-    while (lo < hi) {
-        const int32_t mid = lo + (hi - lo) / 2;
-        if (tptr[mid] >= p) hi = mid; else lo = mid + 1;
-    }
-    return lo;
-}
-
-// The comparators of a sorting network on indices [0, np), np a power of two, that orders every
-// pair ascending (merge steps start with a mirrored partner), so positions padded with the
-// largest key never move.  step(i, partner) is called for i < partner; `sync` between levels.
-template <typename Step, typename Sync>
-__device__ __forceinline__ void ascending_network(int32_t np, int32_t threads, Step step, Sync sync)
-{
-    for (int32_t k = 2; k <= np; k <<= 1) {
-        for (int32_t t = threadIdx.x; t < np / 2; t += threads) {
-            const int32_t half = k >> 1, blk = t / half, off = t % half;
-            step(blk * k + off, blk * k + k - 1 - off);
-        }
-        sync();
-        for (int32_t d = k >> 2; d > 0; d >>= 1) {
-            for (int32_t t = threadIdx.x; t < np / 2; t += threads) {
-                const int32_t i = 2 * d * (t / d) + t % d;
-                step(i, i + d);
-            }
-            sync();
-        }
-    }
-}
-
-// Workgroup t owns the columns whose first slot lies in [t*kSortHalf, (t+1)*kSortHalf).  Only the
-// last of them can be longer than kSortHalf; it is then left out and appended to long_cols (in
-// any order).  The rest, fewer than kSortTile slots, is sorted by key in LDS: the column is the
-// major part of the key, so every column ends up sorted by entry id in its own slots.
-__global__ __launch_bounds__(kBlock) void transpose_sort_tiles_kernel(int32_t ncols, int32_t nnz,
-                                                                      const int32_t *__restrict__ tptr,
-                                                                      uint64_t *__restrict__ key,
-                                                                      int32_t *__restrict__ trow,
-                                                                      int32_t *__restrict__ long_cols,
-                                                                      int32_t *__restrict__ num_long)
-{
-    __shared__ uint64_t s_key[kSortTile];
-    __shared__ int32_t s_row[kSortTile];
-    __shared__ int32_t s_col[2];
-    const int32_t lo = (int32_t)blockIdx.x * kSortHalf;
-    const int32_t hi = (nnz - lo > kSortHalf) ? lo + kSortHalf : nnz;
-    if (threadIdx.x < 2) s_col[threadIdx.x] = first_column_starting_at_or_after(tptr, ncols, threadIdx.x == 0 ? lo : hi);
-    __syncthreads();
-    const int32_t c_first = s_col[0], c_end = s_col[1];
-    if (c_first >= c_end) return;                       // no column starts here (inside a long column)
-    const int32_t c_last = c_end - 1;
-    const int32_t last_begin = tptr[c_last], last_end = tptr[c_last + 1];
-    const bool last_is_long = last_end - last_begin > kSortHalf;
-    if (last_is_long && threadIdx.x == 0) long_cols[atomicAdd(num_long, 1)] = c_last;
-    const int32_t p0 = tptr[c_first];
-    const int32_t n = (last_is_long ? last_begin : last_end) - p0;     // < kSortTile
-    if (n <= 1) return;
-    int32_t np = 2;
-    while (np < n) np <<= 1;
-    for (int32_t i = threadIdx.x; i < np; i += kBlock) {
-        s_key[i] = (i < n) ? key[p0 + i] : kSortPad;
-        s_row[i] = (i < n) ? trow[p0 + i] : 0;
-    }
-    __syncthreads();
-    ascending_network(
-        np, kBlock,
-        [&](int32_t i, int32_t partner) {
-            const uint64_t a = s_key[i], b = s_key[partner];
-            if (a > b) {
-                s_key[i] = b; s_key[partner] = a;
-                const int32_t ra = s_row[i];
-                s_row[i] = s_row[partner]; s_row[partner] = ra;
-            }
-        },
-        [] { __syncthreads(); });
-    for (int32_t i = threadIdx.x; i < n; i += kBlock) {
-        key[p0 + i] = s_key[i];
-        trow[p0 + i] = s_row[i];
-    }
-}
-
-// One workgroup of kSortLongBlock threads per column longer than kSortHalf: the same network on the
-// column's slots in memory (comparators that reach beyond the column's end meet the padding and
-// are skipped).
-constexpr int kSortLongBlock = 1024;
-__global__ __launch_bounds__(kSortLongBlock) void transpose_sort_long_kernel(const int32_t *__restrict__ long_cols,
-                                                                             const int32_t *__restrict__ tptr,
-                                                                             uint64_t *key, int32_t *trow)
-{
-    const int32_t c = long_cols[blockIdx.x];
-    const int32_t p0 = tptr[c], n = tptr[c + 1] - p0;
-    int32_t np = 2;
-    while (np < n) np <<= 1;
-    uint64_t *k = key + p0;
-    int32_t *r = trow + p0;
-    ascending_network(
-        np, kSortLongBlock,
-        [&](int32_t i, int32_t partner) {
-            if (partner < n) {
-                const uint64_t a = k[i], b = k[partner];
-                if (a > b) {
-                    k[i] = b; k[partner] = a;
-                    const int32_t ra = r[i];
-                    r[i] = r[partner]; r[partner] = ra;
-                }
-            }
-        },
-        [] { __syncthreads(); });
-}
-
-// tvals[p] = vals[entry id of slot p]
-template <typename T>
-__global__ __launch_bounds__(kBlock) void transpose_gather_kernel(int32_t nnz, const uint64_t *__restrict__ key,
-                                                                  const T *__restrict__ vals, T *__restrict__ tvals)
-{
-    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * kBlock)
-        tvals[p] = vals[(uint32_t)load_stream(key + p)];
 }
 
 }  // namespace lapis
