@@ -382,7 +382,9 @@ int lapis_spmv_dualview(const lapis_csr_t *A, double alpha, lapis_dualview_t *x,
  *   1 <= m, n, k <= LAPIS_BATCHED_MAX_DIM; batch >= 0 (0: nothing is done, pointers may be NULL)
  *   alpha, beta are rounded to dtype; beta == 0: C is write-only (NaN or Inf in old C does not
  *   propagate)
- * Every element is one dot product summed over l = 0 .. k-1 in that order, in dtype.
+ * Every element is one dot product of k terms accumulated in dtype with fused multiply-adds; the
+ * order of the terms depends on the sizes only (small entries: l = 0 .. k-1; larger ones, on the
+ * matrix cores: another fixed order), so equal calls give equal results.
  * Asynchronous on hip_stream (NULL = default stream): no allocation, no copy, no host
  * synchronisation.  Errors: LAPIS_ERR_INVALID_ARG (sizes out of range, NULL operand with
  * batch > 0), LAPIS_ERR_UNSUPPORTED (dtype), LAPIS_ERR_DEVICE (launch failure).

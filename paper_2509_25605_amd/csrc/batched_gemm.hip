@@ -1,6 +1,7 @@
-// Batched GEMM for many small matrices, the batch dimension vectorised (Section 5 of the paper
-// lowers this kernel as its example of a batched operation: the matrices are too small to be
-// worth a tile each, so the lanes of a wavefront go across the batch).
+// Batched GEMM for many small matrices (Section 5 of the paper lowers this kernel as its example
+// of a batched operation, with the batch dimension as the vectorised one).  Two kernels: for the
+// small entries the lanes of a wavefront go across the batch (below); entries from about 12 x 12
+// x 12 on get a wavefront each and the matrix cores (batched_gemm_mfma_kernel, further down).
 // C[b] = alpha * A[b] * B[b] + beta * C[b], every matrix row-major, the matrices of an operand
 // back to back (the layout of a contiguous (batch, rows, cols) tensor).
 //
@@ -26,6 +27,8 @@ constexpr int kGemmMaxDim = LAPIS_BATCHED_MAX_DIM;
 // 16 entries of 8 x 8 doubles with their padding (9 wavefronts per CU at that size)
 constexpr int kGemmTileBytes = 2080 * 8;
 static_assert(kGemmTileBytes >= (2 * kGemmMaxDim * kGemmMaxDim + 1) * 8, "one entry of the largest size must fit");
+static_assert(kGemmMaxDim == 32, "the matrix-core path has at most 2 x 2 tiles of 16 x 16");
+constexpr int kGemmMfmaMinElements = 400;   // elements of A, B and C of one entry from which the matrix cores take over
 constexpr int kGemmMaxVec = (kGemmTileBytes / 16 + kWave - 1) / kWave;      // 16-byte loads per lane and tile
 
 // floor(g / d) for 0 <= g < 2^20 and 1 <= d (inv = 1.0f / d): the float estimate is off by at
@@ -208,10 +211,155 @@ __global__ __launch_bounds__(kWave) void batched_gemm_kernel(
     }
 }
 
+// Matrices whose sides are multiples of the 16 x 16 x 4 matrix-core tile: one wavefront per batch
+// entry (kWavesPerBlock of them in a workgroup), no LDS.  Every lane loads its fragments of A (16 bytes = H consecutive k of one row) and
+// of B (one element of H rows) straight from memory, all loads of the entry in flight together;
+// lane (i, g) = (lane % 16, lane / 16) supplies A[16 rt + i][kk] and B[kk][16 ct + i] with
+// kk = 4 H q + H g + h for the instruction (q, h) - the k index only has to agree between the
+// two operands, so it is chosen to make A's loads 16 bytes wide.  Each matrix element is read
+// once.  M = 16 MT, N = 16 NT, K = 4 H KQ; A 16-byte aligned.
+template <typename T> struct MfmaTile;
+template <> struct MfmaTile<double> {
+    typedef double acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    // row of the tile that register v of lane group g holds (the column is lane % 16)
+    static __device__ __forceinline__ int row(int g, int v) { return g + 4 * v; }
+};
+template <> struct MfmaTile<float> {
+    typedef float acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row(int g, int v) { return 4 * g + v; }
+};
+
+// MODE 2 (exact): m = 16 MT, n = 16 NT, k = 4 H KQ and A is 16-byte aligned.  Otherwise those are
+// the sizes rounded up: elements outside the matrices are not loaded and count as zeros (rows of
+// C past m and columns past n may then pick up anything, they are not stored).  MODE 1: k is a
+// multiple of H and A 16-byte aligned, so A's 16-byte pieces are whole and aligned; MODE 0: A is
+// read element by element.
+template <typename T, int MT, int NT, int KQ, int MODE>
+__global__ __launch_bounds__(kBlock) void batched_gemm_mfma_kernel(int64_t batch, int m_arg, int n_arg, int k_arg,
+                                                                   T alpha, const T *__restrict__ A,
+                                                                   const T *__restrict__ B, T beta, T *__restrict__ C)
+{
+    constexpr int H = 16 / (int)sizeof(T);
+    constexpr bool EXACT = MODE == 2;
+    const int m = EXACT ? 16 * MT : m_arg, n = EXACT ? 16 * NT : n_arg, k = EXACT ? 4 * H * KQ : k_arg;
+    typedef T vec_t __attribute__((ext_vector_type(16 / sizeof(T))));
+    typedef typename MfmaTile<T>::acc_t acc_t;
+    const int lane = threadIdx.x % kWave, i = lane % 16, g = lane / 16;
+    const int64_t b = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (b >= batch) return;                              // whole wavefronts leave together
+    const T *__restrict__ a = A + b * (m * k);
+    const T *__restrict__ bm = B + b * (k * n);
+    T *__restrict__ c = C + b * (m * n);
+    vec_t af[MT][KQ];
+    T bf[KQ][H][NT];
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int q = 0; q < KQ; ++q) {
+            const int row = rt * 16 + i, kk = q * 4 * H + g * H;
+            if constexpr (EXACT) {
+                af[rt][q] = *reinterpret_cast<const vec_t *>(a + row * k + kk);
+            } else if constexpr (MODE == 1) {
+                vec_t zero;
+#pragma unroll
+                for (int h = 0; h < H; ++h) zero[h] = T(0);
+                af[rt][q] = (row < m && kk < k) ? *reinterpret_cast<const vec_t *>(a + row * k + kk) : zero;
+            } else {
+#pragma unroll
+                for (int h = 0; h < H; ++h) af[rt][q][h] = (row < m && kk + h < k) ? a[row * k + kk + h] : T(0);
+            }
+        }
+#pragma unroll
+    for (int q = 0; q < KQ; ++q)
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                // 16 doubles are a whole 128-byte line, read by nobody else; 16 floats share their
+                // line with another load of this wavefront (and so do A's 16 bytes per lane)
+                const int kk = q * 4 * H + g * H + h, col = ct * 16 + i;
+                const T *src = bm + kk * n + col;
+                if constexpr (EXACT) bf[q][h][ct] = sizeof(T) == 8 ? __builtin_nontemporal_load(src) : *src;
+                else bf[q][h][ct] = (kk < k && col < n) ? *src : T(0);
+            }
+    acc_t acc[MT][NT];
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) acc[rt][ct] = acc_t{0, 0, 0, 0};
+#pragma unroll
+    for (int q = 0; q < KQ; ++q)
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) acc[rt][ct] = MfmaTile<T>::mma(af[rt][q][h], bf[q][h][ct], acc[rt][ct]);
+#pragma unroll
+    for (int rt = 0; rt < MT; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = rt * 16 + MfmaTile<T>::row(g, v), col = ct * 16 + i;
+                if (EXACT || (row < m && col < n)) {
+                    T *dst = c + row * n + col;
+                    *dst = beta == T(0) ? alpha * acc[rt][ct][v] : alpha * acc[rt][ct][v] + beta * *dst;
+                }
+            }
+}
+
 template <typename T>
 int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const void *A, const void *B, double beta,
                        void *C, hipStream_t stream)
 {
+    // entries of kGemmMfmaMinElements and more go to the matrix cores, one wavefront per entry
+    // (measured: 12 x 12 x 12 and up are faster there, 8 x 8 x 8 and 10 x 20 x 5 are not)
+    if (m * k + k * n + m * n >= kGemmMfmaMinElements) {
+        constexpr int kStep = 4 * (16 / (int)sizeof(T));
+        constexpr int kMaxKq = kGemmMaxDim / kStep;
+        if (batch > INT32_MAX) return fail(LAPIS_ERR_INVALID_ARG, "lapis_batched_gemm: batch is too large");
+        const int mt = (m + 15) / 16, nt = (n + 15) / 16, kq = (k + kStep - 1) / kStep;
+        const bool aligned = reinterpret_cast<uintptr_t>(A) % 16 == 0;
+        const bool exact = m % 16 == 0 && n % 16 == 0 && k % kStep == 0 && aligned;
+        const bool whole = k % (kStep / 4) == 0 && aligned;       // A's 16-byte pieces
+#define LAPIS_GEMM_MFMA(MT, NT, KQ, MODE)                                                                        \
+    batched_gemm_mfma_kernel<T, MT, NT, KQ, MODE>                                                                \
+        <<<dim3((uint32_t)((batch + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(          \
+            batch, m, n, k, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta, static_cast<T *>(C))
+#define LAPIS_GEMM_MFMA_E(MT, NT, KQ)                    \
+    do {                                                 \
+        if (exact) LAPIS_GEMM_MFMA(MT, NT, KQ, 2);       \
+        else if (whole) LAPIS_GEMM_MFMA(MT, NT, KQ, 1);  \
+        else LAPIS_GEMM_MFMA(MT, NT, KQ, 0);             \
+    } while (0)
+        // kq <= kMaxKq (2 for floats, 4 for doubles); the clamps keep the other cases from being built
+#define LAPIS_GEMM_MFMA_K(MT, NT)                                                        \
+    do {                                                                                 \
+        if (kq == 1) LAPIS_GEMM_MFMA_E(MT, NT, 1);                                       \
+        else if (kq == 2) LAPIS_GEMM_MFMA_E(MT, NT, 2);                                  \
+        else if (kq == 3) LAPIS_GEMM_MFMA_E(MT, NT, (kMaxKq >= 3 ? 3 : 1));              \
+        else LAPIS_GEMM_MFMA_E(MT, NT, (kMaxKq >= 4 ? 4 : 1));                           \
+    } while (0)
+        if (mt == 1 && nt == 1) LAPIS_GEMM_MFMA_K(1, 1);
+        else if (mt == 1) LAPIS_GEMM_MFMA_K(1, 2);
+        else if (nt == 1) LAPIS_GEMM_MFMA_K(2, 1);
+        else LAPIS_GEMM_MFMA_K(2, 2);
+#undef LAPIS_GEMM_MFMA_K
+#undef LAPIS_GEMM_MFMA_E
+#undef LAPIS_GEMM_MFMA
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return fail(LAPIS_ERR_DEVICE, std::string("lapis_batched_gemm: ") + hipGetErrorString(err));
+        return LAPIS_OK;
+    }
     int stride = m * k + k * n;
     if (stride % 2 == 0) stride += 1;
     const int capacity = kGemmTileBytes / (int)sizeof(T);
@@ -254,7 +402,6 @@ int batched_gemm_typed(int64_t batch, int m, int n, int k, double alpha, const v
             batch, m, n, k, E, stride, (T)alpha, static_cast<const T *>(A), static_cast<const T *>(B), (T)beta,
             static_cast<T *>(C));
     else if (cube && m == 8) LAPIS_GEMM_CUBE(8);
-    else if (cube && m == 16) LAPIS_GEMM_CUBE(16);       // (32: the unrolled nest is slower than the loop)
     else if (vec && vecc) LAPIS_GEMM_PICK(true, true);
     else if (vec) LAPIS_GEMM_PICK(true, false);
     else if (vecc) LAPIS_GEMM_PICK(false, true);

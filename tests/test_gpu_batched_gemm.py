@@ -46,7 +46,9 @@ def _check(A, B, alpha=1.0, beta=0.0, C0=None, what=""):
 
 
 SHAPES = [(1, 1, 1), (2, 3, 4), (3, 3, 3), (4, 4, 4), (5, 7, 6), (8, 8, 8), (7, 1, 9), (1, 13, 2), (12, 12, 12),
-          (16, 16, 16), (10, 20, 5), (17, 5, 31), (32, 32, 32), (32, 1, 32), (2, 32, 2)]
+          (16, 16, 16), (10, 20, 5), (17, 5, 31), (32, 32, 32), (32, 1, 32), (2, 32, 2),
+          # whole matrix-core tiles in m and n, k in whole steps (8 doubles / 16 floats) and not
+          (16, 32, 8), (32, 16, 24), (16, 16, 32), (32, 32, 16), (32, 32, 8), (16, 32, 12), (32, 32, 20)]
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
@@ -59,6 +61,34 @@ def test_batched_gemm_shapes(m, n, k, dtype):
     C0 = gen.uniform(51, 3, batch * m * n).reshape(batch, m, n).astype(dtype)
     _check(A, B, what="alpha=1 beta=0")
     _check(A, B, -0.5, 1.25, C0, what="alpha=-0.5 beta=1.25")
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("m,n,k", [(8, 8, 8), (12, 12, 12), (16, 16, 16), (24, 20, 32), (32, 32, 32)])
+def test_batched_gemm_operands_one_element_off_alignment(m, n, k, dtype):
+    """Operands that start one element into their allocations: aligned to the element only, so neither
+    kernel may use its 16-byte accesses."""
+    say(f"batched gemm {m}x{n}x{k} {np.dtype(dtype).name}, operands one element past 16-byte alignment")
+    batch = 301
+    A = gen.uniform(53, 1, batch * m * k).reshape(batch, m, k).astype(dtype)
+    B = gen.uniform(53, 2, batch * k * n).reshape(batch, k, n).astype(dtype)
+    C0 = gen.uniform(53, 3, batch * m * n).reshape(batch, m, n).astype(dtype)
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.from_numpy(a).dtype, device="cuda")
+        view = buf[1:].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 != 0
+        return view
+
+    dA, dB, dC = shifted(A), shifted(B), shifted(C0)
+    code = L.LAPIS_F64 if dtype == np.float64 else L.LAPIS_F32
+    L.lapis_batched_gemm(batch, m, n, k, 0.75, dA, dB, -1.5, dC, code, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    ref, absAB = oracle.batched_gemm(A, B, 0.75, -1.5, C0)
+    bound = 8.0 * (k + 2) * EPS[dtype] * (0.75 * absAB + 1.5 * np.abs(C0))
+    assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= bound)
 
 
 def test_batched_gemm_small_integers_exact_and_batch_sizes():
