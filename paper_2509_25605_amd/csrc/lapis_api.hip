@@ -970,6 +970,8 @@ int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, i
     if (A->nrows > 0 && !d_Y) return fail(LAPIS_ERR_INVALID_ARG, "d_Y is NULL");
     if (A->nnz > 0 && !d_X) return fail(LAPIS_ERR_INVALID_ARG, "d_X is NULL");
     if (A->nrows == 0) return LAPIS_OK;
+    // one column stored as a plain vector is the matrix-vector product, which has the faster kernels
+    if (k == 1 && ldx == 1 && ldy == 1) return lapis_spmv(A, alpha, d_X, beta, d_Y, hip_stream);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     return A->dtype == LAPIS_F64 ? spmm_typed<double>(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream)
                                  : spmm_typed<float>(A, k, alpha, d_X, ldx, beta, d_Y, ldy, stream);

@@ -672,7 +672,7 @@ def test_workload4_wide_reduced():
 # SpMM
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
-@pytest.mark.parametrize("k,ldx,ldy", [(1, None, None), (2, None, None), (3, 5, 4), (16, None, None),
+@pytest.mark.parametrize("k,ldx,ldy", [(1, None, None), (1, 3, 2), (2, None, None), (3, 5, 4), (16, None, None),
                                        (16, 20, 24), (17, None, None), (40, 40, 44), (130, None, None)])
 def test_spmm_general_matrices(dtype, k, ldx, ldy):
     say(f"spmm general k={k} ldx={ldx} ldy={ldy} {np.dtype(dtype).name}")
