@@ -741,6 +741,111 @@ def test_workload4_exponent_two_full_size():
 
 
 # ---------------------------------------------------------------------------
+# the largest matrix the interface takes: LAPIS_MAX_NNZ entries (entry ids up to 2^31 - 2^16 - 1)
+# ---------------------------------------------------------------------------
+MAX_NNZ = 2 ** 31 - 2 ** 16          # LAPIS_MAX_NNZ of the header
+
+
+@pytest.mark.parametrize("kind", ["diagonals", "scattered"])
+def test_spmv_at_the_entry_limit(kind):
+    """32 entries in every row, built on the device.  All values are small integers, so every sum is
+    exact in float and the whole result can be compared with one computed by plain tensor operations
+    (a property that holds at any size); rows sampled across the range, the ones holding the entries
+    around 2^30 and the last ones among them, are also computed by the oracle from a copy of their entries."""
+    import torch
+    import paper_2509_25605_amd as lapis
+    per = 32
+    nnz = MAX_NNZ
+    n = nnz // per
+    assert n * per == nnz
+    say(f"entry limit, {kind}: nrows={n} nnz={nnz} float32")
+    dev = torch.device("cuda")
+    step = 1 << 22
+
+    def columns(r0, r1):
+        i = torch.arange(r0, r1, dtype=torch.int64, device=dev).view(-1, 1)
+        t = torch.arange(per, dtype=torch.int64, device=dev).view(1, -1)
+        if kind == "diagonals":                       # the same 32 diagonals in every row
+            c = i + (t - 16) * 1025
+        else:                                         # anywhere within 2046 columns of the diagonal
+            c = i + (t * 2654435761 + i * 40503) % 4093 - 2046
+        return c.clamp_(0, n - 1), (1 + (i + t) % 3).to(torch.float32)
+
+    rowptr = (torch.arange(n + 1, dtype=torch.int64, device=dev) * per).to(torch.int32)
+    colidx = torch.empty(nnz, dtype=torch.int32, device=dev)
+    vals = torch.empty(nnz, dtype=torch.float32, device=dev)
+    for r0 in range(0, n, step):
+        r1 = min(n, r0 + step)
+        c, v = columns(r0, r1)
+        colidx[r0 * per:r1 * per] = c.reshape(-1).to(torch.int32)
+        vals[r0 * per:r1 * per] = v.reshape(-1)
+    x = (torch.arange(n, dtype=torch.int64, device=dev) % 7).to(torch.float32)
+    expected = torch.empty(n, dtype=torch.float32, device=dev)
+    for r0 in range(0, n, step):
+        r1 = min(n, r0 + step)
+        c, v = columns(r0, r1)
+        expected[r0:r1] = (v.double() * x[c].double()).sum(1).to(torch.float32)
+    del c, v
+    rows = np.unique(np.concatenate([
+        [0, 1, 31, 32, n // 2, (2 ** 30) // per - 1, (2 ** 30) // per, n - 33, n - 32, n - 2, n - 1],
+        (gen.uniform(77, 1, 40, 0.0, 1.0) * n).astype(np.int64)]))
+    pick = torch.from_numpy(rows).to(dev)
+    sub_col = colidx.view(n, per)[pick].cpu().numpy().reshape(-1)
+    sub_val = vals.view(n, per)[pick].cpu().numpy().reshape(-1)
+    sub_ptr = (np.arange(rows.size + 1) * per).astype(np.int32)
+    ref, absAx = oracle.spmv(sub_ptr, sub_col, sub_val, x.cpu().numpy())
+    assert np.array_equal(ref, expected[pick].cpu().numpy())       # the two references agree
+
+    say("create")
+    M = lapis.CsrMatrix(n, n, rowptr, colidx, vals)
+    try:
+        y = torch.full((n,), float("nan"), dtype=torch.float32, device=dev)
+        say("tuned product")
+        M.spmv(x, y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, expected)
+        assert np.array_equal(y[pick].cpu().numpy(), ref)
+        say("paper-shape product")
+        y.fill_(float("nan"))
+        lapis.lapis_spmv_paper_shape(M.handle, 1.0, x, 0.0, y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, expected)
+        say("two columns")
+        X = torch.stack([x, 2.0 * x], dim=1).contiguous()
+        Y = torch.full((n, 2), float("nan"), dtype=torch.float32, device=dev)
+        M.spmm(X, Y)
+        torch.cuda.synchronize()
+        assert torch.equal(Y[:, 0], expected) and torch.equal(Y[:, 1], 2.0 * expected)
+        del X, Y
+        # the transposed product, by atomics and through a handle for A^T (integer sums below 2^24:
+        # exact in float in any order)
+        expected_t = torch.zeros(n, dtype=torch.float64, device=dev)
+        for r0 in range(0, n, step):
+            r1 = min(n, r0 + step)
+            c, v = columns(r0, r1)
+            expected_t.index_add_(0, c.reshape(-1), (v.double() * x[r0:r1].double().view(-1, 1)).reshape(-1))
+        del c, v
+        assert float(expected_t.max()) < 2 ** 24
+        expected_t = expected_t.to(torch.float32)
+        say("transposed product by atomics")
+        y.fill_(float("nan"))
+        M.spmv_transpose(x, y)
+        torch.cuda.synchronize()
+        assert torch.equal(y, expected_t)
+        say("transposed handle")
+        T = M.transposed()
+        try:
+            y.fill_(float("nan"))
+            T.spmv(x, y)
+            torch.cuda.synchronize()
+            assert torch.equal(y, expected_t)
+        finally:
+            T.close()
+    finally:
+        M.close()
+
+
+# ---------------------------------------------------------------------------
 # seeded sweep over structures: sections of a matrix built in different ways, so that patterned,
 # narrow, framed and plain chunks, grouped and single wavefronts, bins and tiles meet in one handle
 # ---------------------------------------------------------------------------
