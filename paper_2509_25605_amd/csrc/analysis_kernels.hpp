@@ -295,8 +295,11 @@ __global__ __launch_bounds__(kCompactBlock) void narrow_count_kernel(int32_t nro
 // one wavefront per chunk: the distinct frames (column >> 11) are taken out smallest first; with
 // at most 32 of them the chunk becomes "framed": chunk_base = -2 and frame_table[32*c + k] = the
 // k-th smallest frame (the largest one repeated above the count).  frame_table must be 0 on entry.
+// Where the chunk's frames span fewer than kFrameBitmapBits they are marked in a bitmap (two
+// passes over the entries in all); otherwise every frame taken out costs a pass.
 constexpr int kAnalysisFrameShift = 11;
 constexpr int kAnalysisFrameSlots = 32;
+constexpr int kFrameBitmapBits = 8192;     // widest range of frames (16.8 M columns) handled with a bitmap in LDS
 __global__ __launch_bounds__(kBlock) void chunk_frames_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                               const int32_t *__restrict__ chunk_flag,
                                                               const int32_t *__restrict__ rowptr,
@@ -311,21 +314,75 @@ __global__ __launch_bounds__(kBlock) void chunk_frames_kernel(int32_t nrows, int
     const int64_t first = c * chunk_rows;
     const int64_t last_row = (first + chunk_rows < nrows) ? first + chunk_rows : nrows;
     const int32_t b = rowptr[first], e = rowptr[last_row];
-    int32_t last = -1, mine = 0, count = 0;
-    for (int k = 0; k <= kAnalysisFrameSlots; ++k) {
-        int32_t rev = 0;                               // INT32_MAX - (smallest frame above `last` seen by this lane)
-        for (int32_t j = b + lane; j < e; j += kWave) {
-            const int32_t f = colidx[j] >> kAnalysisFrameShift;
-            if (f > last) rev = max(rev, INT32_MAX - f);
-        }
-        rev = wave_max_nonneg(rev);
-        if (rev == 0) break;                           // no frame left
-        if (k == kAnalysisFrameSlots) { count = kAnalysisFrameSlots + 1; break; }
-        last = INT32_MAX - rev;
-        if (lane == k) mine = last;
-        count = k + 1;
+    // smallest and largest frame of the chunk
+    int32_t rev_lo = 0, hi = 0;
+    for (int32_t j = b + lane; j < e; j += kWave) {
+        const int32_t f = load_stream(colidx + j) >> kAnalysisFrameShift;
+        rev_lo = max(rev_lo, INT32_MAX - f);
+        hi = max(hi, f);
     }
-    if (count > kAnalysisFrameSlots) return;           // too scattered: stays -1
+    rev_lo = wave_max_nonneg(rev_lo);
+    hi = wave_max_nonneg(hi);
+    if (rev_lo == 0) return;                           // no entries (cannot happen for a flagged chunk)
+    const int32_t lo = INT32_MAX - rev_lo;
+    int32_t last = -1, mine = 0, count = 0;
+    if (hi - lo < kFrameBitmapBits) {
+        // one more pass marks the frames in a bitmap in LDS; the set bits in ascending order are the table
+        __shared__ uint32_t s_bits[kWavesPerBlock][kFrameBitmapBits / 32];
+        uint32_t *bits = s_bits[threadIdx.x / kWave];
+        constexpr int kWordsPerLane = kFrameBitmapBits / 32 / kWave;
+#pragma unroll
+        for (int q = 0; q < kWordsPerLane; ++q) bits[lane * kWordsPerLane + q] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int32_t j = b + lane; j < e; j += kWave) {
+            const int32_t f = (load_stream(colidx + j) >> kAnalysisFrameShift) - lo;
+            atomicOr(&bits[f >> 5], 1u << (f & 31));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t word[kWordsPerLane];
+        int32_t set = 0;
+#pragma unroll
+        for (int q = 0; q < kWordsPerLane; ++q) {
+            word[q] = bits[lane * kWordsPerLane + q];
+            set += __popc(word[q]);
+        }
+        count = 0;
+        for (int d = 0; d < kWave; ++d) count += __builtin_amdgcn_readlane(set, d);
+        if (count > kAnalysisFrameSlots) return;       // too scattered: stays -1
+        for (int k = 0; k < count; ++k) {              // uniform: the k-th smallest marked frame
+            int32_t rev = 0;
+#pragma unroll
+            for (int q = kWordsPerLane - 1; q >= 0; --q) {
+                if (word[q]) rev = INT32_MAX - (lo + (lane * kWordsPerLane + q) * 32 + (__ffs(word[q]) - 1));
+            }
+            rev = wave_max_nonneg(rev);
+            last = INT32_MAX - rev;
+            if (lane == k) mine = last;
+            const int32_t at = last - lo;              // clear it in the lane that holds it
+#pragma unroll
+            for (int q = 0; q < kWordsPerLane; ++q)
+                if ((at >> 5) == lane * kWordsPerLane + q) word[q] &= ~(1u << (at & 31));
+        }
+    } else {
+        for (int k = 0; k <= kAnalysisFrameSlots; ++k) {
+            int32_t rev = 0;                           // INT32_MAX - (smallest frame above `last` seen by this lane)
+            for (int32_t j = b + lane; j < e; j += kWave) {
+                const int32_t f = colidx[j] >> kAnalysisFrameShift;
+                if (f > last) rev = max(rev, INT32_MAX - f);
+            }
+            rev = wave_max_nonneg(rev);
+            if (rev == 0) break;                       // no frame left
+            if (k == kAnalysisFrameSlots) { count = kAnalysisFrameSlots + 1; break; }
+            last = INT32_MAX - rev;
+            if (lane == k) mine = last;
+            count = k + 1;
+        }
+        if (count > kAnalysisFrameSlots) return;       // too scattered: stays -1
+    }
     if (lane < kAnalysisFrameSlots) frame_table[c * kAnalysisFrameSlots + lane] = lane < count ? mine : last;
     if (lane == 0) chunk_base[c] = -2;
 }
