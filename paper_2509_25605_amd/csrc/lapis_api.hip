@@ -785,6 +785,18 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         for (int cls = 1; cls <= kStreamClasses; ++cls)
             all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
+            bool launched = false;
+            if constexpr (kStreamLanes == 8) {
+                // four rows per slot and row patterns: chunks of repeating diagonals share rows of X
+                if (all16 && A->d_pat_off) {
+                    spmm_stream_kernel<T, VEC, kStreamLanes, true, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                        (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                        A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b,
+                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, (int32_t)A->ncols);
+                    launched = true;
+                }
+            }
+            if (launched) continue;
             if (all16)
                 spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
                     (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,

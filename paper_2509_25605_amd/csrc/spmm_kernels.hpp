@@ -60,14 +60,24 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 // ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
-template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false>
+//
+// WINDOW (needs ALL16 and four rows per slot; pats = the row patterns of the matrix, ncols its
+// columns): a chunk whose rows repeat the diagonals of its longest row, or ordered subsets of
+// them, is worked on differently.  A slot takes 4 CONSECUTIVE rows, and for every run of up to 3
+// consecutive diagonals d, d+1, d+2 of that longest row it loads the rows r0+d .. r0+d+5 of X
+// once: row r0+p needs X rows r0+p+d+e = the p+e-th of them, so 6 loads serve 12 products (a
+// stencil's neighbouring rows share two thirds of their columns).  Rows with fewer diagonals
+// (grid boundaries) carry a bit mask of the diagonals they have and skip the others.  Chunks
+// that do not qualify take the ordinary path.
+template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false, bool WINDOW = false>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     uint32_t xcd_block, const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
     const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16,
     const T *__restrict__ vals, int64_t k,
-    int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
+    int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta,
+    StreamPatterns pats = StreamPatterns{nullptr, nullptr, nullptr}, int32_t ncols = 0)
 {
     static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
     constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
@@ -119,9 +129,151 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
         for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
 
+    bool staged = false;               // the chunk's entries already are in LDS (one window holds them all)
+    if constexpr (WINDOW) {
+        static_assert(ALL16 && kPasses == 4 && kSlots * 4 == kStreamRows, "a slot takes 4 consecutive rows");
+        __shared__ int32_t s_pat[kPatternTable];
+        __shared__ uint64_t s_mask[kStreamRows];
+        const int32_t w0 = base & ~7;
+        const int32_t pat_begin = pats.pat_off[chunk];
+        const int32_t pat_len = pats.pat_off[chunk + 1] - pat_begin;   // wave-uniform; 0: not patterned
+        if (pat_len > 0 && end - w0 <= kStreamWindow && cbase >= 0) {
+            // the chunk's pattern table, and lane r < 32: row r of the chunk
+            constexpr int kLoads = kPatternTable / kWave;
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i)
+                if (i * kWave < pat_len) s_pat[i * kWave + lane] = (i * kWave + lane < pat_len) ? pats.pool[pat_begin + i * kWave + lane] : 0;
+            const int64_t my_row = row0 + (lane < kStreamRows ? lane : 0);
+            const int32_t my_len = (lane < kStreamRows) ? s_rp[lane + 1] - s_rp[lane] : 0;
+            const int32_t my_pat = (lane < kStreamRows && my_row < nrows && my_len > 0) ? (int32_t)pats.row_pat[my_row] : 0;
+            stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, end, nnz4, lane, s_col, s_val);
+            staged = true;
+            // the reference list: the diagonals of the first longest row, one per lane
+            const int32_t ref_len = wave_max_nonneg(my_len);
+            const uint64_t longest = __builtin_amdgcn_ballot_w64(my_len == ref_len);
+            const int ref_lane = (int)__builtin_ctzll(longest);
+            const int32_t ref_pat = __builtin_amdgcn_readlane(my_pat, ref_lane);
+            bool all_ok = ref_len <= kWave;
+            uint64_t breaks = 0;                                       // where a run of consecutive diagonals starts
+            int32_t pstar = 0;
+            uint64_t mask = 0;
+            if (all_ok) {
+                const bool in_ref = lane < ref_len;
+                pstar = in_ref ? s_pat[ref_pat + lane] : 0;
+                const int32_t before = (in_ref && lane > 0) ? s_pat[ref_pat + lane - 1] : INT32_MIN;
+                all_ok = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before) == 0;   // ascends strictly
+                // the runs of consecutive diagonals have to come in whole threes (27-point stencils, blocks
+                // of 3 unknowns): the loop below takes three diagonals and six rows of X at a time
+                breaks = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));
+                all_ok = all_ok && ref_len % 3 == 0 && (breaks & ~0x9249249249249249ull) == 0;
+                const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
+                const bool is_row = lane < kStreamRows;
+                mask = (is_row && my_len > 0) ? full : 0;
+                // rows with another list: which of the reference diagonals they have
+                uint64_t other = __builtin_amdgcn_ballot_w64(is_row && my_len > 0 && !(my_pat == ref_pat && my_len == ref_len));
+                while (other != 0 && all_ok) {                         // uniform
+                    const int r = (int)__builtin_ctzll(other);
+                    other &= other - 1;
+                    const int32_t pr = __builtin_amdgcn_readlane(my_pat, r);
+                    const int32_t nr = __builtin_amdgcn_readlane(my_len, r);
+                    bool has = false;
+                    for (int u = 0; u < nr; ++u) has = has || (s_pat[pr + u] == pstar);   // uniform trip count, broadcast reads
+                    const uint64_t mk = __builtin_amdgcn_ballot_w64(in_ref && has);
+                    // all of the row's diagonals met, and in ascending order like the reference
+                    const bool falls = lane > 0 && lane < nr && s_pat[pr + lane] <= s_pat[pr + lane - 1];
+                    all_ok = __popcll(mk) == nr && __builtin_amdgcn_ballot_w64(falls) == 0;
+                    if (lane == r) mask = mk;
+                }
+                if (is_row) s_mask[lane] = mask;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (all_ok) {
+                if (active) {
+                    const int r0 = slot * 4;
+                    uint64_t m[4];
+                    int32_t first[4];
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) {
+                        m[pp] = s_mask[r0 + pp];
+                        first[pp] = s_rp[r0 + pp] - w0;
+                    }
+                    const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
+                    // uniform: the p-th row of every slot at work here has the whole reference list (no mask,
+                    // no select); a grid boundary usually touches one of the four
+                    bool whole[4];
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) whole[pp] = __builtin_amdgcn_ballot_w64(m[pp] != full) == 0;
+                    // X row (r0 + d + q) as an offset from row cbase, kept inside X and inside 16 bits
+                    const int32_t rel0 = (int32_t)(row0 + r0 - cbase);
+                    const int32_t rel_max = (ncols - 1 - cbase) < 0xffff ? (ncols - 1 - cbase) : 0xffff;
+                    auto x_at = [&](int32_t d, int q) {
+                        int32_t rel = rel0 + d + q;
+                        rel = rel < 0 ? 0 : (rel > rel_max ? rel_max : rel);
+                        return x_row(rel);
+                    };
+                    constexpr int kRuns = 3;                           // runs whose rows of X are in flight together
+#pragma unroll 1
+                    for (int t0 = 0; t0 < ref_len; t0 += 3 * kRuns) {  // uniform
+                        Pack<T, VEC> xw[kRuns][6];
+#pragma unroll
+                        for (int rr = 0; rr < kRuns; ++rr) {
+                            if (t0 + 3 * rr < ref_len) {               // uniform
+                                const int32_t d = __builtin_amdgcn_readlane(pstar, t0 + 3 * rr);
+#pragma unroll
+                                for (int q = 0; q < 6; ++q) xw[rr][q] = x_at(d, q);
+                            }
+                        }
+#pragma unroll
+                        for (int rr = 0; rr < kRuns; ++rr) {
+                            const int tb = t0 + 3 * rr;
+                            if (tb >= ref_len) continue;               // uniform
+                            T v[3][4];
+#pragma unroll
+                            for (int e = 0; e < 3; ++e)
+#pragma unroll
+                                for (int pp = 0; pp < 4; ++pp) {
+                                    int at = tb + e;
+                                    if (!whole[pp]) {                                     // uniform
+                                        at = __popcll(m[pp] & ((1ull << (tb + e)) - 1));
+                                        at = first[pp] + at < kStreamWindow ? at : 0;
+                                    }
+                                    v[e][pp] = s_val[first[pp] + at];
+                                }
+#pragma unroll
+                            for (int e = 0; e < 3; ++e)
+#pragma unroll
+                                for (int pp = 0; pp < 4; ++pp) {
+                                    if (whole[pp]) {                                      // uniform
+#pragma unroll
+                                        for (int q = 0; q < VEC; ++q)
+                                            acc[pp][q] = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
+                                    } else {
+                                        const bool has = (m[pp] >> (tb + e)) & 1;
+#pragma unroll
+                                        for (int q = 0; q < VEC; ++q) {
+                                            const T sum = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
+                                            acc[pp][q] = has ? sum : acc[pp][q];
+                                        }
+                                    }
+                                }
+                        }
+                    }
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) {
+                        const int64_t row = row0 + r0 + pp;
+                        if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[pp], col, k, alpha, beta);
+                    }
+                }
+                return;
+            }
+            // not all rows fit the reference list: the ordinary path below finds the window staged
+        }
+    }
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
-        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
+        if (!staged) stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
             const int r = active ? p * kSlots + slot : 0;

@@ -694,6 +694,39 @@ def test_spmm_general_matrices(dtype, k, ldx, ldy):
         dev.close()
 
 
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float64, 13), (np.float32, 32), (np.float32, 16)])
+@pytest.mark.parametrize("grid", [(128, 5, 4), (96, 3, 3), (64, 6, 5), (33, 9, 7)])
+def test_spmm_rows_of_x_shared_between_neighbouring_rows(grid, dtype, k):
+    """27-point stencils with grid lines of 4, 3, 2 and about 1 chunks: chunks whose rows all repeat
+    one list of diagonals, chunks with a boundary row in their first or last slot (a shorter,
+    masked list), and chunks that straddle grid lines.  With 8 lanes per row of X (f64 k = 16,
+    f32 k = 32) a slot takes 4 consecutive rows and loads 6 rows of X per run of 3 diagonals."""
+    nx, ny, nz = grid
+    say(f"spmm shared rows of X, stencil {nx}x{ny}x{nz} k={k} {np.dtype(dtype).name}")
+    rowptr, colidx, vals = gen.stencil27(nx, ny, nz, 41)
+    vals = vals.astype(dtype)
+    n = nx * ny * nz
+    X = gen.uniform(43, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+    Y0 = gen.uniform(43, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, -0.75, 0.5, Y0, what="alpha=-0.75 beta=0.5", ldx=k + 3, ldy=k + 1)
+        # a row of X that is not finite reaches exactly the rows of Y whose matrix rows hold that column:
+        # no product of an absent entry (a masked diagonal, a row of X loaded for a neighbour) may leak in
+        for j in (0, n // 2 + 1, n - 1):
+            Xi = X.copy()
+            Xi[j, :] = np.inf
+            ref, _ = oracle.spmm(rowptr, colidx, vals, Xi)
+            got = dev.spmm(Xi)
+            assert np.array_equal(np.isfinite(got), np.isfinite(ref)), f"non-finite row {j} of X spread differently"
+            hit = ~np.isfinite(ref)
+            assert np.array_equal(got[hit], ref[hit])
+            assert hit.any(axis=1).sum() == np.count_nonzero(colidx == j)
+    finally:
+        dev.close()
+
+
 # ---------------------------------------------------------------------------
 # the five workloads: reduced sizes (several tiles + ragged tail) and full size
 # ---------------------------------------------------------------------------
