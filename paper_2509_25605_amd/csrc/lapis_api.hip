@@ -788,11 +788,18 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
             bool launched = false;
             if constexpr (kStreamLanes == 8) {
                 // four rows per slot and row patterns: chunks of repeating diagonals share rows of X
-                if (all16 && A->d_pat_off) {
-                    spmm_stream_kernel<T, VEC, kStreamLanes, true, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                        (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                        A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b,
-                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, (int32_t)A->ncols);
+                if (A->d_pat_off && ldx * (int64_t)sizeof(T) <= 0xffff) {
+                    const StreamPatterns pats{A->d_pat_off, A->d_row_pat, A->d_pat_pool};
+                    if (all16)
+                        spmm_stream_kernel<T, VEC, kStreamLanes, true, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                            A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b, pats,
+                            (int32_t)A->ncols);
+                    else
+                        spmm_stream_kernel<T, VEC, kStreamLanes, true, false, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
+                            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
+                            A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b, pats,
+                            (int32_t)A->ncols);
                     launched = true;
                 }
             }

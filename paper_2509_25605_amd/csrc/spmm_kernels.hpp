@@ -61,9 +61,10 @@ constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 // ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
 //
-// WINDOW (needs ALL16 and four rows per slot; pats = the row patterns of the matrix, ncols its
-// columns): a chunk whose rows repeat the diagonals of its longest row, or ordered subsets of
-// them, is worked on differently.  A slot takes 4 CONSECUTIVE rows, and for every run of up to 3
+// WINDOW (needs four rows per slot and rows of X shorter than 64 KiB; pats = the row patterns
+// of the matrix, ncols its columns): a chunk whose rows repeat the diagonals of its longest row,
+// or ordered subsets of them, is worked on differently, from the values and the pattern table
+// alone (no column index is read).  A slot takes 4 CONSECUTIVE rows, and for every run of up to 3
 // consecutive diagonals d, d+1, d+2 of that longest row it loads the rows r0+d .. r0+d+5 of X
 // once: row r0+p needs X rows r0+p+d+e = the p+e-th of them, so 6 loads serve 12 products (a
 // stencil's neighbouring rows share two thirds of their columns).  Rows with fewer diagonals
@@ -129,15 +130,16 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
         for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
 
-    bool staged = false;               // the chunk's entries already are in LDS (one window holds them all)
     if constexpr (WINDOW) {
-        static_assert(ALL16 && kPasses == 4 && kSlots * 4 == kStreamRows, "a slot takes 4 consecutive rows");
-        __shared__ int32_t s_pat[kPatternTable];
+        static_assert(kPasses == 4 && kSlots * 4 == kStreamRows, "a slot takes 4 consecutive rows");
+        // the pattern table takes the place of the column window, which this path does not fill
+        static_assert(kPatternTable * sizeof(int32_t) <= kStreamWindow * sizeof(idx_t), "the table fits the column window");
+        int32_t *s_pat = reinterpret_cast<int32_t *>(s_col);
         __shared__ uint64_t s_mask[kStreamRows];
         const int32_t w0 = base & ~7;
         const int32_t pat_begin = pats.pat_off[chunk];
         const int32_t pat_len = pats.pat_off[chunk + 1] - pat_begin;   // wave-uniform; 0: not patterned
-        if (pat_len > 0 && end - w0 <= kStreamWindow && cbase >= 0) {
+        if (pat_len > 0 && end - w0 <= kStreamWindow) {
             // the chunk's pattern table, and lane r < 32: row r of the chunk
             constexpr int kLoads = kPatternTable / kWave;
 #pragma unroll
@@ -146,8 +148,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
             const int64_t my_row = row0 + (lane < kStreamRows ? lane : 0);
             const int32_t my_len = (lane < kStreamRows) ? s_rp[lane + 1] - s_rp[lane] : 0;
             const int32_t my_pat = (lane < kStreamRows && my_row < nrows && my_len > 0) ? (int32_t)pats.row_pat[my_row] : 0;
-            stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, end, nnz4, lane, s_col, s_val);
-            staged = true;
+            // the values are needed either way and their loads overlap those above; no column is read here
+            stream_values_to_lds<T>(vals, w0, end, nnz4, lane, s_val);     // ends with the wavefront's fence
             // the reference list: the diagonals of the first longest row, one per lane
             const int32_t ref_len = wave_max_nonneg(my_len);
             const uint64_t longest = __builtin_amdgcn_ballot_w64(my_len == ref_len);
@@ -166,6 +168,9 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                 // of 3 unknowns): the loop below takes three diagonals and six rows of X at a time
                 breaks = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));
                 all_ok = all_ok && ref_len % 3 == 0 && (breaks & ~0x9249249249249249ull) == 0;
+                // rows of X are addressed by 32-bit byte offsets from the row of the smallest diagonal
+                const int64_t span = (int64_t)__builtin_amdgcn_readlane(pstar, ref_len - 1) - __builtin_amdgcn_readlane(pstar, 0) + 2 * kStreamRows;
+                all_ok = all_ok && span < (1 << 24) && span * (int64_t)row_bytes < ((int64_t)1 << 31);
                 const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
                 const bool is_row = lane < kStreamRows;
                 mask = (is_row && my_len > 0) ? full : 0;
@@ -205,13 +210,17 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                     bool whole[4];
 #pragma unroll
                     for (int pp = 0; pp < 4; ++pp) whole[pp] = __builtin_amdgcn_ballot_w64(m[pp] != full) == 0;
-                    // X row (r0 + d + q) as an offset from row cbase, kept inside X and inside 16 bits
-                    const int32_t rel0 = (int32_t)(row0 + r0 - cbase);
-                    const int32_t rel_max = (ncols - 1 - cbase) < 0xffff ? (ncols - 1 - cbase) : 0xffff;
+                    // X row (r0 + d + q) as an offset from the row of the smallest diagonal, kept inside X
+                    int64_t base_row = row0 + __builtin_amdgcn_readlane(pstar, 0);                 // uniform
+                    base_row = base_row < 0 ? 0 : (base_row > ncols - 1 ? ncols - 1 : base_row);
+                    const char *x_base = reinterpret_cast<const char *>(X + base_row * ldx);
+                    const int32_t rel0 = (int32_t)(row0 + r0 - base_row);
+                    const int32_t rel_max = (int32_t)(ncols - 1 - base_row);
                     auto x_at = [&](int32_t d, int q) {
                         int32_t rel = rel0 + d + q;
                         rel = rel < 0 ? 0 : (rel > rel_max ? rel_max : rel);
-                        return x_row(rel);
+                        return *reinterpret_cast<const Pack<T, VEC> *>(
+                            x_base + (__umul24((uint32_t)rel, row_bytes) + (uint32_t)(col * (int64_t)sizeof(T))));
                     };
                     constexpr int kRuns = 3;                           // runs whose rows of X are in flight together
 #pragma unroll 1
@@ -268,12 +277,12 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                 }
                 return;
             }
-            // not all rows fit the reference list: the ordinary path below finds the window staged
+            // not all rows fit the reference list: the ordinary path
         }
     }
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
-        if (!staged) stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
+        stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
             const int r = active ? p * kSlots + slot : 0;
