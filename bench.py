@@ -32,7 +32,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 DOMINANT_KERNEL = {
     "stencil27_128x128x128_f64": "spmv_stream_kernel<double, 2, true, 4> (4: row patterns)",
-    "stencil27_128x128x128_f64_spmm_k16": "spmm_stream_kernel<double, 2, 8, true, true>",
+    "stencil27_128x128x128_f64_spmm_k16": "spmm_stream_kernel<double, 2, 8, true, true, true> (last: rows of X shared by 4 consecutive rows)",
     "table3_Elasticity3D_60_n648000_f64": "spmv_stream_kernel<double, 8, true, 1> (1: 16-bit column offsets)",
 }
 
