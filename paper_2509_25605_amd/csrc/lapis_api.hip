@@ -786,8 +786,9 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
             all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
             bool launched = false;
-            if constexpr (kStreamLanes == 8) {
-                // four rows per slot and row patterns: chunks of repeating diagonals share rows of X
+            if constexpr (kStreamLanes >= 8) {
+                // four or eight rows per slot and row patterns: chunks of repeating diagonals share rows of X
+                // (with two rows per slot, 4 loads for 6 products, it is slower than the ordinary path)
                 if (A->d_pat_off && ldx * (int64_t)sizeof(T) <= 0xffff) {
                     const StreamPatterns pats{A->d_pat_off, A->d_row_pat, A->d_pat_pool};
                     if (all16)

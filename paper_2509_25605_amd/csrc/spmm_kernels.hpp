@@ -61,13 +61,13 @@ constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 // ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
 //
-// WINDOW (needs four rows per slot and rows of X shorter than 64 KiB; pats = the row patterns
+// WINDOW (needs R >= 2 rows per slot and rows of X shorter than 64 KiB; pats = the row patterns
 // of the matrix, ncols its columns): a chunk whose rows repeat the diagonals of its longest row,
 // or ordered subsets of them, is worked on differently, from the values and the pattern table
-// alone (no column index is read).  A slot takes 4 CONSECUTIVE rows, and for every run of up to 3
-// consecutive diagonals d, d+1, d+2 of that longest row it loads the rows r0+d .. r0+d+5 of X
-// once: row r0+p needs X rows r0+p+d+e = the p+e-th of them, so 6 loads serve 12 products (a
-// stencil's neighbouring rows share two thirds of their columns).  Rows with fewer diagonals
+// alone (no column index is read).  A slot takes R CONSECUTIVE rows (4 with 8 lanes per row of
+// X, 8 with 16), and for every 3 consecutive diagonals d, d+1, d+2 of that longest row it loads
+// the rows r0+d .. r0+d+R+1 of X once: row r0+p needs X rows r0+p+d+e = the p+e-th of them, so
+// R + 2 loads serve 3 R products (a stencil's neighbouring rows share two thirds of their columns).  Rows with fewer diagonals
 // (grid boundaries) carry a bit mask of the diagonals they have and skip the others.  Chunks
 // that do not qualify take the ordinary path.
 template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false, bool WINDOW = false>
@@ -131,7 +131,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
         for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
 
     if constexpr (WINDOW) {
-        static_assert(kPasses == 4 && kSlots * 4 == kStreamRows, "a slot takes 4 consecutive rows");
+        static_assert(kPasses >= 2 && kSlots * kPasses == kStreamRows, "a slot takes kPasses consecutive rows");
+        constexpr int R = kPasses;                 // consecutive rows of a slot: R + 2 rows of X serve 3 R products
         // the pattern table takes the place of the column window, which this path does not fill
         static_assert(kPatternTable * sizeof(int32_t) <= kStreamWindow * sizeof(idx_t), "the table fits the column window");
         int32_t *s_pat = reinterpret_cast<int32_t *>(s_col);
@@ -196,20 +197,20 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             if (all_ok) {
                 if (active) {
-                    const int r0 = slot * 4;
-                    uint64_t m[4];
-                    int32_t first[4];
+                    const int r0 = slot * R;
+                    uint64_t m[R];
+                    int32_t first[R];
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) {
+                    for (int pp = 0; pp < R; ++pp) {
                         m[pp] = s_mask[r0 + pp];
                         first[pp] = s_rp[r0 + pp] - w0;
                     }
                     const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
                     // uniform: the p-th row of every slot at work here has the whole reference list (no mask,
                     // no select); a grid boundary usually touches one of the four
-                    bool whole[4];
+                    bool whole[R];
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) whole[pp] = __builtin_amdgcn_ballot_w64(m[pp] != full) == 0;
+                    for (int pp = 0; pp < R; ++pp) whole[pp] = __builtin_amdgcn_ballot_w64(m[pp] != full) == 0;
                     // X row (r0 + d + q) as an offset from the row of the smallest diagonal, kept inside X
                     int64_t base_row = row0 + __builtin_amdgcn_readlane(pstar, 0);                 // uniform
                     base_row = base_row < 0 ? 0 : (base_row > ncols - 1 ? ncols - 1 : base_row);
@@ -222,27 +223,27 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                         return *reinterpret_cast<const Pack<T, VEC> *>(
                             x_base + (__umul24((uint32_t)rel, row_bytes) + (uint32_t)(col * (int64_t)sizeof(T))));
                     };
-                    constexpr int kRuns = 3;                           // runs whose rows of X are in flight together
+                    constexpr int kRuns = R <= 4 ? 3 : 2;                           // runs whose rows of X are in flight together
 #pragma unroll 1
                     for (int t0 = 0; t0 < ref_len; t0 += 3 * kRuns) {  // uniform
-                        Pack<T, VEC> xw[kRuns][6];
+                        Pack<T, VEC> xw[kRuns][R + 2];
 #pragma unroll
                         for (int rr = 0; rr < kRuns; ++rr) {
                             if (t0 + 3 * rr < ref_len) {               // uniform
                                 const int32_t d = __builtin_amdgcn_readlane(pstar, t0 + 3 * rr);
 #pragma unroll
-                                for (int q = 0; q < 6; ++q) xw[rr][q] = x_at(d, q);
+                                for (int q = 0; q < R + 2; ++q) xw[rr][q] = x_at(d, q);
                             }
                         }
 #pragma unroll
                         for (int rr = 0; rr < kRuns; ++rr) {
                             const int tb = t0 + 3 * rr;
                             if (tb >= ref_len) continue;               // uniform
-                            T v[3][4];
+                            T v[3][R];
 #pragma unroll
                             for (int e = 0; e < 3; ++e)
 #pragma unroll
-                                for (int pp = 0; pp < 4; ++pp) {
+                                for (int pp = 0; pp < R; ++pp) {
                                     int at = tb + e;
                                     if (!whole[pp]) {                                     // uniform
                                         at = __popcll(m[pp] & ((1ull << (tb + e)) - 1));
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
                             for (int e = 0; e < 3; ++e)
 #pragma unroll
-                                for (int pp = 0; pp < 4; ++pp) {
+                                for (int pp = 0; pp < R; ++pp) {
                                     if (whole[pp]) {                                      // uniform
 #pragma unroll
                                         for (int q = 0; q < VEC; ++q)
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                         }
                     }
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) {
+                    for (int pp = 0; pp < R; ++pp) {
                         const int64_t row = row0 + r0 + pp;
                         if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[pp], col, k, alpha, beta);
                     }

@@ -694,13 +694,15 @@ def test_spmm_general_matrices(dtype, k, ldx, ldy):
         dev.close()
 
 
-@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float64, 13), (np.float32, 32), (np.float32, 16)])
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float64, 13), (np.float32, 32), (np.float32, 16),
+                                     (np.float64, 32), (np.float64, 40), (np.float32, 64)])
 @pytest.mark.parametrize("grid", [(128, 5, 4), (96, 3, 3), (64, 6, 5), (33, 9, 7)])
 def test_spmm_rows_of_x_shared_between_neighbouring_rows(grid, dtype, k):
     """27-point stencils with grid lines of 4, 3, 2 and about 1 chunks: chunks whose rows all repeat
     one list of diagonals, chunks with a boundary row in their first or last slot (a shorter,
     masked list), and chunks that straddle grid lines.  With 8 lanes per row of X (f64 k = 16,
-    f32 k = 32) a slot takes 4 consecutive rows and loads 6 rows of X per run of 3 diagonals."""
+    f32 k = 32) a slot takes 4 consecutive rows and loads 6 rows of X per run of 3 diagonals, with 16
+    lanes (f64 k = 32, f32 k = 64) 8 rows and 10 rows of X; k = 40 adds a second block of 8 columns."""
     nx, ny, nz = grid
     say(f"spmm shared rows of X, stencil {nx}x{ny}x{nz} k={k} {np.dtype(dtype).name}")
     rowptr, colidx, vals = gen.stencil27(nx, ny, nz, 41)
