@@ -136,7 +136,9 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
         // the pattern table takes the place of the column window, which this path does not fill
         static_assert(kPatternTable * sizeof(int32_t) <= kStreamWindow * sizeof(idx_t), "the table fits the column window");
         int32_t *s_pat = reinterpret_cast<int32_t *>(s_col);
-        __shared__ uint64_t s_mask[kStreamRows];
+        __shared__ int32_t s_rowpat[kStreamRows];
+        constexpr int kMaxOddRows = 4;            // more rows with a list of their own: the ordinary path
+        constexpr int kOddBatch = 3;              // rows of X in flight per lane for such a row (kSlots times as many entries)
         const int32_t w0 = base & ~7;
         const int32_t pat_begin = pats.pat_off[chunk];
         const int32_t pat_len = pats.pat_off[chunk + 1] - pat_begin;   // wave-uniform; 0: not patterned
@@ -156,41 +158,26 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
             const uint64_t longest = __builtin_amdgcn_ballot_w64(my_len == ref_len);
             const int ref_lane = (int)__builtin_ctzll(longest);
             const int32_t ref_pat = __builtin_amdgcn_readlane(my_pat, ref_lane);
-            bool all_ok = ref_len <= kWave;
-            uint64_t breaks = 0;                                       // where a run of consecutive diagonals starts
+            // rows with another list (grid boundaries, empty rows, rows past the end): computed apart
+            const bool is_row = lane < kStreamRows;
+            const uint64_t odd = __builtin_amdgcn_ballot_w64(is_row && !(my_len == ref_len && my_pat == ref_pat));
+            // the values of a row with the reference list are read at fixed places up to ref_len past
+            // the start of ANY row, so that much room has to be left in the window
+            bool all_ok = ref_len <= kWave && __popcll(odd) <= kMaxOddRows && end - w0 + kWave <= kStreamWindow;
             int32_t pstar = 0;
-            uint64_t mask = 0;
             if (all_ok) {
                 const bool in_ref = lane < ref_len;
                 pstar = in_ref ? s_pat[ref_pat + lane] : 0;
                 const int32_t before = (in_ref && lane > 0) ? s_pat[ref_pat + lane - 1] : INT32_MIN;
                 all_ok = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before) == 0;   // ascends strictly
                 // the runs of consecutive diagonals have to come in whole threes (27-point stencils, blocks
-                // of 3 unknowns): the loop below takes three diagonals and six rows of X at a time
-                breaks = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));
+                // of 3 unknowns): the loop below takes three diagonals and R + 2 rows of X at a time
+                const uint64_t breaks = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));
                 all_ok = all_ok && ref_len % 3 == 0 && (breaks & ~0x9249249249249249ull) == 0;
                 // rows of X are addressed by 32-bit byte offsets from the row of the smallest diagonal
                 const int64_t span = (int64_t)__builtin_amdgcn_readlane(pstar, ref_len - 1) - __builtin_amdgcn_readlane(pstar, 0) + 2 * kStreamRows;
                 all_ok = all_ok && span < (1 << 24) && span * (int64_t)row_bytes < ((int64_t)1 << 31);
-                const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
-                const bool is_row = lane < kStreamRows;
-                mask = (is_row && my_len > 0) ? full : 0;
-                // rows with another list: which of the reference diagonals they have
-                uint64_t other = __builtin_amdgcn_ballot_w64(is_row && my_len > 0 && !(my_pat == ref_pat && my_len == ref_len));
-                while (other != 0 && all_ok) {                         // uniform
-                    const int r = (int)__builtin_ctzll(other);
-                    other &= other - 1;
-                    const int32_t pr = __builtin_amdgcn_readlane(my_pat, r);
-                    const int32_t nr = __builtin_amdgcn_readlane(my_len, r);
-                    bool has = false;
-                    for (int u = 0; u < nr; ++u) has = has || (s_pat[pr + u] == pstar);   // uniform trip count, broadcast reads
-                    const uint64_t mk = __builtin_amdgcn_ballot_w64(in_ref && has);
-                    // all of the row's diagonals met, and in ascending order like the reference
-                    const bool falls = lane > 0 && lane < nr && s_pat[pr + lane] <= s_pat[pr + lane - 1];
-                    all_ok = __popcll(mk) == nr && __builtin_amdgcn_ballot_w64(falls) == 0;
-                    if (lane == r) mask = mk;
-                }
-                if (is_row) s_mask[lane] = mask;
+                if (is_row) s_rowpat[lane] = my_pat;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -198,20 +185,11 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
             if (all_ok) {
                 if (active) {
                     const int r0 = slot * R;
-                    uint64_t m[R];
                     int32_t first[R];
 #pragma unroll
-                    for (int pp = 0; pp < R; ++pp) {
-                        m[pp] = s_mask[r0 + pp];
-                        first[pp] = s_rp[r0 + pp] - w0;
-                    }
-                    const uint64_t full = ref_len == kWave ? ~0ull : ((1ull << ref_len) - 1);
-                    // uniform: the p-th row of every slot at work here has the whole reference list (no mask,
-                    // no select); a grid boundary usually touches one of the four
-                    bool whole[R];
-#pragma unroll
-                    for (int pp = 0; pp < R; ++pp) whole[pp] = __builtin_amdgcn_ballot_w64(m[pp] != full) == 0;
+                    for (int pp = 0; pp < R; ++pp) first[pp] = s_rp[r0 + pp] - w0;
                     // X row (r0 + d + q) as an offset from the row of the smallest diagonal, kept inside X
+                    // (a row of X that only an odd row's place would ask for may lie outside)
                     int64_t base_row = row0 + __builtin_amdgcn_readlane(pstar, 0);                 // uniform
                     base_row = base_row < 0 ? 0 : (base_row > ncols - 1 ? ncols - 1 : base_row);
                     const char *x_base = reinterpret_cast<const char *>(X + base_row * ldx);
@@ -223,7 +201,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
                         return *reinterpret_cast<const Pack<T, VEC> *>(
                             x_base + (__umul24((uint32_t)rel, row_bytes) + (uint32_t)(col * (int64_t)sizeof(T))));
                     };
-                    constexpr int kRuns = R <= 4 ? 3 : 2;                           // runs whose rows of X are in flight together
+                    constexpr int kRuns = R <= 4 ? 3 : 2;              // runs whose rows of X are in flight together
 #pragma unroll 1
                     for (int t0 = 0; t0 < ref_len; t0 += 3 * kRuns) {  // uniform
                         Pack<T, VEC> xw[kRuns][R + 2];
@@ -243,33 +221,67 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
                             for (int e = 0; e < 3; ++e)
 #pragma unroll
-                                for (int pp = 0; pp < R; ++pp) {
-                                    int at = tb + e;
-                                    if (!whole[pp]) {                                     // uniform
-                                        at = __popcll(m[pp] & ((1ull << (tb + e)) - 1));
-                                        at = first[pp] + at < kStreamWindow ? at : 0;
-                                    }
-                                    v[e][pp] = s_val[first[pp] + at];
-                                }
+                                for (int pp = 0; pp < R; ++pp) v[e][pp] = s_val[first[pp] + tb + e];
 #pragma unroll
                             for (int e = 0; e < 3; ++e)
 #pragma unroll
-                                for (int pp = 0; pp < R; ++pp) {
-                                    if (whole[pp]) {                                      // uniform
+                                for (int pp = 0; pp < R; ++pp)
 #pragma unroll
-                                        for (int q = 0; q < VEC; ++q)
-                                            acc[pp][q] = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
-                                    } else {
-                                        const bool has = (m[pp] >> (tb + e)) & 1;
-#pragma unroll
-                                        for (int q = 0; q < VEC; ++q) {
-                                            const T sum = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
-                                            acc[pp][q] = has ? sum : acc[pp][q];
-                                        }
-                                    }
-                                }
+                                    for (int q = 0; q < VEC; ++q)
+                                        acc[pp][q] = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
                         }
                     }
+                }
+                // the odd rows: what the loop above left in their sums is discarded.  All slots share the
+                // entries of such a row (slot s takes entries s, s + kSlots, ...), their partial sums are
+                // added across the slots, and the slot that owns the row keeps the total
+                {
+                    const int r0 = slot * R;
+                    for (uint64_t left = odd; left != 0; left &= left - 1) {               // uniform
+                        const int row = (int)__builtin_ctzll(left);
+                        const int n = s_rp[row + 1] - s_rp[row];                           // uniform
+                        const int32_t *pat = s_pat + s_rowpat[row];
+                        const T *sv = s_val + (s_rp[row] - w0);
+                        const int64_t me = row0 + row;
+                        T sum[VEC];
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) sum[q] = T(0);
+                        for (int u0 = 0; u0 < n; u0 += kOddBatch * kSlots) {               // uniform
+                            Pack<T, VEC> xo[kOddBatch];
+                            T vo[kOddBatch];
+#pragma unroll
+                            for (int t = 0; t < kOddBatch; ++t) {
+                                const int want = u0 + t * kSlots + slot;
+                                const int u = want < n ? want : n - 1;                    // past the end: repeat
+                                vo[t] = sv[u];
+                                if (active) {
+                                    xo[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (me + pat[u]) * ldx + col);
+                                } else {
+#pragma unroll
+                                    for (int q = 0; q < VEC; ++q) xo[t].v[q] = T(0);
+                                }
+                            }
+#pragma unroll
+                            for (int t = 0; t < kOddBatch; ++t)
+#pragma unroll
+                                for (int q = 0; q < VEC; ++q)
+                                    sum[q] += (active && u0 + t * kSlots + slot < n) ? vo[t] * xo[t].v[q] : T(0);
+                        }
+                        // lanes l, l + CL, l + 2 CL, ... hold the same columns: butterfly over the slots
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q)
+#pragma unroll
+                            for (int step = CL; step < kWave; step *= 2) sum[q] += __shfl_xor(sum[q], step);
+#pragma unroll
+                        for (int pp = 0; pp < R; ++pp)
+                            if (row == r0 + pp) {
+#pragma unroll
+                                for (int q = 0; q < VEC; ++q) acc[pp][q] = sum[q];
+                            }
+                    }
+                }
+                if (active) {
+                    const int r0 = slot * R;
 #pragma unroll
                     for (int pp = 0; pp < R; ++pp) {
                         const int64_t row = row0 + r0 + pp;
