@@ -729,6 +729,43 @@ def test_spmm_rows_of_x_shared_between_neighbouring_rows(grid, dtype, k):
         dev.close()
 
 
+@pytest.mark.parametrize("k", [16, 32])
+def test_spmm_shared_rows_of_x_rectangular_and_a_few_other_rows(k):
+    """Every row holds the same 27 diagonals (9 runs of 3, all to the right of the main diagonal, so
+    the matrix is wider than tall), except that a few rows per chunk are emptied, shortened or given
+    other columns: exactly 4 such rows in some chunks (still handled beside the shared rows), 5 in
+    others (the ordinary path)."""
+    say(f"spmm shared rows of X, rectangular band, k={k}")
+    n, per = 32 * 40 + 7, 27
+    diag = np.array([10 * r + e for r in range(9) for e in range(3)], dtype=np.int64)
+    ncols = n + int(diag[-1]) + 1
+    rows = [list(i + diag) for i in range(n)]
+    for c in range(0, n // 32):
+        base = 32 * c
+        changed = [1, 9, 17, 30] if c % 3 == 0 else ([0, 5, 6, 21, 31] if c % 3 == 1 else [13])
+        for j, r in enumerate(changed):
+            i = base + r
+            if j % 3 == 0:
+                rows[i] = []                                      # empty
+            elif j % 3 == 1:
+                rows[i] = rows[i][2:20]                           # a subset of the list
+            else:
+                rows[i] = [(i * 7 + 3 * t) % ncols for t in range(27)][::-1]   # other columns, descending
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    vals = gen.uniform(47, gen.STREAM_VALUES, colidx.size)
+    X = gen.uniform(47, gen.STREAM_X, ncols * k).reshape(ncols, k)
+    Y0 = gen.uniform(47, gen.STREAM_Y0, n * k).reshape(n, k)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        assert dev.patterns()["enabled"]
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, 2.0, -1.0, Y0, what="alpha=2 beta=-1")
+    finally:
+        dev.close()
+
+
 # ---------------------------------------------------------------------------
 # the five workloads: reduced sizes (several tiles + ragged tail) and full size
 # ---------------------------------------------------------------------------
