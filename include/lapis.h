@@ -351,8 +351,8 @@ int lapis_partition_constants(int64_t h_out[10]);
  * allocation has actually performed.
  * lapis_spmv_dualview: y = alpha*A*x + beta*y on dual views holding x (ncols values) and y
  * (nrows values) of A's dtype: syncs x and y to the device if needed (y's host copy is dropped
- * instead when beta == 0 and y is a whole allocation), runs lapis_spmv, marks y modified on the
- * device.  x and y may be sub-views of one allocation but must not overlap; a view smaller than
+ * instead when beta == 0 and y is a whole allocation of exactly nrows values), runs
+ * lapis_spmv, marks y modified on the device.  x and y may be sub-views of one allocation but must not overlap; a view smaller than
  * its operand is LAPIS_ERR_INVALID_ARG.  All functions here return a LAPIS_* status except the
  * two pointer getters (NULL for a NULL view); lapis_dualview_destroy(NULL) is a no-op.
  */

@@ -158,8 +158,10 @@ int lapis_spmv_dualview(const lapis_csr_t *A, double alpha, lapis_dualview_t *x,
         return fail(LAPIS_ERR_INVALID_ARG, "lapis_spmv_dualview: a view is smaller than its operand (x needs " +
                                                std::to_string(x_bytes) + " bytes, y " + std::to_string(y_bytes) + ")");
     int rc = lapis_dualview_sync_device(x, hip_stream);
-    // y is overwritten when beta == 0: its host copy need not travel if y is the whole allocation
-    const bool y_discarded = beta == 0.0 && y->bytes == y->root->bytes && y->root != x->root;
+    // y is overwritten when beta == 0: its host copy need not travel if the product rewrites the
+    // whole allocation (an allocation longer than the operand keeps host-side bytes past the
+    // operand that only a copy can bring to the device)
+    const bool y_discarded = beta == 0.0 && y->offset == 0 && y_bytes == y->root->bytes && y->root != x->root;
     if (rc == LAPIS_OK && !y_discarded) rc = lapis_dualview_sync_device(y, hip_stream);
     if (rc != LAPIS_OK) return rc;
     if (y_discarded) y->root->host_modified = false;

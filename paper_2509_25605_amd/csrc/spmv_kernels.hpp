@@ -592,7 +592,12 @@ __global__ __launch_bounds__(kWave * GW) void spmv_stream_kernel(
         const int32_t ub = (rb > w0 ? rb : w0) - w0;
         const int32_t ue = (re < w1 ? re : w1) - w0;
         const int my_n = (ue - ub - sub + G - 1) / G;                  // <= 0: nothing to do
-        const int first = my_n > 0 ? ub + sub : 0;                     // idle lanes re-read entry 0
+        // Idle lanes re-read the first entry of the window that belongs to this wavefront's rows.
+        // Not entry 0: the window starts at a multiple of 8, so its first entries may belong to the
+        // previous chunk, whose 16-bit code decoded with this chunk's base or frame table can name a
+        // column past the end of x.
+        const int32_t own0 = (base > w0 ? base : w0) - w0;             // uniform
+        const int first = my_n > 0 ? ub + sub : own0;
         if (patterned) {
             // the diagonals of the row's pattern from where this window cuts into the row; idle
             // lanes read the table's first diagonal and gather x[0]

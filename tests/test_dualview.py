@@ -114,3 +114,27 @@ def test_spmv_through_dualviews_matches_oracle_and_skips_copies(dtype):
             v.close()
     finally:
         xv.close(); yv.close(); A.close()
+
+
+@pytest.mark.gpu
+def test_y_allocation_longer_than_the_operand_keeps_its_host_side_tail():
+    """beta == 0 makes y write-only, but only its first nrows values: an allocation longer than
+    that must still travel to the device when the host changed it, or the next copy back would
+    overwrite the host's tail with stale device contents."""
+    rowptr, colidx, vals = gen.random_csr(500, 400, np.full(500, 7), seed=21, dtype=np.float64)
+    x = gen.normal(22, 2, 400)
+    A = DeviceCsr(500, 400, rowptr, colidx, vals)
+    xv, yv = lapis.DualView(400, np.float64), lapis.DualView(500 + 64, np.float64)
+    try:
+        xv.host[:] = x; xv.modify_host()
+        yv.host[:] = -3.0; yv.modify_host()
+        yv.sync_device()                               # device copy: all -3
+        yv.host[500:] = 11.0; yv.modify_host()         # the host rewrites the tail
+        lapis.lapis_spmv_dualview(A.mat.handle, 1.0, xv, 0.0, yv)
+        assert yv.copy_counts() == (2, 0)              # the tail went to the device with the rest
+        yv.sync_host()
+        ref, absax = oracle.spmv(rowptr, colidx, vals, x)
+        assert_close(yv.host[:500], ref, general_bound(np.diff(rowptr), absax, np.float64, 1.0, 0.0, None))
+        assert np.all(yv.host[500:] == 11.0)
+    finally:
+        xv.close(); yv.close(); A.close()
