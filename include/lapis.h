@@ -158,6 +158,29 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
                void *hip_stream);
 
 /*
+ * lapis_spmv_static_scratch - lapis_spmv for callers that must not allocate and cannot rely on
+ * memory the handle allocated: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, result, dtype, beta == 0 and asynchrony rules as lapis_spmv
+ * and the same kernels; the intermediate sums (per-tile sums of rows in bin 9, per-virtual-row
+ * sums of the column split, per-block sums of the rows above LAPIS_HUGE_ROW entries) go to a
+ * buffer of LAPIS_STATIC_SCRATCH_BYTES that is part of the library's code object instead of the
+ * handle's own buffers.  Every GPU the library runs on holds one copy of that buffer until the
+ * process ends; its address is looked up once per device, on the first call made with that
+ * device current.  The call itself allocates nothing, frees nothing and copies nothing.
+ * Nothing in the buffer has to be cleared between calls: every sum a call reads it has written
+ * before.  ALL calls on one GPU share the buffer, whatever their handle or stream: two calls
+ * that overlap in time on one GPU race and give wrong results; order them on one stream or
+ * with events.
+ * lapis_spmv_scratch_bytes(A) is what a product with A needs (0 for matrices without such rows;
+ * -1 for a NULL handle).  A matrix that needs more than LAPIS_STATIC_SCRATCH_BYTES is refused
+ * with LAPIS_ERR_INVALID_ARG and a message that names both numbers; nothing is launched then.
+ */
+#define LAPIS_STATIC_SCRATCH_BYTES 33554432   /* 32 MiB */
+int64_t lapis_spmv_scratch_bytes(const lapis_csr_t *A);
+int lapis_spmv_static_scratch(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+                              void *hip_stream);
+
+/*
  * lapis_spmv_transpose - y = alpha*A^T*x + beta*y from the CSR arrays of A: the column-wise
  * (CSC) traversal of the sparse loop pattern of Section 4.2 (the CSR arrays of A are the CSC
  * arrays of A^T; equivalently, the product of a CSC-stored matrix with a vector).

@@ -29,6 +29,7 @@ EXPORTS = [
     "lapis_dualview_sync_host", "lapis_dualview_copy_counts", "lapis_dualview_destroy",
     "lapis_spmv_dualview",
     "lapis_batched_gemm",
+    "lapis_spmv_static_scratch", "lapis_spmv_scratch_bytes",
     "lapis_last_error",
 ]
 
@@ -58,6 +59,8 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_create.argtypes = [ctypes.POINTER(p), i64, i64, i64, p, p, p, i32, p]
         lib.lapis_spmv.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_spmv_paper_shape.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_spmv_static_scratch.argtypes = [p, f64, p, f64, p, p]
+        lib.lapis_spmv_scratch_bytes.argtypes = [p]
         lib.lapis_spmv_transpose.argtypes = [p, f64, p, f64, p, p]
         lib.lapis_csr_huge_sizes.argtypes = [p] + [ctypes.POINTER(i64)] * 3
         lib.lapis_csr_copy_huge.argtypes = [p, p, p, p]
@@ -88,6 +91,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_batched_gemm.argtypes = [i64, i32, i32, i32, f64, p, p, f64, p, i32, p]
         for name in EXPORTS[:-1]:
             getattr(lib, name).restype = i32
+        lib.lapis_spmv_scratch_bytes.restype = i64
         lib.lapis_dualview_host.restype = p
         lib.lapis_dualview_device.restype = p
         lib.lapis_last_error.restype = ctypes.c_char_p
@@ -133,6 +137,14 @@ def lapis_csr_create(nrows, ncols, nnz, d_rowptr, d_colidx, d_vals, dtype, strea
 
 def lapis_spmv(A, alpha, d_x, beta, d_y, stream=None):
     _check(load().lapis_spmv(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_spmv_static_scratch(A, alpha, d_x, beta, d_y, stream=None):
+    _check(load().lapis_spmv_static_scratch(A, float(alpha), _addr(d_x), float(beta), _addr(d_y), _stream(stream)))
+
+
+def lapis_spmv_scratch_bytes(A) -> int:
+    return int(load().lapis_spmv_scratch_bytes(A))
 
 
 def lapis_csr_copy_index16(A):

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -101,6 +102,12 @@ struct lapis_csr {
 namespace {
 thread_local std::string g_last_error;
 }
+
+// Scratch of lapis_spmv_static_scratch: lives in the code object, one copy per GPU the library
+// runs on, held until the process ends.  In host code the name below is only a stand-in for the
+// symbol; its device address comes from hipGetSymbolAddress (static_scratch_address) and that
+// address, never the name, is what kernels and copies get.
+static __device__ __align__(256) unsigned char scratch[LAPIS_STATIC_SCRATCH_BYTES];
 
 int lapis::fail(int code, const std::string &msg)
 {
@@ -604,7 +611,7 @@ int build_transposed_arrays(const lapis_csr *A, lapis_csr *B, hipStream_t stream
 // Short-row and long-row kernels over one binned set; results go to out[row id of the set].
 template <typename T>
 void launch_binned(const lapis_csr *A, const BinnedSet &s, const ShortPlan &plan, bool with_long, const T *x,
-                   T *out, T a, T b, hipStream_t stream)
+                   T *out, T a, T b, T *partial, hipStream_t stream)
 {
     const T *vals = static_cast<const T *>(A->vals);
     if (plan.num_blocks > 0) {
@@ -614,7 +621,6 @@ void launch_binned(const lapis_csr *A, const BinnedSet &s, const ShortPlan &plan
     if (with_long && s.num_long > 0) {
         const int32_t m = (int32_t)s.num_long;
         const int32_t *long_rows = s.d_row_perm + s.h_bin_offset[kNumBins - 1];
-        T *partial = static_cast<T *>(s.d_partial);
         spmv_long_tile_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)s.num_tiles), dim3(kBlock), 0, stream>>>(
             m, long_rows, s.d_long_off, s.d_tile_row, s.d_tile_nz, s.row_begin, A->colidx, vals, x, partial);
         spmv_long_fixup_kernel<T, LAPIS_TILE_NNZ><<<dim3((uint32_t)((m + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(kBlock), 0, stream>>>(
@@ -683,11 +689,45 @@ int spmv_transpose_typed(const lapis_csr *A, double alpha, const void *d_x, doub
     return LAPIS_OK;
 }
 
+// Device address of `scratch` on the current device: asked for once per device, with that
+// device current, and kept (every GPU holds its own copy of the array at its own address).
+int static_scratch_address(unsigned char **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static unsigned char *address[kMaxDevices] = {nullptr};
+    int dev = -1;
+    LAPIS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(LAPIS_ERR_DEVICE, "device ordinal beyond the static scratch table");
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        LAPIS_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(LAPIS_ERR_DEVICE, "hipGetSymbolAddress returned a null address");
+        address[dev] = static_cast<unsigned char *>(ptr);
+    }
+    *out = address[dev];
+    return LAPIS_OK;
+}
+
 template <typename T>
 const T *vals_of(const lapis_csr *A) { return static_cast<const T *>(A->vals); }
 
+// Where a product keeps its intermediate sums: per-tile sums of the long rows (2 per tile) of the
+// matrix's own rows and of the virtual rows, one sum per virtual row, one per (LDS block, huge row).
+// Every element that is read has been written earlier in the same call, so nothing needs clearing.
+struct SpmvScratch {
+    void *partial_rows, *partial_vrows, *vsum, *fsum;
+};
+
+SpmvScratch handle_scratch(const lapis_csr *A)
+{
+    return SpmvScratch{A->rows.d_partial, A->vrows.d_partial, A->d_vsum, A->d_fsum};
+}
+
 template <typename T>
-int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, hipStream_t stream)
+int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, void *d_y, const SpmvScratch &scr,
+               hipStream_t stream)
 {
     const T a = (T)alpha, b = (T)beta;
     const T *x = static_cast<const T *>(d_x);
@@ -697,17 +737,17 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
     launch_stream<T, 8>(A, 3, x, y, a, b, stream);
     launch_stream<T, 16>(A, 4, x, y, a, b, stream);
     const bool split = A->num_blocks > 0;
-    launch_binned<T>(A, A->rows, A->plan_rows, !split, x, y, a, b, stream);
+    launch_binned<T>(A, A->rows, A->plan_rows, !split, x, y, a, b, static_cast<T *>(scr.partial_rows), stream);
     if (split) {
         // rows above 64 entries: their column-block pieces first, then one sum per row
-        T *vsum = static_cast<T *>(A->d_vsum);
-        launch_binned<T>(A, A->vrows, A->plan_vrows, true, x, vsum, T(1), T(0), stream);
+        T *vsum = static_cast<T *>(scr.vsum);
+        launch_binned<T>(A, A->vrows, A->plan_vrows, true, x, vsum, T(1), T(0), static_cast<T *>(scr.partial_vrows), stream);
         if (A->num_split > 0)
             split_combine_kernel<T><<<dim3((uint32_t)((A->num_split + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(
                 (int32_t)A->num_split, (int32_t)A->num_blocks, A->d_split_rows, vsum, y, a, b);
         if (A->num_huge > 0) {
             // rows above LAPIS_HUGE_ROW entries: pieces per LDS-sized block of x, then one sum per row
-            T *fsum = static_cast<T *>(A->d_fsum);
+            T *fsum = static_cast<T *>(scr.fsum);
             const int64_t H = A->num_huge, nbf = A->num_fblocks;
             int64_t groups = (8 * 256 + nbf - 1) / nbf;                      // about 8 workgroups per CU in all
             const int64_t most = (H + kLdsBlockWaves - 1) / kLdsBlockWaves;  // one piece per wavefront at least
@@ -944,8 +984,45 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
     if (A->nnz > 0 && !d_x) return fail(LAPIS_ERR_INVALID_ARG, "d_x is NULL");
     if (A->nrows == 0) return LAPIS_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, stream)
-                                 : spmv_typed<float>(A, alpha, d_x, beta, d_y, stream);
+    const SpmvScratch scr = handle_scratch(A);
+    return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, scr, stream)
+                                 : spmv_typed<float>(A, alpha, d_x, beta, d_y, scr, stream);
+}
+
+int64_t lapis_spmv_scratch_bytes(const lapis_csr_t *A)
+{
+    if (!A) return -1;
+    const int64_t e = (int64_t)value_size(A);
+    auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
+    return up(e * 2 * A->rows.num_tiles) + up(e * 2 * A->vrows.num_tiles) + up(e * A->num_blocks * A->num_split) +
+           up(e * A->num_fblocks * A->num_huge);
+}
+
+int lapis_spmv_static_scratch(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
+                              void *hip_stream)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    if (A->nrows > 0 && !d_y) return fail(LAPIS_ERR_INVALID_ARG, "d_y is NULL");
+    if (A->nnz > 0 && !d_x) return fail(LAPIS_ERR_INVALID_ARG, "d_x is NULL");
+    const int64_t need = lapis_spmv_scratch_bytes(A);
+    if (need > (int64_t)LAPIS_STATIC_SCRATCH_BYTES)
+        return fail(LAPIS_ERR_INVALID_ARG, "lapis_spmv_static_scratch: this matrix needs " + std::to_string(need) +
+                                               " bytes of scratch, the static buffer holds " +
+                                               std::to_string((int64_t)LAPIS_STATIC_SCRATCH_BYTES) + "; use lapis_spmv");
+    if (A->nrows == 0) return LAPIS_OK;
+    unsigned char *base = nullptr;
+    if (int rc = static_scratch_address(&base)) return rc;
+    // the four pieces back to back, each starting at a multiple of 256 bytes
+    const int64_t e = (int64_t)value_size(A);
+    auto up = [](int64_t b) { return (b + 255) / 256 * 256; };
+    SpmvScratch scr;
+    scr.partial_rows = base;
+    scr.partial_vrows = base + up(e * 2 * A->rows.num_tiles);
+    scr.vsum = static_cast<unsigned char *>(scr.partial_vrows) + up(e * 2 * A->vrows.num_tiles);
+    scr.fsum = static_cast<unsigned char *>(scr.vsum) + up(e * A->num_blocks * A->num_split);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, scr, stream)
+                                 : spmv_typed<float>(A, alpha, d_x, beta, d_y, scr, stream);
 }
 
 int lapis_spmv_transpose(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
