@@ -136,3 +136,29 @@ def test_header_is_plain_c_and_declares_what_the_library_exports(tmp_path):
            "-Wl,--allow-shlib-undefined"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
+
+
+def test_ceilings_library_exports_what_its_header_declares(tmp_path):
+    """include/lapis_ceilings.h (the measurement kernels of bench.py) is plain C, and every function it
+    declares is exported by libceilings_mi355x.so; argument checks answer without touching a GPU."""
+    import subprocess
+    from paper_2509_25605_amd import ceilings
+    if not os.path.exists(ceilings.LIB_PATH):
+        from paper_2509_25605_amd.build import build
+        build()
+    text = open(os.path.join(ROOT, "include", "lapis_ceilings.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(lapis_\w+)\s*\(", text)))
+    assert set(names) == set(ceilings.EXPORTS)
+    lib = ceilings.load()
+    for name in names:
+        assert getattr(lib, name) is not None
+    src = tmp_path / "c.c"
+    src.write_text('#include "lapis_ceilings.h"\nint main(void) { return 0; }\n')
+    res = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-c",
+                          str(src), "-o", str(tmp_path / "c.o")], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    assert lib.lapis_ceiling_read(None, 1024, 0, None, None) == 1
+    assert lib.lapis_ceiling_read(16, 1000, 0, 16, None) == 1          # not a multiple of 16 bytes
+    assert lib.lapis_ceiling_gather(None, 8, None, 8, None, None) == 1
+    assert lib.lapis_ceiling_rows(16, 1000, 1, 1, 0, 16, None) == 1    # not a power of two

@@ -26,3 +26,38 @@ def test_algorithmic_bytes_are_the_csr_arrays_and_the_vectors_once_each():
     w = gen.workload(5, {"nx": 8, "ny": 8, "nz": 8})           # SpMM, k = 16
     assert bench.algorithmic_bytes(w) == w.nnz * 12 + (w.nrows + 1) * 4 + (w.ncols + w.nrows) * 16 * 8
     assert bench.HBM_PEAK_GBS == 8000.0
+
+
+def test_parity_check_of_the_bench_flags_what_it_should():
+    """The in-run check of bench.py: exact results pass, an error above the bound, an error on a row
+    without entries and a NaN all fail."""
+    sys.path.insert(0, ROOT)
+    import bench
+    import gen
+    import oracle
+    w = gen.workload(1)
+    ref, absAx = oracle.spmv(w.rowptr, w.colidx, w.vals, w.x, w.alpha, w.beta, w.y0)
+    good = bench.parity_check(w, ref.copy(), ref, absAx)
+    assert good["checked"] and good["ok"] and good["max_err_over_tol"] == 0.0 and good["elements"] == w.nrows
+    near = ref.copy()
+    near[10] += 4 * 5 * 2.0 ** -53 * absAx[10]                 # half of the bound of a 5-entry row
+    res = bench.parity_check(w, near, ref, absAx)
+    assert res["ok"] and 0.3 < res["max_err_over_tol"] <= 1.0
+    far = ref.copy()
+    far[10] += 16 * 5 * 2.0 ** -53 * absAx[10]
+    res = bench.parity_check(w, far, ref, absAx)
+    assert not res["ok"] and res["max_err_over_tol"] > 1.0
+    nan = ref.copy()
+    nan[3] = np.nan
+    assert not bench.parity_check(w, nan, ref, absAx)["ok"]
+    zero_tol = bench.parity_check(w, np.nextafter(ref, np.inf), ref, np.zeros_like(absAx))
+    assert not zero_tol["ok"] and zero_tol["max_err_over_tol"] is None
+
+
+def test_source_fingerprint_follows_the_kernel_sources():
+    sys.path.insert(0, ROOT)
+    import bench
+    fp = bench.source_fingerprint()
+    assert len(fp) == 12 and int(fp, 16) >= 0
+    for m in bench.MEASURED.values():
+        assert set(m) == {"traffic", "source", "kernel"}
