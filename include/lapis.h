@@ -101,7 +101,7 @@ extern "C" {
 #define LAPIS_LONG_THRESHOLD  4096
 #define LAPIS_TILE_NNZ        4096
 #define LAPIS_STREAM_ROWS     32
-#define LAPIS_STREAM_MIN_NNZ  256
+#define LAPIS_STREAM_MIN_NNZ  64
 #define LAPIS_SPLIT_BLOCK_BYTES 2097152   /* 2 MiB of x per column block */
 #define LAPIS_MAX_NNZ 2147418112        /* 2^31 - 2^16: entry ids plus a tile stay inside int32 */
 #define LAPIS_SPLIT_MAX_BLOCKS  32

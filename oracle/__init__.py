@@ -3,7 +3,11 @@
 TEST INFRASTRUCTURE ONLY.  Tests, the smoke check and the bench's
 cpu_baseline leg may import this package; the product package never does.
 It builds the C file with gcc (-O2 -ffp-contract=off, no OpenMP: the oracle is
-serial) and marshals NumPy arrays; all arithmetic is in the C file.
+serial) and marshals NumPy arrays.  Every product, sum and index structure is computed in the
+C file; what this module adds in Python is the geometry of the column split (split_geometry:
+two integer divisions), the choice of the rows that are split (split_partition: rows of the
+last two bins by length, the lengths of the virtual rows as differences of the cut table) and
+the "enabled" rules (a structure is kept when its chunks hold at least half of the entries).
 """
 from __future__ import annotations
 
@@ -25,7 +29,7 @@ LONG_THRESHOLD = 4096
 TILE_NNZ = 4096
 NUM_BINS = 10
 STREAM_ROWS = 32
-STREAM_MIN_NNZ = 256
+STREAM_MIN_NNZ = 64
 SPLIT_BLOCK_BYTES = 1 << 21   # target size of one column block of x
 SPLIT_MAX_BLOCKS = 32
 HUGE_ROW = 16384            # rows with more entries are cut at LDS-sized column blocks

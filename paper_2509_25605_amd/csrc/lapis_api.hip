@@ -81,6 +81,10 @@ struct lapis_csr {
     int64_t pattern_pool = 0;            // diagonals in the pool
     bool class_allpattern[kStreamClasses] = {false, false, false, false};  // every chunk of the class is patterned
     bool class_pattern16[kStreamClasses] = {false, false, false, false};   // ... is patterned, narrow or framed
+    // SpMM: the stream chunks whose neighbouring rows share rows of X (spmm_share_flag_kernel), then the others
+    int32_t *d_spmm_chunks = nullptr;    // [num_stream]; null when no chunk shares rows
+    int32_t *d_share_flag = nullptr;     // [num_chunks] 1: shares rows, 2: another stream chunk, 0: not a stream chunk
+    int64_t num_share = 0;               // length of the first list
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -132,10 +136,12 @@ int fail_hip(hipError_t e, const char *what)
                 std::string(what) + ": " + hipGetErrorString(e));
 }
 
+#define LAPIS_STR2(x) #x
+#define LAPIS_STR(x) LAPIS_STR2(x)
 #define LAPIS_HIP(call)                                        \
     do {                                                       \
         hipError_t e_ = (call);                                \
-        if (e_ != hipSuccess) return fail_hip(e_, #call);      \
+        if (e_ != hipSuccess) return fail_hip(e_, #call " (lapis_api.hip:" LAPIS_STR(__LINE__) ")"); \
     } while (0)
 
 template <typename P>
@@ -174,38 +180,56 @@ struct DeviceTemp {
     int alloc(size_t bytes) { return device_alloc(&p, bytes); }
 };
 
-void free_set(BinnedSet &s)
+// hipFree that remembers the first failure (a pointer freed twice or never allocated here would
+// otherwise surface later, as the "last error" of an unrelated call).
+struct Freer {
+    hipError_t first = hipSuccess;
+    const char *what = nullptr;
+    void operator()(void *p, const char *name)
+    {
+        const hipError_t e = hipFree(p);
+        if (e != hipSuccess && first == hipSuccess) { first = e; what = name; }
+    }
+};
+#define LAPIS_FREE(f, p) f((void *)(p), #p)
+
+void free_set(BinnedSet &s, Freer &f)
 {
-    (void)hipFree(s.d_bin_offset);
-    (void)hipFree(s.d_row_perm);
-    (void)hipFree(s.d_long_off);
-    (void)hipFree(s.d_tile_row);
-    (void)hipFree(s.d_tile_nz);
-    (void)hipFree(s.d_partial);
+    LAPIS_FREE(f, s.d_bin_offset);
+    LAPIS_FREE(f, s.d_row_perm);
+    LAPIS_FREE(f, s.d_long_off);
+    LAPIS_FREE(f, s.d_tile_row);
+    LAPIS_FREE(f, s.d_tile_nz);
+    LAPIS_FREE(f, s.d_partial);
 }
 
-void free_handle(lapis_csr *A)
+int free_handle(lapis_csr *A)
 {
-    if (!A) return;
-    (void)hipFree(A->d_stream_chunks);
-    (void)hipFree(A->d_cut);
-    (void)hipFree(A->d_split_rows);
-    (void)hipFree(A->d_huge_rows);
-    (void)hipFree(A->d_fcut);
-    (void)hipFree(A->d_fsum);
-    (void)hipFree(A->d_vsum);
-    (void)hipFree(A->d_chunk_base);
-    (void)hipFree(A->d_col16);
-    (void)hipFree(A->d_frame_table);
-    (void)hipFree(A->d_pat_off);
-    (void)hipFree(A->d_row_pat);
-    (void)hipFree(A->d_pat_pool);
-    (void)hipFree(A->own_rowptr);
-    (void)hipFree(A->own_colidx);
-    (void)hipFree(A->own_vals);
-    free_set(A->rows);
-    free_set(A->vrows);
+    if (!A) return LAPIS_OK;
+    Freer f;
+    LAPIS_FREE(f, A->d_stream_chunks);
+    LAPIS_FREE(f, A->d_cut);
+    LAPIS_FREE(f, A->d_split_rows);
+    LAPIS_FREE(f, A->d_huge_rows);
+    LAPIS_FREE(f, A->d_fcut);
+    LAPIS_FREE(f, A->d_fsum);
+    LAPIS_FREE(f, A->d_vsum);
+    LAPIS_FREE(f, A->d_chunk_base);
+    LAPIS_FREE(f, A->d_col16);
+    LAPIS_FREE(f, A->d_frame_table);
+    LAPIS_FREE(f, A->d_pat_off);
+    LAPIS_FREE(f, A->d_row_pat);
+    LAPIS_FREE(f, A->d_pat_pool);
+    LAPIS_FREE(f, A->d_spmm_chunks);
+    LAPIS_FREE(f, A->d_share_flag);
+    LAPIS_FREE(f, A->own_rowptr);
+    LAPIS_FREE(f, A->own_colidx);
+    LAPIS_FREE(f, A->own_vals);
+    free_set(A->rows, f);
+    free_set(A->vrows, f);
     delete A;
+    if (f.first != hipSuccess) return fail_hip(f.first, f.what);
+    return LAPIS_OK;
 }
 
 size_t value_size(const lapis_csr *A) { return A->dtype == LAPIS_F64 ? sizeof(double) : sizeof(float); }
@@ -418,6 +442,32 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
             pattern_pool_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
                 (int32_t)n, num_chunks, LAPIS_STREAM_ROWS, A->rowptr, A->colidx, A->d_pat_off, A->d_row_pat, A->d_pat_pool);
             LAPIS_HIP(hipGetLastError());
+            // SpMM: which stream chunks share rows of X between neighbouring rows; two lists
+            if (num_stream > 0) {
+                DeviceTemp share_offsets;
+                if (int rc = device_alloc(&A->d_share_flag, sizeof(int32_t) * (size_t)num_chunks)) return rc;
+                if (int rc = share_offsets.alloc(sizeof(int32_t) * (kChunkClasses + 1))) return rc;
+                if (int rc = device_alloc(&A->d_spmm_chunks, sizeof(int32_t) * (size_t)num_stream)) return rc;
+                spmm_share_flag_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
+                    (int32_t)n, (int32_t)A->ncols, num_chunks, chunk_flag.as<int32_t>(), A->rowptr,
+                    StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, A->d_share_flag);
+                chunk_class_hist_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
+                    num_chunks, A->d_share_flag, class_hist.as<int32_t>());
+                chunk_class_scan_kernel<<<dim3(1), dim3(kCompactBlock), 0, stream>>>(compact_blocks, class_hist.as<int32_t>(),
+                                                                                     share_offsets.as<int32_t>());
+                chunk_compact_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
+                    num_chunks, A->d_share_flag, class_hist.as<int32_t>(), A->d_spmm_chunks);
+                LAPIS_HIP(hipGetLastError());
+                int32_t h_share[kChunkClasses + 1] = {0};
+                if (int rc = read_back(h_share, share_offsets.p, sizeof(h_share), stream)) return rc;
+                A->num_share = h_share[1];
+                if (A->num_share == 0) {
+                    (void)hipFree(A->d_spmm_chunks);
+                    (void)hipFree(A->d_share_flag);
+                    A->d_spmm_chunks = nullptr;
+                    A->d_share_flag = nullptr;
+                }
+            }
             LAPIS_HIP(hipStreamSynchronize(stream));       // pat_len and tile_sums are released on return
             for (int cls = 1; cls <= kStreamClasses; ++cls) {
                 const int32_t size = A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
@@ -824,35 +874,41 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         bool all16 = A->d_col16 != nullptr && ldx * (int64_t)sizeof(T) <= 0xffff;
         for (int cls = 1; cls <= kStreamClasses; ++cls)
             all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
+        // chunks whose neighbouring rows share rows of X go to the kernel that loads those rows once per
+        // R rows (8 or 16 lanes per row of X; a row of X shorter than 64 MiB); the other chunks follow
+        uint32_t n_share = 0;
+        if constexpr (kStreamLanes >= 8) {
+            if (A->d_spmm_chunks && ldx * (int64_t)sizeof(T) < ((int64_t)1 << 26)) n_share = (uint32_t)A->num_share;
+        }
+        const uint32_t n_plain = chunks - n_share;
+        // When every chunk of the matrix streams and nearly all of them share rows (all but a few at the
+        // ends of the matrix), the kernel is launched over all chunks in the block-cyclic order above and
+        // skips the others by their flag: no list to read before the first load, windows still shared.
+        const bool share_by_flag = !list && (uint64_t)n_share * 10 >= (uint64_t)chunks * 9;
+        const uint32_t share_count = share_by_flag ? chunks : n_share;
+        const uint32_t share_padded = share_by_flag ? padded : (n_share + kXcds - 1) / kXcds * kXcds;
+        const int32_t *share_list = share_by_flag ? nullptr : A->d_spmm_chunks;
+        const int32_t *share_flag = (share_by_flag && n_share != chunks) ? A->d_share_flag : nullptr;
+        const int32_t *plain_list = n_share ? A->d_spmm_chunks + n_share : list;
+        const uint32_t plain_padded = n_share ? (n_plain + kXcds - 1) / kXcds * kXcds : padded;
+        const uint32_t plain_xcd_block = n_share ? 0 : xcd_block;
         for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
-            bool launched = false;
             if constexpr (kStreamLanes >= 8) {
-                // four or eight rows per slot and row patterns: chunks of repeating diagonals share rows of X
-                // (with two rows per slot, 4 loads for 6 products, it is slower than the ordinary path)
-                if (A->d_pat_off && ldx * (int64_t)sizeof(T) <= 0xffff) {
-                    const StreamPatterns pats{A->d_pat_off, A->d_row_pat, A->d_pat_pool};
-                    if (all16)
-                        spmm_stream_kernel<T, VEC, kStreamLanes, true, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                            A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b, pats,
-                            (int32_t)A->ncols);
-                    else
-                        spmm_stream_kernel<T, VEC, kStreamLanes, true, false, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                            (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                            A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b, pats,
-                            (int32_t)A->ncols);
-                    launched = true;
-                }
+                if (n_share)
+                    spmm_shared_kernel<T, VEC, kStreamLanes, true><<<dim3(share_padded), dim3(kWave), 0, stream>>>(
+                        (int32_t)A->nrows, (int32_t)A->nnz, share_count, share_padded, share_list, share_flag,
+                        A->rowptr, share_by_flag ? xcd_block : 0u, vals, k, c0, X, ldx, Y, ldy, a, b,
+                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool});
             }
-            if (launched) continue;
+            if (n_plain == 0) continue;
             if (all16)
-                spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                    (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                    A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(plain_padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, n_plain, plain_padded, plain_list, A->rowptr, plain_xcd_block,
+                    A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
             else
-                spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(padded), dim3(kWave), 0, stream>>>(
-                    (int32_t)A->nrows, (int32_t)A->nnz, chunks, padded, list, A->rowptr, xcd_block, A->colidx,
-                    A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(plain_padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, n_plain, plain_padded, plain_list, A->rowptr, plain_xcd_block,
+                    A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
         }
     }
     if (n_rows_a > 0) {
@@ -929,7 +985,7 @@ int lapis_csr_create_transpose(lapis_csr_t **out, const lapis_csr_t *A, void *hi
         B->rowptr = B->own_rowptr; B->colidx = B->own_colidx; B->vals = B->own_vals;
         rc = run_analysis(B, stream);
     }
-    if (rc) { free_handle(B); return rc; }
+    if (rc) { const std::string why = g_last_error; (void)free_handle(B); return fail(rc, why); }
     *out = B;
     return LAPIS_OK;
 }
@@ -972,7 +1028,7 @@ int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nn
     A->nrows = nrows; A->ncols = ncols; A->nnz = nnz; A->dtype = dtype;
     A->rowptr = d_rowptr; A->colidx = d_colidx; A->vals = d_vals;
     const int rc = run_analysis(A, static_cast<hipStream_t>(hip_stream));
-    if (rc) { free_handle(A); return rc; }
+    if (rc) { const std::string why = g_last_error; (void)free_handle(A); return fail(rc, why); }
     *out = A;
     return LAPIS_OK;
 }
@@ -1076,8 +1132,7 @@ int lapis_spmm(const lapis_csr_t *A, int64_t k, double alpha, const void *d_X, i
 
 int lapis_csr_destroy(lapis_csr_t *A)
 {
-    free_handle(A);
-    return LAPIS_OK;
+    return free_handle(A);
 }
 
 int lapis_csr_partition_sizes(const lapis_csr_t *A, int64_t *num_stream, int64_t *num_binned,

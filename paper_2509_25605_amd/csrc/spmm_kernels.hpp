@@ -60,25 +60,14 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 // ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
-//
-// WINDOW (needs R >= 2 rows per slot and rows of X shorter than 64 KiB; pats = the row patterns
-// of the matrix, ncols its columns): a chunk whose rows repeat the diagonals of its longest row,
-// or ordered subsets of them, is worked on differently, from the values and the pattern table
-// alone (no column index is read).  A slot takes R CONSECUTIVE rows (4 with 8 lanes per row of
-// X, 8 with 16), and for every 3 consecutive diagonals d, d+1, d+2 of that longest row it loads
-// the rows r0+d .. r0+d+R+1 of X once: row r0+p needs X rows r0+p+d+e = the p+e-th of them, so
-// R + 2 loads serve 3 R products (a stencil's neighbouring rows share two thirds of their columns).  Rows with fewer diagonals
-// (grid boundaries) carry a bit mask of the diagonals they have and skip the others.  Chunks
-// that do not qualify take the ordinary path.
-template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false, bool WINDOW = false>
+template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
     uint32_t xcd_block, const int32_t *__restrict__ colidx, const int32_t *__restrict__ chunk_base,
     const int32_t *__restrict__ frame_table, const uint16_t *__restrict__ col16,
     const T *__restrict__ vals, int64_t k,
-    int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta,
-    StreamPatterns pats = StreamPatterns{nullptr, nullptr, nullptr}, int32_t ncols = 0)
+    int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y, int64_t ldy, T alpha, T beta)
 {
     static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
     constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
@@ -130,169 +119,6 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 #pragma unroll
         for (int q = 0; q < VEC; ++q) acc[p][q] = T(0);
 
-    if constexpr (WINDOW) {
-        static_assert(kPasses >= 2 && kSlots * kPasses == kStreamRows, "a slot takes kPasses consecutive rows");
-        constexpr int R = kPasses;                 // consecutive rows of a slot: R + 2 rows of X serve 3 R products
-        // the pattern table takes the place of the column window, which this path does not fill
-        static_assert(kPatternTable * sizeof(int32_t) <= kStreamWindow * sizeof(idx_t), "the table fits the column window");
-        int32_t *s_pat = reinterpret_cast<int32_t *>(s_col);
-        __shared__ int32_t s_rowpat[kStreamRows];
-        constexpr int kMaxOddRows = 4;            // more rows with a list of their own: the ordinary path
-        constexpr int kOddBatch = 3;              // rows of X in flight per lane for such a row (kSlots times as many entries)
-        const int32_t w0 = base & ~7;
-        const int32_t pat_begin = pats.pat_off[chunk];
-        const int32_t pat_len = pats.pat_off[chunk + 1] - pat_begin;   // wave-uniform; 0: not patterned
-        if (pat_len > 0 && end - w0 <= kStreamWindow) {
-            // the chunk's pattern table, and lane r < 32: row r of the chunk
-            constexpr int kLoads = kPatternTable / kWave;
-#pragma unroll
-            for (int i = 0; i < kLoads; ++i)
-                if (i * kWave < pat_len) s_pat[i * kWave + lane] = (i * kWave + lane < pat_len) ? pats.pool[pat_begin + i * kWave + lane] : 0;
-            const int64_t my_row = row0 + (lane < kStreamRows ? lane : 0);
-            const int32_t my_len = (lane < kStreamRows) ? s_rp[lane + 1] - s_rp[lane] : 0;
-            const int32_t my_pat = (lane < kStreamRows && my_row < nrows && my_len > 0) ? (int32_t)pats.row_pat[my_row] : 0;
-            // the values are needed either way and their loads overlap those above; no column is read here
-            stream_values_to_lds<T>(vals, w0, end, nnz4, lane, s_val);     // ends with the wavefront's fence
-            // the reference list: the diagonals of the first longest row, one per lane
-            const int32_t ref_len = wave_max_nonneg(my_len);
-            const uint64_t longest = __builtin_amdgcn_ballot_w64(my_len == ref_len);
-            const int ref_lane = (int)__builtin_ctzll(longest);
-            const int32_t ref_pat = __builtin_amdgcn_readlane(my_pat, ref_lane);
-            // rows with another list (grid boundaries, empty rows, rows past the end): computed apart
-            const bool is_row = lane < kStreamRows;
-            const uint64_t odd = __builtin_amdgcn_ballot_w64(is_row && !(my_len == ref_len && my_pat == ref_pat));
-            // the values of a row with the reference list are read at fixed places up to ref_len past
-            // the start of ANY row, so that much room has to be left in the window
-            bool all_ok = ref_len <= kWave && __popcll(odd) <= kMaxOddRows && end - w0 + kWave <= kStreamWindow;
-            int32_t pstar = 0;
-            if (all_ok) {
-                const bool in_ref = lane < ref_len;
-                pstar = in_ref ? s_pat[ref_pat + lane] : 0;
-                const int32_t before = (in_ref && lane > 0) ? s_pat[ref_pat + lane - 1] : INT32_MIN;
-                all_ok = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before) == 0;   // ascends strictly
-                // the runs of consecutive diagonals have to come in whole threes (27-point stencils, blocks
-                // of 3 unknowns): the loop below takes three diagonals and R + 2 rows of X at a time
-                const uint64_t breaks = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));
-                all_ok = all_ok && ref_len % 3 == 0 && (breaks & ~0x9249249249249249ull) == 0;
-                // rows of X are addressed by 32-bit byte offsets from the row of the smallest diagonal
-                const int64_t span = (int64_t)__builtin_amdgcn_readlane(pstar, ref_len - 1) - __builtin_amdgcn_readlane(pstar, 0) + 2 * kStreamRows;
-                all_ok = all_ok && span < (1 << 24) && span * (int64_t)row_bytes < ((int64_t)1 << 31);
-                if (is_row) s_rowpat[lane] = my_pat;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (all_ok) {
-                if (active) {
-                    const int r0 = slot * R;
-                    int32_t first[R];
-#pragma unroll
-                    for (int pp = 0; pp < R; ++pp) first[pp] = s_rp[r0 + pp] - w0;
-                    // X row (r0 + d + q) as an offset from the row of the smallest diagonal, kept inside X
-                    // (a row of X that only an odd row's place would ask for may lie outside)
-                    int64_t base_row = row0 + __builtin_amdgcn_readlane(pstar, 0);                 // uniform
-                    base_row = base_row < 0 ? 0 : (base_row > ncols - 1 ? ncols - 1 : base_row);
-                    const char *x_base = reinterpret_cast<const char *>(X + base_row * ldx);
-                    const int32_t rel0 = (int32_t)(row0 + r0 - base_row);
-                    const int32_t rel_max = (int32_t)(ncols - 1 - base_row);
-                    auto x_at = [&](int32_t d, int q) {
-                        int32_t rel = rel0 + d + q;
-                        rel = rel < 0 ? 0 : (rel > rel_max ? rel_max : rel);
-                        return *reinterpret_cast<const Pack<T, VEC> *>(
-                            x_base + (__umul24((uint32_t)rel, row_bytes) + (uint32_t)(col * (int64_t)sizeof(T))));
-                    };
-                    constexpr int kRuns = R <= 4 ? 3 : 2;              // runs whose rows of X are in flight together
-#pragma unroll 1
-                    for (int t0 = 0; t0 < ref_len; t0 += 3 * kRuns) {  // uniform
-                        Pack<T, VEC> xw[kRuns][R + 2];
-#pragma unroll
-                        for (int rr = 0; rr < kRuns; ++rr) {
-                            if (t0 + 3 * rr < ref_len) {               // uniform
-                                const int32_t d = __builtin_amdgcn_readlane(pstar, t0 + 3 * rr);
-#pragma unroll
-                                for (int q = 0; q < R + 2; ++q) xw[rr][q] = x_at(d, q);
-                            }
-                        }
-#pragma unroll
-                        for (int rr = 0; rr < kRuns; ++rr) {
-                            const int tb = t0 + 3 * rr;
-                            if (tb >= ref_len) continue;               // uniform
-                            T v[3][R];
-#pragma unroll
-                            for (int e = 0; e < 3; ++e)
-#pragma unroll
-                                for (int pp = 0; pp < R; ++pp) v[e][pp] = s_val[first[pp] + tb + e];
-#pragma unroll
-                            for (int e = 0; e < 3; ++e)
-#pragma unroll
-                                for (int pp = 0; pp < R; ++pp)
-#pragma unroll
-                                    for (int q = 0; q < VEC; ++q)
-                                        acc[pp][q] = fused_madd(v[e][pp], xw[rr][pp + e].v[q], acc[pp][q]);
-                        }
-                    }
-                }
-                // the odd rows: what the loop above left in their sums is discarded.  All slots share the
-                // entries of such a row (slot s takes entries s, s + kSlots, ...), their partial sums are
-                // added across the slots, and the slot that owns the row keeps the total
-                {
-                    const int r0 = slot * R;
-                    for (uint64_t left = odd; left != 0; left &= left - 1) {               // uniform
-                        const int row = (int)__builtin_ctzll(left);
-                        const int n = s_rp[row + 1] - s_rp[row];                           // uniform
-                        const int32_t *pat = s_pat + s_rowpat[row];
-                        const T *sv = s_val + (s_rp[row] - w0);
-                        const int64_t me = row0 + row;
-                        T sum[VEC];
-#pragma unroll
-                        for (int q = 0; q < VEC; ++q) sum[q] = T(0);
-                        for (int u0 = 0; u0 < n; u0 += kOddBatch * kSlots) {               // uniform
-                            Pack<T, VEC> xo[kOddBatch];
-                            T vo[kOddBatch];
-#pragma unroll
-                            for (int t = 0; t < kOddBatch; ++t) {
-                                const int want = u0 + t * kSlots + slot;
-                                const int u = want < n ? want : n - 1;                    // past the end: repeat
-                                vo[t] = sv[u];
-                                if (active) {
-                                    xo[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (me + pat[u]) * ldx + col);
-                                } else {
-#pragma unroll
-                                    for (int q = 0; q < VEC; ++q) xo[t].v[q] = T(0);
-                                }
-                            }
-#pragma unroll
-                            for (int t = 0; t < kOddBatch; ++t)
-#pragma unroll
-                                for (int q = 0; q < VEC; ++q)
-                                    sum[q] += (active && u0 + t * kSlots + slot < n) ? vo[t] * xo[t].v[q] : T(0);
-                        }
-                        // lanes l, l + CL, l + 2 CL, ... hold the same columns: butterfly over the slots
-#pragma unroll
-                        for (int q = 0; q < VEC; ++q)
-#pragma unroll
-                            for (int step = CL; step < kWave; step *= 2) sum[q] += __shfl_xor(sum[q], step);
-#pragma unroll
-                        for (int pp = 0; pp < R; ++pp)
-                            if (row == r0 + pp) {
-#pragma unroll
-                                for (int q = 0; q < VEC; ++q) acc[pp][q] = sum[q];
-                            }
-                    }
-                }
-                if (active) {
-                    const int r0 = slot * R;
-#pragma unroll
-                    for (int pp = 0; pp < R; ++pp) {
-                        const int64_t row = row0 + r0 + pp;
-                        if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[pp], col, k, alpha, beta);
-                    }
-                }
-                return;
-            }
-            // not all rows fit the reference list: the ordinary path
-        }
-    }
     for (int32_t w0 = base & ~7; w0 < end; w0 += kStreamWindow) {      // uniform
         const int32_t w1 = (end - w0 < kStreamWindow) ? end : w0 + kStreamWindow;
         stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
@@ -371,6 +197,272 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
             const int64_t row = row0 + p * kSlots + slot;
             if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[p], col, k, alpha, beta);
         }
+    }
+}
+
+// ---- rows of X shared between neighbouring matrix rows ---------------------------------------
+// On matrices of regular grids row i + 1 needs the rows of X that row i needs, shifted by one.  A
+// chunk of 32 rows "shares rows" when (a) it is patterned (its rows repeat a few lists of diagonals
+// = column - row, spmv_kernels.hpp), (b) its longest row's list - the reference list, at most 64
+// diagonals - ascends strictly, (c) at most kShareMaxOdd of its rows have another list or are empty
+// (grid boundaries: the "odd" rows), (d) its values fit one LDS window with 64 entries to spare
+// (a row with the reference list reads its values at fixed places past the start of ANY row), and
+// (e) every row of X that the scheme below may ask for exists: row0 + smallest diagonal >= 0 and
+// row0 + 33 + largest diagonal <= ncols - 1.  The reference list is cut into runs of consecutive
+// diagonals and every run into pieces of 3 and a rest of 2 or 1.  A slot (CL lanes = one row of
+// X per load) takes R CONSECUTIVE rows r0 .. r0 + R - 1 (R = 4 with 8 lanes per row of X, 8 with
+// 16); for a piece of LEN diagonals starting at d it loads the rows r0 + d .. r0 + d + R + LEN - 2
+// of X once: row r0 + p multiplies its entry of diagonal d + e with the (p + e)-th of them, so
+// R + LEN - 1 loads serve R * LEN products (6 for 12, 10 for 24).  No column index is read: the
+// chunk is worked on from its values and its pattern table alone.
+constexpr int kShareMaxOdd = 4;
+
+// What a wavefront knows about its chunk after the first round trip; lane r < 32 holds row r.
+struct ShareRows {
+    int32_t my_rp, my_len, my_pat;     // lane r: first entry, length and pattern start of row r (0 past the end)
+    int32_t base, end, w0;             // the chunk's entries [base, end), w0 = base rounded down to 8
+    int32_t ref_len, ref_pat;          // the reference list: length, start in the chunk's table
+    uint64_t odd;                      // rows (below nrows) whose list is not the reference list
+    bool fits;                         // (a), (c), (d) and ref_len in 1..64
+};
+
+__device__ __forceinline__ ShareRows share_rows_setup(int lane, int32_t nrows, int64_t row0,
+                                                      const int32_t *__restrict__ rowptr,
+                                                      const uint16_t *__restrict__ row_pat, int32_t pat_len)
+{
+    ShareRows c;
+    const bool is_row = lane < kStreamRows;
+    const int64_t my_row = row0 + (is_row ? lane : kStreamRows);
+    const int64_t my_row_c = my_row < nrows ? my_row : nrows;
+    c.my_rp = rowptr[my_row_c];
+    const int32_t my_re = rowptr[my_row_c < nrows ? my_row_c + 1 : nrows];
+    c.my_len = is_row ? my_re - c.my_rp : 0;
+    const int32_t pat_raw = (is_row && my_row < nrows) ? (int32_t)row_pat[my_row] : 0;
+    c.my_pat = c.my_len > 0 ? pat_raw : 0;
+    c.base = __builtin_amdgcn_readfirstlane(c.my_rp);
+    c.end = __builtin_amdgcn_readlane(c.my_rp, kStreamRows);
+    c.w0 = c.base & ~7;
+    c.ref_len = wave_max_nonneg(c.my_len);
+    const uint64_t longest = __builtin_amdgcn_ballot_w64(is_row && c.my_len == c.ref_len);
+    c.ref_pat = __builtin_amdgcn_readlane(c.my_pat, (int)__builtin_ctzll(longest));
+    c.odd = __builtin_amdgcn_ballot_w64(is_row && my_row < nrows && !(c.my_len == c.ref_len && c.my_pat == c.ref_pat));
+    c.fits = pat_len > 0 && c.ref_len > 0 && c.ref_len <= kWave && __popcll(c.odd) <= kShareMaxOdd &&
+             c.end - c.w0 + kWave <= kStreamWindow;
+    return c;
+}
+
+// Analysis, one wavefront per chunk: flag_out[c] = 0 if c is not a stream chunk (stream_flag[c] == 0),
+// 1 if it shares rows of X as defined above, 2 otherwise.
+__global__ __launch_bounds__(kBlock) void spmm_share_flag_kernel(
+    int32_t nrows, int32_t ncols, int32_t num_chunks, const int32_t *__restrict__ stream_flag,
+    const int32_t *__restrict__ rowptr, StreamPatterns pats, int32_t *__restrict__ flag_out)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (chunk >= num_chunks) return;                                       // whole wavefronts leave
+    const int lane = threadIdx.x % kWave;
+    int32_t result = 0;
+    if (stream_flag[chunk] != 0) {
+        result = 2;
+        const int64_t row0 = chunk * kStreamRows;
+        const int32_t pat_begin = pats.pat_off[chunk];
+        const int32_t pat_len = pats.pat_off[chunk + 1] - pat_begin;
+        const ShareRows c = share_rows_setup(lane, nrows, row0, rowptr, pats.row_pat, pat_len);
+        if (c.fits) {                                                      // uniform
+            const bool in_ref = lane < c.ref_len;
+            const int32_t pstar = in_ref ? pats.pool[pat_begin + c.ref_pat + lane] : 0;
+            const int32_t before = __builtin_amdgcn_update_dpp(0, pstar, 0x138, 0xf, 0xf, false);   // lane t gets lane t - 1
+            const uint64_t descending = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before);
+            const int64_t d_min = __builtin_amdgcn_readlane(pstar, 0);
+            const int64_t d_max = __builtin_amdgcn_readlane(pstar, c.ref_len - 1);
+            const bool inside = row0 + d_min >= 0 && row0 + kStreamRows + 1 + d_max <= (int64_t)ncols - 1;
+            if (descending == 0 && inside) result = 1;
+        }
+    }
+    if (lane == 0) flag_out[chunk] = result;
+}
+
+// Columns [c0, min(c0 + CL*VEC, k)) of Y for chunks that share rows of X (spmm_share_flag_kernel said
+// 1 for every listed chunk; stream_chunks == nullptr: every chunk of the matrix, of which those with
+// share_flag[chunk] != 1 are skipped when share_flag is given).  One wavefront per chunk.  vals 16-byte aligned; a row of X shorter than 64 MiB (32-bit offsets of a lane from the
+// wave-uniform row address).  The odd rows are computed first, each by all slots together (slot s
+// takes its entries s, s + kSlots, ...; the partial sums meet in a butterfly of lane exchanges and
+// the slot that owns the row stores it), so no product of an absent entry is ever formed and a
+// non-finite row of X reaches exactly the rows that hold its column.  What the main loop leaves in
+// the sums of odd rows is never stored.  The pieces are taken longest first (all pieces of 3, then
+// of 2, then of 1), NB of them in flight; a piece's registers are refilled as soon as it has been
+// multiplied out.
+template <typename T, int VEC, int CL, bool XCD_REMAP>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(CL <= 8 ? 4 : 2)))
+void spmm_shared_kernel(
+    int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
+    const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ share_flag,
+    const int32_t *__restrict__ rowptr, uint32_t xcd_block,
+    const T *__restrict__ vals, int64_t k, int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y,
+    int64_t ldy, T alpha, T beta, StreamPatterns pats)
+{
+    static_assert(CL == 8 || CL == 16, "a slot is 8 or 16 lanes");
+    constexpr int kSlots = kWave / CL;
+    constexpr int R = kStreamRows / kSlots;            // consecutive rows of a slot
+    constexpr int kOddBatch = 3;                       // rows of X in flight per lane for an odd row
+    __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
+
+    const uint32_t id = !XCD_REMAP ? blockIdx.x
+                        : xcd_block ? xcd_block_cyclic_id(blockIdx.x, xcd_block)
+                                    : xcd_contiguous_id(blockIdx.x, padded_chunks);
+    if (id >= num_chunks) return;
+    const int lane = threadIdx.x;
+    const int slot = lane / CL;
+    const int l = lane % CL;
+    const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
+    const int64_t row0 = chunk * kStreamRows;
+    // round trip 1: row pointers, the rows' pattern starts, the chunk's place in the pool
+    const int32_t flag = share_flag ? share_flag[chunk] : 1;               // wave-uniform
+    const int32_t pat_begin = pats.pat_off[chunk];
+    const ShareRows c = share_rows_setup(lane, nrows, row0, rowptr, pats.row_pat, 1);
+    if (flag != 1) return;                                                 // another kernel's chunk
+    const int32_t w0 = c.w0;
+    const int64_t col = c0 + (int64_t)l * VEC;
+    const bool active = col < k;
+    const uint32_t row_bytes = (uint32_t)(ldx * (int64_t)sizeof(T));
+    // round trip 2: the values into LDS, the reference list one diagonal per lane
+    const bool in_ref = lane < c.ref_len;
+    const int32_t pstar = in_ref ? pats.pool[pat_begin + c.ref_pat + lane] : 0;
+    stream_values_to_lds<T>(vals, w0, c.end, nnz & ~3, lane, s_val);           // ends with the wavefront's fence
+    // pieces: every run of consecutive diagonals is cut into pieces of 3 and a rest of 1 or 2; lane t
+    // knows whether a piece starts at diagonal t and how long it is
+    const int32_t before = __builtin_amdgcn_update_dpp(0, pstar, 0x138, 0xf, 0xf, false);   // lane t gets lane t - 1
+    const uint64_t brk = __builtin_amdgcn_ballot_w64(in_ref && (lane == 0 || pstar != before + 1));   // run starts
+    const uint64_t upto = (2ull << lane) - 1;                                  // lanes 0 .. this one
+    const int run_start = 63 - (int)__builtin_clzll((brk & upto) | 1);
+    const uint64_t above = (brk | (c.ref_len >= kWave ? 0 : (1ull << c.ref_len))) & ~upto;
+    const int run_end = above ? (int)__builtin_ctzll(above) : kWave;           // first lane past this lane's run
+    const bool piece_start = in_ref && (lane - run_start) % 3 == 0;
+    const int piece_len = run_end - lane < 3 ? run_end - lane : 3;
+    const uint64_t m3 = __builtin_amdgcn_ballot_w64(piece_start && piece_len == 3);
+    const uint64_t m2 = __builtin_amdgcn_ballot_w64(piece_start && piece_len == 2);
+    const uint64_t m1 = __builtin_amdgcn_ballot_w64(piece_start && piece_len == 1);
+
+    const int r0 = slot * R;
+    int32_t first[R];
+#pragma unroll
+    for (int pp = 0; pp < R; ++pp) first[pp] = __shfl(c.my_rp, r0 + pp) - w0;
+    // row (row0 + r0 + d + q) of X = a wave-uniform address (row row0 + d + q) + this lane's fixed offset
+    const uint32_t lane_off = (uint32_t)r0 * row_bytes + (uint32_t)(col * (int64_t)sizeof(T));
+    const char *x0 = reinterpret_cast<const char *>(X) + row0 * (int64_t)row_bytes;
+
+    for (uint64_t left = c.odd; left != 0; left &= left - 1) {               // uniform
+        const int row = (int)__builtin_ctzll(left);
+        const int32_t rb = __builtin_amdgcn_readlane(c.my_rp, row), n = __builtin_amdgcn_readlane(c.my_len, row);
+        const int32_t *pat = pats.pool + pat_begin + __builtin_amdgcn_readlane(c.my_pat, row);
+        const T *sv = s_val + (rb - w0);
+        const int64_t me = row0 + row;
+        T sum[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) sum[q] = T(0);
+        for (int u0 = 0; u0 < n; u0 += kOddBatch * kSlots) {                   // uniform
+            Pack<T, VEC> xo[kOddBatch];
+            T vo[kOddBatch];
+            int32_t dd[kOddBatch];
+#pragma unroll
+            for (int t = 0; t < kOddBatch; ++t) {
+                const int want = u0 + t * kSlots + slot;
+                const int u = want < n ? want : n - 1;                        // past the end: repeat
+                dd[t] = pat[u];
+                vo[t] = sv[u];
+            }
+#pragma unroll
+            for (int t = 0; t < kOddBatch; ++t) {
+                if (active) xo[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (me + dd[t]) * ldx + col);
+                else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) xo[t].v[q] = T(0);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kOddBatch; ++t)
+#pragma unroll
+                for (int q = 0; q < VEC; ++q)
+                    sum[q] += (active && u0 + t * kSlots + slot < n) ? vo[t] * xo[t].v[q] : T(0);
+        }
+        // lanes l, l + CL, l + 2 CL, ... hold the same columns: butterfly over the slots
+#pragma unroll
+        for (int q = 0; q < VEC; ++q)
+#pragma unroll
+            for (int step = CL; step < kWave; step *= 2) sum[q] += __shfl_xor(sum[q], step);
+        if (active && row / R == slot) store_row<T, VEC>(Y + me * ldy, sum, col, k, alpha, beta);
+    }
+
+    if (!active) return;
+    T acc[R][VEC];
+#pragma unroll
+    for (int pp = 0; pp < R; ++pp)
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[pp][q] = T(0);
+    auto run_class = [&](auto len_tag, uint64_t mask) {
+        constexpr int LEN = decltype(len_tag)::value;
+        constexpr int NX = R + LEN - 1;                    // rows of X per piece
+        constexpr int NB = R > 4 ? 2 : (LEN == 1 ? 4 : 3); // pieces in flight
+        Pack<T, VEC> xw[NB][NX];
+        int tt[NB];
+        auto fill = [&](int b) {
+            tt[b] = (int)__builtin_ctzll(mask);
+            mask &= mask - 1;
+            const int32_t d = __builtin_amdgcn_readlane(pstar, tt[b]);
+            const char *xb = x0 + (int64_t)d * (int64_t)row_bytes;            // uniform: scalar arithmetic
+#pragma unroll
+            for (int q = 0; q < NX; ++q) {
+                xw[b][q] = *reinterpret_cast<const Pack<T, VEC> *>(xb + lane_off);
+                xb += row_bytes;
+            }
+        };
+        auto use = [&](int b) {
+            T v[LEN][R];
+#pragma unroll
+            for (int e = 0; e < LEN; ++e)
+#pragma unroll
+                for (int pp = 0; pp < R; ++pp) v[e][pp] = s_val[first[pp] + tt[b] + e];
+#pragma unroll
+            for (int e = 0; e < LEN; ++e)
+#pragma unroll
+                for (int pp = 0; pp < R; ++pp)
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) acc[pp][q] = fused_madd(v[e][pp], xw[b][pp + e].v[q], acc[pp][q]);
+        };
+        int left = __popcll(mask);                         // pieces not yet asked for
+        if (left >= NB) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) fill(b);
+            left -= NB;
+#pragma unroll 1
+            while (left >= NB) {                           // steady state: every piece multiplied out is replaced
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    use(b);
+                    __builtin_amdgcn_sched_barrier(0);     // the refill stays below the products it replaces
+                    fill(b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                left -= NB;
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) use(b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // fewer than NB pieces are left
+#pragma unroll
+        for (int b = 0; b < NB - 1; ++b)
+            if (b < left) fill(b);
+#pragma unroll
+        for (int b = 0; b < NB - 1; ++b)
+            if (b < left) use(b);
+    };
+    if (m3) run_class(std::integral_constant<int, 3>(), m3);
+    if (m2) run_class(std::integral_constant<int, 2>(), m2);
+    if (m1) run_class(std::integral_constant<int, 1>(), m1);
+#pragma unroll
+    for (int pp = 0; pp < R; ++pp) {
+        const int64_t row = row0 + r0 + pp;
+        if (row < nrows && !((c.odd >> (r0 + pp)) & 1)) store_row<T, VEC>(Y + row * ldy, acc[pp], col, k, alpha, beta);
     }
 }
 

@@ -766,6 +766,64 @@ def test_spmm_shared_rows_of_x_rectangular_and_a_few_other_rows(k):
         dev.close()
 
 
+SHARE_LISTS = {
+    # reference lists of diagonals (ascending); runs of consecutive diagonals are cut into pieces of 3, 2 and 1
+    "runs_of_3": [-40, -39, -38, -1, 0, 1, 50, 51, 52],                       # three pieces of 3
+    "seven_point": [-400, -20, -1, 0, 1, 20, 400],                            # 1, 1, 3, 1, 1
+    "pairs": [-31, -30, -11, -10, 0, 1, 10, 11, 30, 31, 60, 61],              # six pieces of 2
+    "singles": [-90, -70, -50, -30, -10, 0, 10, 30, 50, 70, 90, 110, 130],    # thirteen pieces of 1
+    "long_runs": list(range(-9, 2)) + list(range(20, 27)) + [40, 41, 50],     # 11 = 3+3+3+2, 7 = 3+3+1, 2, 1
+    "dense_band": list(range(-30, 31)),                                       # one run of 61: 20 pieces of 3 and a 1
+    "five_pieces_of_3": list(range(0, 15)),                                   # more pieces than are in flight
+}
+
+
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float32, 32), (np.float64, 32), (np.float64, 11),
+                                     (np.float32, 7), (np.float64, 48)])
+@pytest.mark.parametrize("kind", sorted(SHARE_LISTS))
+def test_spmm_shared_rows_every_piece_length(kind, dtype, k):
+    """Band matrices whose rows all hold one list of diagonals, so that every chunk away from the ends
+    shares rows of X between neighbouring rows: pieces of 3, 2 and 1 diagonals, runs longer than 3,
+    more pieces than are in flight at once; a few emptied or shortened rows per chunk (computed apart);
+    8 and 16 lanes per row of X, element-wise loads (k = 11, 7), two column blocks (k = 48).  The first
+    and last chunks reach outside the matrix with some diagonal and take the ordinary path."""
+    say(f"spmm shared rows, list {kind} k={k} {np.dtype(dtype).name}")
+    lst = SHARE_LISTS[kind]
+    n = 32 * 37 + 11
+    rows = []
+    for i in range(n):
+        cols = [i + d for d in lst if 0 <= i + d < n]
+        c = i // 32
+        if i % 32 == 5 and c % 2 == 0:
+            cols = []                                            # an empty row
+        elif i % 32 == 30 and c % 3 == 0:
+            cols = cols[1:-1]                                    # a subset of the list
+        elif i % 32 == 17 and c % 5 == 0:
+            cols = cols[::-1]                                    # the same columns, descending
+        rows.append(cols)
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    vals = gen.uniform(53, gen.STREAM_VALUES, colidx.size).astype(dtype)
+    X = gen.uniform(53, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+    Y0 = gen.uniform(53, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        if len(lst) * 32 >= 256:
+            assert dev.patterns()["enabled"]
+        check_partition(dev, rowptr)
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, 0.5, -2.0, Y0, what="alpha=0.5 beta=-2", ldx=k + 1, ldy=k + 2)
+        for j in (3, n // 2, n - 2):                             # a non-finite row of X reaches exactly its column's rows
+            Xi = X.copy()
+            Xi[j, :] = np.nan
+            ref, _ = oracle.spmm(rowptr, colidx, vals, Xi)
+            got = dev.spmm(Xi)
+            assert np.array_equal(np.isnan(got), np.isnan(ref)), f"NaN row {j} of X spread differently"
+    finally:
+        dev.close()
+
+
 # ---------------------------------------------------------------------------
 # the five workloads: reduced sizes (several tiles + ragged tail) and full size
 # ---------------------------------------------------------------------------

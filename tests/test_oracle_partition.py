@@ -95,17 +95,17 @@ def test_partition_matches_independent_construction(wave, lt, tile, srows, smin,
 def test_stream_chunks_hand_worked():
     """Chunks of 32 rows; class k = smallest k with max row length <= 2^k * 32 and entries <=
     2^k * 512 (k <= 4; the length alone if no k fits the entries), class 0 (binned) when the chunk
-    holds fewer than 256 entries or a row exceeds 512 entries."""
-    L = np.array([8] * 32            # chunk 0: 256 entries, max 8                -> class 1
+    holds fewer than 64 entries or a row exceeds 512 entries."""
+    L = np.array([2] * 32            # chunk 0: 64 entries, max 2                 -> class 1
                  + [8] * 31 + [65]   # chunk 1: max 65                            -> class 2
-                 + [7] * 32          # chunk 2: 224 entries, below the minimum    -> binned
+                 + [1] * 31 + [32]   # chunk 2: 63 entries, below the minimum     -> binned
                  + [64] * 32         # chunk 3: rows at 64, 2048 entries > 2*512  -> class 2
-                 + [0] * 31 + [64]   # chunk 4: 64 entries                        -> binned
+                 + [0] * 31 + [63]   # chunk 4: 63 entries                        -> binned
                  + [128] * 2 + [1] * 30   # chunk 5: max 128                      -> class 2
                  + [129] + [5] * 31  # chunk 6: max 129 (284 entries)             -> class 3
                  + [512] + [0] * 31  # chunk 7: max 512                           -> class 4
                  + [513] + [9] * 31  # chunk 8: a row above 512                   -> binned
-                 + [40] * 7,         # chunk 9 (ragged, 7 rows): 280 entries      -> class 1
+                 + [10] * 7,         # chunk 9 (ragged, 7 rows): 70 entries       -> class 1
                  dtype=np.int64)
     rowptr = np.zeros(L.size + 1, dtype=np.int32)
     np.cumsum(L, out=rowptr[1:])
@@ -120,9 +120,9 @@ def test_stream_chunks_hand_worked():
     assert oracle.partition(rp)["stream_offset"].tolist() == [0, 0, 0, 1, 1]
     binned = list(range(64, 96)) + list(range(128, 160)) + list(range(256, 288))
     assert sorted(part["row_perm"].tolist()) == binned
-    # bins: 31 empty rows; 32 rows of 7 (bin 4); 31 rows of 9 (bin 5); one row of 64 (bin 7); one of 513 (bin 8)
-    assert np.diff(part["bin_offset"]).tolist() == [31, 0, 0, 0, 32, 31, 0, 1, 1, 0]
-    # with 6 rows in the ragged chunk: 240 entries -> binned
+    # bins: 31 empty rows; 31 rows of 1 (bin 1); 31 rows of 9 (bin 5); rows of 32 and 63 (bins 6, 7); one of 513 (bin 8)
+    assert np.diff(part["bin_offset"]).tolist() == [31, 31, 0, 0, 0, 31, 1, 1, 1, 0]
+    # with 6 rows in the ragged chunk: 60 entries -> binned
     part = oracle.partition(rowptr[:-1].copy())
     assert part["stream_chunks"].tolist() == [0, 1, 3, 5, 6, 7]
 
@@ -193,9 +193,9 @@ def test_split_cuts_hand_worked():
     cols1 = [5] * 3 + [12] * 60 + [29] * 7        # row 2: duplicates allowed (non-decreasing)
     rowptr = np.array([0, 70, 72, 142], dtype=np.int32)
     colidx = np.array(cols0 + [1, 2] + cols1, dtype=np.int32)
-    part = oracle.partition(rowptr)
+    part = oracle.partition(rowptr, stream_min_nnz=1000)            # no stream chunk: the rows are binned
     assert part["row_perm"].tolist() == [1, 0, 2]                   # bin 2 (row 1), bin 8 (rows 0, 2)
-    assert part["stream_chunks"].size == 0                           # 142 entries: below the minimum
+    assert part["stream_chunks"].size == 0
     sp = oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, max_blocks=32)
     assert (sp["num_blocks"], sp["block_width"], sp["num_split_rows"]) == (3, 10, 2)
     # cut[b*S + r]: b = 0..3, r = 0 (row 0), 1 (row 2)
@@ -237,7 +237,7 @@ def test_split_huge_rows_hand_worked():
     cols2 = np.sort(np.concatenate([np.arange(30), np.arange(30), np.arange(6)])).tolist()    # 66 entries
     rowptr = np.array([0, 72, 74, 140], dtype=np.int32)
     colidx = np.array(cols0 + [1, 2] + cols2, dtype=np.int32)
-    part = oracle.partition(rowptr)
+    part = oracle.partition(rowptr, stream_min_nnz=1000)            # no stream chunk: the rows are binned
     sp = oracle.split_partition(rowptr, colidx, 30, 8, part, block_bytes=80, huge_row=70, lds_block_bytes=32)
     assert (sp["num_blocks"], sp["num_split_rows"], sp["num_huge_rows"]) == (3, 1, 1)
     assert sp["split_rows"].tolist() == [2] and sp["huge_rows"].tolist() == [0]
@@ -382,8 +382,8 @@ def test_index16_threshold_is_65535():
 
 
 def test_index16_off_without_stream_chunks_and_below_half():
-    rowptr = (np.arange(33) * 4).astype(np.int32)            # 128 entries: below the stream minimum
-    colidx = np.tile(np.arange(4, dtype=np.int32), 32)
+    rowptr = np.concatenate([np.arange(32), [63]]).astype(np.int32)   # 63 entries: below the stream minimum
+    colidx = np.arange(63, dtype=np.int32) % 32
     got = oracle.index16(rowptr, colidx)
     assert not got["enabled"] and np.all(got["chunk_base"] == -1) and got["narrow_entries"] == 0
     # one narrow chunk of 256 entries and one chunk of 320 entries over 40 frames: 256 * 2 < 576
@@ -530,7 +530,7 @@ def test_row_patterns_limits():
     wider = [w[:] for w in wide]
     wider[7] = wider[7] + [999]
     assert oracle.row_patterns(*chunk_with(wider))["pat_off"].tolist() == [0, 0]
-    # a row of 128 entries is allowed, 129 is not (one pattern, 4 rows of it make 512 >= 256 entries)
+    # a row of 128 entries is allowed, 129 is not (one pattern, 4 rows of it)
     for length, expect in ((128, [0, 128]), (129, [0, 0])):
         rows = [list(range(i, i + length)) if i < 4 else [] for i in range(32)]
         assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == expect
@@ -540,8 +540,8 @@ def test_row_patterns_limits():
     # exactly twice the table: two patterns, each used twice
     rows = [[i + t * (1 + i % 2) for t in range(64)] for i in range(4)]
     assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == [0, 128]
-    # chunks below the stream minimum (255 entries) have no patterns
-    rows = [list(range(i, i + 8)) for i in range(31)] + [list(range(31, 38))]
+    # chunks below the stream minimum (63 entries) have no patterns
+    rows = [list(range(i, i + 2)) for i in range(31)] + [[31]]
     assert oracle.row_patterns(*_csr_from_rows(rows))["pat_off"].tolist() == [0, 0]
 
 
@@ -594,7 +594,9 @@ def test_row_patterns_reconstruct_columns_and_are_minimal(cfg, scale):
             assert len(starts) == len(pats) and all(len(v) == 1 for v in starts.values())
         else:
             assert not got["row_pat"][rows[0]:rows[-1] + 1].any()
-    if cfg in (1, 3, 4):      # 5-point chunks are below the stream minimum; random columns repeat nothing
+    if cfg in (3, 4):         # random columns repeat nothing
         assert not got["enabled"]
+    if cfg == 1:              # every chunk of the 5-point grid is patterned
+        assert got["enabled"] and got["entries"] == w.nnz
     if cfg == 2:              # everything but a last chunk below the stream minimum
         assert got["enabled"] and got["entries"] >= w.nnz - 255
