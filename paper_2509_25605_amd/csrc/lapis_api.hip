@@ -449,7 +449,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
                 if (int rc = share_offsets.alloc(sizeof(int32_t) * (kChunkClasses + 1))) return rc;
                 if (int rc = device_alloc(&A->d_spmm_chunks, sizeof(int32_t) * (size_t)num_stream)) return rc;
                 spmm_share_flag_kernel<<<dim3(wblocks), dim3(kBlock), 0, stream>>>(
-                    (int32_t)n, (int32_t)A->ncols, num_chunks, chunk_flag.as<int32_t>(), A->rowptr,
+                    (int32_t)n, num_chunks, chunk_flag.as<int32_t>(), A->rowptr,
                     StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, A->d_share_flag);
                 chunk_class_hist_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
                     num_chunks, A->d_share_flag, class_hist.as<int32_t>());
@@ -898,7 +898,7 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
                     spmm_shared_kernel<T, VEC, kStreamLanes, true><<<dim3(share_padded), dim3(kWave), 0, stream>>>(
                         (int32_t)A->nrows, (int32_t)A->nnz, share_count, share_padded, share_list, share_flag,
                         A->rowptr, share_by_flag ? xcd_block : 0u, vals, k, c0, X, ldx, Y, ldy, a, b,
-                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool});
+                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, (int32_t)A->ncols);
             }
             if (n_plain == 0) continue;
             if (all16)

@@ -206,9 +206,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 // = column - row, spmv_kernels.hpp), (b) its longest row's list - the reference list, at most 64
 // diagonals - ascends strictly, (c) at most kShareMaxOdd of its rows have another list or are empty
 // (grid boundaries: the "odd" rows), (d) its values fit one LDS window with 64 entries to spare
-// (a row with the reference list reads its values at fixed places past the start of ANY row), and
-// (e) every row of X that the scheme below may ask for exists: row0 + smallest diagonal >= 0 and
-// row0 + 33 + largest diagonal <= ncols - 1.  The reference list is cut into runs of consecutive
+// (a row with the reference list reads its values at fixed places past the start of ANY row).
+// The reference list is cut into runs of consecutive
 // diagonals and every run into pieces of 3 and a rest of 2 or 1.  A slot (CL lanes = one row of
 // X per load) takes R CONSECUTIVE rows r0 .. r0 + R - 1 (R = 4 with 8 lanes per row of X, 8 with
 // 16); for a piece of LEN diagonals starting at d it loads the rows r0 + d .. r0 + d + R + LEN - 2
@@ -254,7 +253,7 @@ __device__ __forceinline__ ShareRows share_rows_setup(int lane, int32_t nrows, i
 // Analysis, one wavefront per chunk: flag_out[c] = 0 if c is not a stream chunk (stream_flag[c] == 0),
 // 1 if it shares rows of X as defined above, 2 otherwise.
 __global__ __launch_bounds__(kBlock) void spmm_share_flag_kernel(
-    int32_t nrows, int32_t ncols, int32_t num_chunks, const int32_t *__restrict__ stream_flag,
+    int32_t nrows, int32_t num_chunks, const int32_t *__restrict__ stream_flag,
     const int32_t *__restrict__ rowptr, StreamPatterns pats, int32_t *__restrict__ flag_out)
 {
     const int64_t chunk = (int64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
@@ -272,10 +271,7 @@ __global__ __launch_bounds__(kBlock) void spmm_share_flag_kernel(
             const int32_t pstar = in_ref ? pats.pool[pat_begin + c.ref_pat + lane] : 0;
             const int32_t before = __builtin_amdgcn_update_dpp(0, pstar, 0x138, 0xf, 0xf, false);   // lane t gets lane t - 1
             const uint64_t descending = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before);
-            const int64_t d_min = __builtin_amdgcn_readlane(pstar, 0);
-            const int64_t d_max = __builtin_amdgcn_readlane(pstar, c.ref_len - 1);
-            const bool inside = row0 + d_min >= 0 && row0 + kStreamRows + 1 + d_max <= (int64_t)ncols - 1;
-            if (descending == 0 && inside) result = 1;
+            if (descending == 0) result = 1;
         }
     }
     if (lane == 0) flag_out[chunk] = result;
@@ -298,7 +294,7 @@ void spmm_shared_kernel(
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ share_flag,
     const int32_t *__restrict__ rowptr, uint32_t xcd_block,
     const T *__restrict__ vals, int64_t k, int64_t c0, const T *__restrict__ X, int64_t ldx, T *__restrict__ Y,
-    int64_t ldy, T alpha, T beta, StreamPatterns pats)
+    int64_t ldy, T alpha, T beta, StreamPatterns pats, int32_t ncols)
 {
     static_assert(CL == 8 || CL == 16, "a slot is 8 or 16 lanes");
     constexpr int kSlots = kWave / CL;
@@ -346,9 +342,14 @@ void spmm_shared_kernel(
     int32_t first[R];
 #pragma unroll
     for (int pp = 0; pp < R; ++pp) first[pp] = __shfl(c.my_rp, r0 + pp) - w0;
-    // row (row0 + r0 + d + q) of X = a wave-uniform address (row row0 + d + q) + this lane's fixed offset
+    // row (row0 + r0 + d + q) of X = a wave-uniform address (row row0 + d + q) + this lane's fixed offset.
+    // Every row of X that a slot of regular rows asks for is the column of one of its entries; a slot with
+    // an odd row (or rows past the end) also asks for rows that no entry names.  Only near the ends of
+    // the matrix can those lie outside X: such chunks (`inside` false) clamp every row number.
     const uint32_t lane_off = (uint32_t)r0 * row_bytes + (uint32_t)(col * (int64_t)sizeof(T));
     const char *x0 = reinterpret_cast<const char *>(X) + row0 * (int64_t)row_bytes;
+    const int64_t d_min = __builtin_amdgcn_readlane(pstar, 0), d_max = __builtin_amdgcn_readlane(pstar, c.ref_len - 1);
+    const bool inside = row0 + d_min >= 0 && row0 + kStreamRows + 1 + d_max <= (int64_t)ncols - 1;   // uniform
 
     for (uint64_t left = c.odd; left != 0; left &= left - 1) {               // uniform
         const int row = (int)__builtin_ctzll(left);
@@ -398,10 +399,11 @@ void spmm_shared_kernel(
     for (int pp = 0; pp < R; ++pp)
 #pragma unroll
         for (int q = 0; q < VEC; ++q) acc[pp][q] = T(0);
-    auto run_class = [&](auto len_tag, uint64_t mask) {
+    auto run_class = [&](auto len_tag, auto inside_tag, uint64_t mask) {
         constexpr int LEN = decltype(len_tag)::value;
+        constexpr bool kInside = decltype(inside_tag)::value;
         constexpr int NX = R + LEN - 1;                    // rows of X per piece
-        constexpr int NB = R > 4 ? 2 : (LEN == 1 ? 4 : 3); // pieces in flight
+        constexpr int NB = !kInside ? 2 : R > 4 ? 2 : (LEN == 1 ? 4 : 3);   // pieces in flight (the rare clamped variant: fewer registers)
         Pack<T, VEC> xw[NB][NX];
         int tt[NB];
         auto fill = [&](int b) {
@@ -411,8 +413,14 @@ void spmm_shared_kernel(
             const char *xb = x0 + (int64_t)d * (int64_t)row_bytes;            // uniform: scalar arithmetic
 #pragma unroll
             for (int q = 0; q < NX; ++q) {
-                xw[b][q] = *reinterpret_cast<const Pack<T, VEC> *>(xb + lane_off);
-                xb += row_bytes;
+                if constexpr (kInside) {
+                    xw[b][q] = *reinterpret_cast<const Pack<T, VEC> *>(xb + lane_off);
+                    xb += row_bytes;
+                } else {
+                    int64_t r = row0 + r0 + d + q;
+                    r = r < 0 ? 0 : (r > (int64_t)ncols - 1 ? (int64_t)ncols - 1 : r);
+                    xw[b][q] = *reinterpret_cast<const Pack<T, VEC> *>(X + r * ldx + col);
+                }
             }
         };
         auto use = [&](int b) {
@@ -456,9 +464,15 @@ void spmm_shared_kernel(
         for (int b = 0; b < NB - 1; ++b)
             if (b < left) use(b);
     };
-    if (m3) run_class(std::integral_constant<int, 3>(), m3);
-    if (m2) run_class(std::integral_constant<int, 2>(), m2);
-    if (m1) run_class(std::integral_constant<int, 1>(), m1);
+    if (inside) {
+        if (m3) run_class(std::integral_constant<int, 3>(), std::true_type(), m3);
+        if (m2) run_class(std::integral_constant<int, 2>(), std::true_type(), m2);
+        if (m1) run_class(std::integral_constant<int, 1>(), std::true_type(), m1);
+    } else {
+        if (m3) run_class(std::integral_constant<int, 3>(), std::false_type(), m3);
+        if (m2) run_class(std::integral_constant<int, 2>(), std::false_type(), m2);
+        if (m1) run_class(std::integral_constant<int, 1>(), std::false_type(), m1);
+    }
 #pragma unroll
     for (int pp = 0; pp < R; ++pp) {
         const int64_t row = row0 + r0 + pp;
