@@ -149,10 +149,16 @@ int lapis_csr_create(lapis_csr_t **out, int64_t nrows, int64_t ncols, int64_t nn
  * beta == 0 makes d_y write-only: its old contents (NaN included) are ignored.
  * Rows without entries receive beta*y (exactly +0 when beta == 0).
  * Asynchronous: the kernels are enqueued on hip_stream and the call returns;
- * no allocation, no host-device copy, no synchronisation.  Matrices with rows
+ * no allocation, no host-device copy, no host synchronisation.  Matrices with rows
  * in bin 9 or with a column split use scratch owned by the handle (per-tile and
- * per-virtual-row sums), so two calls on the same handle must not run
- * concurrently on different streams.
+ * per-virtual-row sums).  Calls on one handle from different streams are therefore
+ * ordered by the library: every such product records an event on its stream, and a
+ * product enqueued on another stream than the previous one first makes its stream wait
+ * for that event (the products of one handle run one after the other, whatever their
+ * streams; handles without scratch - no bin-9 row, no split - are not ordered and may
+ * overlap freely).  The one exception is a stream that is being captured into a HIP
+ * graph: nothing is recorded or waited for there, and the caller must not let a captured
+ * product of such a handle overlap another product of the same handle.
  */
 int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta, void *d_y,
                void *hip_stream);

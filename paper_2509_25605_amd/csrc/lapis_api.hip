@@ -101,6 +101,13 @@ struct lapis_csr {
     // launch plans for spmv_short_kernel
     ShortPlan plan_rows;       // bins 0..8 of `rows` (0..7 when the split is on)
     ShortPlan plan_vrows;      // bins 0..8 of `vrows`
+    // Products that use the handle's scratch (tile sums, virtual-row sums, block sums) are ordered among
+    // themselves: each records scratch_event on its stream, and one that is enqueued on another stream
+    // than the last first makes its stream wait for that event.  Null when the handle has no scratch.
+    mutable std::mutex scratch_lock;
+    mutable hipEvent_t scratch_event = nullptr;
+    mutable hipStream_t scratch_stream = nullptr;
+    mutable bool scratch_used = false;
 };
 
 namespace {
@@ -227,6 +234,10 @@ int free_handle(lapis_csr *A)
     LAPIS_FREE(f, A->own_vals);
     free_set(A->rows, f);
     free_set(A->vrows, f);
+    if (A->scratch_event) {
+        const hipError_t e = hipEventDestroy(A->scratch_event);
+        if (e != hipSuccess && f.first == hipSuccess) { f.first = e; f.what = "hipEventDestroy(scratch_event)"; }
+    }
     delete A;
     if (f.first != hipSuccess) return fail_hip(f.first, f.what);
     return LAPIS_OK;
@@ -575,6 +586,7 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
     }
     build_short_plan(A->rows, split ? kNumBins - 3 : kShortBins - 1, &A->plan_rows);
     if (split) build_short_plan(A->vrows, kShortBins - 1, &A->plan_vrows);
+    if (split || A->rows.num_long > 0) LAPIS_HIP(hipEventCreateWithFlags(&A->scratch_event, hipEventDisableTiming));
     return LAPIS_OK;
 }
 
@@ -1041,8 +1053,26 @@ int lapis_spmv(const lapis_csr_t *A, double alpha, const void *d_x, double beta,
     if (A->nrows == 0) return LAPIS_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const SpmvScratch scr = handle_scratch(A);
-    return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, scr, stream)
-                                 : spmv_typed<float>(A, alpha, d_x, beta, d_y, scr, stream);
+    if (!A->scratch_event)
+        return A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, scr, stream)
+                                     : spmv_typed<float>(A, alpha, d_x, beta, d_y, scr, stream);
+    // this handle's products share its scratch: order them across streams (not while a stream is being
+    // captured into a graph: there the caller orders the captured products, as the header says)
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    LAPIS_HIP(hipStreamIsCapturing(stream, &capturing));
+    std::lock_guard<std::mutex> guard(A->scratch_lock);
+    const bool ordered = capturing == hipStreamCaptureStatusNone;
+    if (ordered && A->scratch_used && A->scratch_stream != stream)
+        LAPIS_HIP(hipStreamWaitEvent(stream, A->scratch_event, 0));
+    const int rc = A->dtype == LAPIS_F64 ? spmv_typed<double>(A, alpha, d_x, beta, d_y, scr, stream)
+                                         : spmv_typed<float>(A, alpha, d_x, beta, d_y, scr, stream);
+    if (rc != LAPIS_OK) return rc;
+    if (ordered) {
+        LAPIS_HIP(hipEventRecord(A->scratch_event, stream));
+        A->scratch_stream = stream;
+        A->scratch_used = true;
+    }
+    return LAPIS_OK;
 }
 
 int64_t lapis_spmv_scratch_bytes(const lapis_csr_t *A)
