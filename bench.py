@@ -32,20 +32,36 @@ EPS = {np.dtype(np.float64): 2.0 ** -53, np.dtype(np.float32): 2.0 ** -24}
 # the kernels of one step; commands and figures in profiles/), each scaled by what the same counter
 # reads for a plain 1 GiB device copy (FETCH_SIZE x2.000, WRITE_SIZE x1.000).  "source" is the
 # fingerprint (see source_fingerprint) of the kernel sources the figure was measured with: when the
-# sources on disk differ, the line reports the figure with "traffic_stale": true.
+# sources on disk differ, the line reports the figure with "traffic_stale": true.  "profile" is the
+# summary the figure is taken from.
 MEASURED = {
-    "stencil27_128x128x128_f64": {
-        "traffic": 505.30e6, "source": "",
+    "poisson2d_64x64_f64": {
+        "traffic": 0.42e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_poisson2d_64_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
-    "stencil27_128x128x128_f64_spmm_k16": {
-        "traffic": 1036.91e6, "source": "",
-        "kernel": "spmm_stream_kernel<double, 2, 8, true, true, true> (last: rows of X shared by 4 consecutive rows)"},
-    "table3_Elasticity3D_60_n648000_f64": {
-        "traffic": 522.18e6, "source": "",
-        "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 1> (1: 16-bit column offsets)"},
+    "stencil27_128x128x128_f64": {
+        "traffic": 507.82e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_stencil27_128_f64.md",
+        "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
+    "uniform16_n4194304_f64": {
+        "traffic": 8439.70e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_uniform16_f64.md",
+        "kernel": "spmv_stream_kernel<double, 2, true, 0, 16, 1> (0: 32-bit columns)"},
     "zipf1.8_cap200000_n8388608_f32": {
-        "traffic": 9123.91e6, "source": "",
-        "kernel": "spmv_short_kernel<float, true> (2 launches) + spmv_ldsblock_kernel<float> + spmv_long_tile_kernel<float, 4096>"},
+        "traffic": 8690.29e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_powerlaw_zipf_f32.md",
+        "kernel": "spmv_short_kernel<float, true> (2 launches) + spmv_ldsblock_kernel<float> + spmv_stream_kernel<float, ...>"},
+    "stencil27_128x128x128_f64_spmm_k16": {
+        "traffic": 1039.22e6, "source": "1d6e9e0979cd", "profile": "profiles/spmm_shared_stencil27_128_k16_f64.md",
+        "kernel": "spmm_shared_kernel<double, 2, 8, true> (rows of X shared by 4 consecutive rows)"},
+    "table3_StocF-1465_n1465137_f64": {
+        "traffic": 243.83e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_stocf_standin_f64.md",
+        "kernel": "spmv_stream_kernel<double, 2, true, 1, 16, 1> (1: 16-bit column offsets)"},
+    "table3_PFlow_742_n742793_f64": {
+        "traffic": 399.99e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_pflow_standin_f64.md",
+        "kernel": "spmv_stream_kernel<double, 4, true, 1, 16, 2> (1: 16-bit column offsets; 2 wavefronts per workgroup)"},
+    "table3_Elasticity3D_60_n648000_f64": {
+        "traffic": 522.14e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_elasticity3d_60_standin_f64.md",
+        "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 1> (1: 16-bit column offsets)"},
+    "table3_audikw_1_n943695_f64": {
+        "traffic": 814.74e6, "source": "1d6e9e0979cd", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
+        "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 4> (1: 16-bit column offsets; 4 wavefronts per workgroup)"},
 }
 FINGERPRINT_FILES = ["spmv_kernels.hpp", "spmm_kernels.hpp", "analysis_kernels.hpp", "lapis_api.hip", "device_utils.hpp"]
 

@@ -60,4 +60,5 @@ def test_source_fingerprint_follows_the_kernel_sources():
     fp = bench.source_fingerprint()
     assert len(fp) == 12 and int(fp, 16) >= 0
     for m in bench.MEASURED.values():
-        assert set(m) == {"traffic", "source", "kernel"}
+        assert set(m) == {"traffic", "source", "kernel", "profile"}
+        assert os.path.exists(os.path.join(ROOT, m["profile"]))
