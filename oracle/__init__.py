@@ -268,11 +268,12 @@ def row_patterns(rowptr, colidx, ncols=None, itemsize=None, wave=WAVE, stream_ro
                  max_table=PATTERN_TABLE):
     """Row patterns of the stream chunks: dict(enabled, entries, pat_off[num_chunks + 1],
     row_pat[nrows] (uint16), pool[pat_off[-1]]): row i of a patterned chunk c has the columns
-    i + pool[pat_off[c] + row_pat[i] + k].  With ncols and itemsize the demoted chunks are
+    i + shift_i + pool[pat_off[c] + (row_pat[i] & 511) + k], shift_i = bits 9..15 of row_pat[i] as a
+    signed 7-bit number (pattern_start_shift splits the two).  With ncols and itemsize the demoted chunks are
     left out, as in partition().  enabled when the patterned chunks hold at least half of
     the entries."""
     assert rowptr.dtype == np.int32 and colidx.dtype == np.int32
-    assert max_table <= 4096 and max_patterns <= 64
+    assert max_table <= 512 and max_patterns <= 64
     n = rowptr.size - 1
     nchunks = (n + stream_rows - 1) // stream_rows
     demoted = None
@@ -289,6 +290,13 @@ def row_patterns(rowptr, colidx, ncols=None, itemsize=None, wave=WAVE, stream_ro
     e = int(entries.value)
     return {"enabled": e > 0 and 2 * e >= colidx.size, "entries": e, "pat_off": pat_off,
             "row_pat": row_pat, "pool": pool}
+
+
+def pattern_start_shift(row_pat):
+    """(start in the chunk's table, shift) of every row from the packed row_pat values."""
+    rp = np.asarray(row_pat).astype(np.int64)
+    shift = rp >> 9
+    return rp & 511, np.where(shift >= 64, shift - 128, shift)
 
 
 def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):

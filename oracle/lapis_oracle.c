@@ -395,17 +395,24 @@ void oracle_demoted_chunks(int64_t nrows, const int32_t *rowptr, int64_t chunk_r
 }
 
 /* Level 1c: row patterns of the stream chunks (final class >= 1).
- * The pattern of a non-empty row i is the list of its diagonals colidx[j] - i in stored order.
- * Going through the rows of a chunk in ascending order, every pattern not seen before in the
- * chunk is appended to the chunk's table; row_pat[i] = where the pattern of row i starts in
- * that table (0 for empty rows).  A chunk is "patterned" when no row has more than max_row
- * entries, at most max_patterns patterns were needed, the table has at most max_table
- * diagonals and twice the table length does not exceed the chunk's entry count; otherwise its
+ * The list of a non-empty row i is its diagonals colidx[j] - i in stored order; its SHAPE is the
+ * same list minus its first element.  Going through the rows of a chunk in ascending order, a
+ * row takes the first stored list (in order of insertion) that has its length and its shape and
+ * whose shift = (the row's first diagonal) - (the stored list's first diagonal) lies in
+ * [-64, 63]; a row for which no stored list qualifies appends its own list to the chunk's table
+ * (shift 0).
+ * row_pat[i] = (where the taken list starts in the table) | ((shift & 127) << 9), 0 for empty
+ * rows.  Rows of a regular grid all have one list and shift 0; the rows of the unknowns of one
+ * grid point in a matrix with several unknowns per point hold the same columns, so their lists
+ * are one shape with shifts 0, -1, -2, ...
+ * A chunk is "patterned" when no row has more than max_row entries, at most max_patterns lists
+ * were stored, the table has at most max_table (<= 512) diagonals and twice the table length
+ * does not exceed the chunk's entry count; otherwise its
  * table is empty and row_pat is 0 for its rows.
  * pat_off[0 .. nchunks] = exclusive scan of the table lengths (pat_off[c+1] == pat_off[c] for
  * chunks without patterns); pool (may be NULL to get the sizes only) receives the tables back
  * to back.  *entries = number of matrix entries in patterned chunks.
- * Reconstruction: colidx[rowptr[i] + k] == i + pool[pat_off[c] + row_pat[i] + k]. */
+ * Reconstruction: colidx[rowptr[i] + k] == i + shift_i + pool[pat_off[c] + (row_pat[i] & 511) + k]. */
 void oracle_row_patterns(int64_t nrows, const int32_t *rowptr, const int32_t *colidx, int64_t chunk_rows,
                          int64_t chunk_min_nnz, const uint8_t *demoted, int64_t max_row, int64_t max_patterns,
                          int64_t max_table, int32_t *pat_off, uint16_t *row_pat, int32_t *pool,
@@ -431,9 +438,11 @@ void oracle_row_patterns(int64_t nrows, const int32_t *rowptr, const int32_t *co
             int64_t found = -1;
             for (int64_t p = 0; p < P && found < 0; ++p) {
                 if (length[p] != len) continue;
+                int64_t shift = ((int64_t)colidx[b] - i) - table[start[p]];
+                if (shift < -64 || shift > 63) continue;    /* too far away to be coded: not a match */
                 int same = 1;
-                for (int64_t k = 0; k < len; ++k)
-                    if (table[start[p] + k] != colidx[b + k] - (int32_t)i) same = 0;
+                for (int64_t k = 0; k < len; ++k)          /* shapes: differences from the first element */
+                    if ((int64_t)table[start[p] + k] - table[start[p]] != (int64_t)colidx[b + k] - colidx[b]) same = 0;
                 if (same) found = p;
             }
             if (found < 0) {
@@ -444,7 +453,8 @@ void oracle_row_patterns(int64_t nrows, const int32_t *rowptr, const int32_t *co
                 found = P++;
                 L += len;
             }
-            row_pat[i] = (uint16_t)start[found];
+            int64_t shift = ((int64_t)colidx[b] - i) - table[start[found]];
+            row_pat[i] = (uint16_t)(start[found] | ((shift & 127) << 9));
         }
         int64_t chunk_entries = rowptr[last] - rowptr[first];
         if (!ok || 2 * L > chunk_entries) {

@@ -468,16 +468,17 @@ def _banded(n, half):
 
 
 def _columns_from_patterns(rowptr, got):
-    """Columns back from the patterns (-1 where the chunk has none): row + pool[pat_off + row_pat + k]."""
+    """Columns back from the patterns (-1 where the chunk has none): row + shift + pool[pat_off + start + k]."""
     n = rowptr.size - 1
     L = np.diff(rowptr)
     row_of_entry = np.repeat(np.arange(n, dtype=np.int64), L)
     k = np.arange(rowptr[-1], dtype=np.int64) - np.repeat(rowptr[:-1].astype(np.int64), L)
     chunk = row_of_entry // oracle.STREAM_ROWS
     has = (got["pat_off"][1:] > got["pat_off"][:-1])[chunk]
-    at = got["pat_off"][chunk].astype(np.int64) + got["row_pat"][row_of_entry] + k
+    start, shift = oracle.pattern_start_shift(got["row_pat"])
+    at = got["pat_off"][chunk].astype(np.int64) + start[row_of_entry] + k
     cols = np.full(rowptr[-1], -1, dtype=np.int64)
-    cols[has] = row_of_entry[has] + got["pool"][at[has]]
+    cols[has] = row_of_entry[has] + shift[row_of_entry][has] + got["pool"][at[has]]
     return cols, has
 
 
@@ -510,6 +511,58 @@ def test_row_patterns_first_appearance_order_and_prefixes():
     assert got["pat_off"].tolist() == [0, 26]
     assert got["row_pat"][:5].tolist() == [0, 9, 0, 18, 0]
     assert got["pool"].tolist() == A + B + C
+
+
+def test_row_patterns_with_shifts_hand_worked():
+    """Three unknowns per grid point, 1-D grid with neighbours -1, 0, +1: row 3p + a holds the columns
+    3(p-1) .. 3(p+1)+2 whatever a is, so the three rows of a point have the list of its first row moved
+    by 0, -1, -2: one stored list of 9 for the interior, the two cut-off lists of the end points, and the
+    shift in bits 9..15 of row_pat."""
+    npts = 16                                                  # 48 rows: one full chunk and half a chunk
+    rows = []
+    for p in range(npts):
+        cols = [3 * q + c for q in (p - 1, p, p + 1) if 0 <= q < npts for c in range(3)]
+        rows += [cols] * 3
+    rowptr, colidx = _csr_from_rows(rows)
+    got = oracle.row_patterns(rowptr, colidx)
+    start, shift = oracle.pattern_start_shift(got["row_pat"])
+    # chunk 0 (rows 0..31): point 0 has 6 columns 0..5: list (0..5) stored at 0; rows 1, 2 are it moved by -1, -2;
+    # point 1 (rows 3, 4, 5) has columns 0..8: list (-3..5) stored at 6; every later row has that shape
+    assert got["pat_off"].tolist() == [0, 15, 30]
+    assert got["pool"][:15].tolist() == [0, 1, 2, 3, 4, 5] + [-3, -2, -1, 0, 1, 2, 3, 4, 5]
+    assert start[:32].tolist() == [0, 0, 0] + [6] * 29
+    assert shift[:32].tolist() == [0, -1, -2] + [0, -1, -2] * 9 + [0, -1]
+    assert got["row_pat"][1] == (127 << 9) and got["row_pat"][5] == 6 | (126 << 9)
+    # chunk 1 (rows 32..47) starts with the third row of point 10: ITS list (-5..3) is stored, and the rows
+    # of the next points are that list moved by +2, +1, 0; the last point (rows 45, 46, 47) has 6 columns
+    assert got["pool"][15:30].tolist() == [-5, -4, -3, -2, -1, 0, 1, 2, 3] + [-3, -2, -1, 0, 1, 2]
+    assert start[32:].tolist() == [0] * 13 + [9] * 3
+    assert shift[32:].tolist() == [0] + [2, 1, 0] * 4 + [0, -1, -2]
+    cols, has = _columns_from_patterns(rowptr, got)
+    assert has.all() and np.array_equal(cols, colidx)
+
+
+def test_row_patterns_shift_limits_and_order_of_the_search():
+    """A row whose shift to a stored list of its shape is outside [-64, 63] does not take that list: it
+    stores its own, and later rows take whichever stored list of the shape comes first within reach."""
+    shape = [0, 1, 2, 3, 4, 5, 6, 7]
+    firsts = [0, 63, 64, -64, -65, 100, 128 + 63, 1]            # first diagonal of rows 0..7 (row i: columns i + first + shape)
+    rows = [[i + f + d for d in shape] for i, f in enumerate(firsts)]
+    rows += [[i + 10 + d for d in shape] for i in range(8, 32)]
+    rows = [[c + 200 for c in r] for r in rows]                 # keep every column non-negative
+    rowptr, colidx = _csr_from_rows(rows)
+    got = oracle.row_patterns(rowptr, colidx)
+    start, shift = oracle.pattern_start_shift(got["row_pat"])
+    # row 0 stores list A (first 200).  row 1: +63 -> A.  row 2: +64 is too far -> stores B (first 264).
+    # row 3: -64 -> A.  row 4: -65 from A, -129 from B -> stores C (first 135).  row 5: first 300: +100 from A,
+    # +36 from B -> B.  row 6: first 391: from A 191, from B 127, from C 256 -> stores D.  row 7: +1 -> A.
+    assert got["pat_off"].tolist() == [0, 32]
+    assert start[:8].tolist() == [0, 0, 8, 0, 16, 8, 24, 0]
+    assert shift[:8].tolist() == [0, 63, 0, -64, 0, 36, 0, 1]
+    assert np.all(start[8:] == 0) and np.all(shift[8:] == 10)
+    assert got["pool"].tolist() == [200 + d for d in shape] + [264 + d for d in shape] + [135 + d for d in shape] + [391 + d for d in shape]
+    cols, has = _columns_from_patterns(rowptr, got)
+    assert has.all() and np.array_equal(cols, colidx)
 
 
 def test_row_patterns_limits():
@@ -559,10 +612,13 @@ def test_row_patterns_of_the_27_point_stencil_are_its_neighbour_offsets():
             left = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (0, 1)]
             mid = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (-1, 0, 1)]
             right = [a * nx * ny + b * nx + e for a in dz for b in dy for e in (-1, 0)]
-            assert lens[c] == len(left) + len(mid) + len(right)
-            assert got["pool"][got["pat_off"][c]:got["pat_off"][c + 1]].tolist() == left + mid + right
+            # the row on the right face holds the list of the row on the left face moved by -1: the same
+            # stored list, shift -1 (bits 9..15 of row_pat = 127)
+            assert [r - right[0] for r in right] == [l - left[0] for l in left] and right[0] - left[0] == -1
+            assert lens[c] == len(left) + len(mid)
+            assert got["pool"][got["pat_off"][c]:got["pat_off"][c + 1]].tolist() == left + mid
             rp = got["row_pat"][32 * c:32 * c + 32]
-            assert rp[0] == 0 and np.all(rp[1:31] == len(left)) and rp[31] == len(left) + len(mid)
+            assert rp[0] == 0 and np.all(rp[1:31] == len(left)) and rp[31] == (127 << 9)
 
 
 @pytest.mark.parametrize("cfg,scale", [(1, None), (2, {"nx": 24, "ny": 24, "nz": 24}),
@@ -578,20 +634,34 @@ def test_row_patterns_reconstruct_columns_and_are_minimal(cfg, scale):
     part = oracle.partition(w.rowptr, colidx=w.colidx, ncols=w.ncols, itemsize=w.vals.dtype.itemsize)
     streams = set(part["stream_chunks"].tolist())
     L = np.diff(w.rowptr)
+    start, shift = oracle.pattern_start_shift(got["row_pat"])
     for c in range(got["pat_off"].size - 1):
         rows = range(32 * c, min(32 * c + 32, w.nrows))
-        pats = {tuple((w.colidx[w.rowptr[i]:w.rowptr[i + 1]] - i).tolist()) for i in rows if L[i]}
-        size = sum(len(p) for p in pats)
+        # the table built again, directly from the rule: a row takes the first stored list with its length,
+        # its shape (the list minus its first element) and a shift within [-64, 63], else stores its own
+        stored, where, expect = [], 0, {}
+        for i in rows:
+            if not L[i]:
+                continue
+            lst = (w.colidx[w.rowptr[i]:w.rowptr[i + 1]].astype(np.int64) - i).tolist()
+            for at, other in stored:
+                if len(other) == len(lst) and -64 <= lst[0] - other[0] <= 63 and \
+                        [a - lst[0] for a in lst] == [a - other[0] for a in other]:
+                    expect[i] = (at, lst[0] - other[0])
+                    break
+            else:
+                stored.append((where, lst))
+                expect[i] = (where, 0)
+                where += len(lst)
+        size = where
         entries = int(w.rowptr[rows[-1] + 1] - w.rowptr[rows[0]])
-        fits = (c in streams and len(pats) <= 8 and size <= 512 and 2 * size <= entries
+        fits = (c in streams and len(stored) <= 8 and size <= 512 and 2 * size <= entries
                 and max(L[i] for i in rows) <= 128)
         assert got["pat_off"][c + 1] - got["pat_off"][c] == (size if fits else 0), c
-        if fits:      # equal rows share a start, different rows do not
-            starts = {}
+        if fits:
+            assert got["pool"][got["pat_off"][c]:got["pat_off"][c + 1]].tolist() == sum((l for _, l in stored), [])
             for i in rows:
-                if L[i]:
-                    starts.setdefault(int(got["row_pat"][i]), set()).add(tuple((w.colidx[w.rowptr[i]:w.rowptr[i + 1]] - i).tolist()))
-            assert len(starts) == len(pats) and all(len(v) == 1 for v in starts.values())
+                assert (int(start[i]), int(shift[i])) == expect.get(i, (0, 0)), i
         else:
             assert not got["row_pat"][rows[0]:rows[-1] + 1].any()
     if cfg in (3, 4):         # random columns repeat nothing
