@@ -335,15 +335,22 @@ int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_e
  * bit for bit with a CPU reference).  Matrices of regular grids repeat the same list of
  * diagonals (column - row, in stored order) row after row; where the rows of a chunk share a
  * few such lists, lapis_spmv reads no column index per entry at all for that chunk.
- * For a stream chunk c (after the demotion above), going through its rows in ascending order,
- * every list not met before in the chunk is appended to the chunk's table, and row_pat[i] is
- * where the list of row i starts in that table (0 for empty rows).  The chunk is patterned if no
- * row has more than LAPIS_PATTERN_MAX_ROW entries, at most LAPIS_PATTERN_SLOTS lists were needed,
- * the table has at most LAPIS_PATTERN_TABLE diagonals and twice its length does not exceed the
- * chunk's entries; otherwise its table is empty and row_pat is 0 for its rows.
+ * For a stream chunk c (after the demotion above), going through its rows in ascending order:
+ * the list of a row is its diagonals in stored order, its shape that list minus its first
+ * element.  A row takes the first list stored so far (in order of insertion) that has its
+ * length and its shape and whose first diagonal differs from the row's by a shift in [-64, 63]
+ * (shift = the row's first diagonal - the stored one); a row that finds none appends its own
+ * list to the chunk's table (shift 0).  row_pat[i] = (where the taken list starts in the table)
+ * | ((shift & 127) << 9), 0 for empty rows.  Rows of a regular grid repeat one list with shift
+ * 0; the rows of the unknowns of one grid point (several unknowns per point) hold the same
+ * columns and share one stored list with shifts 0, -1, -2, ...  The chunk is patterned if no
+ * row has more than LAPIS_PATTERN_MAX_ROW entries, at most LAPIS_PATTERN_SLOTS lists were
+ * stored, the table has at most LAPIS_PATTERN_TABLE diagonals and twice its length does not
+ * exceed the chunk's entries; otherwise its table is empty and row_pat is 0 for its rows.
  * pat_off[0..C] (C = ceil(nrows / LAPIS_STREAM_ROWS)) is the exclusive scan of the table lengths
- * and pool holds the tables back to back, so that for a row i of a patterned chunk c
- *   colidx[rowptr[i] + k] == i + pool[pat_off[c] + row_pat[i] + k].
+ * and pool holds the tables back to back, so that for a row i of a patterned chunk c, with
+ * start = row_pat[i] & 511 and shift = bits 9..15 of row_pat[i] as a signed number,
+ *   colidx[rowptr[i] + k] == i + shift + pool[pat_off[c] + start + k].
  * The structure is kept (*enabled = 1) only if the patterned chunks hold at least half of the
  * matrix's entries; *pattern_entries is that count and *pool_size = pat_off[C] either way.
  *   h_pat_off HOST int32[C + 1]    h_row_pat HOST uint16[nrows]    h_pool HOST int32[*pool_size]

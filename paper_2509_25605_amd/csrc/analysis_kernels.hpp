@@ -422,15 +422,20 @@ __global__ __launch_bounds__(kBlock) void col16_fill_kernel(int32_t nrows, int32
     }
 }
 
-// Level 1c, one wavefront per chunk: the row patterns of a stream chunk.  The pattern of a
-// non-empty row i is the list of its diagonals colidx[j] - i in stored order; going through the
-// rows in ascending order every pattern not met before in the chunk is appended to the chunk's
-// table (LDS here), and row_pat[i] = where the pattern of row i starts in it (0 for empty rows).
+// Level 1c, one wavefront per chunk: the row patterns of a stream chunk.  The list of a
+// non-empty row i is its diagonals colidx[j] - i in stored order, its shape that list minus its
+// first element.  Going through the rows in ascending order, a row takes the first stored list
+// (in order of insertion) with its length, its shape and a shift = (its first diagonal) - (the
+// stored list's first diagonal) in [-64, 63]; a row that finds none appends its own list to the
+// chunk's table (LDS here), shift 0.  row_pat[i] = (where the taken list starts in the table) |
+// ((shift & 127) << 9), 0 for empty rows.
 // pat_len[c] = length of the table if no row has more than kPatternMaxRow entries, at most
 // kPatternSlots patterns were needed, the table has at most kPatternTableSize diagonals and
 // twice its length does not exceed the chunk's entries; otherwise 0 (and row_pat 0 for the
 // chunk's rows).  Chunks that do not stream get 0 as well.  chunk_rows divides 64.
 constexpr int kPatternMaxRow = 128, kPatternSlots = 8, kPatternTableSize = 512;
+constexpr int kPatternShiftBit = 9, kPatternShiftMax = 63;     // row_pat: start in bits 0..8, shift (-64..63) in bits 9..15
+static_assert(kPatternTableSize == 1 << kPatternShiftBit, "a start fits below the shift bits");
 __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                                 const int32_t *__restrict__ chunk_flag,
                                                                 const int32_t *__restrict__ rowptr,
@@ -483,13 +488,17 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
         const int32_t len = __builtin_amdgcn_readlane(len_mine, t * per_row);
         const int32_t d0 = lane < len ? colidx[b + lane] - (int32_t)r : 0;
         const int32_t d1 = lane + kWave < len ? colidx[b + kWave + lane] - (int32_t)r : 0;
-        int32_t found = -1;
+        const int32_t head = __builtin_amdgcn_readfirstlane(d0);          // the row's first diagonal (len >= 1)
+        int32_t found = -1, found_shift = 0;
 #pragma unroll
         for (int p = 0; p < kPatternSlots; ++p) {
             if (found < 0 && p < P && p_len[p] == len) {
-                const bool same = (lane >= len || tab[p_start[p] + lane] == d0) &&
-                                  (lane + kWave >= len || tab[p_start[p] + kWave + lane] == d1);
-                if (__ballot(!same) == 0) found = p_start[p];
+                const int32_t shift = head - tab[p_start[p]];              // uniform
+                if (shift >= -kPatternShiftMax - 1 && shift <= kPatternShiftMax) {
+                    const bool same = (lane >= len || tab[p_start[p] + lane] + shift == d0) &&
+                                      (lane + kWave >= len || tab[p_start[p] + kWave + lane] + shift == d1);
+                    if (__ballot(!same) == 0) { found = p_start[p]; found_shift = shift; }
+                }
             }
         }
         if (found < 0) {
@@ -506,7 +515,7 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
             P += 1;
             L += len;
         }
-        if (lane == t) mine = found;
+        if (lane == t) mine = found | ((found_shift & (2 * kPatternShiftMax + 1)) << kPatternShiftBit);
     }
     // lane r < chunk_rows answers for row first + r: a row that repeats its predecessor takes the
     // answer of the nearest searched row below it; empty rows keep 0
@@ -523,8 +532,9 @@ __global__ __launch_bounds__(kBlock) void chunk_patterns_kernel(int32_t nrows, i
     if (lane < chunk_rows && first + lane < last) row_pat[first + lane] = (uint16_t)mine;
 }
 
-// The tables of the patterned chunks back to back: pool[pat_off[c] + row_pat[i] + k] = diagonal
-// of the k-th entry of row i.  One wavefront per chunk; chunk_rows <= 64.
+// The tables of the patterned chunks back to back: pool[pat_off[c] + start + k] = diagonal of the
+// k-th entry of the first row of the chunk whose row_pat has that start (the row that stored the
+// list: its shift is 0).  One wavefront per chunk; chunk_rows <= 64.
 __global__ __launch_bounds__(kBlock) void pattern_pool_kernel(int32_t nrows, int32_t num_chunks, int32_t chunk_rows,
                                                               const int32_t *__restrict__ rowptr,
                                                               const int32_t *__restrict__ colidx,
@@ -543,7 +553,7 @@ __global__ __launch_bounds__(kBlock) void pattern_pool_kernel(int32_t nrows, int
     const bool has_row = lane < chunk_rows && r < nrows;
     const int32_t b = has_row ? rowptr[r] : 0;
     const int32_t len = has_row ? rowptr[r + 1] - b : 0;
-    const int32_t start = has_row ? (int32_t)row_pat[r] : 0;
+    const int32_t start = has_row ? (int32_t)row_pat[r] & (kPatternTableSize - 1) : 0;    // without the shift bits
     bool writer = len > 0;
     for (int t = 0; t < chunk_rows; ++t) {             // uniform
         const int32_t t_start = __builtin_amdgcn_readlane(start, t);

@@ -218,9 +218,9 @@ constexpr int kShareMaxOdd = 4;
 
 // What a wavefront knows about its chunk after the first round trip; lane r < 32 holds row r.
 struct ShareRows {
-    int32_t my_rp, my_len, my_pat;     // lane r: first entry, length and pattern start of row r (0 past the end)
+    int32_t my_rp, my_len, my_pat;     // lane r: first entry, length and packed pattern (start | shift << 9) of row r (0 past the end)
     int32_t base, end, w0;             // the chunk's entries [base, end), w0 = base rounded down to 8
-    int32_t ref_len, ref_pat;          // the reference list: length, start in the chunk's table
+    int32_t ref_len, ref_pat;          // the reference list: length, packed pattern of the row it is taken from
     uint64_t odd;                      // rows (below nrows) whose list is not the reference list
     bool fits;                         // (a), (c), (d) and ref_len in 1..64
 };
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kBlock) void spmm_share_flag_kernel(
         const ShareRows c = share_rows_setup(lane, nrows, row0, rowptr, pats.row_pat, pat_len);
         if (c.fits) {                                                      // uniform
             const bool in_ref = lane < c.ref_len;
-            const int32_t pstar = in_ref ? pats.pool[pat_begin + c.ref_pat + lane] : 0;
+            const int32_t pstar = in_ref ? pats.pool[pat_begin + pattern_start(c.ref_pat) + lane] : 0;   // (a shift moves all alike)
             const int32_t before = __builtin_amdgcn_update_dpp(0, pstar, 0x138, 0xf, 0xf, false);   // lane t gets lane t - 1
             const uint64_t descending = __builtin_amdgcn_ballot_w64(in_ref && lane > 0 && pstar <= before);
             if (descending == 0) result = 1;
@@ -322,7 +322,7 @@ void spmm_shared_kernel(
     const uint32_t row_bytes = (uint32_t)(ldx * (int64_t)sizeof(T));
     // round trip 2: the values into LDS, the reference list one diagonal per lane
     const bool in_ref = lane < c.ref_len;
-    const int32_t pstar = in_ref ? pats.pool[pat_begin + c.ref_pat + lane] : 0;
+    const int32_t pstar = in_ref ? pats.pool[pat_begin + pattern_start(c.ref_pat) + lane] + pattern_shift(c.ref_pat) : 0;
     stream_values_to_lds<T>(vals, w0, c.end, nnz & ~3, lane, s_val);           // ends with the wavefront's fence
     // pieces: every run of consecutive diagonals is cut into pieces of 3 and a rest of 1 or 2; lane t
     // knows whether a piece starts at diagonal t and how long it is
@@ -354,9 +354,11 @@ void spmm_shared_kernel(
     for (uint64_t left = c.odd; left != 0; left &= left - 1) {               // uniform
         const int row = (int)__builtin_ctzll(left);
         const int32_t rb = __builtin_amdgcn_readlane(c.my_rp, row), n = __builtin_amdgcn_readlane(c.my_len, row);
-        const int32_t *pat = pats.pool + pat_begin + __builtin_amdgcn_readlane(c.my_pat, row);
+        const int32_t packed = __builtin_amdgcn_readlane(c.my_pat, row);
+        const int32_t *pat = pats.pool + pat_begin + pattern_start(packed);
         const T *sv = s_val + (rb - w0);
         const int64_t me = row0 + row;
+        const int64_t me_x = me + pattern_shift(packed);                       // its columns: me_x + pat[u]
         T sum[VEC];
 #pragma unroll
         for (int q = 0; q < VEC; ++q) sum[q] = T(0);
@@ -373,7 +375,7 @@ void spmm_shared_kernel(
             }
 #pragma unroll
             for (int t = 0; t < kOddBatch; ++t) {
-                if (active) xo[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (me + dd[t]) * ldx + col);
+                if (active) xo[t] = *reinterpret_cast<const Pack<T, VEC> *>(X + (me_x + dd[t]) * ldx + col);
                 else {
 #pragma unroll
                     for (int q = 0; q < VEC; ++q) xo[t].v[q] = T(0);

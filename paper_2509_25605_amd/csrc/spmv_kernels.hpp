@@ -503,12 +503,17 @@ __device__ __forceinline__ T stream_share(const IDX *sc, const T *sv, int my_n, 
 // mix, 32-bit columns in the window.  RAW == kColsPattern: every chunk is patterned
 // (pat_off[chunk + 1] > pat_off[chunk]): only the values are streamed, the chunk's table of
 // diagonals (pool + pat_off[chunk]) takes the window's place in LDS and row_pat[row] says where
-// the row's list starts in it.  RAW == kColsPatternOr16: patterned, else narrow or framed.
+// the row's list starts in it and by how much it is shifted.  RAW == kColsPatternOr16: patterned, else narrow or framed.
 struct StreamPatterns {
     const int32_t *__restrict__ pat_off;     // [num_chunks + 1]
-    const uint16_t *__restrict__ row_pat;    // [nrows]
+    const uint16_t *__restrict__ row_pat;    // [nrows] start of the row's list in its chunk's table | shift << 9
     const int32_t *__restrict__ pool;
 };
+// row_pat[i] packs where the row's list starts in the chunk's table (bits 0..8) and the shift
+// (-64..63, bits 9..15) that turns the stored list into the row's own:
+// column k of row i = i + shift + table[start + k].
+__device__ __forceinline__ int32_t pattern_start(int32_t packed) { return packed & 511; }
+__device__ __forceinline__ int32_t pattern_shift(int32_t packed) { return (int32_t)(int16_t)(uint16_t)packed >> 9; }
 
 template <typename T, int G, bool XCD_REMAP, int RAW = kCols32, int UNR = kStreamUnroll, int GW = 1>  // UNR must be 16
 __global__ __launch_bounds__(kWave * GW) void spmv_stream_kernel(
@@ -549,11 +554,13 @@ __global__ __launch_bounds__(kWave * GW) void spmv_stream_kernel(
     const bool row_ok = row < nrows;
     const int64_t row_c = row_ok ? row : nrows - 1;
     const int32_t p0 = rowptr[row_c], p1 = rowptr[row_c + 1];
-    int32_t pat_begin = 0, pat_len = 0, pat_start = 0;
+    int32_t pat_begin = 0, pat_len = 0, pat_start = 0, pat_shift = 0;
     if constexpr (kHasPatterns) {
         pat_begin = pats.pat_off[chunk];
         pat_len = pats.pat_off[chunk + 1] - pat_begin;                  // wave-uniform
-        pat_start = pats.row_pat[row_c];
+        const int32_t packed = pats.row_pat[row_c];
+        pat_start = pattern_start(packed);
+        pat_shift = pattern_shift(packed);
     }
     const bool patterned = RAW == kColsPattern || (RAW == kColsPatternOr16 && pat_len > 0);
     int32_t cbase = -1;                                                 // wave-uniform
@@ -602,7 +609,7 @@ __global__ __launch_bounds__(kWave * GW) void spmv_stream_kernel(
             // the diagonals of the row's pattern from where this window cuts into the row; idle
             // lanes read the table's first diagonal and gather x[0]
             const int32_t *sc = s_pat + (my_n > 0 ? pat_start + (ub + w0 - rb) + sub : 0);
-            const T *xb = my_n > 0 ? x + row_c : x - s_pat[0];
+            const T *xb = my_n > 0 ? x + (row_c + pat_shift) : x - s_pat[0];
             s = stream_share<T, G, int32_t, kCols32, UNR>(sc, s_val + first, my_n, xb, nullptr, 0, s);
         } else {
             const T *xb = RAW == kColsNarrow ? x + cbase : x;

@@ -463,6 +463,41 @@ def test_row_patterns_every_chunk_patterned(kind, dtype):
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("dof,grid", [(3, (9, 7, 5)), (2, (17, 6, 4)), (4, (8, 5, 5)), (6, (6, 5, 3))])
+def test_row_patterns_with_shifts_block_rows(dof, grid, dtype):
+    """Several unknowns per grid point: the rows of a point hold the same columns, i.e. one list of
+    diagonals moved by 0, -1, -2, ...: the chunk stores the list once and every row carries its shift.
+    Structure bit for bit against the oracle, SpMV and SpMM element by element."""
+    nx, ny, nz = grid
+    say(f"block rows: {dof} unknowns per point, grid {nx}x{ny}x{nz} {np.dtype(dtype).name}")
+    rowptr, colidx, vals = gen.block_stencil(nx, ny, nz, dof, 61)
+    vals = vals.astype(dtype)
+    n = nx * ny * nz * dof
+    x = gen.uniform(62, gen.STREAM_X, n).astype(dtype)
+    y0 = gen.uniform(62, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        pats = dev.patterns()
+        if dof * 27 <= 128:                                     # rows of at most 128 entries can be patterned
+            assert pats["enabled"]
+            start, shift = oracle.pattern_start_shift(pats["row_pat"])
+            assert shift.min() < 0                              # rows that take a stored list moved to the left
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, -1.25, 0.75, y0, what="alpha=-1.25 beta=0.75")
+        X = gen.uniform(63, gen.STREAM_X, n * 16).astype(dtype).reshape(n, 16)
+        check_spmm(dev, rowptr, colidx, vals, X, what="spmm k=16")
+        for j in (0, n // 2, n - 1):                             # a non-finite x[j] reaches exactly the rows with column j
+            xi = x.copy()
+            xi[j] = np.inf
+            ref, _ = oracle.spmv(rowptr, colidx, vals, xi)
+            got = dev.spmv(xi)
+            assert np.array_equal(np.isfinite(got), np.isfinite(ref))
+    finally:
+        dev.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("others", ["narrow", "framed", "plain", "few_patterned"])
 def test_row_patterns_beside_other_chunks(others, dtype):
     """Patterned chunks in one launch with chunks that have 16-bit codes, and matrices where a
