@@ -360,6 +360,34 @@ int lapis_csr_copy_index16(const lapis_csr_t *A, int *enabled, int64_t *narrow_e
 int lapis_csr_copy_patterns(const lapis_csr_t *A, int *enabled, int64_t *pattern_entries, int64_t *pool_size,
                             int32_t *h_pat_off, uint16_t *h_row_pat, int32_t *h_pool);
 
+/*
+ * lapis_csr_copy_share_classes - how lapis_spmm treats each stream chunk (an implementation choice of
+ * this library, exposed for comparison with a CPU reference).  On grid matrices neighbouring rows
+ * need neighbouring rows of X; chunks whose rows say so through their row patterns get kernels that
+ * load a row of X once for several matrix rows.  h_class[c], c < C = ceil(nrows / LAPIS_STREAM_ROWS):
+ *   0  c is not a stream chunk;   LAPIS_SHARE_NONE  a stream chunk without such sharing;
+ *   LAPIS_SHARE_PLAIN, LAPIS_SHARE_BLOCK3, LAPIS_SHARE_BLOCK2 as follows.
+ * Of a patterned chunk take the lengths of its 32 rows (0 past the end of the matrix) and, of the first
+ * row of the greatest length L, the stored list it uses (its start in the chunk's table) and its shift:
+ * the reference.  A row is regular if it has length L and the reference's start - and, for PLAIN, the
+ * reference's shift.  The chunk qualifies if L > 0, the stored list ascends strictly and at most
+ * LAPIS_SHARE_MAX_ODD rows of the matrix in it are not regular.
+ *   PLAIN: it qualifies with shifts compared, L <= 64, and (last entry of the chunk) - (its first entry
+ *     rounded down to a multiple of 8) + 64 <= 1024;
+ *   otherwise BLOCK3 or BLOCK2: it qualifies with shifts ignored, L <= 128, and with v = (row's place in
+ *     the chunk) + (its shift), the regular rows of every aligned group of four rows have v equal to the
+ *     group's least v or to that plus D, with the same D = 3 (BLOCK3) or 2 (BLOCK2) in the whole chunk and
+ *     at least one row at D (rows of grid points with three or two unknowns each).
+ * *enabled = 1 if the classes were computed (row patterns enabled and at least one stream chunk), else
+ * h_class is left alone.  h_class HOST int32[C], may be NULL.  Synchronises the device.
+ */
+#define LAPIS_SHARE_PLAIN   1
+#define LAPIS_SHARE_NONE    2
+#define LAPIS_SHARE_BLOCK3  3
+#define LAPIS_SHARE_BLOCK2  4
+#define LAPIS_SHARE_MAX_ODD 4
+int lapis_csr_copy_share_classes(const lapis_csr_t *A, int *enabled, int32_t *h_class);
+
 /* max |column - row| over the matrix's entries, found by lapis_csr_create; lapis_spmm uses it to
  * decide how workgroups are dealt to the 8 XCDs (band-wide windows of X rows that overflow one
  * L2 are shared by all 8). */

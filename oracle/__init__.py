@@ -7,7 +7,9 @@ serial) and marshals NumPy arrays.  Every product, sum and index structure is co
 C file; what this module adds in Python is the geometry of the column split (split_geometry:
 two integer divisions), the choice of the rows that are split (split_partition: rows of the
 last two bins by length, the lengths of the virtual rows as differences of the cut table) and
-the "enabled" rules (a structure is kept when its chunks hold at least half of the entries).
+the "enabled" rules (a structure is kept when its chunks hold at least half of the entries) and
+share_classes (which kernel family the product with a block of vectors may use for a chunk: a
+decision about speed that no result depends on, read off the partition and the row patterns).
 """
 from __future__ import annotations
 
@@ -297,6 +299,61 @@ def pattern_start_shift(row_pat):
     rp = np.asarray(row_pat).astype(np.int64)
     shift = rp >> 9
     return rp & 511, np.where(shift >= 64, shift - 128, shift)
+
+
+SHARE_PLAIN, SHARE_NONE, SHARE_BLOCK3, SHARE_BLOCK2 = 1, 2, 3, 4
+SHARE_MAX_ODD = 4
+
+
+def share_classes(rowptr, part, pats, stream_rows=STREAM_ROWS, max_odd=SHARE_MAX_ODD, window=1024, wave=WAVE,
+                  only=None):
+    """The class of every chunk for the product with a block of vectors: 0 not a stream chunk, SHARE_NONE,
+    SHARE_PLAIN (neighbouring rows use neighbouring rows of X), SHARE_BLOCK3 / SHARE_BLOCK2 (so do the rows
+    of grid points with 3 / 2 unknowns), from the partition `part` and the row patterns `pats` as the
+    library's header defines them; None when the patterns are not enabled or no chunk streams.  Written out
+    chunk by chunk, row by row; with `only` (chunk numbers) the other chunks are left at -1."""
+    n = rowptr.size - 1
+    nchunks = (n + stream_rows - 1) // stream_rows
+    if not pats["enabled"] or part["stream_chunks"].size == 0:
+        return None
+    start, shift = pattern_start_shift(pats["row_pat"])
+    out = np.zeros(nchunks, dtype=np.int32)
+    streams = set(int(c) for c in part["stream_chunks"])
+    if only is not None:
+        out[:] = -1
+        out[[c for c in only if c not in streams]] = 0
+        streams &= set(int(c) for c in only)
+    for c in sorted(streams):
+        out[c] = SHARE_NONE
+        rows = list(range(c * stream_rows, min((c + 1) * stream_rows, n)))
+        table = pats["pool"][pats["pat_off"][c]:pats["pat_off"][c + 1]]
+        length = [int(rowptr[i + 1] - rowptr[i]) for i in rows]
+        L = max(length)
+        if table.size == 0 or L == 0:
+            continue
+        ref = rows[length.index(L)]                                   # the first row of the greatest length
+        stored = [int(d) for d in table[start[ref]:start[ref] + L]]
+        if any(b <= a for a, b in zip(stored, stored[1:])):
+            continue
+        same_list = [length[j] == L and start[i] == start[ref] for j, i in enumerate(rows)]
+        same_both = [same_list[j] and shift[i] == shift[ref] for j, i in enumerate(rows)]
+        first_entry, last_entry = int(rowptr[rows[0]]), int(rowptr[rows[-1] + 1])
+        if (same_both.count(False) <= max_odd and L <= wave
+                and last_entry - first_entry // 8 * 8 + wave <= window):
+            out[c] = SHARE_PLAIN
+            continue
+        if same_list.count(False) > max_odd or L > 2 * wave:
+            continue
+        steps = set()
+        for g in range(0, stream_rows, 4):
+            v = [j + int(shift[rows[j]]) for j in range(g, min(g + 4, len(rows))) if same_list[j]]
+            steps |= {x - min(v) for x in v}
+        steps.discard(0)
+        if steps == {3}:
+            out[c] = SHARE_BLOCK3
+        elif steps == {2}:
+            out[c] = SHARE_BLOCK2
+    return out
 
 
 def split_geometry(ncols, itemsize, block_bytes=SPLIT_BLOCK_BYTES, max_blocks=SPLIT_MAX_BLOCKS):

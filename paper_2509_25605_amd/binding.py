@@ -22,7 +22,7 @@ EXPORTS = [
     "lapis_csr_create", "lapis_spmv", "lapis_spmv_paper_shape", "lapis_paper_vector_length", "lapis_spmm", "lapis_csr_destroy",
     "lapis_csr_partition_sizes", "lapis_csr_copy_partition", "lapis_csr_split_sizes",
     "lapis_csr_copy_split", "lapis_csr_half_bandwidth", "lapis_partition_constants",
-    "lapis_csr_copy_index16", "lapis_csr_copy_patterns", "lapis_csr_huge_sizes", "lapis_csr_copy_huge",
+    "lapis_csr_copy_index16", "lapis_csr_copy_patterns", "lapis_csr_copy_share_classes", "lapis_csr_huge_sizes", "lapis_csr_copy_huge",
     "lapis_spmv_transpose", "lapis_csr_create_transpose", "lapis_csr_shape", "lapis_csr_copy_arrays",
     "lapis_dualview_create", "lapis_dualview_subview", "lapis_dualview_host", "lapis_dualview_device",
     "lapis_dualview_modify_host", "lapis_dualview_modify_device", "lapis_dualview_sync_device",
@@ -66,6 +66,7 @@ def load() -> ctypes.CDLL:
         lib.lapis_csr_copy_huge.argtypes = [p, p, p, p]
         lib.lapis_csr_copy_index16.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), p, p, p]
         lib.lapis_csr_copy_patterns.argtypes = [p, ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(i64), p, p, p]
+        lib.lapis_csr_copy_share_classes.argtypes = [p, ctypes.POINTER(i32), p]
         lib.lapis_csr_create_transpose.argtypes = [ctypes.POINTER(p), p, p]
         lib.lapis_csr_shape.argtypes = [p] + [ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(i32)]
         lib.lapis_csr_copy_arrays.argtypes = [p, p, p, p]
@@ -163,6 +164,18 @@ def lapis_csr_copy_index16(A):
         out["col16"] = np.empty(z, dtype=np.uint16)
         _check(load().lapis_csr_copy_index16(A, None, None, None, out["chunk_base"].ctypes.data,
                                              out["frame_table"].ctypes.data, out["col16"].ctypes.data))
+    return out
+
+
+def lapis_csr_copy_share_classes(A):
+    """int32 array of the share class of every chunk of a handle, or None when the classes were not computed."""
+    n, _, _, _ = lapis_csr_shape(A)
+    on = ctypes.c_int()
+    _check(load().lapis_csr_copy_share_classes(A, ctypes.byref(on), None))
+    if not on.value:
+        return None
+    out = np.zeros((n + 31) // 32, dtype=np.int32)
+    _check(load().lapis_csr_copy_share_classes(A, ctypes.byref(on), out.ctypes.data_as(ctypes.c_void_p)))
     return out
 
 

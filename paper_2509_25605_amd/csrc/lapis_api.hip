@@ -84,7 +84,7 @@ struct lapis_csr {
     // SpMM: the stream chunks whose neighbouring rows share rows of X (spmm_share_flag_kernel), then the others
     int32_t *d_spmm_chunks = nullptr;    // [num_stream]; null when no chunk shares rows
     int32_t *d_share_flag = nullptr;     // [num_chunks] 1: shares rows, 2: another stream chunk, 0: not a stream chunk
-    int64_t num_share = 0;               // length of the first list
+    int32_t h_spmm_offset[kChunkClasses + 1] = {0};   // lists of the share classes 1..4 (kSharePlain, kShareNone, kShareBlock3, kShareBlock2)
     // level 2: bins over the rows outside stream chunks
     BinnedSet rows;
     // column split of the rows of bins 8-9 into virtual rows (num_blocks == 0: off)
@@ -469,14 +469,14 @@ int run_analysis(lapis_csr *A, hipStream_t stream)
                 chunk_compact_kernel<<<dim3((uint32_t)compact_blocks), dim3(kCompactBlock), 0, stream>>>(
                     num_chunks, A->d_share_flag, class_hist.as<int32_t>(), A->d_spmm_chunks);
                 LAPIS_HIP(hipGetLastError());
-                int32_t h_share[kChunkClasses + 1] = {0};
-                if (int rc = read_back(h_share, share_offsets.p, sizeof(h_share), stream)) return rc;
-                A->num_share = h_share[1];
-                if (A->num_share == 0) {
+                static_assert(kSharePlain == 1 && kShareNone == 2 && kShareBlock3 == 3 && kShareBlock2 == 4 && kChunkClasses == 4,
+                              "the share classes are the four classes of the compaction");
+                static_assert(kSharePlain == LAPIS_SHARE_PLAIN && kShareNone == LAPIS_SHARE_NONE && kShareBlock3 == LAPIS_SHARE_BLOCK3 &&
+                              kShareBlock2 == LAPIS_SHARE_BLOCK2 && kShareMaxOdd == LAPIS_SHARE_MAX_ODD, "as the header says");
+                if (int rc = read_back(A->h_spmm_offset, share_offsets.p, sizeof(A->h_spmm_offset), stream)) return rc;
+                if (A->h_spmm_offset[kShareNone] - A->h_spmm_offset[kShareNone - 1] == num_stream) {   // nothing shares
                     (void)hipFree(A->d_spmm_chunks);
-                    (void)hipFree(A->d_share_flag);
                     A->d_spmm_chunks = nullptr;
-                    A->d_share_flag = nullptr;
                 }
             }
             LAPIS_HIP(hipStreamSynchronize(stream));       // pat_len and tile_sums are released on return
@@ -887,39 +887,54 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
         for (int cls = 1; cls <= kStreamClasses; ++cls)
             all16 = all16 && (A->class_all16[cls - 1] || A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]);
         // chunks whose neighbouring rows share rows of X go to the kernel that loads those rows once per
-        // R rows (8 or 16 lanes per row of X; a row of X shorter than 64 MiB); the other chunks follow
-        uint32_t n_share = 0;
-        if constexpr (kStreamLanes >= 8) {
-            if (A->d_spmm_chunks && ldx * (int64_t)sizeof(T) < ((int64_t)1 << 26)) n_share = (uint32_t)A->num_share;
-        }
-        const uint32_t n_plain = chunks - n_share;
-        // When every chunk of the matrix streams and nearly all of them share rows (all but a few at the
-        // ends of the matrix), the kernel is launched over all chunks in the block-cyclic order above and
-        // skips the others by their flag: no list to read before the first load, windows still shared.
-        const bool share_by_flag = !list && (uint64_t)n_share * 10 >= (uint64_t)chunks * 9;
-        const uint32_t share_count = share_by_flag ? chunks : n_share;
-        const uint32_t share_padded = share_by_flag ? padded : (n_share + kXcds - 1) / kXcds * kXcds;
-        const int32_t *share_list = share_by_flag ? nullptr : A->d_spmm_chunks;
-        const int32_t *share_flag = (share_by_flag && n_share != chunks) ? A->d_share_flag : nullptr;
-        const int32_t *plain_list = n_share ? A->d_spmm_chunks + n_share : list;
-        const uint32_t plain_padded = n_share ? (n_plain + kXcds - 1) / kXcds * kXcds : padded;
-        const uint32_t plain_xcd_block = n_share ? 0 : xcd_block;
-        for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
+        // R rows (8 or 16 lanes per row of X; a row of X shorter than 16 MiB), by share class; the others follow
+        bool share_ok = false;
+        if constexpr (kStreamLanes >= 8) share_ok = A->d_spmm_chunks && ldx * (int64_t)sizeof(T) < ((int64_t)1 << 24);
+        const StreamPatterns pats{A->d_pat_off, A->d_row_pat, A->d_pat_pool};
+        // One share class over columns [c0, ...): when every chunk of the matrix streams and nearly all of them
+        // are of this class (all but a few at the ends of the matrix), the kernel is launched over all chunks in
+        // the block-cyclic order above and skips the others by their flag: no list to read before the first
+        // load, windows of X still shared by the XCDs.  Otherwise over the class's list.
+        auto launch_share = [&](auto delta_tag, int32_t cls, int64_t c0) {
+            constexpr int DELTA = decltype(delta_tag)::value;
+            const uint32_t first = (uint32_t)A->h_spmm_offset[cls - 1], n = (uint32_t)A->h_spmm_offset[cls] - first;
+            if (n == 0) return;
+            const bool by_flag = !list && (uint64_t)n * 10 >= (uint64_t)chunks * 9;
+            const uint32_t count = by_flag ? chunks : n;
+            const uint32_t grid = by_flag ? padded : (n + kXcds - 1) / kXcds * kXcds;
+            const int32_t *ids = by_flag ? nullptr : A->d_spmm_chunks + first;
+            const int32_t *flags = (by_flag && n != chunks) ? A->d_share_flag : nullptr;
             if constexpr (kStreamLanes >= 8) {
-                if (n_share)
-                    spmm_shared_kernel<T, VEC, kStreamLanes, true><<<dim3(share_padded), dim3(kWave), 0, stream>>>(
-                        (int32_t)A->nrows, (int32_t)A->nnz, share_count, share_padded, share_list, share_flag,
-                        A->rowptr, share_by_flag ? xcd_block : 0u, vals, k, c0, X, ldx, Y, ldy, a, b,
-                        StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool}, (int32_t)A->ncols);
+                if constexpr (DELTA == 0) {
+                    spmm_shared_kernel<T, VEC, kStreamLanes, true><<<dim3(grid), dim3(kWave), 0, stream>>>(
+                        (int32_t)A->nrows, (int32_t)A->nnz, count, grid, ids, flags, A->rowptr, by_flag ? xcd_block : 0u,
+                        vals, k, c0, X, ldx, Y, ldy, a, b, pats, (int32_t)A->ncols);
+                } else {   // block rows: 8 lanes per row of X, so a block of 16 lanes is two launches
+                    for (int64_t c1 = c0; c1 < k && c1 < c0 + (int64_t)kStreamLanes * VEC; c1 += 8 * VEC)
+                        spmm_block_shared_kernel<T, VEC, true, DELTA, kShareBlockSeg><<<dim3(grid), dim3(kWave), 0, stream>>>(
+                            (int32_t)A->nrows, count, grid, ids, flags, cls, A->rowptr, by_flag ? xcd_block : 0u,
+                            vals, k, c1, X, ldx, Y, ldy, a, b, pats, (int32_t)A->ncols);
+                }
             }
-            if (n_plain == 0) continue;
+        };
+        const uint32_t n_none = share_ok ? (uint32_t)(A->h_spmm_offset[kShareNone] - A->h_spmm_offset[kShareNone - 1]) : chunks;
+        const int32_t *none_list = share_ok ? A->d_spmm_chunks + A->h_spmm_offset[kShareNone - 1] : list;
+        const uint32_t none_padded = share_ok ? (n_none + kXcds - 1) / kXcds * kXcds : padded;
+        const uint32_t none_xcd_block = share_ok ? 0 : xcd_block;
+        for (int64_t c0 = 0; c0 < k; c0 += kStreamLanes * VEC) {
+            if (share_ok) {
+                launch_share(std::integral_constant<int, 0>(), kSharePlain, c0);
+                launch_share(std::integral_constant<int, 3>(), kShareBlock3, c0);
+                launch_share(std::integral_constant<int, 2>(), kShareBlock2, c0);
+            }
+            if (n_none == 0) continue;
             if (all16)
-                spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(plain_padded), dim3(kWave), 0, stream>>>(
-                    (int32_t)A->nrows, (int32_t)A->nnz, n_plain, plain_padded, plain_list, A->rowptr, plain_xcd_block,
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(none_padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, n_none, none_padded, none_list, A->rowptr, none_xcd_block,
                     A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
             else
-                spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(plain_padded), dim3(kWave), 0, stream>>>(
-                    (int32_t)A->nrows, (int32_t)A->nnz, n_plain, plain_padded, plain_list, A->rowptr, plain_xcd_block,
+                spmm_stream_kernel<T, VEC, kStreamLanes, true, false><<<dim3(none_padded), dim3(kWave), 0, stream>>>(
+                    (int32_t)A->nrows, (int32_t)A->nnz, n_none, none_padded, none_list, A->rowptr, none_xcd_block,
                     A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
         }
     }
@@ -1271,6 +1286,17 @@ int lapis_csr_copy_patterns(const lapis_csr_t *A, int *enabled, int64_t *pattern
         LAPIS_HIP(hipMemcpy(h_row_pat, A->d_row_pat, sizeof(uint16_t) * (size_t)A->nrows, hipMemcpyDeviceToHost));
     if (h_pool && A->pattern_pool > 0)
         LAPIS_HIP(hipMemcpy(h_pool, A->d_pat_pool, sizeof(int32_t) * (size_t)A->pattern_pool, hipMemcpyDeviceToHost));
+    return LAPIS_OK;
+}
+
+int lapis_csr_copy_share_classes(const lapis_csr_t *A, int *enabled, int32_t *h_class)
+{
+    if (!A) return fail(LAPIS_ERR_INVALID_ARG, "handle is NULL");
+    const bool on = A->d_share_flag != nullptr;
+    if (enabled) *enabled = on ? 1 : 0;
+    if (!on || !h_class || A->num_chunks == 0) return LAPIS_OK;
+    LAPIS_HIP(hipDeviceSynchronize());
+    LAPIS_HIP(hipMemcpy(h_class, A->d_share_flag, sizeof(int32_t) * (size_t)A->num_chunks, hipMemcpyDeviceToHost));
     return LAPIS_OK;
 }
 

@@ -75,6 +75,10 @@ class CsrMatrix:
         """The row patterns of the stream chunks (see lapis_csr_copy_patterns)."""
         return B.lapis_csr_copy_patterns(self.handle)
 
+    def share_classes(self):
+        """How lapis_spmm treats every chunk (see lapis_csr_copy_share_classes); None when not computed."""
+        return B.lapis_csr_copy_share_classes(self.handle)
+
     def partition(self):
         return B.lapis_csr_copy_partition(self.handle)
 

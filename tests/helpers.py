@@ -103,6 +103,9 @@ class DeviceCsr:
     def patterns(self):
         return self.mat.patterns()
 
+    def share_classes(self):
+        return self.mat.share_classes()
+
     def split(self):
         return self.mat.split()
 

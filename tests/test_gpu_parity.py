@@ -52,6 +52,22 @@ def check_patterns(dev):
     return ref["enabled"]
 
 
+def check_share_classes(dev, part):
+    """How lapis_spmm treats every chunk against the oracle's reading of the same rule (all chunks, or
+    4000 of them spread over the matrix)."""
+    pats = oracle.row_patterns(dev.h_rowptr, dev.h_colidx, dev.ncols, np.dtype(dev.np_dtype).itemsize)
+    nchunks = (dev.nrows + 31) // 32
+    only = None if nchunks <= 6000 else sorted(set(np.linspace(0, nchunks - 1, 4000).astype(np.int64).tolist()))
+    ref = oracle.share_classes(dev.h_rowptr, part, pats, only=only)
+    got = dev.share_classes()
+    assert (got is None) == (ref is None)
+    if ref is not None:
+        assert got.dtype == np.int32 and got.size == nchunks
+        sel = ref >= 0
+        assert np.array_equal(got[sel], ref[sel]), f"share classes differ at chunks {np.flatnonzero(sel & (got != ref))[:8]}"
+    return got
+
+
 def check_partition(dev, rowptr):
     assert rowptr is dev.h_rowptr or np.array_equal(rowptr, dev.h_rowptr)
     ref = oracle.partition(rowptr, colidx=dev.h_colidx, ncols=dev.ncols, itemsize=np.dtype(dev.np_dtype).itemsize)
@@ -61,6 +77,7 @@ def check_partition(dev, rowptr):
         assert np.array_equal(got[key], ref[key]), f"partition field {key} differs"
     check_index16(dev)
     check_patterns(dev)
+    check_share_classes(dev, ref)
 
 
 def check_split(dev, rowptr, colidx, ncols, itemsize, expect_on=None):
@@ -850,6 +867,68 @@ def test_spmm_shared_rows_every_piece_length(kind, dtype, k):
         check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
         check_spmm(dev, rowptr, colidx, vals, X, 0.5, -2.0, Y0, what="alpha=0.5 beta=-2", ldx=k + 1, ldy=k + 2)
         for j in (3, n // 2, n - 2):                             # a non-finite row of X reaches exactly its column's rows
+            Xi = X.copy()
+            Xi[j, :] = np.nan
+            ref, _ = oracle.spmm(rowptr, colidx, vals, Xi)
+            got = dev.spmm(Xi)
+            assert np.array_equal(np.isnan(got), np.isnan(ref)), f"NaN row {j} of X spread differently"
+    finally:
+        dev.close()
+
+
+BLOCK_GRIDS = {
+    # (unknowns per point, neighbour offsets of a point on a line of points)
+    "seven_point_3": (3, [-400, -20, -1, 0, 1, 20, 400]),                 # 21 diagonals: runs of 3, 3, 9, 3, 3
+    "nine_point_2": (2, [-21, -20, -19, -1, 0, 1, 19, 20, 21]),           # 18 diagonals: three runs of 6
+    "singles_3": (3, [-50, -30, -10, 0, 10, 30, 50, 70]),                 # 24 diagonals, eight runs of 3
+    "plane27_3": (3, [z * 400 + y * 20 + x for z in (-1, 0, 1) for y in (-1, 0, 1) for x in (-1, 0, 1)]),   # 81: three passes
+    "dense_3": (3, list(range(-20, 21))),                                 # one run of 123 diagonals: both halves of the list
+    "dense_2": (2, list(range(-31, 33))),                                 # 128 diagonals, the most a pattern may have
+    "pairs_2": (2, [-7, -3, 0, 5, 9]),                                    # 10 diagonals: pieces of 2 only
+}
+
+
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float32, 32), (np.float64, 32), (np.float64, 13),
+                                     (np.float32, 7), (np.float64, 40)])
+@pytest.mark.parametrize("kind", sorted(BLOCK_GRIDS))
+def test_spmm_block_rows_share_rows_of_x(kind, dtype, k):
+    """Two or three unknowns per grid point: the rows of a point hold the same columns, the chunk stores one
+    list of diagonals and the rows differ in their shifts; the product loads a point's rows of X once for
+    its rows.  Lists of up to 128 diagonals worked through in passes, a few emptied or shortened rows per
+    chunk (computed apart), chunks at the ends of the matrix (cut-off lists; row numbers clamped),
+    unaligned k (element-wise loads), two column blocks; the share classes bit for bit against the oracle."""
+    dof, nbrs = BLOCK_GRIDS[kind]
+    say(f"spmm block rows, {kind} k={k} {np.dtype(dtype).name}")
+    npts = 1000 if len(nbrs) * dof <= 30 else 700
+    n = npts * dof
+    rows = []
+    for p in range(npts):
+        cols = [dof * (p + d) + b for d in nbrs if 0 <= p + d < npts for b in range(dof)]
+        rows += [list(cols) for _ in range(dof)]
+    for i in range(n):
+        c = i // 32
+        if i % 32 == 7 and c % 2 == 0:
+            rows[i] = []                                         # an empty row
+        elif i % 32 == 29 and c % 3 == 0:
+            rows[i] = rows[i][1:-1]                              # a subset of the list
+        elif i % 32 == 16 and c % 5 == 0:
+            rows[i] = rows[i][::-1]                              # the same columns, descending
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    vals = gen.uniform(57, gen.STREAM_VALUES, colidx.size).astype(dtype)
+    X = gen.uniform(57, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+    Y0 = gen.uniform(57, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        classes = dev.share_classes()
+        want = oracle.SHARE_BLOCK3 if dof == 3 else oracle.SHARE_BLOCK2
+        assert classes is not None and np.count_nonzero(classes == want) * 2 > classes.size, \
+            f"classes {np.bincount(classes, minlength=5)}: the block rows are not shared"
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, 0.5, -2.0, Y0, what="alpha=0.5 beta=-2", ldx=k + 1, ldy=k + 2)
+        for j in (1, n // 2, n - 2):                             # a non-finite row of X reaches exactly its column's rows
             Xi = X.copy()
             Xi[j, :] = np.nan
             ref, _ = oracle.spmm(rowptr, colidx, vals, Xi)

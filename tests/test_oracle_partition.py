@@ -565,6 +565,78 @@ def test_row_patterns_shift_limits_and_order_of_the_search():
     assert has.all() and np.array_equal(cols, colidx)
 
 
+# ---- level 1d: which chunks share rows of X in the product with a block of vectors ------------
+def _share(rows):
+    rowptr, colidx = _csr_from_rows(rows)
+    part = oracle.partition(rowptr)
+    pats = oracle.row_patterns(rowptr, colidx)
+    return oracle.share_classes(rowptr, part, pats)
+
+
+def _block_rows(npts, dof, nbrs):
+    """dof unknowns per point of a 1-D grid: row dof*p + a holds the columns dof*q + b, q = p + a neighbour."""
+    rows = []
+    for p in range(npts):
+        cols = [dof * (p + d) + b for d in nbrs if 0 <= p + d < npts for b in range(dof)]
+        rows += [cols] * dof
+    return rows
+
+
+def test_share_classes_hand_worked():
+    P, N, B3, B2 = oracle.SHARE_PLAIN, oracle.SHARE_NONE, oracle.SHARE_BLOCK3, oracle.SHARE_BLOCK2
+    # a band of 9 diagonals over 96 rows: rows 0-3 and 92-95 are cut off (4 odd rows in the end chunks)
+    assert _share(_banded(96, 4)).tolist() == [P, P, P]
+    # 11 diagonals: 5 cut-off rows at each end are one too many
+    assert _share(_banded(96, 5)).tolist() == [N, P, N]
+    # the three-unknowns example of the row patterns above: rows 0-2 are odd (the first point), the others
+    # stand at v = 3, 3, 3, 6, 6, 6, ...: every aligned four rows see two points, three apart
+    assert _share(_block_rows(16, 3, (-1, 0, 1))).tolist() == [B3, B3]
+    # two unknowns per point: the four rows of a group are two points, two apart
+    assert _share(_block_rows(40, 2, (-1, 0, 1))).tolist() == [B2, B2, B2]
+    # four unknowns: every aligned group is ONE point, all its rows need the same rows of X: no class for that
+    assert _share(_block_rows(24, 4, (-1, 0, 1))).tolist() == [N, N, N]
+    # five unknowns: groups see steps of 5
+    assert _share(_block_rows(16, 5, (-1, 0, 1))).tolist() == [N, N, N]
+    # the reference list must ascend: every row with the same two runs, the second first
+    assert _share([[i + 50, i + 51, i + 52, i + 10, i + 11] for i in range(64)]).tolist() == [N, N]
+    assert _share([[i + 10, i + 11, i + 50, i + 51, i + 52] for i in range(64)]).tolist() == [P, P]
+
+
+def test_share_classes_limits():
+    P, N, B3 = oracle.SHARE_PLAIN, oracle.SHARE_NONE, oracle.SHARE_BLOCK3
+    # plain rows: at most 64 diagonals, and the chunk's values within one window of 1024 with 64 to spare
+    wide = lambda w, n=64: [[i + d for d in range(w)] for i in range(n)]
+    assert _share(wide(30)).tolist() == [P, P]                   # 960 + 64 = 1024
+    assert _share(wide(31)).tolist() == [N, N]                   # 992 + 64 > 1024
+    # ... counted from the chunk's first entry rounded down to a multiple of 8: 28 entries before the second chunk
+    rows = [[0]] * 28 + [[]] * 4 + wide(30, 32)
+    assert _share(rows).tolist() == [0, N]                       # chunk 0 has too few entries to stream; 28 % 8 = 4 more
+    rows = [[0]] * 24 + [[]] * 8 + wide(30, 32)
+    assert _share(rows).tolist() == [0, P]
+    # block rows: up to 128 diagonals (the longest row a pattern may have), values unlimited
+    got = _share(_block_rows(200, 3, range(-21, 21))).tolist()   # 42 points * 3 = 126 diagonals; points 21 .. 178 are whole
+    assert got[2:16] == [B3] * 14
+    assert _share(_block_rows(200, 3, range(-21, 22))) is None   # 129 diagonals: rows too long for a pattern
+    # odd rows: empty rows count, rows past the end of the matrix do not
+    rows = _block_rows(32, 3, (-1, 0, 1))[:80]                   # 2.5 chunks; the last point is cut like an inner one
+    for i in (35, 40, 41, 50):
+        rows[i] = []
+    assert _share(rows).tolist() == [B3, B3, B3]
+    rows[51] = rows[51][:-1]
+    assert _share(rows).tolist() == [B3, N, B3]
+    # a shorter reference list among longer odd rows is not looked for: the first longest row decides
+    rows = _banded(64, 4)
+    rows[40] = list(range(30, 45))
+    assert _share(rows).tolist() == [P, N]
+
+
+def test_share_classes_off_without_patterns():
+    rowptr, colidx, _ = gen.random_csr(256, 256, np.full(256, 12, dtype=np.int64), 5, np.float64)
+    part = oracle.partition(rowptr)
+    pats = oracle.row_patterns(rowptr, colidx)
+    assert not pats["enabled"] and oracle.share_classes(rowptr, part, pats) is None
+
+
 def test_row_patterns_limits():
     base = list(range(9))
 
