@@ -231,9 +231,21 @@ def parity_check(w, got, ref, absAx):
             "elements": int(err.size), "bound": "8*nnz_row*eps*(|A||x|)_i"}
 
 
-def run_workload(cfg, scale, variant, steps, warmup, cpu_seconds, torch, gen, L, dev, fingerprint):
+def as_spmm(w, k, gen, cfg):
+    """The matrix of an SpMV workload with a block of k vectors (row-major X from the workload's own
+    seed and stream, Y = A X): the shape of workload 5 on another matrix."""
+    import dataclasses
+    X = gen.uniform(gen.BASE_SEED + cfg, gen.STREAM_X, w.ncols * k, dtype=w.dtype).reshape(w.ncols, k)
+    return dataclasses.replace(w, name=f"{w.name}_spmm_k{k}", x=X, alpha=1.0, beta=0.0, y0=None, k=k)
+
+
+def run_workload(cfg, scale, variant, steps, warmup, cpu_seconds, torch, gen, L, dev, fingerprint, spmm_k=0):
     """Times one workload and returns its entry: times, rates, roofline figures, oracle baseline, parity."""
     w = gen.workload(cfg, scale or None)
+    if spmm_k:
+        if w.k:
+            sys.exit("bench.py: --spmm-k applies to the SpMV workloads")
+        w = as_spmm(w, spmm_k, gen, cfg)
     tdt = torch.float64 if w.dtype == np.float64 else torch.float32
     rowptr = torch.from_numpy(w.rowptr).to(dev)
     colidx = torch.from_numpy(w.colidx).to(dev)
@@ -348,6 +360,8 @@ def main():
     ap.add_argument("--scale", default=None,
                     help="override size parameters of the workload's recipe, e.g. nx=288,ny=288,nz=288 "
                          "(labelled in config.workload; the default sizes are the benchmark's)")
+    ap.add_argument("--spmm-k", type=int, default=0,
+                    help="with --config N (an SpMV workload): time lapis_spmm on its matrix with this many columns")
     ap.add_argument("--zipf-s", type=float, default=None,
                     help="workload 4 only: Zipf exponent (default 1.8; 2.0 gives the 'mean about 8' variant)")
     ap.add_argument("--variant", choices=["tuned", "paper-shape", "transpose", "transposed-handle", "host-buffers",
@@ -406,13 +420,16 @@ def main():
     if args.variant == "batched-gemm":
         batched_gemm_bench(args, scale, torch, gen, L, dev)
         return
+    if args.spmm_k and (args.config is None or args.variant != "tuned"):
+        sys.exit("bench.py: --spmm-k needs --config N and the tuned variant")
     all_five = args.config is None and args.variant == "tuned" and not scale
     cfg = 2 if args.config is None else args.config
     if args.zipf_s is not None and cfg == 4:
         scale["s"] = args.zipf_s
     fingerprint = source_fingerprint()
     head, w = run_workload(cfg, scale, args.variant, args.steps, args.warmup,
-                           None if args.no_cpu else args.cpu_seconds, torch, gen, L, dev, fingerprint)
+                           None if args.no_cpu else args.cpu_seconds, torch, gen, L, dev, fingerprint,
+                           spmm_k=args.spmm_k)
     ceilings = ceiling_read(torch, dev, reps=10) if args.variant == "tuned" else {}
 
     configs = None

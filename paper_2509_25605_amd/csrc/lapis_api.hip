@@ -690,24 +690,51 @@ void launch_binned(const lapis_csr *A, const BinnedSet &s, const ShortPlan &plan
     }
 }
 
-// Stream chunks of one class (G lanes per row): one wavefront per 64/G rows.
-template <typename T, int G>
-void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipStream_t stream)
+// Which instantiation of the stream kernel serves the chunks of the classes lo..hi when they are launched
+// together with G lanes per row: decided by what ALL their chunks have (empty classes do not count).
+enum StreamVariant { kVariantGrouped, kVariantPattern, kVariantPatternOr16, kVariantNarrow, kVariantFramed,
+                     kVariantEither, kVariant32 };
+StreamVariant stream_variant(const lapis_csr *A, int lo, int hi, int G)
 {
-    const int64_t count = A->h_stream_offset[cls] - A->h_stream_offset[cls - 1];
+    bool all16 = true, allframed = true, allcoded = true, allpattern = true, pattern16 = true;
+    for (int cls = lo; cls <= hi; ++cls) {
+        if (A->h_stream_offset[cls] == A->h_stream_offset[cls - 1]) continue;
+        all16 = all16 && A->class_all16[cls - 1];
+        allframed = allframed && A->class_allframed[cls - 1];
+        allcoded = allcoded && A->class_allcoded[cls - 1];
+        allpattern = allpattern && A->class_allpattern[cls - 1];
+        pattern16 = pattern16 && (A->class_pattern16[cls - 1] || A->class_allpattern[cls - 1]);
+    }
+    // With scattered columns every gather is a cache line of its own and the time goes into L1
+    // misses: the wavefronts of a chunk then run as one workgroup, on one CU, where the lines one
+    // of them fetched serve the others (stand-ins 7 and 9: 143 -> 137 us, 309 -> 291 us).  Where
+    // columns come in runs the same grouping costs time (Elasticity3D stand-in 94 -> 107 us).
+    // Neighbouring one-wavefront chunks (G == 2) gain nothing from it.
+    if (A->scattered_columns && all16 && !allpattern && !pattern16 && G >= 4) return kVariantGrouped;
+    if (allpattern) return kVariantPattern;
+    if (pattern16) return kVariantPatternOr16;
+    if (all16) return kVariantNarrow;
+    if (allframed) return kVariantFramed;
+    if (allcoded) return kVariantEither;
+    return kVariant32;
+}
+
+// Stream chunks of the classes lo..hi (their lists are neighbours) with the lane groups of class hi,
+// G lanes per row: one wavefront per 64/G rows.  A chunk of a lower class meets the limits of every
+// higher one (rows and entries per chunk), only with more lanes per row than it needs.
+template <typename T, int G>
+void launch_stream(const lapis_csr *A, int lo, int hi, const T *x, T *y, T a, T b, hipStream_t stream)
+{
+    const int64_t count = A->h_stream_offset[hi] - A->h_stream_offset[lo - 1];
     if (count == 0) return;
     const uint32_t waves = (uint32_t)(count * (G / 2));
     const uint32_t padded = (waves + kXcds - 1) / kXcds * kXcds;
-    const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[cls - 1];
+    const int32_t *list = (count == A->num_chunks) ? nullptr : A->d_stream_chunks + A->h_stream_offset[lo - 1];
 #define LAPIS_STREAM_LAUNCH(RAW)                                                                             \
     spmv_stream_kernel<T, G, true, RAW><<<dim3(padded), dim3(kWave), 0, stream>>>(                            \
         (int32_t)A->nrows, (int32_t)A->nnz, waves, padded, list, A->rowptr, A->colidx, A->d_chunk_base,        \
         A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},              \
         static_cast<const T *>(A->vals), x, y, a, b)
-    // With scattered columns every gather is a cache line of its own and the time goes into L1
-    // misses: the wavefronts of a chunk then run as one workgroup, on one CU, where the lines one
-    // of them fetched serve the others (stand-ins 7 and 9: 143 -> 137 us, 309 -> 291 us).  Where
-    // columns come in runs the same grouping costs time (Elasticity3D stand-in 94 -> 107 us).
 #define LAPIS_STREAM_GROUPED(GWV)                                                                            \
     do {                                                                                                     \
         const uint32_t groups = (waves + (GWV) - 1) / (GWV), pgroups = (groups + kXcds - 1) / kXcds * kXcds;  \
@@ -716,20 +743,58 @@ void launch_stream(const lapis_csr *A, int cls, const T *x, T *y, T a, T b, hipS
             A->d_frame_table, A->d_col16, StreamPatterns{A->d_pat_off, A->d_row_pat, A->d_pat_pool},          \
             static_cast<const T *>(A->vals), x, y, a, b);                                                     \
     } while (0)
-    if (A->scattered_columns && A->class_all16[cls - 1] && !A->class_allpattern[cls - 1] && !A->class_pattern16[cls - 1]) {
-        if constexpr (G >= 4) {      // neighbouring one-wavefront chunks (G == 2) gain nothing from it
-            LAPIS_STREAM_GROUPED(G / 2);
-            return;
-        }
+    switch (stream_variant(A, lo, hi, G)) {
+    case kVariantGrouped:
+        if constexpr (G >= 4) LAPIS_STREAM_GROUPED(G / 2);
+        break;
+    case kVariantPattern: LAPIS_STREAM_LAUNCH(kColsPattern); break;
+    case kVariantPatternOr16: LAPIS_STREAM_LAUNCH(kColsPatternOr16); break;
+    case kVariantNarrow: LAPIS_STREAM_LAUNCH(kColsNarrow); break;
+    case kVariantFramed: LAPIS_STREAM_LAUNCH(kColsFramed); break;
+    case kVariantEither: LAPIS_STREAM_LAUNCH(kColsEither); break;
+    case kVariant32: LAPIS_STREAM_LAUNCH(kCols32); break;
     }
 #undef LAPIS_STREAM_GROUPED
-    if (A->class_allpattern[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPattern);
-    else if (A->class_pattern16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsPatternOr16);
-    else if (A->class_all16[cls - 1]) LAPIS_STREAM_LAUNCH(kColsNarrow);
-    else if (A->class_allframed[cls - 1]) LAPIS_STREAM_LAUNCH(kColsFramed);
-    else if (A->class_allcoded[cls - 1]) LAPIS_STREAM_LAUNCH(kColsEither);
-    else LAPIS_STREAM_LAUNCH(kCols32);
 #undef LAPIS_STREAM_LAUNCH
+}
+
+template <typename T>
+void launch_stream_classes(const lapis_csr *A, int lo, int hi, const T *x, T *y, T a, T b, hipStream_t stream)
+{
+    switch (hi) {
+    case 1: launch_stream<T, 2>(A, lo, hi, x, y, a, b, stream); break;
+    case 2: launch_stream<T, 4>(A, lo, hi, x, y, a, b, stream); break;
+    case 3: launch_stream<T, 8>(A, lo, hi, x, y, a, b, stream); break;
+    default: launch_stream<T, 16>(A, lo, hi, x, y, a, b, stream); break;
+    }
+}
+
+// All stream chunks.  Kernels of one stream run one after the other, so a class with few chunks costs a
+// launch that cannot fill the GPU (7 to 8 us on the Elasticity3D stand-in: the chunks at the grid's
+// faces).  Such a class rides with the next class up that has chunks - at most an eighth as many as
+// that class has, and only if the kernel variant that class would get by itself still serves both.
+template <typename T>
+void launch_all_streams(const lapis_csr *A, const T *x, T *y, T a, T b, hipStream_t stream)
+{
+    const int32_t *off = A->h_stream_offset;
+    int lo = 1, top = 0;                       // pending classes lo..top (top = the highest of them with chunks)
+    for (int cls = 1; cls <= kStreamClasses; ++cls) {
+        const int64_t here = off[cls] - off[cls - 1];
+        if (here == 0) continue;
+        const int64_t pending = off[cls - 1] - off[lo - 1];
+        if (pending > 0) {
+            const int G = 1 << cls;
+            const bool rides = pending * 8 <= here && stream_variant(A, lo, cls, G) == stream_variant(A, cls, cls, G);
+            if (!rides) {
+                launch_stream_classes<T>(A, lo, top, x, y, a, b, stream);
+                lo = cls;
+            }
+        } else {
+            lo = cls;
+        }
+        top = cls;
+    }
+    if (top > 0) launch_stream_classes<T>(A, lo, top, x, y, a, b, stream);
 }
 
 // y (ncols values) = beta*y, then every entry of A adds alpha*vals[j]*x[row] into y[colidx[j]].
@@ -794,10 +859,7 @@ int spmv_typed(const lapis_csr *A, double alpha, const void *d_x, double beta, v
     const T a = (T)alpha, b = (T)beta;
     const T *x = static_cast<const T *>(d_x);
     T *y = static_cast<T *>(d_y);
-    launch_stream<T, 2>(A, 1, x, y, a, b, stream);
-    launch_stream<T, 4>(A, 2, x, y, a, b, stream);
-    launch_stream<T, 8>(A, 3, x, y, a, b, stream);
-    launch_stream<T, 16>(A, 4, x, y, a, b, stream);
+    launch_all_streams<T>(A, x, y, a, b, stream);
     const bool split = A->num_blocks > 0;
     launch_binned<T>(A, A->rows, A->plan_rows, !split, x, y, a, b, static_cast<T *>(scr.partial_rows), stream);
     if (split) {
@@ -855,6 +917,8 @@ int spmv_paper_shape_typed(const lapis_csr *A, double alpha, const void *d_x, do
     LAPIS_HIP(hipGetLastError());
     return LAPIS_OK;
 }
+
+constexpr uint32_t kFewChunks = 8192;    // launches over fewer stream chunks give every pass of a chunk a wavefront of its own
 
 template <typename T, int VEC, int CL>
 int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b, T *Y, int64_t ldy,
@@ -928,7 +992,21 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
                 launch_share(std::integral_constant<int, 2>(), kShareBlock2, c0);
             }
             if (n_none == 0) continue;
-            if (all16)
+            // few chunks (what the share classes left over): a wavefront per pass of a chunk instead of one per
+            // chunk, or 12 wavefronts per CU at most would each walk their 32 rows alone
+            constexpr uint32_t kParts = kStreamRows / (kWave / kStreamLanes);
+            const bool per_pass = kParts > 1 && n_none <= kFewChunks;
+            if (per_pass) {
+                const uint32_t units = n_none * kParts, padded_units = (units + kXcds - 1) / kXcds * kXcds;
+                if (all16)
+                    spmm_stream_kernel<T, VEC, kStreamLanes, true, true, true><<<dim3(padded_units), dim3(kWave), 0, stream>>>(
+                        (int32_t)A->nrows, (int32_t)A->nnz, units, padded_units, none_list, A->rowptr, 0u,
+                        A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+                else
+                    spmm_stream_kernel<T, VEC, kStreamLanes, true, false, true><<<dim3(padded_units), dim3(kWave), 0, stream>>>(
+                        (int32_t)A->nrows, (int32_t)A->nnz, units, padded_units, none_list, A->rowptr, 0u,
+                        A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);
+            } else if (all16)
                 spmm_stream_kernel<T, VEC, kStreamLanes, true, true><<<dim3(none_padded), dim3(kWave), 0, stream>>>(
                     (int32_t)A->nrows, (int32_t)A->nnz, n_none, none_padded, none_list, A->rowptr, none_xcd_block,
                     A->colidx, A->d_chunk_base, A->d_frame_table, A->d_col16, vals, k, c0, X, ldx, Y, ldy, a, b);

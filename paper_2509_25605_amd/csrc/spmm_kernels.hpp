@@ -60,7 +60,10 @@ __device__ __forceinline__ void store_row(T *__restrict__ yrow, const T (&acc)[V
 constexpr int kSpmmUnroll = 16;  // X rows in flight per lane and batch
 
 // ALL16: every listed chunk has 16-bit column offsets; the LDS window keeps them as 2-byte values.
-template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false>
+// PER_PASS: a chunk is shared by kPasses wavefronts, each taking the kSlots consecutive rows of one pass
+// (num_chunks and padded_chunks then count those wavefronts): for launches over so few chunks that one
+// wavefront per chunk would leave most of the GPU idle while each walks its 32 rows.
+template <typename T, int VEC, int CL, bool XCD_REMAP, bool ALL16 = false, bool PER_PASS = false>
 __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     int32_t nrows, int32_t nnz, uint32_t num_chunks, uint32_t padded_chunks,
     const int32_t *__restrict__ stream_chunks, const int32_t *__restrict__ rowptr,
@@ -71,7 +74,8 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
 {
     static_assert(CL <= 16, "column blocks wider than 16 lanes are split by the host");
     constexpr int kSlots = (kWave / CL > kStreamRows) ? kStreamRows : kWave / CL;
-    constexpr int kPasses = kStreamRows / kSlots;
+    constexpr int kParts = PER_PASS ? kStreamRows / kSlots : 1;      // wavefronts per chunk
+    constexpr int kPasses = kStreamRows / kSlots / kParts;           // passes of one wavefront
     __shared__ __attribute__((aligned(16))) T s_val[kStreamWindow];
     typedef typename std::conditional<ALL16, uint16_t, int32_t>::type idx_t;
     __shared__ __attribute__((aligned(16))) idx_t s_col[kStreamWindow];
@@ -85,7 +89,9 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     const int lane = threadIdx.x;
     const int slot = lane / CL;
     const int l = lane % CL;
-    const int64_t chunk = stream_chunks ? stream_chunks[id] : (int64_t)id;
+    const uint32_t listed = id / kParts;
+    const int first_row = (int)(id % kParts) * kPasses * kSlots;        // this wavefront's rows of the chunk
+    const int64_t chunk = stream_chunks ? stream_chunks[listed] : (int64_t)listed;
     const int64_t row0 = chunk * kStreamRows;
     const int32_t cbase = chunk_base ? chunk_base[chunk] : -1;          // wave-uniform
     if constexpr (!ALL16) load_frame_table(frame_table, chunk, cbase, lane, s_tab);
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int32_t base = s_rp[0], end = s_rp[kStreamRows];
+    const int32_t base = s_rp[first_row], end = s_rp[first_row + kPasses * kSlots];
     const int32_t nnz4 = nnz & ~3;
     const int64_t col = c0 + (int64_t)l * VEC;
     const bool active = slot < kSlots && col < k;
@@ -124,7 +130,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
         stream_window_to_lds<T, idx_t>(colidx, col16, cbase, s_tab, vals, w0, w1, nnz4, lane, s_col, s_val);
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
-            const int r = active ? p * kSlots + slot : 0;
+            const int r = active ? first_row + p * kSlots + slot : 0;
             const int32_t rb = s_rp[r], re = s_rp[r + 1];
             const int32_t ub = (rb > w0 ? rb : w0) - w0;
             const int32_t ue = (re < w1 ? re : w1) - w0;
@@ -194,7 +200,7 @@ __global__ __launch_bounds__(kWave) void spmm_stream_kernel(
     if (active) {
 #pragma unroll
         for (int p = 0; p < kPasses; ++p) {
-            const int64_t row = row0 + p * kSlots + slot;
+            const int64_t row = row0 + first_row + p * kSlots + slot;
             if (row < nrows) store_row<T, VEC>(Y + row * ldy, acc[p], col, k, alpha, beta);
         }
     }
