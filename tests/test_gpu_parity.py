@@ -262,6 +262,44 @@ STREAM_LAYOUTS = {
 
 
 @pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("mix", ["small_below", "small_between", "two_small", "too_many", "scattered16"])
+def test_spmv_small_stream_classes_ride_with_the_next_class(mix, dtype):
+    """Stream classes with few chunks are launched with the next class up that has chunks (its lane
+    groups, its kernel variant) when they are at most an eighth of it; the results must not care."""
+    say(f"stream classes {mix} {np.dtype(dtype).name}")
+    # (row length, number of chunks) per population; rows of 20 / 60 / 100 / 200 entries make chunks of class 1 / 2 / 3 / 4
+    chunks = {
+        "small_below": [(20, 3), (60, 60)],               # class 1 rides with class 2
+        "small_between": [(20, 80), (60, 4), (100, 70)],  # class 2 rides with class 3; class 1 is too large to
+        "two_small": [(20, 2), (60, 3), (200, 64)],       # classes 1 and 2 ride with class 4
+        "too_many": [(20, 30), (100, 60)],                # half as many: a launch of its own
+        "scattered16": [(20, 4), (100, 70)],              # few columns: 16-bit offsets, grouped wavefronts above class 1
+    }[mix]
+    L = np.concatenate([np.full(32 * c, length, dtype=np.int64) for length, c in chunks])
+    order = np.argsort(gen.uniform(17, 0, L.size // 32, 0.0, 1.0), kind="stable")     # shuffle whole chunks
+    L = L.reshape(-1, 32)[order].ravel()
+    n = L.size
+    ncols = 200_000                                       # x within one column block: no chunk is demoted
+    if mix == "scattered16":
+        ncols = 3000
+        rowptr, colidx, vals = gen.random_csr(n, ncols, L, 19, dtype)
+    else:
+        rowptr, colidx, vals = gen.random_csr(n, ncols, L, 19, dtype)
+    x = gen.uniform(20, gen.STREAM_X, ncols).astype(dtype)
+    y0 = gen.uniform(20, gen.STREAM_Y0, n).astype(dtype)
+    dev = DeviceCsr(n, ncols, rowptr, colidx, vals)
+    try:
+        part = dev.partition()
+        sizes = np.diff(part["stream_offset"])
+        assert np.count_nonzero(sizes) >= 2, f"class sizes {sizes}: the case needs several stream classes"
+        check_partition(dev, rowptr)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        check_spmv(dev, rowptr, colidx, vals, x, 0.75, -1.25, y0, what="alpha=0.75 beta=-1.25")
+    finally:
+        dev.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
 @pytest.mark.parametrize("layout", sorted(STREAM_LAYOUTS))
 def test_spmv_stream_chunks(layout, dtype):
     say(f"stream layout={layout} {np.dtype(dtype).name}")
@@ -742,6 +780,26 @@ def test_spmm_general_matrices(dtype, k, ldx, ldy):
             ref, absAx = oracle.spmv(rowptr, colidx, vals, np.ascontiguousarray(X[:, 0]))
             assert_close(dev.spmm(X)[:, 0], ref, general_bound(np.diff(rowptr), absAx, dtype, 1.0, 0.0, None))
             assert_close(y, ref, general_bound(np.diff(rowptr), absAx, dtype, 1.0, 0.0, None))
+    finally:
+        dev.close()
+
+
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float32, 8), (np.float64, 3)])
+def test_spmm_many_stream_chunks_one_wavefront_per_chunk(dtype, k):
+    """More than 8192 stream chunks without shared rows of X: the launch with one wavefront per chunk
+    (smaller matrices give every 8 or 16 rows of a chunk a wavefront of their own)."""
+    say(f"spmm over 9000 stream chunks k={k} {np.dtype(dtype).name}")
+    n = 32 * 9000 + 13
+    L = (6 + np.floor(gen.uniform(91, 0, n, 0.0, 1.0) * 7)).astype(np.int64)      # 6..12 entries per row
+    L[::97] = 0
+    rowptr, colidx, vals = gen.random_csr(n, n, L, 92, dtype)
+    X = gen.uniform(93, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+    Y0 = gen.uniform(93, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        assert dev.partition()["stream_chunks"].size > 8192
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, -0.5, 2.0, Y0, what="alpha=-0.5 beta=2", ldx=k + 1, ldy=k + 3)
     finally:
         dev.close()
 
