@@ -918,7 +918,10 @@ int spmv_paper_shape_typed(const lapis_csr *A, double alpha, const void *d_x, do
     return LAPIS_OK;
 }
 
-constexpr uint32_t kFewChunks = 8192;    // launches over fewer stream chunks give every pass of a chunk a wavefront of its own
+// SpMM launches over at most kFewChunks stream chunks of a matrix with kLongRowsMean entries per row or more
+// give every pass of a chunk a wavefront of its own
+constexpr uint32_t kFewChunks = 8192;
+constexpr int64_t kLongRowsMean = 48;
 
 template <typename T, int VEC, int CL>
 int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b, T *Y, int64_t ldy,
@@ -992,10 +995,11 @@ int spmm_launch(const lapis_csr *A, int64_t k, T a, const T *X, int64_t ldx, T b
                 launch_share(std::integral_constant<int, 2>(), kShareBlock2, c0);
             }
             if (n_none == 0) continue;
-            // few chunks (what the share classes left over): a wavefront per pass of a chunk instead of one per
-            // chunk, or 12 wavefronts per CU at most would each walk their 32 rows alone
+            // few chunks of long rows (what the share classes left over): a wavefront per pass of a chunk instead
+            // of one per chunk, or a dozen wavefronts per CU would each walk their 32 rows alone (Elasticity3D
+            // stand-in, 3150 chunks of 81-entry rows: 83 -> 48 us; with 9 entries per row it costs 10 %)
             constexpr uint32_t kParts = kStreamRows / (kWave / kStreamLanes);
-            const bool per_pass = kParts > 1 && n_none <= kFewChunks;
+            const bool per_pass = kParts > 1 && n_none <= kFewChunks && A->nnz >= kLongRowsMean * A->nrows;
             if (per_pass) {
                 const uint32_t units = n_none * kParts, padded_units = (units + kXcds - 1) / kXcds * kXcds;
                 if (all16)

@@ -784,10 +784,35 @@ def test_spmm_general_matrices(dtype, k, ldx, ldy):
         dev.close()
 
 
+@pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float64, 32), (np.float32, 32), (np.float64, 8), (np.float64, 11),
+                                     (np.float32, 70)])
+@pytest.mark.parametrize("per_row", [9, 70])
+def test_spmm_few_stream_chunks_long_and_short_rows(per_row, dtype, k):
+    """Few stream chunks without shared rows of X: with long rows (48 entries per row or more on average)
+    every pass of a chunk - the 4, 8 or 16 rows that the slots of a wavefront take together - gets a
+    wavefront of its own, with short rows a chunk keeps its one wavefront.  Rows of mixed lengths, a ragged
+    last chunk, leading dimensions wider than k."""
+    say(f"spmm few stream chunks, about {per_row} per row, k={k} {np.dtype(dtype).name}")
+    n = 32 * 150 + 21
+    L = (per_row - 4 + np.floor(gen.uniform(94, 0, n, 0.0, 1.0) * 9)).astype(np.int64)
+    L[::53] = 0
+    L[7::211] = 3 * per_row
+    rowptr, colidx, vals = gen.random_csr(n, n, L, 95, dtype, sorted_cols=False)
+    X = gen.uniform(96, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+    Y0 = gen.uniform(96, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        assert dev.partition()["stream_chunks"].size > 100
+        assert (colidx.size >= 48 * n) == (per_row == 70)
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0")
+        check_spmm(dev, rowptr, colidx, vals, X, 1.5, -0.25, Y0, what="alpha=1.5 beta=-0.25", ldx=k + 2, ldy=k + 1)
+    finally:
+        dev.close()
+
+
 @pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float32, 8), (np.float64, 3)])
 def test_spmm_many_stream_chunks_one_wavefront_per_chunk(dtype, k):
-    """More than 8192 stream chunks without shared rows of X: the launch with one wavefront per chunk
-    (smaller matrices give every 8 or 16 rows of a chunk a wavefront of their own)."""
+    """More than 8192 stream chunks without shared rows of X: the launch with one wavefront per chunk."""
     say(f"spmm over 9000 stream chunks k={k} {np.dtype(dtype).name}")
     n = 32 * 9000 + 13
     L = (6 + np.floor(gen.uniform(91, 0, n, 0.0, 1.0) * 7)).astype(np.int64)      # 6..12 entries per row
