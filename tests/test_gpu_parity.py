@@ -1269,3 +1269,61 @@ def test_seeded_structure_sweep(seed):
         check_spmm(dev, rowptr, colidx, vals, X, what=f"spmm k={k}")
     finally:
         dev.close()
+
+
+def _grid_section(kind, r0, r1, ncols, seed):
+    """Rows r0..r1-1 of a grid-like section: every row the same neighbours, with 1, 2 or 3 unknowns per point."""
+    u = gen.uniform(seed, 14, 16, 0.0, 1.0)
+    dof = {"scalar": 1, "block2": 2, "block3": 3}[kind]
+    nbrs = sorted(set([0] + [int(d) for d in (np.floor(u[:6] * 60) - 30)] + [int(u[6] * 3) * 40 + e for e in (-1, 0, 1)]))
+    rows = []
+    for i in range(r0, r1):
+        p, base = (i - r0) // dof, r0
+        cols = [base + dof * (p + d) + b for d in nbrs for b in range(dof)]
+        rows.append([c for c in cols if 0 <= c < ncols])       # cut off at the ends of the matrix only
+    for t in range(int(u[7] * 4)):                              # a few rows emptied or shortened
+        j = int(u[8 + t] * (r1 - r0))
+        rows[j] = rows[j][::2] if t % 2 else []
+    return rows
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_seeded_share_class_sweep(seed):
+    """Sections of scalar grids and of grids with 2 and 3 unknowns per point, of lengths that are not multiples
+    of 32, so that chunks straddle two kinds, start in the middle of a grid point and hold a few altered rows:
+    every share class beside every other in one matrix; classes bit for bit, SpMM with 8 and 16 lanes per row of X."""
+    kinds = ["scalar", "block2", "block3"]
+    pick = gen.uniform(4100 + seed, 1, 24, 0.0, 1.0)
+    dtype = np.float64 if seed % 2 == 0 else np.float32
+    sections, r = [], 0
+    for t in range(4 + seed % 3):
+        length = 32 * (3 + int(pick[t] * 12)) + int(pick[t + 8] * 31)
+        sections.append((kinds[int(pick[t + 16] * 3) % 3], r, r + length))
+        r += length
+    n = r
+    say(f"share sweep seed={seed} n={n} {np.dtype(dtype).name} " + " ".join(k for k, _, _ in sections))
+    rows = []
+    for kd, a, b in sections:
+        rows += _grid_section(kd, a, b, n, 5100 + 89 * seed + a)
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum([len(x) for x in rows], out=rowptr[1:])
+    colidx = np.array([c for x in rows for c in x], dtype=np.int32)
+    vals = gen.uniform(6200 + seed, gen.STREAM_VALUES, colidx.size).astype(dtype)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        check_partition(dev, rowptr)
+        classes = dev.share_classes()
+        assert classes is not None and np.count_nonzero(classes != oracle.SHARE_NONE) > 0
+        x = gen.uniform(6200 + seed, gen.STREAM_X, n).astype(dtype)
+        check_spmv(dev, rowptr, colidx, vals, x, what="alpha=1 beta=0")
+        for k in ((16, 32) if dtype == np.float64 else (32, 64)):
+            X = gen.uniform(6300 + seed, gen.STREAM_X, n * k).astype(dtype).reshape(n, k)
+            Y0 = gen.uniform(6300 + seed, gen.STREAM_Y0, n * k).astype(dtype).reshape(n, k)
+            check_spmm(dev, rowptr, colidx, vals, X, what=f"spmm k={k}")
+            check_spmm(dev, rowptr, colidx, vals, X, -1.5, 0.5, Y0, what=f"spmm k={k} alpha=-1.5 beta=0.5", ldx=k + 4, ldy=k + 2)
+            Xi = X.copy()
+            Xi[n // 3, :] = np.nan
+            ref, _ = oracle.spmm(rowptr, colidx, vals, Xi)
+            assert np.array_equal(np.isnan(dev.spmm(Xi)), np.isnan(ref)), "a NaN row of X spread differently"
+    finally:
+        dev.close()
