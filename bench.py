@@ -36,48 +36,74 @@ EPS = {np.dtype(np.float64): 2.0 ** -53, np.dtype(np.float32): 2.0 ** -24}
 # summary the figure is taken from.
 MEASURED = {
     "poisson2d_64x64_f64": {
-        "traffic": 0.44e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_poisson2d_64_f64.md",
+        "traffic": 0.44e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_poisson2d_64_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
     "stencil27_128x128x128_f64": {
-        "traffic": 505.35e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_stencil27_128_f64.md",
+        "traffic": 505.35e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_stencil27_128_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
     "uniform16_n4194304_f64": {
-        "traffic": 8439.92e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_uniform16_f64.md",
+        "traffic": 8439.92e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_uniform16_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 0, 16, 1> (0: 32-bit columns)"},
     "zipf1.8_cap200000_n8388608_f32": {
-        "traffic": 8689.40e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_powerlaw_zipf_f32.md",
+        "traffic": 8689.40e6, "source": "d44fc9c294de", "profile": "profiles/spmv_powerlaw_zipf_f32.md",
         "kernel": "spmv_short_kernel<float, true> (2 launches) + spmv_ldsblock_kernel<float> + spmv_stream_kernel<float, ...>"},
     "stencil27_128x128x128_f64_spmm_k16": {
-        "traffic": 1039.14e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmm_shared_stencil27_128_k16_f64.md",
+        "traffic": 1039.14e6, "source": "d44fc9c294de", "profile": "profiles/spmm_shared_stencil27_128_k16_f64.md",
         "kernel": "spmm_shared_kernel<double, 2, 8, true> (rows of X shared by 4 consecutive rows)"},
     "table3_StocF-1465_n1465137_f64": {
-        "traffic": 243.82e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_stocf_standin_f64.md",
+        "traffic": 243.82e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_stocf_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 1, 16, 1> (1: 16-bit column offsets)"},
     "table3_PFlow_742_n742793_f64": {
-        "traffic": 399.93e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_pflow_standin_f64.md",
+        "traffic": 399.93e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_pflow_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 4, true, 1, 16, 2> (1: 16-bit column offsets; 2 wavefronts per workgroup)"},
     "table3_Elasticity3D_60_n648000_f64": {
-        "traffic": 430.27e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_elasticity3d_60_standin_f64.md",
+        "traffic": 430.27e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_elasticity3d_60_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 8, true, 4, 16, 1> (4: row patterns, with shifts)"},
     "table3_Elasticity3D_60_n648000_f64_spmm_k16": {
-        "traffic": 1007.47e6, "source": "ba6f1bb1cadf",
+        "traffic": 1007.47e6, "source": "d44fc9c294de",
         "profile": "profiles/spmm_block_shared_elasticity3d_60_standin_k16_f64.md",
         "kernel": "spmm_block_shared_kernel<double, 2, true, 3, 32> (rows of X shared by the rows of a grid point) + "
                   "spmm_stream_kernel<double, 2, 8, true, true, true> (the other chunks)"},
     "table3_audikw_1_n943695_f64": {
-        "traffic": 814.08e6, "source": "ba6f1bb1cadf", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
+        "traffic": 814.08e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 4> (1: 16-bit column offsets; 4 wavefronts per workgroup)"},
 }
 FINGERPRINT_FILES = ["spmv_kernels.hpp", "spmm_kernels.hpp", "analysis_kernels.hpp", "lapis_api.hip", "device_utils.hpp"]
 
 
+def strip_comments(text):
+    """C++ source without its comments and with every run of white space as one blank (string and
+    character literals are kept as they are), so that rewording a comment is not a change of the code."""
+    out, i, n = [], 0, len(text)
+    while i < n:
+        c = text[i]
+        if c in "\"'":
+            j = i + 1
+            while j < n and text[j] != c:
+                j += 2 if text[j] == "\\" else 1
+            out.append(text[i:j + 1])
+            i = j + 1
+        elif text.startswith("//", i):
+            j = text.find("\n", i)
+            i = n if j < 0 else j
+        elif text.startswith("/*", i):
+            j = text.find("*/", i + 2)
+            i = n if j < 0 else j + 2
+            out.append(" ")
+        else:
+            out.append(c)
+            i += 1
+    return " ".join("".join(out).split())
+
+
 def source_fingerprint():
-    """First 12 hex digits of the SHA-256 of the kernel and launch sources (csrc/), so that a traffic
-    figure measured with other sources is recognisable as stale."""
+    """First 12 hex digits of the SHA-256 of the kernel and launch sources (csrc/) without their comments,
+    so that a traffic figure measured with other code is recognisable as stale."""
     h = hashlib.sha256()
     for name in FINGERPRINT_FILES:
-        with open(os.path.join(ROOT, "paper_2509_25605_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2509_25605_amd", "csrc", name), "r", encoding="utf-8") as f:
+            h.update(strip_comments(f.read()).encode("utf-8"))
+            h.update(b"\0")
     return h.hexdigest()[:12]
 
 

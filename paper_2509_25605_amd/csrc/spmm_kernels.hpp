@@ -12,6 +12,13 @@
 //    lane, in whole batches of 16 / 8 / 4 / 2 / 1 entries while all rows of the
 //    wavefront have that many left.  Consecutive rows sit in consecutive slots, so
 //    on banded matrices one load instruction reads consecutive rows of X.
+//    Launches over few chunks of long rows give every pass of a chunk (the rows
+//    the slots take together) a wavefront of its own.
+//  * spmm_shared_kernel (stream chunks whose rows repeat one list of diagonals):
+//    a slot takes 4 or 8 consecutive rows and loads the rows of X that they have
+//    in common once; no column index is read.  spmm_block_shared_kernel does the
+//    same for the rows of grid points with 2 or 3 unknowns.  Which chunks these
+//    are is decided once per matrix (spmm_share_flag_kernel).
 //  * spmm_rows_kernel (other rows of up to 64 entries): one slot per row.  The slot's
 //    lanes load CL consecutive (column, value) pairs of the row at once, park
 //    them in LDS, and every lane then reads them back one by one as LDS

@@ -62,3 +62,10 @@ def test_source_fingerprint_follows_the_kernel_sources():
     for m in bench.MEASURED.values():
         assert set(m) == {"traffic", "source", "kernel", "profile"}
         assert os.path.exists(os.path.join(ROOT, m["profile"]))
+    # comments and layout do not count, code does
+    code = 'int f(int a) { return a + 1; }  // adds one\n/* block\n comment */ const char *s = "// not a comment";\n'
+    same = 'int f(int a)\n{\n    return a + 1;   // one more\n}\nconst char *s = "// not a comment";\n'
+    other = 'int f(int a) { return a + 2; }\nconst char *s = "// not a comment";\n'
+    assert bench.strip_comments(code) == bench.strip_comments(same)
+    assert bench.strip_comments(code) != bench.strip_comments(other)
+    assert '"// not a comment"' in bench.strip_comments(code) and "adds one" not in bench.strip_comments(code)
