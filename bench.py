@@ -64,6 +64,9 @@ MEASURED = {
         "profile": "profiles/spmm_block_shared_elasticity3d_60_standin_k16_f64.md",
         "kernel": "spmm_block_shared_kernel<double, 2, true, 3, 32> (rows of X shared by the rows of a grid point) + "
                   "spmm_stream_kernel<double, 2, 8, true, true, true> (the other chunks)"},
+    "table3_PFlow_742_n742793_f64_spmm_k16": {
+        "traffic": 576.97e6, "source": "d44fc9c294de", "profile": "profiles/spmm_stream_pflow_standin_k16_f64.md",
+        "kernel": "spmm_stream_kernel<double, 2, 8, true, true, false> (16-bit column offsets, one wavefront per chunk)"},
     "table3_audikw_1_n943695_f64": {
         "traffic": 814.08e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 4> (1: 16-bit column offsets; 4 wavefronts per workgroup)"},
