@@ -213,7 +213,7 @@ def ceiling_gather(torch, dev, table_len=1 << 22, n=1 << 26, reps=10):
     return {"gather_G_per_s": round(n / (ms * 1e-3) / 1e9, 2), "gather_table_bytes": table_len * 8, "gathers": n}
 
 
-def ceiling_rows(torch, dev, table_bytes=(1 << 20, 8 << 20, 1 << 30), waves_per_cu=12, iters=200):
+def ceiling_rows(torch, dev, table_bytes=(1 << 20, 2 << 20, 4 << 20, 8 << 20, 32 << 20, 1 << 30), waves_per_cu=12, iters=200):
     """128-byte rows through the L1 of every CU (16 bytes per lane, 16 rows in flight): TB/s by table size."""
     from paper_2509_25605_amd import ceilings as C
     sink = torch.zeros(8, dtype=torch.float64, device=dev)
