@@ -36,42 +36,46 @@ EPS = {np.dtype(np.float64): 2.0 ** -53, np.dtype(np.float32): 2.0 ** -24}
 # summary the figure is taken from.
 MEASURED = {
     "poisson2d_64x64_f64": {
-        "traffic": 0.44e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_poisson2d_64_f64.md",
+        "traffic": 0.44e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_poisson2d_64_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
     "stencil27_128x128x128_f64": {
-        "traffic": 505.35e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_stencil27_128_f64.md",
+        "traffic": 505.35e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_stencil27_128_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 4, 16, 1> (4: row patterns)"},
     "uniform16_n4194304_f64": {
-        "traffic": 8439.92e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_uniform16_f64.md",
+        "traffic": 8439.92e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_uniform16_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 0, 16, 1> (0: 32-bit columns)"},
     "zipf1.8_cap200000_n8388608_f32": {
-        "traffic": 8689.40e6, "source": "d44fc9c294de", "profile": "profiles/spmv_powerlaw_zipf_f32.md",
+        "traffic": 8689.40e6, "source": "5101719d3314", "profile": "profiles/spmv_powerlaw_zipf_f32.md",
         "kernel": "spmv_short_kernel<float, true> (2 launches) + spmv_ldsblock_kernel<float> + spmv_stream_kernel<float, ...>"},
     "stencil27_128x128x128_f64_spmm_k16": {
-        "traffic": 1039.14e6, "source": "d44fc9c294de", "profile": "profiles/spmm_shared_stencil27_128_k16_f64.md",
+        "traffic": 1038.58e6, "source": "536874115369", "profile": "profiles/spmm_shared_stencil27_128_k16_f64.md",
         "kernel": "spmm_shared_kernel<double, 2, 8, true> (rows of X shared by 4 consecutive rows)"},
     "table3_StocF-1465_n1465137_f64": {
-        "traffic": 243.82e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_stocf_standin_f64.md",
+        "traffic": 243.82e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_stocf_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 2, true, 1, 16, 1> (1: 16-bit column offsets)"},
     "table3_PFlow_742_n742793_f64": {
-        "traffic": 399.93e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_pflow_standin_f64.md",
+        "traffic": 399.93e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_pflow_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 4, true, 1, 16, 2> (1: 16-bit column offsets; 2 wavefronts per workgroup)"},
     "table3_Elasticity3D_60_n648000_f64": {
-        "traffic": 430.27e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_elasticity3d_60_standin_f64.md",
+        "traffic": 430.27e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_elasticity3d_60_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 8, true, 4, 16, 1> (4: row patterns, with shifts)"},
     "table3_Elasticity3D_60_n648000_f64_spmm_k16": {
-        "traffic": 1007.47e6, "source": "d44fc9c294de",
+        "traffic": 996.11e6, "source": "536874115369",
         "profile": "profiles/spmm_block_shared_elasticity3d_60_standin_k16_f64.md",
         "kernel": "spmm_block_shared_kernel<double, 2, true, 3, 32> (rows of X shared by the rows of a grid point) + "
                   "spmm_stream_kernel<double, 2, 8, true, true, true> (the other chunks)"},
     "table3_PFlow_742_n742793_f64_spmm_k16": {
-        "traffic": 576.97e6, "source": "d44fc9c294de", "profile": "profiles/spmm_stream_pflow_standin_k16_f64.md",
+        "traffic": 576.93e6, "source": "536874115369", "profile": "profiles/spmm_stream_pflow_standin_k16_f64.md",
         "kernel": "spmm_stream_kernel<double, 2, 8, true, true, false> (16-bit column offsets, one wavefront per chunk)"},
     "table3_audikw_1_n943695_f64": {
-        "traffic": 814.08e6, "source": "d44fc9c294de", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
+        "traffic": 814.08e6, "source": "5101719d3314", "profile": "profiles/spmv_stream_audikw_standin_f64.md",
         "kernel": "spmv_stream_kernel<double, 8, true, 1, 16, 4> (1: 16-bit column offsets; 4 wavefronts per workgroup)"},
 }
-FINGERPRINT_FILES = ["spmv_kernels.hpp", "spmm_kernels.hpp", "analysis_kernels.hpp", "lapis_api.hip", "device_utils.hpp"]
+# The sources a product is compiled from: lapis_spmv does not include the SpMM kernels.
+FINGERPRINT_FILES = {
+    "spmv": ["spmv_kernels.hpp", "analysis_kernels.hpp", "lapis_api.hip", "device_utils.hpp"],
+    "spmm": ["spmv_kernels.hpp", "spmm_kernels.hpp", "analysis_kernels.hpp", "lapis_api.hip", "device_utils.hpp"],
+}
 
 
 def strip_comments(text):
@@ -99,11 +103,11 @@ def strip_comments(text):
     return " ".join("".join(out).split())
 
 
-def source_fingerprint():
-    """First 12 hex digits of the SHA-256 of the kernel and launch sources (csrc/) without their comments,
-    so that a traffic figure measured with other code is recognisable as stale."""
+def source_fingerprint(product="spmv"):
+    """First 12 hex digits of the SHA-256 of the kernel and launch sources (csrc/) of a product ("spmv" or
+    "spmm") without their comments, so that a traffic figure measured with other code is recognisable as stale."""
     h = hashlib.sha256()
-    for name in FINGERPRINT_FILES:
+    for name in FINGERPRINT_FILES[product]:
         with open(os.path.join(ROOT, "paper_2509_25605_amd", "csrc", name), "r", encoding="utf-8") as f:
             h.update(strip_comments(f.read()).encode("utf-8"))
             h.update(b"\0")
@@ -372,7 +376,7 @@ def run_workload(cfg, scale, variant, steps, warmup, cpu_seconds, torch, gen, L,
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": traffic,
         "traffic_frac": round(traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
-        "traffic_stale": (m["source"] != fingerprint) if m else None,
+        "traffic_stale": (m["source"] != source_fingerprint("spmm" if w.k else "spmv")) if m else None,
         "kernel": (m["kernel"] if m else "all kernels of the step") if variant == "tuned" else VARIANT_KERNEL[variant],
         "cpu_baseline": cpu, "parity": parity,
     }
@@ -418,7 +422,7 @@ def main():
     ap.add_argument("--fingerprint", action="store_true", help="print the fingerprint of the kernel sources and exit")
     args = ap.parse_args()
     if args.fingerprint:
-        print(source_fingerprint())
+        print(f"spmv {source_fingerprint('spmv')} spmm {source_fingerprint('spmm')}")
         return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1")
@@ -460,7 +464,7 @@ def main():
     cfg = 2 if args.config is None else args.config
     if args.zipf_s is not None and cfg == 4:
         scale["s"] = args.zipf_s
-    fingerprint = source_fingerprint()
+    fingerprint = source_fingerprint("spmm" if (args.spmm_k or (args.config == 5)) else "spmv")
     head, w = run_workload(cfg, scale, args.variant, args.steps, args.warmup,
                            None if args.no_cpu else args.cpu_seconds, torch, gen, L, dev, fingerprint,
                            spmm_k=args.spmm_k)

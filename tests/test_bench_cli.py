@@ -59,6 +59,7 @@ def test_source_fingerprint_follows_the_kernel_sources():
     import bench
     fp = bench.source_fingerprint()
     assert len(fp) == 12 and int(fp, 16) >= 0
+    assert bench.source_fingerprint("spmm") != bench.source_fingerprint("spmv")      # the SpMM kernels count for SpMM only
     for m in bench.MEASURED.values():
         assert set(m) == {"traffic", "source", "kernel", "profile"}
         assert os.path.exists(os.path.join(ROOT, m["profile"]))
