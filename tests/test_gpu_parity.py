@@ -810,6 +810,28 @@ def test_spmm_few_stream_chunks_long_and_short_rows(per_row, dtype, k):
         dev.close()
 
 
+@pytest.mark.parametrize("ldx", [(1 << 21) - 8, 1 << 21])
+def test_spmm_rows_of_x_sixteen_mebibytes_apart(ldx):
+    """The kernels that share rows of X address them with 32-bit offsets from a row near the chunk's own and
+    are used while a row of X is shorter than 16 MiB; at that length and beyond the ordinary path runs.
+    A band matrix whose chunks all qualify, with leading dimensions just below and at the limit."""
+    say(f"spmm with ldx={ldx} doubles")
+    n, k = 32 * 6 + 5, 16
+    rows = [[j for j in range(i - 4, i + 5) if 0 <= j < n] for i in range(n)]
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in r], dtype=np.int32)
+    vals = gen.uniform(71, gen.STREAM_VALUES, colidx.size)
+    X = gen.uniform(71, gen.STREAM_X, n * k).reshape(n, k)
+    dev = DeviceCsr(n, n, rowptr, colidx, vals)
+    try:
+        classes = dev.share_classes()
+        assert classes is not None and np.all(classes[:-1] == oracle.SHARE_PLAIN)     # the last 5 rows are too few to stream
+        check_spmm(dev, rowptr, colidx, vals, X, what="alpha=1 beta=0", ldx=ldx, ldy=k + 1)
+    finally:
+        dev.close()
+
+
 @pytest.mark.parametrize("dtype,k", [(np.float64, 16), (np.float32, 8), (np.float64, 3)])
 def test_spmm_many_stream_chunks_one_wavefront_per_chunk(dtype, k):
     """More than 8192 stream chunks without shared rows of X: the launch with one wavefront per chunk."""
